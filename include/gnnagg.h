@@ -1,0 +1,178 @@
+/*
+ * gnnagg -- neighbour aggregation for full-batch GNN training on one MI355X.
+ *
+ * C ABI of libgnnagg.so.  Plain pointers and sizes only; every array argument
+ * is a DEVICE pointer unless a comment says "host".  The library never frees
+ * or keeps a caller's buffer beyond the stream work of the call it was passed
+ * to.  No exception or abort crosses this boundary: every call returns a
+ * gnn_status; gnn_status_string() names it.
+ *
+ * Graph convention (Section 4.1 of the DistGNN paper): the adjacency matrix is
+ * stored in CSR by DESTINATION.  Row v of (indptr, indices) lists the sources
+ * u of the edges u->v; features are pulled from the sources and reduced into
+ * the destination, one owner per output row.
+ *
+ * Preconditions that the hot calls do NOT check (gnn_validate_csr does):
+ * indptr[0] == 0, indptr non-decreasing, 0 <= indices[e] < N.
+ */
+#ifndef GNNAGG_H
+#define GNNAGG_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GNN_API __attribute__((visibility("default")))
+
+typedef enum gnn_status {
+    GNN_OK = 0,
+    GNN_ERR_INVALID_ARG = 1, /* null required pointer, negative size, unknown enum, ld < F, misaligned base */
+    GNN_ERR_UNSUPPORTED = 2, /* valid request this build cannot serve (e.g. an op that needs a plan, without one) */
+    GNN_ERR_ALLOC = 3,       /* device or host allocation failed (plan creation / workspace growth only) */
+    GNN_ERR_LAUNCH = 4,      /* the HIP runtime reported an error at launch or copy */
+    GNN_ERR_INVALID_GRAPH = 5 /* gnn_validate_csr found a violated precondition */
+} gnn_status;
+
+/* Reduce variants.  All are sum-reductions over the in-neighbours (Table 1:
+ * reducer "sum", message "copylhs", or "mul" by a scalar edge feature when
+ * edge_w is given); they differ in the scaling:
+ *   SUM      Y[v] = sum_e c_e X[u_e]                c_e = edge_w[e] or 1
+ *   MEAN     SUM divided by the row length din[v] (stored edges; empty row -> 0)
+ *   GCN_SYM  c_e = 1/sqrt(max(dout[u],1) * max(din[v],1)) when edge_w == NULL;
+ *            with edge_w the weights are taken as given (same as SUM).
+ * (The paper's own runs use sum plus a degree normalisation, Section 6.1.) */
+typedef enum gnn_op { GNN_SUM = 0, GNN_MEAN = 1, GNN_GCN_SYM = 2 } gnn_op;
+
+typedef enum gnn_dtype { GNN_F32 = 0, GNN_BF16 = 1 } gnn_dtype;
+
+typedef struct gnn_plan gnn_plan; /* opaque; owns its device buffers */
+
+/* Options of the hot calls.  Zero-initialise, then set what differs. */
+typedef struct gnn_opts {
+    int32_t dtype;         /* gnn_dtype of X and Y (same for both).  Accumulation is always fp32;
+                              BF16 output is rounded to nearest-even once, at the store. */
+    int32_t indptr_is_64;  /* 0: indptr is int32_t[N+1];  1: int64_t[N+1] */
+    int64_t ldx;           /* row stride of the gathered matrix in elements; 0 means F */
+    int64_t ldy;           /* row stride of the output matrix in elements; 0 means F */
+    void *stream;          /* hipStream_t to enqueue on; NULL = the null stream */
+    gnn_plan *plan;        /* degree-binning plan OF THE GRAPH PASSED IN THE SAME CALL (forward plan
+                              for _fwd, plan of the transposed graph for _bwd); NULL = un-binned
+                              wavefront-per-row kernel, no hub splitting */
+    void *workspace;       /* optional device scratch for hub-row partial sums; NULL = plan-owned
+                              scratch, grown (allocation!) on the first call that needs more */
+    int64_t workspace_bytes;
+} gnn_opts;
+
+/* Degree-binning parameters.  thresholds t[0] < ... < t[k-1], all > 0, cut the
+ * row-length axis into k+1 bins, bin(v) = #{i : t[i] <= deg(v)}.  If
+ * hub_chunk > 0 the rows of the LAST bin are "hub" rows: each is cut into
+ * pieces of hub_chunk consecutive edges that different wavefronts reduce, and a
+ * second kernel adds the pieces in a fixed order (deterministic, no float
+ * atomics).  NULL params = defaults (gnn_plan_default_params). */
+#define GNN_MAX_THRESHOLDS 15
+typedef struct gnn_plan_params {
+    int32_t n_thresholds;
+    int64_t thresholds[GNN_MAX_THRESHOLDS];
+    int64_t hub_chunk;
+} gnn_plan_params;
+
+/* ---------------------------------------------------------------- hot path */
+
+/* Forward aggregation (Section 4.1, Algorithm 1; equals the sparse-times-dense
+ * product of Section 2.1):
+ *     Y[v, 0:F] = scale_v * sum_{e in row v} c_e * X[indices[e], 0:F]
+ * indptr   [N+1] int32 or int64 (opts->indptr_is_64), CSR by destination
+ * indices  [E] int32 source ids, E = indptr[N]
+ * edge_w   [E] fp32 in CSR edge order, or NULL
+ * X        [N, ldx] gathered matrix, Y [N, ldy] output; fp32 or bf16 per opts->dtype
+ * Y is OVERWRITTEN (rows without edges become +0); X and Y must not overlap.
+ * Base pointers must be aligned to 16 bytes when the row stride in bytes is a
+ * multiple of 16 (8 / 4 / 2 likewise); otherwise narrower loads are used.
+ * Asynchronous: returns after enqueueing on opts->stream.  N == 0 or F == 0 is
+ * GNN_OK and does nothing.  opts == NULL means all defaults.
+ * MEAN needs no plan; GCN_SYM without edge_w needs a plan (it holds dout). */
+GNN_API int gnn_aggregate_fwd(const void *indptr, const int32_t *indices, const float *edge_w,
+                      const void *X, void *Y, int64_t N, int64_t F, int op, const gnn_opts *opts);
+
+/* Backward aggregation: the adjoint of the forward map over the transposed
+ * graph (the paper only implies it, Section 6.3 "Memory"):
+ *     dX[u, 0:F] = sum_{e' in transposed row u} c_e' * dY[indices_t[e'], 0:F]
+ * indptr_t / indices_t / edge_w_t describe the TRANSPOSED graph (CSR by
+ * source; gnn_transpose_csr builds them).  c_e' carries the same factors as in
+ * the forward pass: for MEAN 1/din[v] of the GATHERED vertex v, for GCN_SYM
+ * without weights 1/sqrt(max(dout[u],1)*max(din[v],1)).  MEAN and weight-less
+ * GCN_SYM therefore need opts->plan (a plan of the transposed graph, which
+ * holds din as its column counts); without one they return
+ * GNN_ERR_UNSUPPORTED.  No gradient with respect to edge weights is produced.
+ * Everything else as for gnn_aggregate_fwd. */
+GNN_API int gnn_aggregate_bwd(const void *indptr_t, const int32_t *indices_t, const float *edge_w_t,
+                      const void *dY, void *dX, int64_t N, int64_t F, int op, const gnn_opts *opts);
+
+/* ------------------------------------------------------- once-per-graph setup */
+
+/* Row pointers of the destination-indexed CSR (Section 4.1 requires the graph
+ * in CSR) from a destination array sorted ascending:
+ * indptr[v] = #{e : dst_sorted[e] < v}.  indptr_out has N+1 entries of the
+ * width indptr_is_64 selects.  E may be 0.  Asynchronous on `stream`. */
+GNN_API int gnn_csr_from_sorted_coo(const int32_t *dst_sorted, int64_t E, int64_t N,
+                            void *indptr_out, int indptr_is_64, void *stream);
+
+/* Transposed graph (what the backward pass runs over), by a STABLE sort on the
+ * source id: inside transposed row u the edges keep their CSR order, so a CSR
+ * with ascending neighbours gives ascending destinations.
+ * Outputs (caller-allocated): indptr_t [N+1] (same width as indptr),
+ * indices_t [E] int32, and optionally perm [E] int64 (perm[e'] = CSR position
+ * of transposed edge e'; may be NULL) and edge_w_t [E] = edge_w[perm] (only if
+ * edge_w != NULL).  E is read from the device (indptr[N]); the call allocates
+ * temporary device memory (about 24 bytes per edge), frees it and is
+ * SYNCHRONOUS with respect to `stream`. */
+GNN_API int gnn_transpose_csr(const void *indptr, const int32_t *indices, const float *edge_w,
+                      int64_t N, int indptr_is_64, void *indptr_t, int32_t *indices_t,
+                      int64_t *perm, float *edge_w_t, void *stream);
+
+/* Checks the preconditions of the hot calls on the device (debug aid; reads E
+ * back, synchronous).  GNN_OK or GNN_ERR_INVALID_GRAPH. */
+GNN_API int gnn_validate_csr(const void *indptr, const int32_t *indices, int64_t N, int64_t E,
+                     int indptr_is_64, void *stream);
+
+/* Degree-binning plan of one graph orientation: the GPU replacement for the
+ * dynamic scheduling of destination rows in Section 4.2 ("Multithreading").
+ * Holds row_perm (rows grouped by bin, ascending row id inside a bin),
+ * bin_offsets, the hub-row piece list and the per-vertex column counts
+ * (#occurrences of each vertex in `indices`: dout for a forward graph, din for
+ * a transposed one).  Synchronous; allocates device memory owned by the plan.
+ * params == NULL: defaults.  *out receives the plan. */
+GNN_API void gnn_plan_default_params(gnn_plan_params *params /* host, out */);
+GNN_API int gnn_plan_create(const void *indptr, const int32_t *indices, int64_t N, int indptr_is_64,
+                    const gnn_plan_params *params /* host */, void *stream, gnn_plan **out);
+GNN_API void gnn_plan_destroy(gnn_plan *plan);
+
+/* Sizes of what gnn_plan_export would write (host outputs). */
+GNN_API int gnn_plan_sizes(const gnn_plan *plan, int64_t *n_rows, int32_t *n_bins, int64_t *n_chunks);
+/* Copies the plan to HOST arrays for inspection / bit-exact checks:
+ * bin_offsets int64[n_bins+1], row_perm int32[n_rows], chunks int64[n_chunks*3]
+ * as (row, e_begin, e_end), col_counts int32[n_rows].  Any may be NULL. */
+GNN_API int gnn_plan_export(const gnn_plan *plan, int64_t *bin_offsets, int32_t *row_perm,
+                    int64_t *chunks, int32_t *col_counts);
+/* Bytes of scratch a hot call with this plan and width F needs (hub partials). */
+GNN_API int64_t gnn_plan_workspace_bytes(const gnn_plan *plan, int64_t F);
+/* Grow the plan-owned scratch now, so later hot calls do not allocate. */
+GNN_API int gnn_plan_reserve(gnn_plan *plan, int64_t F);
+
+/* ---------------------------------------------------------------- utilities */
+GNN_API const char *gnn_status_string(int status);
+
+/* Bandwidth calibration kernels used by the bench to print measured ceilings
+ * next to each result: a streaming copy of n_bytes (multiple of 16), and a
+ * gather of n_rows_out rows of row_bytes (multiple of 16) from a table of
+ * n_rows_table rows at pseudo-random row ids, written to a stream. */
+GNN_API int gnn_calib_copy(const void *src, void *dst, int64_t n_bytes, void *stream);
+GNN_API int gnn_calib_gather(const void *table, int64_t n_rows_table, int64_t row_bytes,
+                     void *out, int64_t n_rows_out, uint64_t seed, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GNNAGG_H */

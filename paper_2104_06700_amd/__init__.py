@@ -1,0 +1,16 @@
+"""MI355X-native neighbour aggregation (forward over CSR, backward over the
+transposed graph) behind the C ABI declared in include/gnnagg.h.
+
+The Python layer only marshals arguments; all arithmetic and all graph
+preprocessing (row pointers, transpose, degree binning) run in the library's
+HIP kernels.
+"""
+from .binding import (  # noqa: F401
+    GNN_OK, GNN_ERR_INVALID_ARG, GNN_ERR_UNSUPPORTED, GNN_ERR_ALLOC, GNN_ERR_LAUNCH, GNN_ERR_INVALID_GRAPH,
+    GNN_SUM, GNN_MEAN, GNN_GCN_SYM, GNN_F32, GNN_BF16, GNN_MAX_THRESHOLDS, EXPORTED_SYMBOLS, LIB_PATH,
+    GnnError, GnnOpts, GnnPlanParams, Plan,
+    load_library, status_string, make_plan_params,
+    gnn_aggregate_fwd, gnn_aggregate_bwd, gnn_csr_from_sorted_coo, gnn_transpose_csr, gnn_validate_csr,
+    gnn_plan_default_params, gnn_plan_create, gnn_calib_copy, gnn_calib_gather,
+)
+from .graph import DeviceGraph, build_device_graph  # noqa: F401

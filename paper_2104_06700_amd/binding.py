@@ -1,0 +1,256 @@
+"""ctypes binding of libgnnagg.so: same names as the C ABI, argument marshalling only.
+
+Every step of the path runs inside the library's HIP kernels; torch is used here
+for device memory and the current stream.  There is no CPU fallback: if the
+shared library is missing, importing a symbol from it raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libgnnagg.so")
+
+GNN_OK, GNN_ERR_INVALID_ARG, GNN_ERR_UNSUPPORTED, GNN_ERR_ALLOC, GNN_ERR_LAUNCH, GNN_ERR_INVALID_GRAPH = range(6)
+GNN_SUM, GNN_MEAN, GNN_GCN_SYM = 0, 1, 2
+GNN_F32, GNN_BF16 = 0, 1
+GNN_MAX_THRESHOLDS = 15
+
+EXPORTED_SYMBOLS = (
+    "gnn_aggregate_fwd", "gnn_aggregate_bwd", "gnn_csr_from_sorted_coo", "gnn_transpose_csr",
+    "gnn_validate_csr", "gnn_plan_default_params", "gnn_plan_create", "gnn_plan_destroy",
+    "gnn_plan_sizes", "gnn_plan_export", "gnn_plan_workspace_bytes", "gnn_plan_reserve",
+    "gnn_status_string", "gnn_calib_copy", "gnn_calib_gather",
+)
+
+
+class GnnOpts(ctypes.Structure):
+    _fields_ = [
+        ("dtype", ctypes.c_int32), ("indptr_is_64", ctypes.c_int32),
+        ("ldx", ctypes.c_int64), ("ldy", ctypes.c_int64),
+        ("stream", ctypes.c_void_p), ("plan", ctypes.c_void_p),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_int64),
+    ]
+
+
+class GnnPlanParams(ctypes.Structure):
+    _fields_ = [
+        ("n_thresholds", ctypes.c_int32),
+        ("thresholds", ctypes.c_int64 * GNN_MAX_THRESHOLDS),
+        ("hub_chunk", ctypes.c_int64),
+    ]
+
+
+class GnnError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        self.status = status
+        super().__init__(f"{fn} failed: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """dlopen the in-tree library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                              "(there is no fallback path)")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+        lib.gnn_aggregate_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, ctypes.POINTER(GnnOpts)]
+        lib.gnn_aggregate_bwd.argtypes = lib.gnn_aggregate_fwd.argtypes
+        lib.gnn_csr_from_sorted_coo.argtypes = [vp, i64, i64, vp, i32, vp]
+        lib.gnn_transpose_csr.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, vp, vp]
+        lib.gnn_validate_csr.argtypes = [vp, vp, i64, i64, i32, vp]
+        lib.gnn_plan_default_params.argtypes = [ctypes.POINTER(GnnPlanParams)]
+        lib.gnn_plan_default_params.restype = None
+        lib.gnn_plan_create.argtypes = [vp, vp, i64, i32, ctypes.POINTER(GnnPlanParams), vp, ctypes.POINTER(vp)]
+        lib.gnn_plan_destroy.argtypes = [vp]
+        lib.gnn_plan_destroy.restype = None
+        lib.gnn_plan_sizes.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(i64)]
+        lib.gnn_plan_export.argtypes = [vp, vp, vp, vp, vp]
+        lib.gnn_plan_workspace_bytes.argtypes = [vp, i64]
+        lib.gnn_plan_workspace_bytes.restype = i64
+        lib.gnn_plan_reserve.argtypes = [vp, i64]
+        lib.gnn_status_string.argtypes = [i32]
+        lib.gnn_status_string.restype = ctypes.c_char_p
+        lib.gnn_calib_copy.argtypes = [vp, vp, i64, vp]
+        lib.gnn_calib_gather.argtypes = [vp, i64, i64, vp, i64, ctypes.c_uint64, vp]
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load_library().gnn_status_string(int(status)).decode()
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_contiguous() and t.dim() == 1:
+        raise ValueError("1-D arguments must be contiguous")
+    return t.data_ptr() if t.numel() > 0 else (t.data_ptr() or None)
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream or None
+    return int(stream) or None
+
+
+def _check(fn: str, status: int) -> None:
+    if status != GNN_OK:
+        raise GnnError(fn, status)
+
+
+def _is64(indptr: torch.Tensor) -> int:
+    if indptr.dtype == torch.int64:
+        return 1
+    if indptr.dtype == torch.int32:
+        return 0
+    raise TypeError("indptr must be int32 or int64")
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return GNN_F32
+    if t.dtype == torch.bfloat16:
+        return GNN_BF16
+    raise TypeError("features must be float32 or bfloat16")
+
+
+class Plan:
+    """Owner of a gnn_plan handle (destroyed with the object)."""
+
+    def __init__(self, handle: int, n_thresholds: int):
+        self.handle = handle
+        self.n_thresholds = n_thresholds
+
+    def __del__(self):
+        h, self.handle = getattr(self, "handle", None), None
+        if h and _lib is not None:
+            _lib.gnn_plan_destroy(h)
+
+    def sizes(self):
+        n = ctypes.c_int64(); b = ctypes.c_int32(); c = ctypes.c_int64()
+        _check("gnn_plan_sizes", load_library().gnn_plan_sizes(self.handle, ctypes.byref(n), ctypes.byref(b), ctypes.byref(c)))
+        return n.value, b.value, c.value
+
+    def export(self):
+        """Host copies: (bin_offsets int64[n_bins+1], row_perm int32[N], chunks int64[n_chunks,3], col_counts int32[N])."""
+        import numpy as np
+        n, b, c = self.sizes()
+        bin_offsets = np.zeros(b + 1, dtype=np.int64)
+        row_perm = np.zeros(n, dtype=np.int32)
+        chunks = np.zeros((c, 3), dtype=np.int64)
+        col_counts = np.zeros(n, dtype=np.int32)
+        _check("gnn_plan_export", load_library().gnn_plan_export(
+            self.handle, bin_offsets.ctypes.data, row_perm.ctypes.data if n else None,
+            chunks.ctypes.data if c else None, col_counts.ctypes.data if n else None))
+        return bin_offsets, row_perm, chunks, col_counts
+
+    def workspace_bytes(self, F: int) -> int:
+        return int(load_library().gnn_plan_workspace_bytes(self.handle, int(F)))
+
+    def reserve(self, F: int) -> None:
+        _check("gnn_plan_reserve", load_library().gnn_plan_reserve(self.handle, int(F)))
+
+
+def gnn_plan_default_params() -> GnnPlanParams:
+    p = GnnPlanParams()
+    load_library().gnn_plan_default_params(ctypes.byref(p))
+    return p
+
+
+def make_plan_params(thresholds: Sequence[int], hub_chunk: int) -> GnnPlanParams:
+    p = GnnPlanParams()
+    p.n_thresholds = len(thresholds)
+    for i, t in enumerate(thresholds):
+        p.thresholds[i] = int(t)
+    p.hub_chunk = int(hub_chunk)
+    return p
+
+
+def gnn_plan_create(indptr: torch.Tensor, indices: torch.Tensor, N: int,
+                    params: Optional[GnnPlanParams] = None, stream=None) -> Plan:
+    out = ctypes.c_void_p()
+    st = load_library().gnn_plan_create(_ptr(indptr), _ptr(indices), int(N), _is64(indptr),
+                                        ctypes.byref(params) if params is not None else None,
+                                        _stream(stream), ctypes.byref(out))
+    _check("gnn_plan_create", st)
+    k = params.n_thresholds if params is not None else gnn_plan_default_params().n_thresholds
+    return Plan(out.value, k)
+
+
+def _aggregate(fn_name, indptr, indices, edge_w, X, Y, N, F, op, plan, stream, workspace, ldx, ldy):
+    lib = load_library()
+    if X.dtype != Y.dtype:
+        raise TypeError("input and output features must have the same dtype")
+    o = GnnOpts()
+    o.dtype = _dtype_code(X)
+    o.indptr_is_64 = _is64(indptr)
+    o.ldx = int(ldx if ldx is not None else (X.stride(0) if X.dim() == 2 and X.shape[0] > 1 else 0))
+    o.ldy = int(ldy if ldy is not None else (Y.stride(0) if Y.dim() == 2 and Y.shape[0] > 1 else 0))
+    o.stream = _stream(stream)
+    o.plan = plan.handle if plan is not None else None
+    if workspace is not None:
+        o.workspace = workspace.data_ptr()
+        o.workspace_bytes = workspace.numel() * workspace.element_size()
+    st = getattr(lib, fn_name)(_ptr(indptr), _ptr(indices), _ptr(edge_w), _ptr(X), _ptr(Y),
+                               int(N), int(F), int(op), ctypes.byref(o))
+    _check(fn_name, st)
+
+
+def gnn_aggregate_fwd(indptr, indices, edge_w, X, Y, N, F, op, plan: Optional[Plan] = None, stream=None,
+                      workspace=None, ldx=None, ldy=None) -> None:
+    """Y[v] = scale_v * sum_e c_e X[indices[e]] over the CSR by destination (see include/gnnagg.h)."""
+    _aggregate("gnn_aggregate_fwd", indptr, indices, edge_w, X, Y, N, F, op, plan, stream, workspace, ldx, ldy)
+
+
+def gnn_aggregate_bwd(indptr_t, indices_t, edge_w_t, dY, dX, N, F, op, plan: Optional[Plan] = None, stream=None,
+                      workspace=None, ldx=None, ldy=None) -> None:
+    """dX = adjoint of the forward map, over the transposed graph (see include/gnnagg.h)."""
+    _aggregate("gnn_aggregate_bwd", indptr_t, indices_t, edge_w_t, dY, dX, N, F, op, plan, stream, workspace, ldx, ldy)
+
+
+def gnn_csr_from_sorted_coo(dst_sorted: torch.Tensor, N: int, indptr_out: torch.Tensor, stream=None) -> None:
+    st = load_library().gnn_csr_from_sorted_coo(_ptr(dst_sorted), int(dst_sorted.numel()), int(N), _ptr(indptr_out),
+                                                _is64(indptr_out), _stream(stream))
+    _check("gnn_csr_from_sorted_coo", st)
+
+
+def gnn_transpose_csr(indptr, indices, edge_w, N, indptr_t, indices_t, perm=None, edge_w_t=None, stream=None) -> None:
+    if indptr_t.dtype != indptr.dtype:
+        raise TypeError("indptr_t must have the dtype of indptr")
+    if perm is not None and perm.dtype != torch.int64:
+        raise TypeError("perm must be int64")
+    st = load_library().gnn_transpose_csr(_ptr(indptr), _ptr(indices), _ptr(edge_w), int(N), _is64(indptr),
+                                          _ptr(indptr_t), _ptr(indices_t), _ptr(perm), _ptr(edge_w_t), _stream(stream))
+    _check("gnn_transpose_csr", st)
+
+
+def gnn_validate_csr(indptr, indices, N, E, stream=None) -> int:
+    """Returns the status (GNN_OK or GNN_ERR_INVALID_GRAPH); raises on other errors."""
+    st = load_library().gnn_validate_csr(_ptr(indptr), _ptr(indices), int(N), int(E), _is64(indptr), _stream(stream))
+    if st not in (GNN_OK, GNN_ERR_INVALID_GRAPH):
+        raise GnnError("gnn_validate_csr", st)
+    return st
+
+
+def gnn_calib_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
+    st = load_library().gnn_calib_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), _stream(stream))
+    _check("gnn_calib_copy", st)
+
+
+def gnn_calib_gather(table: torch.Tensor, out: torch.Tensor, seed: int = 1, stream=None) -> None:
+    row_bytes = table.shape[1] * table.element_size()
+    st = load_library().gnn_calib_gather(_ptr(table), table.shape[0], row_bytes, _ptr(out), out.shape[0], seed, _stream(stream))
+    _check("gnn_calib_gather", st)

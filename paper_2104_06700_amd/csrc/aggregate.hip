@@ -1,0 +1,514 @@
+// Neighbour aggregation kernels (Section 4.1, Algorithm 1) for gfx950.
+//
+//   Y[v, :] = dst_scale(v) * sum_{e in row v} coef(e) * X[indices[e], :]
+//
+// The same kernel serves the forward pass (CSR by destination) and the
+// backward pass (the transposed graph): only the arrays and the scale modes
+// differ.  This is HBM/cache-bandwidth-bound gather work, not a dense
+// contraction, so there is no MFMA here; the design points are
+//   * a 64-lane wavefront is cut into row groups of G lanes; a group owns one
+//     output row (one owner per row, as in the paper, so no atomics).  Inside a
+//     group, C lanes span the feature row with 16/8/4-byte loads and SR = G/C
+//     "edge slots" walk the neighbour list SR edges at a time; the slots are
+//     combined with wavefront shuffles at the end of the row.  G, SR come from
+//     the degree bin of the row (light rows: many rows per wavefront; heavy
+//     rows: the whole wavefront on one row).
+//   * neighbour ids (and per-edge coefficients) are fetched as one coalesced
+//     tile per group and handed to the slots by cross-lane shuffles, so the
+//     index stream is read once, fully coalesced;
+//   * accumulation stays in registers for the whole neighbour loop and the
+//     output row is written once (the loop order of Algorithm 3);
+//   * rows of the hub bin are cut into pieces reduced by different wavefronts
+//     into an fp32 scratch; a second kernel adds the pieces in fixed order.
+#include "common.h"
+
+namespace {
+
+constexpr int kBlockThreads = 256;
+constexpr int kWavesPerBlock = kBlockThreads / 64;
+
+enum ScaleMode : int { kScaleNone = 0, kScaleInv = 1, kScaleRsqrt = 2 };
+enum BinKind : int { kKindRows = 0, kKindHubPieces = 1 };
+
+struct BinDesc {
+    int64_t first_block;  // first blockIdx.x of this bin
+    int64_t item_begin;   // offset into row_perm (rows) or into the piece list (hub pieces)
+    int64_t n_items;      // rows or pieces
+    int32_t log2_g;       // lanes per row group
+    int32_t log2_sr;      // edge slots per group
+    int32_t kind;
+    int32_t pad;
+};
+
+struct AggArgs {
+    const void *indptr;
+    const int32_t *indices;
+    const float *w;
+    const void *X;
+    void *Y;
+    int64_t ldx, ldy;
+    int32_t F;
+    int32_t ip64;
+    const int32_t *row_perm;    // nullptr: identity
+    const int32_t *col_counts;  // degree of the gathered vertex (for src scaling)
+    int32_t src_mode, dst_mode;
+    const int64_t *chunks;      // hub pieces (row, e_begin, e_end)
+    float *partial;             // [n_chunks, ldp] fp32
+    int64_t ldp;
+    int32_t n_bins;
+    int32_t pad;
+    BinDesc bins[GNN_MAX_BINS + 1];
+};
+
+// ------------------------------------------------------------ element access
+struct bf16_t { uint16_t bits; };
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(uint32_t(b) << 16); }
+
+// Round to nearest even; NaN stays NaN (quiet).
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return uint16_t((u >> 16) | 0x0040u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return uint16_t(u >> 16);
+}
+
+template <typename T, int VEC> struct VecIO;
+
+template <> struct VecIO<float, 4> {
+    static __device__ __forceinline__ void load(const float *p, float (&v)[4]) {
+        float4 t = *reinterpret_cast<const float4 *>(p); v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    }
+    static __device__ __forceinline__ void store(float *p, const float (&v)[4]) {
+        *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+};
+template <> struct VecIO<float, 2> {
+    static __device__ __forceinline__ void load(const float *p, float (&v)[2]) {
+        float2 t = *reinterpret_cast<const float2 *>(p); v[0] = t.x; v[1] = t.y;
+    }
+    static __device__ __forceinline__ void store(float *p, const float (&v)[2]) {
+        *reinterpret_cast<float2 *>(p) = make_float2(v[0], v[1]);
+    }
+};
+template <> struct VecIO<float, 1> {
+    static __device__ __forceinline__ void load(const float *p, float (&v)[1]) { v[0] = *p; }
+    static __device__ __forceinline__ void store(float *p, const float (&v)[1]) { *p = v[0]; }
+};
+template <> struct VecIO<bf16_t, 8> {
+    static __device__ __forceinline__ void load(const bf16_t *p, float (&v)[8]) {
+        uint4 t = *reinterpret_cast<const uint4 *>(p);
+        uint32_t w[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { v[2 * i] = __uint_as_float(w[i] << 16); v[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u); }
+    }
+    static __device__ __forceinline__ void store(bf16_t *p, const float (&v)[8]) {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = uint32_t(f32_to_bf16(v[2 * i])) | (uint32_t(f32_to_bf16(v[2 * i + 1])) << 16);
+        *reinterpret_cast<uint4 *>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
+template <> struct VecIO<bf16_t, 4> {
+    static __device__ __forceinline__ void load(const bf16_t *p, float (&v)[4]) {
+        uint2 t = *reinterpret_cast<const uint2 *>(p);
+        v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xFFFF0000u);
+        v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xFFFF0000u);
+    }
+    static __device__ __forceinline__ void store(bf16_t *p, const float (&v)[4]) {
+        uint2 t;
+        t.x = uint32_t(f32_to_bf16(v[0])) | (uint32_t(f32_to_bf16(v[1])) << 16);
+        t.y = uint32_t(f32_to_bf16(v[2])) | (uint32_t(f32_to_bf16(v[3])) << 16);
+        *reinterpret_cast<uint2 *>(p) = t;
+    }
+};
+template <> struct VecIO<bf16_t, 2> {
+    static __device__ __forceinline__ void load(const bf16_t *p, float (&v)[2]) {
+        uint32_t t = *reinterpret_cast<const uint32_t *>(p);
+        v[0] = __uint_as_float(t << 16); v[1] = __uint_as_float(t & 0xFFFF0000u);
+    }
+    static __device__ __forceinline__ void store(bf16_t *p, const float (&v)[2]) {
+        *reinterpret_cast<uint32_t *>(p) = uint32_t(f32_to_bf16(v[0])) | (uint32_t(f32_to_bf16(v[1])) << 16);
+    }
+};
+template <> struct VecIO<bf16_t, 1> {
+    static __device__ __forceinline__ void load(const bf16_t *p, float (&v)[1]) { v[0] = bf16_to_f32(p->bits); }
+    static __device__ __forceinline__ void store(bf16_t *p, const float (&v)[1]) { p->bits = f32_to_bf16(v[0]); }
+};
+
+// fp32 store of VEC consecutive values (hub partial sums are fp32 whatever T is)
+template <int VEC>
+__device__ __forceinline__ void store_f32(float *p, const float (&v)[VEC]) {
+    if constexpr (VEC % 4 == 0) {
+#pragma unroll
+        for (int i = 0; i < VEC; i += 4) *reinterpret_cast<float4 *>(p + i) = make_float4(v[i], v[i + 1], v[i + 2], v[i + 3]);
+    } else if constexpr (VEC == 2) {
+        *reinterpret_cast<float2 *>(p) = make_float2(v[0], v[1]);
+    } else {
+        *p = v[0];
+    }
+}
+
+__device__ __forceinline__ int64_t load_ip(const void *indptr, int ip64, int64_t i) {
+    return ip64 ? static_cast<const int64_t *>(indptr)[i]
+                : static_cast<int64_t>(static_cast<const int32_t *>(indptr)[i]);
+}
+
+__device__ __forceinline__ float scale_of(int mode, int64_t deg) {
+    float d = static_cast<float>(deg > 1 ? deg : 1);
+    if (mode == kScaleInv) return 1.0f / d;
+    if (mode == kScaleRsqrt) return 1.0f / sqrtf(d);
+    return 1.0f;
+}
+
+// ---------------------------------------------------------------- main kernel
+// T: storage type of X and Y.  VEC: elements per lane per load.  NPASS: feature
+// passes (a lane owns NPASS strips of VEC columns, C*VEC apart).  COEF: edges
+// carry a coefficient (explicit weight and/or a scale of the gathered vertex).
+template <typename T, int VEC, int NPASS, bool COEF>
+__global__ void __launch_bounds__(kBlockThreads) aggregate_kernel(const AggArgs a) {
+    constexpr int U = NPASS >= 4 ? 2 : (NPASS >= 2 ? 4 : 8);  // edges in flight per slot
+    const int lane = threadIdx.x & 63;
+    const int wave_in_block = threadIdx.x >> 6;
+
+    // which bin does this workgroup serve (wave-uniform scan of a tiny table)
+    int b = 0;
+    for (int i = 1; i < a.n_bins; ++i)
+        if (int64_t(blockIdx.x) >= a.bins[i].first_block) b = i;
+    const BinDesc bin = a.bins[b];
+    const int64_t wave_in_bin = (int64_t(blockIdx.x) - bin.first_block) * kWavesPerBlock + wave_in_block;
+
+    const int G = 1 << bin.log2_g;
+    const int SR = 1 << bin.log2_sr;
+    const int log2_c = bin.log2_g - bin.log2_sr;
+    const int C = 1 << log2_c;
+    const int lane_in_g = lane & (G - 1);
+    const int gbase = lane - lane_in_g;
+    const int s = lane_in_g >> log2_c;  // edge slot of this lane
+    const int c = lane_in_g & (C - 1);  // feature strip of this lane
+
+    // the row (or hub piece) this group owns
+    int64_t e0 = 0, e1 = 0, row = -1, row_len = 0;
+    float *partial_out = nullptr;
+    if (bin.kind == kKindHubPieces) {
+        const int64_t piece = wave_in_bin;  // G == 64: one piece per wavefront
+        if (piece < bin.n_items) {
+            const int64_t *p = a.chunks + 3 * (bin.item_begin + piece);
+            row = p[0]; e0 = p[1]; e1 = p[2];
+            partial_out = a.partial + (bin.item_begin + piece) * a.ldp;
+        }
+    } else {
+        const int64_t item = wave_in_bin * (64 >> bin.log2_g) + (lane >> bin.log2_g);
+        if (item < bin.n_items) {
+            row = a.row_perm ? int64_t(a.row_perm[bin.item_begin + item]) : bin.item_begin + item;
+            e0 = load_ip(a.indptr, a.ip64, row);
+            e1 = load_ip(a.indptr, a.ip64, row + 1);
+            row_len = e1 - e0;
+        }
+    }
+
+    float acc[NPASS][VEC];
+#pragma unroll
+    for (int p = 0; p < NPASS; ++p)
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[p][i] = 0.0f;
+
+    const T *__restrict__ X = static_cast<const T *>(a.X);
+    int col[NPASS];
+    bool col_ok[NPASS];
+#pragma unroll
+    for (int p = 0; p < NPASS; ++p) {
+        col[p] = (p * C + c) * VEC;
+        col_ok[p] = col[p] < a.F;
+    }
+
+    for (int64_t tile = e0; __any(tile < e1); tile += G) {
+        // one coalesced tile of neighbour ids (and coefficients) per group
+        const int64_t my_e = tile + lane_in_g;
+        int my_u = 0;
+        float my_cf = 0.0f;
+        if (my_e < e1) {
+            my_u = a.indices[my_e];
+            if (COEF) {
+                my_cf = a.w ? a.w[my_e] : 1.0f;
+                if (a.src_mode != kScaleNone) my_cf *= scale_of(a.src_mode, a.col_counts[my_u]);
+            }
+        }
+        const int64_t left = e1 - tile;
+        const int n_tile = left < G ? (left > 0 ? int(left) : 0) : G;
+
+        for (int j0 = 0; __any(j0 < n_tile); j0 += SR * U) {
+            int u[U];
+            float cf[U];
+            bool ok[U];
+#pragma unroll
+            for (int k = 0; k < U; ++k) {
+                const int j = j0 + k * SR + s;
+                const int src_lane = gbase + (j & (G - 1));
+                u[k] = __shfl(my_u, src_lane);
+                if (COEF) cf[k] = __shfl(my_cf, src_lane);
+                ok[k] = j < n_tile;
+            }
+            float x[U][NPASS][VEC];
+#pragma unroll
+            for (int k = 0; k < U; ++k) {
+                const T *xr = X + int64_t(u[k]) * a.ldx;
+#pragma unroll
+                for (int p = 0; p < NPASS; ++p) {
+                    if (ok[k] && col_ok[p]) {
+                        VecIO<T, VEC>::load(xr + col[p], x[k][p]);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < VEC; ++i) x[k][p][i] = 0.0f;
+                    }
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < U; ++k)
+#pragma unroll
+                for (int p = 0; p < NPASS; ++p)
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) {
+                        if (COEF) acc[p][i] = fmaf(ok[k] ? cf[k] : 0.0f, x[k][p][i], acc[p][i]);
+                        else acc[p][i] += x[k][p][i];
+                    }
+        }
+    }
+
+    // combine the edge slots of the group
+    for (int off = C; off < G; off <<= 1) {
+#pragma unroll
+        for (int p = 0; p < NPASS; ++p)
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[p][i] += __shfl_xor(acc[p][i], off);
+    }
+
+    if (row < 0 || s != 0) return;
+    if (bin.kind == kKindHubPieces) {
+#pragma unroll
+        for (int p = 0; p < NPASS; ++p)
+            if (col_ok[p]) store_f32<VEC>(partial_out + col[p], acc[p]);
+        return;
+    }
+    const float ds = scale_of(a.dst_mode, row_len);
+    T *__restrict__ y = static_cast<T *>(a.Y) + row * a.ldy;
+#pragma unroll
+    for (int p = 0; p < NPASS; ++p) {
+        if (!col_ok[p]) continue;
+        float o[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) o[i] = acc[p][i] * ds;
+        VecIO<T, VEC>::store(y + col[p], o);
+    }
+}
+
+// Adds the pieces of each hub row in their fixed order and writes the row.
+template <typename T>
+__global__ void __launch_bounds__(256) hub_finalize_kernel(const int32_t *__restrict__ hub_rows, int64_t n_hub,
+                                                           const int64_t *__restrict__ piece_offsets,
+                                                           const float *__restrict__ partial, const void *indptr,
+                                                           int ip64, int dst_mode, T *__restrict__ Y, int64_t ldy,
+                                                           int F) {
+    const int64_t i = blockIdx.x;
+    if (i >= n_hub) return;
+    const int64_t row = hub_rows[i];
+    const int64_t p0 = piece_offsets[i], p1 = piece_offsets[i + 1];
+    const float ds = scale_of(dst_mode, load_ip(indptr, ip64, row + 1) - load_ip(indptr, ip64, row));
+    for (int colx = threadIdx.x; colx < F; colx += blockDim.x) {
+        float sum = 0.0f;
+        for (int64_t p = p0; p < p1; ++p) sum += partial[p * F + colx];
+        float o[1] = {sum * ds};
+        VecIO<T, 1>::store(Y + row * ldy + colx, o);
+    }
+}
+
+// ---------------------------------------------------------------- host side
+int pow2_floor_log2(int64_t x) {
+    int l = 0;
+    while ((int64_t(2) << l) <= x) ++l;
+    return l;
+}
+
+template <typename T, int VEC, bool COEF>
+hipError_t launch_npass(int npass, dim3 grid, hipStream_t stream, const AggArgs &a) {
+    switch (npass) {
+        case 1: aggregate_kernel<T, VEC, 1, COEF><<<grid, kBlockThreads, 0, stream>>>(a); break;
+        case 2: aggregate_kernel<T, VEC, 2, COEF><<<grid, kBlockThreads, 0, stream>>>(a); break;
+        case 3: aggregate_kernel<T, VEC, 3, COEF><<<grid, kBlockThreads, 0, stream>>>(a); break;
+        case 4: aggregate_kernel<T, VEC, 4, COEF><<<grid, kBlockThreads, 0, stream>>>(a); break;
+        case 5: aggregate_kernel<T, VEC, 5, COEF><<<grid, kBlockThreads, 0, stream>>>(a); break;
+        case 6: aggregate_kernel<T, VEC, 6, COEF><<<grid, kBlockThreads, 0, stream>>>(a); break;
+        default: aggregate_kernel<T, VEC, 8, COEF><<<grid, kBlockThreads, 0, stream>>>(a); break;
+    }
+    return hipGetLastError();
+}
+
+template <typename T, int VEC>
+hipError_t launch_coef(bool coef, int npass, dim3 grid, hipStream_t stream, const AggArgs &a) {
+    return coef ? launch_npass<T, VEC, true>(npass, grid, stream, a) : launch_npass<T, VEC, false>(npass, grid, stream, a);
+}
+
+constexpr int kMaxPass = 8;
+
+// One direction of the aggregation.  `gathered` is X (forward) or dY (backward).
+int run_aggregate(const void *indptr, const int32_t *indices, const float *w, const void *gathered, void *out,
+                  int64_t N, int64_t F, int op, const gnn_opts *opts_in, bool backward) {
+    gnn_opts o{};
+    if (opts_in) o = *opts_in;
+    if (N < 0 || F < 0) return GNN_ERR_INVALID_ARG;
+    if (op != GNN_SUM && op != GNN_MEAN && op != GNN_GCN_SYM) return GNN_ERR_INVALID_ARG;
+    if (o.dtype != GNN_F32 && o.dtype != GNN_BF16) return GNN_ERR_INVALID_ARG;
+    if (N == 0 || F == 0) return GNN_OK;
+    if (!indptr || !gathered || !out) return GNN_ERR_INVALID_ARG;
+    if (N > INT32_MAX || F > INT32_MAX) return GNN_ERR_INVALID_ARG;
+    const int64_t ldx = o.ldx ? o.ldx : F, ldy = o.ldy ? o.ldy : F;
+    if (ldx < F || ldy < F) return GNN_ERR_INVALID_ARG;
+    gnn_plan *plan = o.plan;
+    if (plan && (plan->n_rows != N || plan->indptr_is_64 != (o.indptr_is_64 ? 1 : 0))) return GNN_ERR_INVALID_ARG;
+    if (plan && plan->n_edges > 0 && !indices) return GNN_ERR_INVALID_ARG;
+
+    // scaling of the edge terms and of the output row
+    int src_mode = kScaleNone, dst_mode = kScaleNone;
+    if (op == GNN_MEAN) {
+        if (backward) src_mode = kScaleInv; else dst_mode = kScaleInv;
+    } else if (op == GNN_GCN_SYM && !w) {
+        src_mode = kScaleRsqrt;
+        dst_mode = kScaleRsqrt;
+    }
+    if (src_mode != kScaleNone && !plan) return GNN_ERR_UNSUPPORTED;  // needs the column counts a plan holds
+    const bool coef = (w != nullptr) || src_mode != kScaleNone;
+
+    // widest load the strides and base addresses allow
+    const int esz = o.dtype == GNN_BF16 ? 2 : 4;
+    const int max_vec = 16 / esz;
+    int vec = max_vec;
+    auto aligned = [&](int v) {
+        const uintptr_t bytes = uintptr_t(v) * esz;
+        return F % v == 0 && ldx % v == 0 && ldy % v == 0 && reinterpret_cast<uintptr_t>(gathered) % bytes == 0 &&
+               reinterpret_cast<uintptr_t>(out) % bytes == 0;
+    };
+    while (vec > 1 && !aligned(vec)) vec >>= 1;
+    if (reinterpret_cast<uintptr_t>(gathered) % esz || reinterpret_cast<uintptr_t>(out) % esz) return GNN_ERR_INVALID_ARG;
+
+    hipStream_t stream = static_cast<hipStream_t>(o.stream);
+
+    // hub scratch
+    float *partial = nullptr;
+    const bool has_hub = plan && plan->n_chunks > 0;
+    if (has_hub) {
+        const int64_t need = gnn_plan_workspace_bytes(plan, F);
+        if (o.workspace && o.workspace_bytes >= need) {
+            partial = static_cast<float *>(o.workspace);
+        } else if (o.workspace) {
+            return GNN_ERR_INVALID_ARG;
+        } else {
+            int rc = gnn_plan_reserve(plan, F);
+            if (rc != GNN_OK) return rc;
+            partial = static_cast<float *>(plan->scratch);
+        }
+        if (reinterpret_cast<uintptr_t>(partial) % 16) return GNN_ERR_INVALID_ARG;
+    }
+
+    // Feature slabs: one launch covers up to 64 lanes * vec * kMaxPass columns.
+    const int64_t slab = int64_t(64) * vec * kMaxPass;
+    for (int64_t f0 = 0; f0 < F; f0 += slab) {
+        const int64_t fw = F - f0 < slab ? F - f0 : slab;
+        const int64_t strips = (fw + vec - 1) / vec;
+        const int log2_c = strips >= 64 ? 6 : gnn_ilog2_ceil(strips);
+        const int C = 1 << log2_c;
+        const int npass = int((strips + C - 1) / C);
+        const int max_log2_sr = 6 - log2_c;
+
+        AggArgs a{};
+        a.indptr = indptr;
+        a.indices = indices;
+        a.w = w;
+        a.X = static_cast<const char *>(gathered) + f0 * esz;
+        a.Y = static_cast<char *>(out) + f0 * esz;
+        a.ldx = ldx;
+        a.ldy = ldy;
+        a.F = int32_t(fw);
+        a.ip64 = o.indptr_is_64 ? 1 : 0;
+        a.src_mode = src_mode;
+        a.dst_mode = dst_mode;
+        int64_t next_block = 0;
+        int nb = 0;
+        auto add_bin = [&](int kind, int64_t begin, int64_t n_items, int log2_sr) {
+            if (n_items <= 0) return;
+            BinDesc &d = a.bins[nb++];
+            d.first_block = next_block;
+            d.item_begin = begin;
+            d.n_items = n_items;
+            d.kind = kind;
+            d.log2_sr = log2_sr;
+            d.log2_g = kind == kKindHubPieces ? 6 : log2_c + log2_sr;
+            const int64_t items_per_block = int64_t(kWavesPerBlock) * (64 >> d.log2_g);
+            next_block += (n_items + items_per_block - 1) / items_per_block;
+        };
+        if (plan) {
+            a.row_perm = plan->row_perm;
+            a.col_counts = plan->col_counts;
+            a.chunks = plan->chunks;
+            // The scratch rows are F wide for every slab; point at this slab's columns.
+            a.partial = partial ? partial + f0 : nullptr;
+            a.ldp = F;
+            const int last = plan->n_bins - 1;
+            // heaviest work first: hub pieces, then bins from long rows to short rows
+            if (has_hub) add_bin(kKindHubPieces, 0, plan->n_chunks, max_log2_sr);
+            for (int bi = last; bi >= 0; --bi) {
+                if (bi == last && plan->params.hub_chunk > 0) continue;  // handled as pieces (+ finalize)
+                const int64_t lo = bi == 0 ? 0 : plan->params.thresholds[bi - 1];
+                // as many edge slots as the shortest row of the bin can keep busy
+                int lsr = lo <= 1 ? 0 : pow2_floor_log2(lo);
+                if (lsr > max_log2_sr) lsr = max_log2_sr;
+                add_bin(kKindRows, plan->bin_offsets[bi], plan->bin_offsets[bi + 1] - plan->bin_offsets[bi], lsr);
+            }
+        } else {
+            add_bin(kKindRows, 0, N, max_log2_sr);
+        }
+        a.n_bins = nb;
+        if (nb == 0 || next_block == 0) continue;
+        if (next_block > INT32_MAX) return GNN_ERR_UNSUPPORTED;
+
+        dim3 grid(static_cast<unsigned>(next_block));
+        hipError_t err = hipSuccess;
+        if (o.dtype == GNN_F32) {
+            if (vec == 4) err = launch_coef<float, 4>(coef, npass, grid, stream, a);
+            else if (vec == 2) err = launch_coef<float, 2>(coef, npass, grid, stream, a);
+            else err = launch_coef<float, 1>(coef, npass, grid, stream, a);
+        } else {
+            if (vec == 8) err = launch_coef<bf16_t, 8>(coef, npass, grid, stream, a);
+            else if (vec == 4) err = launch_coef<bf16_t, 4>(coef, npass, grid, stream, a);
+            else if (vec == 2) err = launch_coef<bf16_t, 2>(coef, npass, grid, stream, a);
+            else err = launch_coef<bf16_t, 1>(coef, npass, grid, stream, a);
+        }
+        if (err != hipSuccess) return GNN_ERR_LAUNCH;
+    }
+
+    if (has_hub) {
+        const int64_t hub_begin = plan->bin_offsets[plan->n_bins - 1];
+        dim3 grid(static_cast<unsigned>(plan->n_hub_rows));
+        if (o.dtype == GNN_F32)
+            hub_finalize_kernel<float><<<grid, 256, 0, stream>>>(plan->row_perm + hub_begin, plan->n_hub_rows, plan->hub_chunk_offsets,
+                                                                 partial, indptr, o.indptr_is_64 ? 1 : 0, dst_mode,
+                                                                 static_cast<float *>(out), ldy, int(F));
+        else
+            hub_finalize_kernel<bf16_t><<<grid, 256, 0, stream>>>(plan->row_perm + hub_begin, plan->n_hub_rows, plan->hub_chunk_offsets,
+                                                                  partial, indptr, o.indptr_is_64 ? 1 : 0, dst_mode,
+                                                                  static_cast<bf16_t *>(out), ldy, int(F));
+        if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
+    }
+    return GNN_OK;
+}
+
+}  // namespace
+
+extern "C" GNN_API int gnn_aggregate_fwd(const void *indptr, const int32_t *indices, const float *edge_w, const void *X,
+                                 void *Y, int64_t N, int64_t F, int op, const gnn_opts *opts) {
+    return run_aggregate(indptr, indices, edge_w, X, Y, N, F, op, opts, /*backward=*/false);
+}
+
+extern "C" GNN_API int gnn_aggregate_bwd(const void *indptr_t, const int32_t *indices_t, const float *edge_w_t,
+                                 const void *dY, void *dX, int64_t N, int64_t F, int op, const gnn_opts *opts) {
+    return run_aggregate(indptr_t, indices_t, edge_w_t, dY, dX, N, F, op, opts, /*backward=*/true);
+}

@@ -1,0 +1,43 @@
+// Internal declarations shared by the translation units of libgnnagg.so.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gnnagg.h"
+
+#define GNN_HIP_TRY(expr)                                  \
+    do {                                                   \
+        hipError_t gnn_err_ = (expr);                      \
+        if (gnn_err_ != hipSuccess) return GNN_ERR_LAUNCH; \
+    } while (0)
+
+#define GNN_MAX_BINS (GNN_MAX_THRESHOLDS + 1)
+
+// One plan = one graph orientation.  All pointers are device memory owned by
+// the plan unless marked host.
+struct gnn_plan {
+    int64_t n_rows = 0;
+    int64_t n_edges = 0;
+    int32_t n_bins = 0;
+    int32_t indptr_is_64 = 0;
+    gnn_plan_params params{};
+    int64_t bin_offsets[GNN_MAX_BINS + 1] = {0};  // host copy
+    int32_t *row_perm = nullptr;      // [n_rows]
+    int32_t *col_counts = nullptr;    // [n_rows] occurrences of each vertex in indices
+    // hub rows = rows of the last bin when params.hub_chunk > 0
+    int64_t n_hub_rows = 0;
+    int64_t n_chunks = 0;
+    int64_t *chunks = nullptr;        // [n_chunks * 3] (row, e_begin, e_end)
+    int64_t *hub_chunk_offsets = nullptr;  // [n_hub_rows + 1] first piece of each hub row
+    // plan-owned scratch for hub partial sums
+    void *scratch = nullptr;
+    int64_t scratch_bytes = 0;
+    const void *indptr_seen = nullptr;  // the indptr the plan was built from (sanity check only)
+};
+
+static inline int gnn_ilog2_ceil(int64_t x) {
+    int l = 0;
+    while ((int64_t(1) << l) < x) ++l;
+    return l;
+}

@@ -1,0 +1,297 @@
+// Degree-binning plan: the GPU-side replacement for dynamic scheduling over
+// destination rows of very different length (Section 4.2, "Multithreading").
+//
+// Rows are grouped by row-length bin with a stable multi-way split (ascending
+// row id inside a bin), rows of the last bin are cut into fixed-size pieces, and
+// the per-vertex column counts (needed for MEAN backward and GCN_SYM scaling)
+// are histogrammed.  Everything is integer work and fully deterministic.
+#include <new>
+
+#include "common.h"
+
+namespace {
+
+constexpr int kSplitThreads = 1024;  // rows per workgroup in the split kernels
+constexpr int kSplitWaves = kSplitThreads / 64;
+
+struct Thresholds {
+    int32_t k;
+    int64_t t[GNN_MAX_THRESHOLDS];
+};
+
+__device__ __forceinline__ int64_t load_ip(const void *indptr, int ip64, int64_t i) {
+    return ip64 ? static_cast<const int64_t *>(indptr)[i]
+                : static_cast<int64_t>(static_cast<const int32_t *>(indptr)[i]);
+}
+
+__device__ __forceinline__ int bin_of(int64_t deg, const Thresholds &thr) {
+    int b = 0;
+    for (int i = 0; i < thr.k; ++i) b += (thr.t[i] <= deg) ? 1 : 0;
+    return b;
+}
+
+__global__ void __launch_bounds__(256) count_cols_kernel(const int32_t *__restrict__ indices, int64_t E,
+                                                         int32_t *__restrict__ col_counts) {
+    int64_t stride = int64_t(gridDim.x) * blockDim.x;
+    for (int64_t e = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; e < E; e += stride)
+        atomicAdd(&col_counts[indices[e]], 1);
+}
+
+// block_counts[b * n_blocks + blk] = rows of bin b among rows [blk*1024, blk*1024+1024)
+__global__ void __launch_bounds__(kSplitThreads) bin_count_kernel(const void *__restrict__ indptr, int ip64,
+                                                                  int64_t N, Thresholds thr, int64_t n_blocks,
+                                                                  int64_t *__restrict__ block_counts) {
+    __shared__ int counts[GNN_MAX_BINS];
+    if (threadIdx.x < GNN_MAX_BINS) counts[threadIdx.x] = 0;
+    __syncthreads();
+    int64_t v = int64_t(blockIdx.x) * kSplitThreads + threadIdx.x;
+    if (v < N) {
+        int64_t deg = load_ip(indptr, ip64, v + 1) - load_ip(indptr, ip64, v);
+        atomicAdd(&counts[bin_of(deg, thr)], 1);  // integer count: order does not matter
+    }
+    __syncthreads();
+    if (threadIdx.x <= thr.k) block_counts[int64_t(threadIdx.x) * n_blocks + blockIdx.x] = counts[threadIdx.x];
+}
+
+// In-place exclusive prefix sum of data[0..n) by ONE workgroup; data[n] receives the total.
+__global__ void __launch_bounds__(1024) scan_exclusive_kernel(int64_t *__restrict__ data, int64_t n) {
+    __shared__ int64_t part[1024];
+    const int t = threadIdx.x;
+    const int64_t chunk = (n + 1023) / 1024;
+    const int64_t lo = chunk * t < n ? chunk * t : n;
+    const int64_t hi = lo + chunk < n ? lo + chunk : n;
+    int64_t s = 0;
+    for (int64_t i = lo; i < hi; ++i) s += data[i];
+    part[t] = s;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {  // Hillis-Steele inclusive scan of the partial sums
+        int64_t add = t >= off ? part[t - off] : 0;
+        __syncthreads();
+        part[t] += add;
+        __syncthreads();
+    }
+    int64_t run = part[t] - s;  // exclusive prefix of this thread's chunk
+    for (int64_t i = lo; i < hi; ++i) {
+        int64_t x = data[i];
+        data[i] = run;
+        run += x;
+    }
+    if (t == 1023) data[n] = part[1023];
+}
+
+// Stable placement: row v goes to block_prefix[bin][blk] + (#rows of the same bin before it in the block).
+__global__ void __launch_bounds__(kSplitThreads) bin_scatter_kernel(const void *__restrict__ indptr, int ip64,
+                                                                    int64_t N, Thresholds thr, int64_t n_blocks,
+                                                                    const int64_t *__restrict__ block_prefix,
+                                                                    int32_t *__restrict__ row_perm) {
+    __shared__ int wave_tot[kSplitWaves][GNN_MAX_BINS];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    int64_t v = int64_t(blockIdx.x) * kSplitThreads + threadIdx.x;
+    int bin = -1;
+    if (v < N) {
+        int64_t deg = load_ip(indptr, ip64, v + 1) - load_ip(indptr, ip64, v);
+        bin = bin_of(deg, thr);
+    }
+    int rank_in_wave = 0;
+    for (int b = 0; b <= thr.k; ++b) {
+        unsigned long long m = __ballot(bin == b);
+        if (bin == b) rank_in_wave = __popcll(m & ((1ull << lane) - 1ull));
+        if (lane == 0) wave_tot[wave][b] = __popcll(m);
+    }
+    __syncthreads();
+    if (bin >= 0) {
+        int before = 0;
+        for (int w = 0; w < wave; ++w) before += wave_tot[w][bin];
+        int64_t pos = block_prefix[int64_t(bin) * n_blocks + blockIdx.x] + before + rank_in_wave;
+        row_perm[pos] = static_cast<int32_t>(v);
+    }
+}
+
+__global__ void __launch_bounds__(256) hub_count_kernel(const int32_t *__restrict__ hub_rows, int64_t n_hub,
+                                                        const void *__restrict__ indptr, int ip64, int64_t chunk,
+                                                        int64_t *__restrict__ counts) {
+    int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i >= n_hub) return;
+    int64_t v = hub_rows[i];
+    int64_t deg = load_ip(indptr, ip64, v + 1) - load_ip(indptr, ip64, v);
+    counts[i] = (deg + chunk - 1) / chunk;
+}
+
+__global__ void __launch_bounds__(256) hub_fill_kernel(const int32_t *__restrict__ hub_rows, int64_t n_hub,
+                                                       const void *__restrict__ indptr, int ip64, int64_t chunk,
+                                                       const int64_t *__restrict__ offsets,
+                                                       int64_t *__restrict__ chunks) {
+    int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i >= n_hub) return;
+    int64_t v = hub_rows[i];
+    int64_t b = load_ip(indptr, ip64, v);
+    const int64_t end = load_ip(indptr, ip64, v + 1);
+    int64_t c = offsets[i];
+    for (; b < end; b += chunk, ++c) {
+        chunks[3 * c + 0] = v;
+        chunks[3 * c + 1] = b;
+        chunks[3 * c + 2] = b + chunk < end ? b + chunk : end;
+    }
+}
+
+int grid_for(int64_t n, int block, int64_t cap = (int64_t(1) << 20)) {
+    int64_t g = (n + block - 1) / block;
+    if (g < 1) g = 1;
+    if (g > cap) g = cap;
+    return static_cast<int>(g);
+}
+
+}  // namespace
+
+extern "C" GNN_API void gnn_plan_default_params(gnn_plan_params *p) {
+    if (!p) return;
+    *p = gnn_plan_params{};
+    const int64_t t[] = {1, 2, 4, 8, 16, 32, 64, 4096};
+    p->n_thresholds = static_cast<int32_t>(sizeof(t) / sizeof(t[0]));
+    for (int i = 0; i < p->n_thresholds; ++i) p->thresholds[i] = t[i];
+    p->hub_chunk = 1024;
+}
+
+extern "C" GNN_API void gnn_plan_destroy(gnn_plan *plan) {
+    if (!plan) return;
+    (void)hipFree(plan->row_perm);
+    (void)hipFree(plan->col_counts);
+    (void)hipFree(plan->chunks);
+    (void)hipFree(plan->hub_chunk_offsets);
+    (void)hipFree(plan->scratch);
+    delete plan;
+}
+
+extern "C" GNN_API int gnn_plan_create(const void *indptr, const int32_t *indices, int64_t N, int indptr_is_64,
+                               const gnn_plan_params *params, void *stream_v, gnn_plan **out) {
+    if (!out) return GNN_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (N < 0 || N > INT32_MAX || (N > 0 && !indptr)) return GNN_ERR_INVALID_ARG;
+    gnn_plan_params prm;
+    if (params) prm = *params; else gnn_plan_default_params(&prm);
+    if (prm.n_thresholds < 0 || prm.n_thresholds > GNN_MAX_THRESHOLDS || prm.hub_chunk < 0)
+        return GNN_ERR_INVALID_ARG;
+    for (int i = 0; i < prm.n_thresholds; ++i) {
+        if (prm.thresholds[i] <= 0) return GNN_ERR_INVALID_ARG;
+        if (i > 0 && prm.thresholds[i] <= prm.thresholds[i - 1]) return GNN_ERR_INVALID_ARG;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    gnn_plan *plan = new (std::nothrow) gnn_plan();
+    if (!plan) return GNN_ERR_ALLOC;
+    plan->n_rows = N;
+    plan->n_bins = prm.n_thresholds + 1;
+    plan->indptr_is_64 = indptr_is_64 ? 1 : 0;
+    plan->params = prm;
+    plan->indptr_seen = indptr;
+    const int nb = plan->n_bins;
+    for (int b = 0; b <= nb; ++b) plan->bin_offsets[b] = 0;
+    if (N == 0) { *out = plan; return GNN_OK; }
+
+    int status = GNN_OK;
+    int64_t *block_counts = nullptr;
+    auto fail = [&](int s) { (void)hipFree(block_counts); gnn_plan_destroy(plan); return s; };
+
+    // number of edges = indptr[N]
+    int64_t E = 0;
+    if (indptr_is_64) {
+        if (hipMemcpyAsync(&E, static_cast<const int64_t *>(indptr) + N, 8, hipMemcpyDeviceToHost, stream) != hipSuccess) return fail(GNN_ERR_LAUNCH);
+        if (hipStreamSynchronize(stream) != hipSuccess) return fail(GNN_ERR_LAUNCH);
+    } else {
+        int32_t e32 = 0;
+        if (hipMemcpyAsync(&e32, static_cast<const int32_t *>(indptr) + N, 4, hipMemcpyDeviceToHost, stream) != hipSuccess) return fail(GNN_ERR_LAUNCH);
+        if (hipStreamSynchronize(stream) != hipSuccess) return fail(GNN_ERR_LAUNCH);
+        E = e32;
+    }
+    if (E < 0 || (E > 0 && !indices)) return fail(GNN_ERR_INVALID_ARG);
+    plan->n_edges = E;
+
+    Thresholds thr{};
+    thr.k = prm.n_thresholds;
+    for (int i = 0; i < thr.k; ++i) thr.t[i] = prm.thresholds[i];
+
+    const int64_t n_blocks = (N + kSplitThreads - 1) / kSplitThreads;
+    const int64_t n_counts = n_blocks * nb;
+    if (hipMalloc(&plan->row_perm, sizeof(int32_t) * N) != hipSuccess) return fail(GNN_ERR_ALLOC);
+    if (hipMalloc(&plan->col_counts, sizeof(int32_t) * N) != hipSuccess) return fail(GNN_ERR_ALLOC);
+    if (hipMalloc(&block_counts, sizeof(int64_t) * (n_counts + 1)) != hipSuccess) return fail(GNN_ERR_ALLOC);
+
+    // column counts.  The zero fill is a kernel-free memset outside any graph capture.
+    if (hipMemsetAsync(plan->col_counts, 0, sizeof(int32_t) * N, stream) != hipSuccess) return fail(GNN_ERR_LAUNCH);
+    if (E > 0) count_cols_kernel<<<grid_for(E, 256, 1 << 16), 256, 0, stream>>>(indices, E, plan->col_counts);
+
+    // stable multi-way split of the rows by bin
+    bin_count_kernel<<<static_cast<int>(n_blocks), kSplitThreads, 0, stream>>>(indptr, plan->indptr_is_64, N, thr, n_blocks, block_counts);
+    scan_exclusive_kernel<<<1, 1024, 0, stream>>>(block_counts, n_counts);
+    bin_scatter_kernel<<<static_cast<int>(n_blocks), kSplitThreads, 0, stream>>>(indptr, plan->indptr_is_64, N, thr, n_blocks, block_counts, plan->row_perm);
+    if (hipGetLastError() != hipSuccess) return fail(GNN_ERR_LAUNCH);
+    for (int b = 0; b < nb; ++b) {
+        if (hipMemcpyAsync(&plan->bin_offsets[b], block_counts + int64_t(b) * n_blocks, 8, hipMemcpyDeviceToHost, stream) != hipSuccess)
+            return fail(GNN_ERR_LAUNCH);
+    }
+    if (hipStreamSynchronize(stream) != hipSuccess) return fail(GNN_ERR_LAUNCH);
+    plan->bin_offsets[nb] = N;
+
+    // hub rows -> pieces
+    if (prm.hub_chunk > 0) {
+        const int64_t hub_begin = plan->bin_offsets[nb - 1];
+        const int64_t n_hub = N - hub_begin;
+        plan->n_hub_rows = n_hub;
+        if (n_hub > 0) {
+            if (hipMalloc(&plan->hub_chunk_offsets, sizeof(int64_t) * (n_hub + 1)) != hipSuccess) return fail(GNN_ERR_ALLOC);
+            const int32_t *hub_rows = plan->row_perm + hub_begin;
+            hub_count_kernel<<<grid_for(n_hub, 256), 256, 0, stream>>>(hub_rows, n_hub, indptr, plan->indptr_is_64, prm.hub_chunk, plan->hub_chunk_offsets);
+            scan_exclusive_kernel<<<1, 1024, 0, stream>>>(plan->hub_chunk_offsets, n_hub);
+            if (hipMemcpyAsync(&plan->n_chunks, plan->hub_chunk_offsets + n_hub, 8, hipMemcpyDeviceToHost, stream) != hipSuccess) return fail(GNN_ERR_LAUNCH);
+            if (hipStreamSynchronize(stream) != hipSuccess) return fail(GNN_ERR_LAUNCH);
+            if (plan->n_chunks > 0) {
+                if (hipMalloc(&plan->chunks, sizeof(int64_t) * 3 * plan->n_chunks) != hipSuccess) return fail(GNN_ERR_ALLOC);
+                hub_fill_kernel<<<grid_for(n_hub, 256), 256, 0, stream>>>(hub_rows, n_hub, indptr, plan->indptr_is_64, prm.hub_chunk, plan->hub_chunk_offsets, plan->chunks);
+            }
+        }
+    }
+    if (hipGetLastError() != hipSuccess) return fail(GNN_ERR_LAUNCH);
+    if (hipStreamSynchronize(stream) != hipSuccess) return fail(GNN_ERR_LAUNCH);
+    (void)hipFree(block_counts);
+    (void)status;
+    *out = plan;
+    return GNN_OK;
+}
+
+extern "C" GNN_API int gnn_plan_sizes(const gnn_plan *plan, int64_t *n_rows, int32_t *n_bins, int64_t *n_chunks) {
+    if (!plan) return GNN_ERR_INVALID_ARG;
+    if (n_rows) *n_rows = plan->n_rows;
+    if (n_bins) *n_bins = plan->n_bins;
+    if (n_chunks) *n_chunks = plan->n_chunks;
+    return GNN_OK;
+}
+
+extern "C" GNN_API int gnn_plan_export(const gnn_plan *plan, int64_t *bin_offsets, int32_t *row_perm, int64_t *chunks,
+                               int32_t *col_counts) {
+    if (!plan) return GNN_ERR_INVALID_ARG;
+    if (bin_offsets) for (int b = 0; b <= plan->n_bins; ++b) bin_offsets[b] = plan->bin_offsets[b];
+    if (row_perm && plan->n_rows > 0)
+        GNN_HIP_TRY(hipMemcpy(row_perm, plan->row_perm, sizeof(int32_t) * plan->n_rows, hipMemcpyDeviceToHost));
+    if (col_counts && plan->n_rows > 0)
+        GNN_HIP_TRY(hipMemcpy(col_counts, plan->col_counts, sizeof(int32_t) * plan->n_rows, hipMemcpyDeviceToHost));
+    if (chunks && plan->n_chunks > 0)
+        GNN_HIP_TRY(hipMemcpy(chunks, plan->chunks, sizeof(int64_t) * 3 * plan->n_chunks, hipMemcpyDeviceToHost));
+    return GNN_OK;
+}
+
+extern "C" GNN_API int64_t gnn_plan_workspace_bytes(const gnn_plan *plan, int64_t F) {
+    if (!plan || F < 0) return 0;
+    return plan->n_chunks * F * int64_t(sizeof(float));
+}
+
+extern "C" GNN_API int gnn_plan_reserve(gnn_plan *plan, int64_t F) {
+    if (!plan || F < 0) return GNN_ERR_INVALID_ARG;
+    const int64_t need = gnn_plan_workspace_bytes(plan, F);
+    if (need <= plan->scratch_bytes) return GNN_OK;
+    (void)hipFree(plan->scratch);
+    plan->scratch = nullptr;
+    plan->scratch_bytes = 0;
+    if (hipMalloc(&plan->scratch, need) != hipSuccess) return GNN_ERR_ALLOC;
+    plan->scratch_bytes = need;
+    return GNN_OK;
+}

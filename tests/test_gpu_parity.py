@@ -1,0 +1,299 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle,
+element by element on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2104_06700_amd as gnn
+import synth
+from helpers import (OP_CODE, assert_close, device_graph, host_csr, run_bwd, run_fwd, strict_relative_error)
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _features(kind, n, f, seed, dtype=torch.float32):
+    if kind == "uniform":
+        return synth.uniform_features(n, f, seed, dtype=dtype)
+    return synth.normal_features(n, f, seed, dtype=dtype)
+
+
+def _check_both_directions(el, f, op_name, dtype=torch.float32, weights=None, indptr64=False, plan_params=None,
+                           dist="normal", use_plan=True, seed=0, nthreads=8):
+    """Forward and backward on one graph / width / op, whole output compared."""
+    op = OP_CODE[op_name]
+    bf16 = dtype == torch.bfloat16
+    dg = device_graph(el, weights=weights, indptr64=indptr64, plan_params=plan_params)
+    indptr, indices, indptr_t, indices_t, perm = host_csr(el)
+    din = np.diff(indptr)
+    dout = np.diff(indptr_t)
+    w = None if weights is None else weights.numpy()
+    wt = None if w is None else w[perm]
+    X = _features(dist, el.n, f, 1000 + seed, dtype)
+    dY = _features(dist, el.n, f, 2000 + seed, dtype)
+    plan_f = "default" if use_plan else None
+    Y = run_fwd(dg, X.to(DEV), op, plan=plan_f)
+    Yo, S = oracle.aggregate_fwd(indptr, indices, X.float().numpy(), op=op, w=w, dout=dout, nthreads=nthreads,
+                                 want_scale=True)
+    assert_close(Y, Yo, S, bf16, f"fwd {op_name} F={f}")
+    dX = run_bwd(dg, dY.to(DEV), op, plan=plan_f)
+    dXo, St = oracle.aggregate_bwd(indptr_t, indices_t, dY.float().numpy(), op=op, wt=wt, din=din,
+                                   nthreads=nthreads, want_scale=True)
+    assert_close(dX, dXo, St, bf16, f"bwd {op_name} F={f}")
+    return strict_relative_error(Y, Yo, S), strict_relative_error(dX, dXo, St)
+
+
+# ------------------------------------------------------------ the five workloads
+def test_workload_er_tiny_full():
+    """Tiny plumbing case at its full size: 4,096 vertices, 65,536 edges, F=64, SUM."""
+    el = synth.make_graph("er_tiny")
+    assert (el.n, el.e) == (4096, 65536)
+    _check_both_directions(el, 64, "sum", dist="uniform")
+
+
+@pytest.mark.parametrize("f", [602, 256])
+def test_workload_dense_wide_scaled(f):
+    """Dense-degree / wide-feature case (MEAN), graph scaled to 2% (mean degree ~490 kept)."""
+    el = synth.make_graph("rmat_dense_wide", scale=0.02)
+    _check_both_directions(el, f, "mean")
+
+
+@pytest.mark.parametrize("f", [100, 256])
+def test_workload_sparse_stack_scaled(f):
+    """Sparse / medium-feature case (MEAN), graph scaled to 2%."""
+    el = synth.make_graph("rmat_sparse_stack", scale=0.02)
+    _check_both_directions(el, f, "mean")
+
+
+@pytest.mark.parametrize("f", [8, 64])
+def test_workload_weighted_narrow_scaled(f):
+    """Narrow-feature case with explicit fp32 GCN weights (SUM with weights), graph scaled to 2%."""
+    el = synth.make_graph("rmat_weighted_narrow", scale=0.02)
+    w = synth.gcn_sym_edge_weights(el.dst, el.src, el.n)
+    _check_both_directions(el, f, "sum", weights=w)
+
+
+@pytest.mark.parametrize("op_name", ["sum", "mean"])
+def test_workload_capacity_scaled(op_name):
+    """Capacity case at 0.05%: directed R-MAT, int64 row pointers, bf16 storage, F=128."""
+    el = synth.make_graph("rmat_capacity", scale=0.0005)
+    _check_both_directions(el, 128, op_name, dtype=torch.bfloat16, indptr64=True)
+
+
+# -------------------------------------------------------------- shapes and ops
+WIDTHS = [1, 2, 3, 4, 6, 8, 12, 30, 64, 100, 128, 130, 255, 256, 258, 602, 1030, 2052]
+
+
+@pytest.mark.parametrize("f", WIDTHS)
+def test_widths_f32(f):
+    el = synth.make_graph("rmat_sparse_stack", scale=0.0008, seed=11)
+    _check_both_directions(el, f, "mean", seed=f)
+
+
+@pytest.mark.parametrize("f", [1, 2, 4, 7, 8, 24, 128, 136, 520, 1000])
+def test_widths_bf16(f):
+    el = synth.make_graph("rmat_sparse_stack", scale=0.0008, seed=12)
+    _check_both_directions(el, f, "sum", dtype=torch.bfloat16, seed=f)
+
+
+@pytest.mark.parametrize("op_name", ["sum", "mean", "gcn"])
+@pytest.mark.parametrize("weighted", [False, True])
+@pytest.mark.parametrize("use_plan", [False, True])
+def test_ops_weights_plan(op_name, weighted, use_plan):
+    if not use_plan and (op_name == "gcn" and not weighted):
+        pytest.skip("weight-less GCN_SYM needs a plan (tested in test_errors)")
+    el = synth.make_graph("rmat_sparse_stack", scale=0.001, seed=21)
+    # properly directed graph: drop a seeded half of the edges so that CSR != CSC
+    keep = torch.from_numpy(np.random.default_rng(3).random(el.e) < 0.5)
+    el = synth.EdgeList(el.n, el.src[keep], el.dst[keep], el.meta)
+    w = None
+    if weighted:
+        w = torch.from_numpy(np.random.default_rng(4).uniform(0.1, 2.0, el.e).astype(np.float32))
+    if not use_plan and op_name == "mean":
+        # backward MEAN needs a plan; check forward only
+        dg = device_graph(el, weights=w, with_plans=False)
+        indptr, indices, *_ = host_csr(el)
+        X = synth.normal_features(el.n, 40, 5)
+        Y = run_fwd(dg, X.to(DEV), OP_CODE["mean"], plan=None)
+        Yo, S = oracle.aggregate_fwd(indptr, indices, X.numpy(), op=oracle.OP_MEAN,
+                                     w=None if w is None else w.numpy(), want_scale=True)
+        assert_close(Y, Yo, S, False, "fwd mean no plan")
+        return
+    _check_both_directions(el, 40, op_name, weights=w, use_plan=use_plan)
+
+
+PLAN_VARIANTS = {
+    "default": None,
+    "all_rows_are_hubs": ([], 7),
+    "all_rows_are_hubs_big_chunk": ([], 1 << 20),
+    "one_bin_no_hub": ([], 0),
+    "two_bins_hub_at_3": ([3], 5),
+    "fine_bins_no_hub": ([1, 2, 3, 5, 9, 17, 33, 65, 129, 257, 513, 1025, 2049, 4097, 8193], 0),
+    "wave_rows_only": ([64], 0),
+    "hub_at_64": ([1, 8, 64], 64),
+}
+
+
+@pytest.mark.parametrize("variant", list(PLAN_VARIANTS))
+@pytest.mark.parametrize("f", [8, 100, 602])
+def test_every_kernel_family_gives_the_same_answer(variant, f):
+    """One owner per output row means scheduling cannot change the result:
+    route the rows through each kernel family by moving the bin thresholds."""
+    el = synth.make_graph("rmat_sparse_stack", scale=0.002, seed=31)
+    pv = PLAN_VARIANTS[variant]
+    params = None if pv is None else gnn.make_plan_params(*pv)
+    _check_both_directions(el, f, "mean", plan_params=params)
+    _check_both_directions(el, f, "gcn", plan_params=params)
+
+
+# -------------------------------------------------------------- integer parts
+@pytest.mark.parametrize("name,scale,ip64", [("er_tiny", 1.0, False), ("rmat_sparse_stack", 0.02, False),
+                                             ("rmat_dense_wide", 0.01, True), ("rmat_capacity", 0.0005, True)])
+def test_csr_and_transpose_bit_exact(name, scale, ip64):
+    el = synth.make_graph(name, scale=scale)
+    w = torch.from_numpy(np.random.default_rng(1).random(el.e).astype(np.float32))
+    dg = device_graph(el, weights=w, indptr64=ip64, want_perm=True, with_plans=False)
+    indptr, indices, indptr_t, indices_t, perm = host_csr(el)
+    assert np.array_equal(dg.indptr.cpu().numpy().astype(np.int64), indptr)
+    assert np.array_equal(dg.indptr_t.cpu().numpy().astype(np.int64), indptr_t)
+    assert np.array_equal(dg.indices_t.cpu().numpy(), indices_t)
+    assert np.array_equal(dg.perm.cpu().numpy(), perm)
+    assert np.array_equal(dg.edge_w_t.cpu().numpy(), w.numpy()[perm])
+    assert gnn.gnn_validate_csr(dg.indptr, dg.indices, el.n, el.e) == gnn.GNN_OK
+    assert gnn.gnn_validate_csr(dg.indptr_t, dg.indices_t, el.n, el.e) == gnn.GNN_OK
+
+
+@pytest.mark.parametrize("variant", list(PLAN_VARIANTS))
+def test_plan_bit_exact(variant):
+    el = synth.make_graph("rmat_sparse_stack", scale=0.02, seed=41)
+    indptr, indices, indptr_t, indices_t, _ = host_csr(el)
+    pv = PLAN_VARIANTS[variant]
+    if pv is None:
+        p = gnn.gnn_plan_default_params()
+        thr, chunk = list(p.thresholds)[:p.n_thresholds], p.hub_chunk
+        params = None
+    else:
+        thr, chunk = pv
+        params = gnn.make_plan_params(thr, chunk)
+    dg = device_graph(el, plan_params=params)
+    for plan, ip, ix in ((dg.plan_fwd, indptr, indices), (dg.plan_bwd, indptr_t, indices_t)):
+        bo, rp, ch, cc = plan.export()
+        obo, orp, och = oracle.plan(ip, thr, chunk)
+        assert np.array_equal(bo, obo)
+        assert np.array_equal(rp, orp)
+        assert np.array_equal(ch, och)
+        assert np.array_equal(cc, np.bincount(ix, minlength=el.n).astype(np.int32))
+
+
+# ------------------------------------------------------------------ edge cases
+def test_empty_and_degenerate_inputs():
+    dev = torch.device(DEV)
+    # N == 0 and F == 0 are no-ops
+    z32 = torch.zeros(1, dtype=torch.int32, device=dev)
+    e = torch.zeros(0, dtype=torch.int32, device=dev)
+    x0 = torch.zeros((0, 4), device=dev)
+    gnn.gnn_aggregate_fwd(z32, e, None, x0, x0.clone(), 0, 4, gnn.GNN_SUM)
+    # graph without edges: every op writes zeros over a poisoned output
+    n = 300
+    el = synth.EdgeList(n, torch.zeros(0, dtype=torch.int32), torch.zeros(0, dtype=torch.int32))
+    dg = device_graph(el)
+    X = synth.normal_features(n, 12, 1).to(dev)
+    for op in (gnn.GNN_SUM, gnn.GNN_MEAN, gnn.GNN_GCN_SYM):
+        assert not run_fwd(dg, X, op).any()
+        assert not run_bwd(dg, X, op).any()
+        assert not run_fwd(dg, X, gnn.GNN_SUM, plan=None).any()
+    gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, None, X[:, :0], X[:, :0].clone(), n, 0, gnn.GNN_SUM)
+    # one vertex with a self-loop, and a multigraph with duplicates and self-loops
+    el = synth.EdgeList(1, torch.zeros(1, dtype=torch.int32), torch.zeros(1, dtype=torch.int32))
+    _check_both_directions(el, 5, "mean")
+    el = synth.small_random_multigraph(37, 500, 3)
+    for op_name in ("sum", "mean", "gcn"):
+        _check_both_directions(el, 9, op_name)
+    # a star: one row with N-1 neighbours, N-1 rows with one
+    n = 5000
+    leaves = torch.arange(1, n, dtype=torch.int32)
+    zeros = torch.zeros(n - 1, dtype=torch.int32)
+    el = synth.EdgeList(n, torch.cat([leaves, zeros]), torch.cat([zeros, leaves]))
+    _check_both_directions(el, 100, "mean")
+    _check_both_directions(el, 100, "gcn", plan_params=gnn.make_plan_params([64], 256))
+
+
+def test_strided_and_misaligned_rows():
+    """ld > F, and base pointers / strides that only allow 8- or 4-byte loads."""
+    dev = torch.device(DEV)
+    el = synth.make_graph("rmat_sparse_stack", scale=0.001, seed=51)
+    dg = device_graph(el)
+    indptr, indices, *_ = host_csr(el)
+    f = 100
+    for ld, off in ((128, 0), (102, 2), (101, 1), (100, 3)):
+        buf = synth.normal_features(el.n, ld + 4, 7).to(dev)
+        flat = buf.view(-1)
+        X = torch.as_strided(flat, (el.n, f), (ld, 1), storage_offset=off)
+        out = torch.full((el.n * ld + 8,), float("nan"), device=dev)
+        Y = torch.as_strided(out, (el.n, f), (ld, 1), storage_offset=off)
+        gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, None, X, Y, el.n, f, gnn.GNN_MEAN, plan=dg.plan_fwd, ldx=ld, ldy=ld)
+        torch.cuda.synchronize()
+        Yo, S = oracle.aggregate_fwd(indptr, indices, X.cpu().numpy(), op=oracle.OP_MEAN, want_scale=True)
+        assert_close(Y, Yo, S, False, f"ld={ld} off={off}")
+        if ld > f:  # the padding columns must stay untouched
+            pad = torch.as_strided(out, (el.n - 1, ld - f), (ld, 1), storage_offset=off + f)
+            assert torch.isnan(pad).all()
+
+
+def test_errors():
+    dev = torch.device(DEV)
+    el = synth.make_graph("er_tiny")
+    dg = device_graph(el)
+    X = synth.uniform_features(el.n, 8, 1).to(dev)
+    Y = torch.empty_like(X)
+
+    def status(fn, *a, **k):
+        with pytest.raises(gnn.GnnError) as ei:
+            fn(*a, **k)
+        return ei.value.status
+
+    assert status(gnn.gnn_aggregate_fwd, dg.indptr, dg.indices, None, X, Y, el.n, 8, 7) == gnn.GNN_ERR_INVALID_ARG
+    assert status(gnn.gnn_aggregate_fwd, dg.indptr, dg.indices, None, X, Y, -1, 8, 0) == gnn.GNN_ERR_INVALID_ARG
+    assert status(gnn.gnn_aggregate_fwd, dg.indptr, dg.indices, None, X, Y, el.n, 8, 0, ldx=4) == gnn.GNN_ERR_INVALID_ARG
+    assert status(gnn.gnn_aggregate_fwd, dg.indptr, dg.indices, None, X, Y, el.n + 1, 8, 0, plan=dg.plan_fwd) == gnn.GNN_ERR_INVALID_ARG
+    assert status(gnn.gnn_aggregate_bwd, dg.indptr_t, dg.indices_t, None, X, Y, el.n, 8, gnn.GNN_MEAN) == gnn.GNN_ERR_UNSUPPORTED
+    assert status(gnn.gnn_aggregate_fwd, dg.indptr, dg.indices, None, X, Y, el.n, 8, gnn.GNN_GCN_SYM) == gnn.GNN_ERR_UNSUPPORTED
+    assert status(gnn.gnn_plan_create, dg.indptr, dg.indices, el.n, gnn.make_plan_params([4, 2], 0)) == gnn.GNN_ERR_INVALID_ARG
+    # a workspace that is too small is rejected, one that is large enough is used
+    params = gnn.make_plan_params([8], 4)
+    dg2 = device_graph(el, plan_params=params)
+    need = dg2.plan_fwd.workspace_bytes(8)
+    assert need > 0
+    small = torch.empty(need // 4 - 1, dtype=torch.float32, device=dev)
+    assert status(gnn.gnn_aggregate_fwd, dg2.indptr, dg2.indices, None, X, Y, el.n, 8, 0, plan=dg2.plan_fwd,
+                  workspace=small) == gnn.GNN_ERR_INVALID_ARG
+    big = torch.empty(need // 4, dtype=torch.float32, device=dev)
+    gnn.gnn_aggregate_fwd(dg2.indptr, dg2.indices, None, X, Y, el.n, 8, 0, plan=dg2.plan_fwd, workspace=big)
+    Y2 = run_fwd(dg, X, 0)
+    torch.cuda.synchronize()
+    assert torch.allclose(Y, Y2, rtol=1e-4, atol=1e-5)
+    # broken graphs are reported by the validator
+    bad = dg.indices.clone(); bad[5] = el.n
+    assert gnn.gnn_validate_csr(dg.indptr, bad, el.n, el.e) == gnn.GNN_ERR_INVALID_GRAPH
+    badp = dg.indptr.clone(); badp[10] = badp[11] + 1
+    assert gnn.gnn_validate_csr(badp, dg.indices, el.n, el.e) == gnn.GNN_ERR_INVALID_GRAPH
+
+
+def test_stream_and_repeatability():
+    """Runs on a side stream, twice: results are bit-identical (no atomics, fixed reduction order)."""
+    dev = torch.device(DEV)
+    el = synth.make_graph("rmat_sparse_stack", scale=0.004, seed=61)
+    dg = device_graph(el, plan_params=gnn.make_plan_params([1, 4, 16, 64, 256], 128))
+    X = synth.normal_features(el.n, 100, 3).to(dev)
+    s = torch.cuda.Stream()
+    outs = []
+    for _ in range(2):
+        Y = torch.empty_like(X)
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, None, X, Y, el.n, 100, gnn.GNN_MEAN, plan=dg.plan_fwd)
+        s.synchronize()
+        outs.append(Y)
+    assert torch.equal(outs[0], outs[1])
