@@ -1,0 +1,265 @@
+#!/usr/bin/env python3
+"""Benchmark of the aggregation hot path on one MI355X.
+
+A step = one pass of the aggregation stack of the workload: for every feature
+width of the workload, one forward call (gnn_aggregate_fwd over the CSR) and one
+backward call (gnn_aggregate_bwd over the transposed graph).  Graph generation,
+the CSR/transpose build and the degree-binning plans are once-per-graph setup
+(full-batch training reuses one static graph for every layer and epoch); they
+run in the library too and are reported under "setup_ms", outside the timed
+region.  All inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line (see the keys below).  `value` is edge-features per second
+(edges x F, forward + backward), the unit of the paper's Table 8 work counts.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import paper_2104_06700_amd as gnn  # noqa: E402
+import synth  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0  # MI355X published peak
+OPS = {"sum": gnn.GNN_SUM, "mean": gnn.GNN_MEAN, "gcn": gnn.GNN_GCN_SYM}
+
+
+def algorithmic_bytes(n, e, f, esz, ip_bytes, weighted, src_scaled):
+    """Compulsory bytes of one aggregation call (one direction): every gathered
+    row read once, every output row written once, the index stream (and the
+    weight stream) read once, the row pointers read once, plus the per-vertex
+    count array when the gathered rows carry a scale (MEAN backward, GCN)."""
+    b = 2 * n * f * esz + 4 * e + (n + 1) * ip_bytes
+    if weighted:
+        b += 4 * e
+    if src_scaled:
+        b += 4 * n
+    return b
+
+
+def read_traffic_note(workload):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), if a
+    summary for this workload has been committed under profiles/."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch_fwd_kernel"):
+            return float(line.split()[1])
+    return None
+
+
+def calibrate(dev):
+    """Measured ceilings printed next to the result: streaming copy, and row gathers
+    (400-byte rows) from tables sized for L2, for the Infinity Cache and for HBM."""
+    out = {}
+
+    def timed(fn, reps=5):
+        fn(); torch.cuda.synchronize()
+        t0 = torch.cuda.Event(enable_timing=True); t1 = torch.cuda.Event(enable_timing=True)
+        t0.record()
+        for _ in range(reps):
+            fn()
+        t1.record(); torch.cuda.synchronize()
+        return t0.elapsed_time(t1) / reps * 1e-3
+
+    src = torch.empty(1 << 28, dtype=torch.float32, device=dev)  # 1 GiB
+    dst = torch.empty_like(src)
+    src.normal_()
+    s = timed(lambda: gnn.gnn_calib_copy(src, dst))
+    out["stream_copy_GBs"] = round(2 * src.numel() * 4 / s / 1e9, 1)
+    del dst
+    n_out = 4_000_000
+    outbuf = torch.empty((n_out, 100), dtype=torch.float32, device=dev)
+    for label, rows in (("gather_L2_resident_GBs", 5_000), ("gather_infcache_resident_GBs", 300_000),
+                        ("gather_hbm_GBs", 2_449_029)):
+        table = src[: rows * 100].view(rows, 100)
+        s = timed(lambda: gnn.gnn_calib_gather(table, outbuf, seed=7))
+        out[label] = round(n_out * 400 / s / 1e9, 1)  # gathered bytes per second (the write stream is extra)
+    return out
+
+
+def cpu_baseline(el, widths, op_name, target_seconds=15.0):
+    """The oracle, as it stands, on this machine's host cores, on a seeded row sample."""
+    import oracle
+    threads = oracle.max_threads()
+    dst, src = synth.to_csr_numpy(el)
+    indptr = oracle.csr_indptr(dst, el.n)
+    f = widths[0]
+    X = synth.normal_features(el.n, f, 1).numpy()
+    rng = np.random.default_rng(12345)
+    op = {"sum": oracle.OP_SUM, "mean": oracle.OP_MEAN, "gcn": oracle.OP_GCN_SYM}[op_name]
+    deg = np.diff(indptr)
+    # probe for speed, then size the sample to the time target
+    probe = rng.choice(el.n, size=min(el.n, 20000), replace=False)
+    t0 = time.perf_counter()
+    oracle.aggregate_fwd(indptr, src, X, op=op, rows=probe, nthreads=threads, dout=deg)
+    dt = max(time.perf_counter() - t0, 1e-4)
+    rate = deg[probe].sum() * f / dt
+    want_edges = rate * target_seconds / f
+    n_rows = int(min(el.n, max(1000, want_edges / max(deg.mean(), 1e-9))))
+    rows = rng.choice(el.n, size=n_rows, replace=False)
+    t0 = time.perf_counter()
+    oracle.aggregate_fwd(indptr, src, X, op=op, rows=rows, nthreads=threads, dout=deg)
+    dt = time.perf_counter() - t0
+    ef = float(deg[rows].sum()) * f
+    return {"value": round(ef / dt / 1e9, 4), "unit": "GEF/s", "cores": threads, "kind": "oracle",
+            "sample": f"forward {op_name} F={f} on {n_rows} uniformly sampled destination rows "
+                      f"({int(deg[rows].sum())} edges) of the same graph, {dt:.1f} s, fp64 scalar loops, "
+                      f"OpenMP dynamic over rows"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="rmat_sparse_stack", choices=list(synth.WORKLOADS))
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the graph (debugging only; invalid as a result)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-calibration", action="store_true")
+    ap.add_argument("--dump-graph", default=None, metavar="DIR",
+                    help="write the CSR and transposed CSR as raw arrays for the stand-alone profiling driver, then exit")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: needs a GPU")
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    gnn.load_library()
+
+    w = synth.WORKLOADS[args.workload]
+    widths = list(w["widths"])
+    op_name = w["op"].split("+")[0]
+    op = OPS[op_name]
+    dtype = torch.bfloat16 if w["dtype"] == "bf16" else torch.float32
+    esz = 2 if dtype == torch.bfloat16 else 4
+
+    # ---- setup (not timed as part of a step) ----
+    t0 = time.perf_counter()
+    el = synth.make_graph(args.workload, device=dev, scale=args.scale)
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t0
+    weights = synth.gcn_sym_edge_weights(el.dst, el.src, el.n) if w.get("weighted") else None
+    t0 = time.perf_counter()
+    dg = gnn.build_device_graph(el.dst, el.src, el.n, edge_w=weights, indptr64=w["indptr64"], with_plans=False)
+    torch.cuda.synchronize()
+    t_csr = time.perf_counter() - t0
+    if args.dump_graph:
+        os.makedirs(args.dump_graph, exist_ok=True)
+        for name_, t in (("indptr", dg.indptr), ("indices", dg.indices), ("indptr_t", dg.indptr_t), ("indices_t", dg.indices_t)):
+            t.cpu().numpy().tofile(os.path.join(args.dump_graph, name_ + ".bin"))
+        with open(os.path.join(args.dump_graph, "meta.txt"), "w") as fh:
+            fh.write(f"{el.n} {el.e} {1 if w['indptr64'] else 0}\n")
+        print(f"dumped {args.workload} to {args.dump_graph}", file=sys.stderr)
+        return
+    t0 = time.perf_counter()
+    dg.plan_fwd = gnn.gnn_plan_create(dg.indptr, dg.indices, el.n)
+    dg.plan_bwd = gnn.gnn_plan_create(dg.indptr_t, dg.indices_t, el.n)
+    torch.cuda.synchronize()
+    t_plan = time.perf_counter() - t0
+    n, e = el.n, el.e
+    fmax = max(widths)
+    dg.plan_fwd.prepare(dg.indices, op, False, fmax)
+    dg.plan_bwd.prepare(dg.indices_t, op, True, fmax)
+
+    bufs = []  # one fresh set of inputs per layer of the stack
+    for layer, f in enumerate(widths):
+        X = synth.normal_features(n, f, 100 + layer, device=dev, dtype=dtype)
+        dY = synth.normal_features(n, f, 200 + layer, device=dev, dtype=dtype)
+        bufs.append((X, torch.empty_like(X), dY, torch.empty_like(dY)))
+    torch.cuda.synchronize()
+
+    calls = [(d, layer) for layer in range(len(widths)) for d in ("fwd", "bwd")]
+
+    def one_call(d, layer):
+        X, Y, dY, dX = bufs[layer]
+        f = widths[layer]
+        if d == "fwd":
+            gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, dg.edge_w, X, Y, n, f, op, plan=dg.plan_fwd)
+        else:
+            gnn.gnn_aggregate_bwd(dg.indptr_t, dg.indices_t, dg.edge_w_t, dY, dX, n, f, op, plan=dg.plan_bwd)
+
+    for _ in range(args.warmup):
+        for d, layer in calls:
+            one_call(d, layer)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps; events on the launch stream bracket every call ----
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in calls]
+          for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for k in range(args.steps):
+        for i, (d, layer) in enumerate(calls):
+            ev[k][i][0].record()
+            one_call(d, layer)
+            ev[k][i][1].record()
+    torch.cuda.synchronize()
+    t_total = time.perf_counter() - t_start
+
+    per_call_ms = [float(np.mean([ev[k][i][0].elapsed_time(ev[k][i][1]) for k in range(args.steps)]))
+                   for i in range(len(calls))]
+    ef_step = sum(2 * e * f for f in widths)
+    ms_per_step = t_total / args.steps * 1e3
+    value = ef_step / (t_total / args.steps) / 1e9
+
+    ip_bytes = 8 if w["indptr64"] else 4
+    weighted = weights is not None
+    call_rows = []
+    for i, (d, layer) in enumerate(calls):
+        f = widths[layer]
+        src_scaled = (op_name == "mean" and d == "bwd") or (op_name == "gcn" and not weighted)
+        b = algorithmic_bytes(n, e, f, esz, ip_bytes, weighted, src_scaled)
+        s = per_call_ms[i] * 1e-3
+        call_rows.append({"dir": d, "F": f, "ms": round(per_call_ms[i], 4), "GEF_per_s": round(e * f / s / 1e9, 2),
+                          "algorithmic_GB": round(b / 1e9, 4), "algorithmic_GBs": round(b / s / 1e9, 1),
+                          "frac_of_hbm_peak": round(b / s / 1e9 / HBM_PEAK_GBS, 4),
+                          "gathered_TBs": round(e * f * esz / s / 1e12, 2)})
+    # Dominant kernel = the forward aggregation kernel (one template instantiation serves all
+    # widths of this workload); its launches are the "fwd" calls of a step.
+    fwd = [r for r in call_rows if r["dir"] == "fwd"]
+    fwd_bytes = sum(r["algorithmic_GB"] for r in fwd)
+    fwd_s = sum(r["ms"] for r in fwd) * 1e-3
+    achieved = fwd_bytes / fwd_s
+    traffic = read_traffic_note(args.workload)
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "kernel": "aggregate_kernel (forward launches of one step)",
+                "launches_per_step": len(fwd), "avg_launch_ms": round(fwd_s * 1e3 / len(fwd), 4)}
+
+    result = {
+        "metric": "aggregation GEdge-features/s (edges*F/s) fwd+bwd; % of HBM peak GB/s",
+        "value": round(value, 2), "unit": "GEF/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if dtype == torch.bfloat16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: R-MAT/ER graph N={n} E={e}, op={w['op']}, widths={widths}, "
+                               f"fwd+bwd per width" + ("" if args.scale == 1.0 else f" (SCALED x{args.scale}: not a result)"),
+                   "N": n, "E": e, "widths": widths, "op": w["op"], "indptr_bits": ip_bytes * 8, "parallelism": "1 GPU"},
+        "roofline": roofline,
+        "calls": call_rows,
+        "setup_ms": {"graph_generation": round(t_gen * 1e3, 1), "csr_and_transpose": round(t_csr * 1e3, 1),
+                     "plans_fwd_and_bwd": round(t_plan * 1e3, 1)},
+    }
+    if not args.no_calibration:
+        result["ceilings"] = calibrate(dev)
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(synth.EdgeList(el.n, el.src.cpu(), el.dst.cpu(), el.meta), widths, op_name)
+    else:
+        result["cpu_baseline"] = None
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

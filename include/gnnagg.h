@@ -59,11 +59,18 @@ typedef struct gnn_opts {
     void *stream;          /* hipStream_t to enqueue on; NULL = the null stream */
     gnn_plan *plan;        /* degree-binning plan OF THE GRAPH PASSED IN THE SAME CALL (forward plan
                               for _fwd, plan of the transposed graph for _bwd); NULL = un-binned
-                              wavefront-per-row kernel, no hub splitting */
+                              wavefront-per-row kernel, no hub splitting.  A hot call may grow
+                              plan-owned buffers on first use (see gnn_plan_prepare); two calls
+                              sharing one plan must not overlap in time. */
     void *workspace;       /* optional device scratch for hub-row partial sums; NULL = plan-owned
                               scratch, grown (allocation!) on the first call that needs more */
     int64_t workspace_bytes;
+    int32_t flags;         /* bit set of GNN_FLAG_*; 0 = defaults */
+    int32_t reserved;      /* must be 0 */
 } gnn_opts;
+
+/* Do not spread column slices of line-aligned rows over the XCDs (for A/B measurements). */
+#define GNN_FLAG_NO_COLUMN_SLICES 1
 
 /* Degree-binning parameters.  thresholds t[0] < ... < t[k-1], all > 0, cut the
  * row-length axis into k+1 bins, bin(v) = #{i : t[i] <= deg(v)}.  If
@@ -160,6 +167,13 @@ GNN_API int gnn_plan_export(const gnn_plan *plan, int64_t *bin_offsets, int32_t 
 GNN_API int64_t gnn_plan_workspace_bytes(const gnn_plan *plan, int64_t F);
 /* Grow the plan-owned scratch now, so later hot calls do not allocate. */
 GNN_API int gnn_plan_reserve(gnn_plan *plan, int64_t F);
+/* Everything a later hot call with (op, direction, F) would otherwise allocate on its first
+ * use: the scratch of gnn_plan_reserve, and the plan-owned per-edge factor stream (4 bytes per
+ * edge: 1/din or 1/sqrt(deg) of the gathered vertex) that MEAN backward and weight-less
+ * GCN_SYM read instead of one random count lookup per edge.  `indices` is the index array
+ * of the plan's graph.  backward: 0 for gnn_aggregate_fwd, 1 for gnn_aggregate_bwd. */
+GNN_API int gnn_plan_prepare(gnn_plan *plan, const int32_t *indices, int op, int backward, int64_t F,
+                             void *stream);
 
 /* ---------------------------------------------------------------- utilities */
 GNN_API const char *gnn_status_string(int status);

@@ -19,11 +19,12 @@ GNN_OK, GNN_ERR_INVALID_ARG, GNN_ERR_UNSUPPORTED, GNN_ERR_ALLOC, GNN_ERR_LAUNCH,
 GNN_SUM, GNN_MEAN, GNN_GCN_SYM = 0, 1, 2
 GNN_F32, GNN_BF16 = 0, 1
 GNN_MAX_THRESHOLDS = 15
+GNN_FLAG_NO_COLUMN_SLICES = 1
 
 EXPORTED_SYMBOLS = (
     "gnn_aggregate_fwd", "gnn_aggregate_bwd", "gnn_csr_from_sorted_coo", "gnn_transpose_csr",
     "gnn_validate_csr", "gnn_plan_default_params", "gnn_plan_create", "gnn_plan_destroy",
-    "gnn_plan_sizes", "gnn_plan_export", "gnn_plan_workspace_bytes", "gnn_plan_reserve",
+    "gnn_plan_sizes", "gnn_plan_export", "gnn_plan_workspace_bytes", "gnn_plan_reserve", "gnn_plan_prepare",
     "gnn_status_string", "gnn_calib_copy", "gnn_calib_gather",
 )
 
@@ -34,6 +35,7 @@ class GnnOpts(ctypes.Structure):
         ("ldx", ctypes.c_int64), ("ldy", ctypes.c_int64),
         ("stream", ctypes.c_void_p), ("plan", ctypes.c_void_p),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_int64),
+        ("flags", ctypes.c_int32), ("reserved", ctypes.c_int32),
     ]
 
 
@@ -78,6 +80,7 @@ def load_library() -> ctypes.CDLL:
         lib.gnn_plan_workspace_bytes.argtypes = [vp, i64]
         lib.gnn_plan_workspace_bytes.restype = i64
         lib.gnn_plan_reserve.argtypes = [vp, i64]
+        lib.gnn_plan_prepare.argtypes = [vp, vp, i32, i32, i64, vp]
         lib.gnn_status_string.argtypes = [i32]
         lib.gnn_status_string.restype = ctypes.c_char_p
         lib.gnn_calib_copy.argtypes = [vp, vp, i64, vp]
@@ -163,6 +166,10 @@ class Plan:
     def reserve(self, F: int) -> None:
         _check("gnn_plan_reserve", load_library().gnn_plan_reserve(self.handle, int(F)))
 
+    def prepare(self, indices: torch.Tensor, op: int, backward: bool, F: int, stream=None) -> None:
+        _check("gnn_plan_prepare", load_library().gnn_plan_prepare(self.handle, _ptr(indices), int(op),
+                                                                   1 if backward else 0, int(F), _stream(stream)))
+
 
 def gnn_plan_default_params() -> GnnPlanParams:
     p = GnnPlanParams()
@@ -190,7 +197,7 @@ def gnn_plan_create(indptr: torch.Tensor, indices: torch.Tensor, N: int,
     return Plan(out.value, k)
 
 
-def _aggregate(fn_name, indptr, indices, edge_w, X, Y, N, F, op, plan, stream, workspace, ldx, ldy):
+def _aggregate(fn_name, indptr, indices, edge_w, X, Y, N, F, op, plan, stream, workspace, ldx, ldy, flags=0):
     lib = load_library()
     if X.dtype != Y.dtype:
         raise TypeError("input and output features must have the same dtype")
@@ -201,6 +208,7 @@ def _aggregate(fn_name, indptr, indices, edge_w, X, Y, N, F, op, plan, stream, w
     o.ldy = int(ldy if ldy is not None else (Y.stride(0) if Y.dim() == 2 and Y.shape[0] > 1 else 0))
     o.stream = _stream(stream)
     o.plan = plan.handle if plan is not None else None
+    o.flags = int(flags)
     if workspace is not None:
         o.workspace = workspace.data_ptr()
         o.workspace_bytes = workspace.numel() * workspace.element_size()
@@ -210,15 +218,15 @@ def _aggregate(fn_name, indptr, indices, edge_w, X, Y, N, F, op, plan, stream, w
 
 
 def gnn_aggregate_fwd(indptr, indices, edge_w, X, Y, N, F, op, plan: Optional[Plan] = None, stream=None,
-                      workspace=None, ldx=None, ldy=None) -> None:
+                      workspace=None, ldx=None, ldy=None, flags=0) -> None:
     """Y[v] = scale_v * sum_e c_e X[indices[e]] over the CSR by destination (see include/gnnagg.h)."""
-    _aggregate("gnn_aggregate_fwd", indptr, indices, edge_w, X, Y, N, F, op, plan, stream, workspace, ldx, ldy)
+    _aggregate("gnn_aggregate_fwd", indptr, indices, edge_w, X, Y, N, F, op, plan, stream, workspace, ldx, ldy, flags)
 
 
 def gnn_aggregate_bwd(indptr_t, indices_t, edge_w_t, dY, dX, N, F, op, plan: Optional[Plan] = None, stream=None,
-                      workspace=None, ldx=None, ldy=None) -> None:
+                      workspace=None, ldx=None, ldy=None, flags=0) -> None:
     """dX = adjoint of the forward map, over the transposed graph (see include/gnnagg.h)."""
-    _aggregate("gnn_aggregate_bwd", indptr_t, indices_t, edge_w_t, dY, dX, N, F, op, plan, stream, workspace, ldx, ldy)
+    _aggregate("gnn_aggregate_bwd", indptr_t, indices_t, edge_w_t, dY, dX, N, F, op, plan, stream, workspace, ldx, ldy, flags)
 
 
 def gnn_csr_from_sorted_coo(dst_sorted: torch.Tensor, N: int, indptr_out: torch.Tensor, stream=None) -> None:

@@ -46,6 +46,9 @@ def build_library(verbose: bool = True) -> str:
     tmp = LIB + ".tmp"
     subprocess.check_call([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])
     os.replace(tmp, LIB)
+    # stand-alone profiling driver (used under rocprofv3 --pmc; links against the library)
+    subprocess.check_call([_hipcc(), "-O2", "-std=c++17", "-I", INCLUDE, os.path.join(CSRC, "agg_profile.cpp"),
+                           "-o", os.path.join(PKG, "agg_profile"), "-L", PKG, "-lgnnagg", "-Wl,-rpath,$ORIGIN"])
     if verbose:
         print(f"built {LIB}", file=sys.stderr)
     return LIB

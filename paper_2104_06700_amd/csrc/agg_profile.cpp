@@ -1,0 +1,108 @@
+// Stand-alone driver for rocprofv3 counter runs (the profiler's counter mode does not
+// survive the Python process on this image): loads a graph dumped by
+// `bench.py --dump-graph DIR`, builds the plans and runs the forward and backward
+// aggregation through the C ABI a few times, preceded by a 1 GiB streaming copy whose
+// counter readings calibrate FETCH_SIZE / WRITE_SIZE.
+//
+// usage: agg_profile DIR OP(0|1|2) REPS [noslice] F [F ...]      (fp32 features)
+// "noslice" switches the XCD column slicing off for the widths that follow it.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstdlib>
+#include <string>
+#include <vector>
+
+#include "gnnagg.h"
+
+#define CHECK(x)                                                                   \
+    do {                                                                           \
+        if ((x) != hipSuccess) { fprintf(stderr, "HIP error at %s:%d\n", __FILE__, __LINE__); return 2; } \
+    } while (0)
+#define GCHECK(x)                                                                  \
+    do {                                                                           \
+        int s_ = (x);                                                              \
+        if (s_ != GNN_OK) { fprintf(stderr, "gnnagg: %s at %s:%d\n", gnn_status_string(s_), __FILE__, __LINE__); return 3; } \
+    } while (0)
+
+static void *load_to_device(const std::string &path, size_t bytes) {
+    std::vector<char> host(bytes);
+    FILE *f = fopen(path.c_str(), "rb");
+    if (!f) { fprintf(stderr, "cannot open %s\n", path.c_str()); return nullptr; }
+    size_t got = fread(host.data(), 1, bytes, f);
+    fclose(f);
+    if (got != bytes) { fprintf(stderr, "short read on %s\n", path.c_str()); return nullptr; }
+    void *d = nullptr;
+    if (hipMalloc(&d, bytes ? bytes : 16) != hipSuccess) return nullptr;
+    if (hipMemcpy(d, host.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) return nullptr;
+    return d;
+}
+
+int main(int argc, char **argv) {
+    if (argc < 5) { fprintf(stderr, "usage: %s DIR OP REPS F [F ...]\n", argv[0]); return 1; }
+    const std::string dir = argv[1];
+    const int op = atoi(argv[2]);
+    const int reps = atoi(argv[3]);
+    long long N = 0, E = 0; int ip64 = 0;
+    {
+        FILE *f = fopen((dir + "/meta.txt").c_str(), "r");
+        if (!f || fscanf(f, "%lld %lld %d", &N, &E, &ip64) != 3) { fprintf(stderr, "bad meta.txt\n"); return 1; }
+        fclose(f);
+    }
+    const size_t ipb = ip64 ? 8 : 4;
+    void *indptr = load_to_device(dir + "/indptr.bin", ipb * (N + 1));
+    void *indices = load_to_device(dir + "/indices.bin", 4 * (size_t)E);
+    void *indptr_t = load_to_device(dir + "/indptr_t.bin", ipb * (N + 1));
+    void *indices_t = load_to_device(dir + "/indices_t.bin", 4 * (size_t)E);
+    if (!indptr || !indices || !indptr_t || !indices_t) return 2;
+
+    // calibration copy: 1 GiB read + 1 GiB write
+    {
+        void *a = nullptr, *b = nullptr;
+        const size_t n = size_t(1) << 30;
+        CHECK(hipMalloc(&a, n)); CHECK(hipMalloc(&b, n));
+        CHECK(hipMemset(a, 0x3c, n));
+        for (int i = 0; i < 3; ++i) GCHECK(gnn_calib_copy(a, b, (int64_t)n, nullptr));
+        CHECK(hipDeviceSynchronize());
+        CHECK(hipFree(a)); CHECK(hipFree(b));
+    }
+
+    gnn_plan *pf = nullptr, *pb = nullptr;
+    GCHECK(gnn_plan_create(indptr, (const int32_t *)indices, N, ip64, nullptr, nullptr, &pf));
+    GCHECK(gnn_plan_create(indptr_t, (const int32_t *)indices_t, N, ip64, nullptr, nullptr, &pb));
+
+    int flags = 0;
+    for (int a = 4; a < argc; ++a) {
+        if (std::string(argv[a]) == "noslice") { flags = GNN_FLAG_NO_COLUMN_SLICES; continue; }
+        const long long F = atoll(argv[a]);
+        const size_t bytes = (size_t)N * F * 4;
+        void *X = nullptr, *Y = nullptr;
+        CHECK(hipMalloc(&X, bytes)); CHECK(hipMalloc(&Y, bytes));
+        CHECK(hipMemset(X, 0x3c, bytes));
+        gnn_opts o{};
+        o.indptr_is_64 = ip64;
+        o.flags = flags;
+        o.plan = pf;
+        hipEvent_t e0, e1;
+        CHECK(hipEventCreate(&e0)); CHECK(hipEventCreate(&e1));
+        GCHECK(gnn_aggregate_fwd(indptr, (const int32_t *)indices, nullptr, X, Y, N, F, op, &o));  // warm-up
+        CHECK(hipEventRecord(e0, nullptr));
+        for (int r = 0; r < reps; ++r) GCHECK(gnn_aggregate_fwd(indptr, (const int32_t *)indices, nullptr, X, Y, N, F, op, &o));
+        CHECK(hipEventRecord(e1, nullptr));
+        CHECK(hipEventSynchronize(e1));
+        float ms_f = 0; CHECK(hipEventElapsedTime(&ms_f, e0, e1));
+        o.plan = pb;
+        GCHECK(gnn_aggregate_bwd(indptr_t, (const int32_t *)indices_t, nullptr, X, Y, N, F, op, &o));
+        CHECK(hipEventRecord(e0, nullptr));
+        for (int r = 0; r < reps; ++r) GCHECK(gnn_aggregate_bwd(indptr_t, (const int32_t *)indices_t, nullptr, X, Y, N, F, op, &o));
+        CHECK(hipEventRecord(e1, nullptr));
+        CHECK(hipEventSynchronize(e1));
+        float ms_b = 0; CHECK(hipEventElapsedTime(&ms_b, e0, e1));
+        printf("N=%lld E=%lld F=%lld op=%d flags=%d fwd %.4f ms  bwd %.4f ms  (%.1f / %.1f GEF/s)\n", N, E, F, op, flags, ms_f / reps,
+               ms_b / reps, E * F / (ms_f / reps) / 1e6, E * F / (ms_b / reps) / 1e6);
+        CHECK(hipFree(X)); CHECK(hipFree(Y));
+    }
+    gnn_plan_destroy(pf);
+    gnn_plan_destroy(pb);
+    return 0;
+}

@@ -31,7 +31,7 @@ enum ScaleMode : int { kScaleNone = 0, kScaleInv = 1, kScaleRsqrt = 2 };
 enum BinKind : int { kKindRows = 0, kKindHubPieces = 1 };
 
 struct BinDesc {
-    int64_t first_block;  // first blockIdx.x of this bin
+    int64_t first_block;  // first (slice-independent) workgroup index of this bin
     int64_t item_begin;   // offset into row_perm (rows) or into the piece list (hub pieces)
     int64_t n_items;      // rows or pieces
     int32_t log2_g;       // lanes per row group
@@ -50,12 +50,15 @@ struct AggArgs {
     int32_t F;
     int32_t ip64;
     const int32_t *row_perm;    // nullptr: identity
-    const int32_t *col_counts;  // degree of the gathered vertex (for src scaling)
-    int32_t src_mode, dst_mode;
+    const float *edge_scale;    // per-edge factor 1/deg or 1/sqrt(deg) of the gathered vertex, or nullptr
+    int32_t dst_mode;
+    int32_t pad0;
     const int64_t *chunks;      // hub pieces (row, e_begin, e_end)
     float *partial;             // [n_chunks, ldp] fp32
     int64_t ldp;
     int32_t n_bins;
+    int32_t log2_slices;  // column slices; workgroup b serves slice b % n_slices (see run_aggregate)
+    int32_t slice_cols;   // columns per slice
     int32_t pad;
     BinDesc bins[GNN_MAX_BINS + 1];
 };
@@ -172,11 +175,16 @@ __global__ void __launch_bounds__(kBlockThreads) aggregate_kernel(const AggArgs 
     const int wave_in_block = threadIdx.x >> 6;
 
     // which bin does this workgroup serve (wave-uniform scan of a tiny table)
+    const int slice = int(blockIdx.x) & ((1 << a.log2_slices) - 1);
+    const int64_t vblock = int64_t(blockIdx.x) >> a.log2_slices;
+    const int col_base = slice * a.slice_cols;
+    const int Fk = a.F - col_base < a.slice_cols ? a.F - col_base : a.slice_cols;  // columns of this slice
+    if (Fk <= 0) return;
     int b = 0;
     for (int i = 1; i < a.n_bins; ++i)
-        if (int64_t(blockIdx.x) >= a.bins[i].first_block) b = i;
+        if (vblock >= a.bins[i].first_block) b = i;
     const BinDesc bin = a.bins[b];
-    const int64_t wave_in_bin = (int64_t(blockIdx.x) - bin.first_block) * kWavesPerBlock + wave_in_block;
+    const int64_t wave_in_bin = (vblock - bin.first_block) * kWavesPerBlock + wave_in_block;
 
     const int G = 1 << bin.log2_g;
     const int SR = 1 << bin.log2_sr;
@@ -218,22 +226,31 @@ __global__ void __launch_bounds__(kBlockThreads) aggregate_kernel(const AggArgs 
     bool col_ok[NPASS];
 #pragma unroll
     for (int p = 0; p < NPASS; ++p) {
-        col[p] = (p * C + c) * VEC;
-        col_ok[p] = col[p] < a.F;
+        col[p] = col_base + (p * C + c) * VEC;
+        col_ok[p] = (p * C + c) * VEC < Fk;
     }
 
-    for (int64_t tile = e0; __any(tile < e1); tile += G) {
-        // one coalesced tile of neighbour ids (and coefficients) per group
-        const int64_t my_e = tile + lane_in_g;
-        int my_u = 0;
-        float my_cf = 0.0f;
-        if (my_e < e1) {
-            my_u = a.indices[my_e];
+    // Neighbour ids (and coefficients) travel one coalesced tile of G edges per group at a
+    // time; the next tile is requested before the current one is consumed, so only the first
+    // index load of a row is exposed latency.
+    auto fetch_tile = [&](int64_t e, int &u_out, float &cf_out) {
+        u_out = 0;
+        cf_out = 0.0f;
+        if (e < e1) {
+            u_out = a.indices[e];
             if (COEF) {
-                my_cf = a.w ? a.w[my_e] : 1.0f;
-                if (a.src_mode != kScaleNone) my_cf *= scale_of(a.src_mode, a.col_counts[my_u]);
+                cf_out = a.w ? a.w[e] : 1.0f;
+                if (a.edge_scale) cf_out *= a.edge_scale[e];
             }
         }
+    };
+    int nxt_u;
+    float nxt_cf;
+    fetch_tile(e0 + lane_in_g, nxt_u, nxt_cf);
+    for (int64_t tile = e0; __any(tile < e1); tile += G) {
+        const int my_u = nxt_u;
+        const float my_cf = nxt_cf;
+        fetch_tile(tile + G + lane_in_g, nxt_u, nxt_cf);
         const int64_t left = e1 - tile;
         const int n_tile = left < G ? (left > 0 ? int(left) : 0) : G;
 
@@ -376,6 +393,13 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         dst_mode = kScaleRsqrt;
     }
     if (src_mode != kScaleNone && !plan) return GNN_ERR_UNSUPPORTED;  // needs the column counts a plan holds
+    const float *edge_scale = nullptr;
+    if (src_mode != kScaleNone && plan->n_edges > 0) {
+        // streamed per-edge factors (built once per plan and mode) instead of a random 4-byte
+        // lookup per edge, which would cost a 128-byte line each
+        int rc = gnn_plan_edge_scale(plan, indices, src_mode, static_cast<hipStream_t>(o.stream), &edge_scale);
+        if (rc != GNN_OK) return rc;
+    }
     const bool coef = (w != nullptr) || src_mode != kScaleNone;
 
     // widest load the strides and base addresses allow
@@ -409,11 +433,41 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         if (reinterpret_cast<uintptr_t>(partial) % 16) return GNN_ERR_INVALID_ARG;
     }
 
-    // Feature slabs: one launch covers up to 64 lanes * vec * kMaxPass columns.
-    const int64_t slab = int64_t(64) * vec * kMaxPass;
+    // Column slices over the XCDs.  Workgroups are handed to the 8 XCDs round-robin by
+    // workgroup id, and every XCD has a private L2.  When the gathered rows are whole 128-byte
+    // lines, workgroup b gathers only column slice (b % S): an XCD's L2 then sees one slice of
+    // every gathered row instead of whole rows of an eighth of the destinations, so S times as
+    // many hot source rows stay resident.  The price is S reads of the index stream.
+    int log2_slices = 0;
+    int64_t slice_cols_all = 0;
+    {
+        const int64_t line_elems = 128 / esz;
+        const bool lines_ok = (ldx % line_elems == 0) && reinterpret_cast<uintptr_t>(gathered) % 128 == 0;
+        const int64_t lines = (F + line_elems - 1) / line_elems;
+        if (lines_ok && lines >= 2 && !(o.flags & GNN_FLAG_NO_COLUMN_SLICES)) {
+            for (int ls = 3; ls >= 1; --ls) {
+                const int64_t S = int64_t(1) << ls;
+                const int64_t per = (lines + S - 1) / S;
+                if (per * (S - 1) < lines && S * per * 5 <= lines * 6) { log2_slices = ls; slice_cols_all = per * line_elems; break; }
+            }
+        }
+    }
+
+    constexpr int sr_shift = 4;
+
+    // Feature slabs: one launch covers up to 64 lanes * vec * kMaxPass columns (per slice).
+    const int64_t slab = (int64_t(64) * vec * kMaxPass) << log2_slices;
     for (int64_t f0 = 0; f0 < F; f0 += slab) {
         const int64_t fw = F - f0 < slab ? F - f0 : slab;
-        const int64_t strips = (fw + vec - 1) / vec;
+        // with slices, a workgroup's lanes span one slice; a wide slice may still need passes
+        int64_t slice_cols = fw;
+        int log2_s = 0;
+        if (log2_slices > 0) {
+            slice_cols = slice_cols_all < int64_t(64) * vec * kMaxPass ? slice_cols_all : int64_t(64) * vec * kMaxPass;
+            log2_s = log2_slices;
+            if (slice_cols << log2_s < fw) { slice_cols = fw; log2_s = 0; }  // does not tile this slab: fall back
+        }
+        const int64_t strips = (slice_cols + vec - 1) / vec;
         const int log2_c = strips >= 64 ? 6 : gnn_ilog2_ceil(strips);
         const int C = 1 << log2_c;
         const int npass = int((strips + C - 1) / C);
@@ -429,8 +483,10 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         a.ldy = ldy;
         a.F = int32_t(fw);
         a.ip64 = o.indptr_is_64 ? 1 : 0;
-        a.src_mode = src_mode;
+        a.edge_scale = edge_scale;
         a.dst_mode = dst_mode;
+        a.log2_slices = log2_s;
+        a.slice_cols = int32_t(slice_cols);
         int64_t next_block = 0;
         int nb = 0;
         auto add_bin = [&](int kind, int64_t begin, int64_t n_items, int log2_sr) {
@@ -447,7 +503,6 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         };
         if (plan) {
             a.row_perm = plan->row_perm;
-            a.col_counts = plan->col_counts;
             a.chunks = plan->chunks;
             // The scratch rows are F wide for every slab; point at this slab's columns.
             a.partial = partial ? partial + f0 : nullptr;
@@ -458,8 +513,11 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
             for (int bi = last; bi >= 0; --bi) {
                 if (bi == last && plan->params.hub_chunk > 0) continue;  // handled as pieces (+ finalize)
                 const int64_t lo = bi == 0 ? 0 : plan->params.thresholds[bi - 1];
-                // as many edge slots as the shortest row of the bin can keep busy
-                int lsr = lo <= 1 ? 0 : pow2_floor_log2(lo);
+                // Edge slots per row: enough that the shortest row of the bin still takes ~16
+                // steps (several batches of loads per group), so short rows share a wavefront
+                // (64/G rows each) and only long rows get a whole wavefront.
+                int lsr = lo <= 1 ? 0 : pow2_floor_log2(lo) - sr_shift;
+                if (lsr < 0) lsr = 0;
                 if (lsr > max_log2_sr) lsr = max_log2_sr;
                 add_bin(kKindRows, plan->bin_offsets[bi], plan->bin_offsets[bi + 1] - plan->bin_offsets[bi], lsr);
             }
@@ -468,6 +526,7 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         }
         a.n_bins = nb;
         if (nb == 0 || next_block == 0) continue;
+        next_block <<= log2_s;
         if (next_block > INT32_MAX) return GNN_ERR_UNSUPPORTED;
 
         dim3 grid(static_cast<unsigned>(next_block));

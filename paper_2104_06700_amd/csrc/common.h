@@ -34,7 +34,13 @@ struct gnn_plan {
     void *scratch = nullptr;
     int64_t scratch_bytes = 0;
     const void *indptr_seen = nullptr;  // the indptr the plan was built from (sanity check only)
+    // per-edge factor of the gathered vertex, streamed by the hot kernels:
+    // [0] 1/max(col_counts[indices[e]],1)   [1] 1/sqrt(max(col_counts[indices[e]],1)); built on first use
+    float *edge_scale[2] = {nullptr, nullptr};
 };
+
+// mode: 1 = reciprocal, 2 = reciprocal square root.  Builds the array on first use (allocation).
+int gnn_plan_edge_scale(gnn_plan *plan, const int32_t *indices, int mode, hipStream_t stream, const float **out);
 
 static inline int gnn_ilog2_ceil(int64_t x) {
     int l = 0;

@@ -135,6 +135,17 @@ __global__ void __launch_bounds__(256) hub_fill_kernel(const int32_t *__restrict
     }
 }
 
+__global__ void __launch_bounds__(256) edge_scale_kernel(const int32_t *__restrict__ indices, int64_t E,
+                                                         const int32_t *__restrict__ col_counts, int mode,
+                                                         float *__restrict__ out) {
+    int64_t stride = int64_t(gridDim.x) * blockDim.x;
+    for (int64_t e = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; e < E; e += stride) {
+        int c = col_counts[indices[e]];
+        float d = static_cast<float>(c > 1 ? c : 1);
+        out[e] = mode == 1 ? 1.0f / d : 1.0f / sqrtf(d);
+    }
+}
+
 int grid_for(int64_t n, int block, int64_t cap = (int64_t(1) << 20)) {
     int64_t g = (n + block - 1) / block;
     if (g < 1) g = 1;
@@ -147,14 +158,40 @@ int grid_for(int64_t n, int block, int64_t cap = (int64_t(1) << 20)) {
 extern "C" GNN_API void gnn_plan_default_params(gnn_plan_params *p) {
     if (!p) return;
     *p = gnn_plan_params{};
-    const int64_t t[] = {1, 2, 4, 8, 16, 32, 64, 4096};
+    const int64_t t[] = {1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048, 4096};
     p->n_thresholds = static_cast<int32_t>(sizeof(t) / sizeof(t[0]));
     for (int i = 0; i < p->n_thresholds; ++i) p->thresholds[i] = t[i];
     p->hub_chunk = 1024;
 }
 
+int gnn_plan_edge_scale(gnn_plan *plan, const int32_t *indices, int mode, hipStream_t stream, const float **out) {
+    if (!plan || !out || (mode != 1 && mode != 2)) return GNN_ERR_INVALID_ARG;
+    float *&arr = plan->edge_scale[mode - 1];
+    if (!arr && plan->n_edges > 0) {
+        if (!indices) return GNN_ERR_INVALID_ARG;
+        if (hipMalloc(&arr, sizeof(float) * plan->n_edges) != hipSuccess) { arr = nullptr; return GNN_ERR_ALLOC; }
+        edge_scale_kernel<<<grid_for(plan->n_edges, 256, 1 << 16), 256, 0, stream>>>(indices, plan->n_edges, plan->col_counts, mode, arr);
+        if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
+    }
+    *out = arr;
+    return GNN_OK;
+}
+
+extern "C" GNN_API int gnn_plan_prepare(gnn_plan *plan, const int32_t *indices, int op, int backward, int64_t F,
+                                        void *stream) {
+    if (!plan || F < 0 || op < GNN_SUM || op > GNN_GCN_SYM) return GNN_ERR_INVALID_ARG;
+    int rc = gnn_plan_reserve(plan, F);
+    if (rc != GNN_OK) return rc;
+    const float *unused = nullptr;
+    if (op == GNN_MEAN && backward) rc = gnn_plan_edge_scale(plan, indices, 1, static_cast<hipStream_t>(stream), &unused);
+    if (op == GNN_GCN_SYM) rc = gnn_plan_edge_scale(plan, indices, 2, static_cast<hipStream_t>(stream), &unused);
+    return rc;
+}
+
 extern "C" GNN_API void gnn_plan_destroy(gnn_plan *plan) {
     if (!plan) return;
+    (void)hipFree(plan->edge_scale[0]);
+    (void)hipFree(plan->edge_scale[1]);
     (void)hipFree(plan->row_perm);
     (void)hipFree(plan->col_counts);
     (void)hipFree(plan->chunks);

@@ -35,8 +35,8 @@ def test_status_strings_and_defaults():
 
 
 def test_struct_layout_matches_header():
-    # gnn_opts: 2 x int32, 2 x int64, 3 pointers, int64; gnn_plan_params: int32 (+pad), 15 x int64, int64
-    assert ctypes.sizeof(gnn.GnnOpts) == 8 + 16 + 24 + 8
+    # gnn_opts: 2 x int32, 2 x int64, 3 pointers, int64, 2 x int32; gnn_plan_params: int32 (+pad), 15 x int64, int64
+    assert ctypes.sizeof(gnn.GnnOpts) == 8 + 16 + 24 + 8 + 8
     assert ctypes.sizeof(gnn.GnnPlanParams) == 8 + 15 * 8 + 8
 
 
