@@ -89,7 +89,10 @@ def _aggregate(fn_name, indptr, indices, w, X, op, other_deg, rows, nthreads, wa
     assert X.ndim == 2
     n = indptr.shape[0] - 1
     f = X.shape[1]
-    assert X.shape[0] == n and indices.shape[0] == indptr[-1]
+    # X may have a different number of rows than the CSR (a compacted sub-problem whose
+    # indices were renumbered into X's rows); the arithmetic is the same.
+    assert indices.shape[0] == indptr[-1]
+    assert indices.size == 0 or (indices.min() >= 0 and indices.max() < X.shape[0])
     w = None if w is None else _f32(w)
     other_deg = None if other_deg is None else _i64(other_deg)
     rows_a = None if rows is None else _i64(rows)
