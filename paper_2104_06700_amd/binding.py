@@ -114,6 +114,17 @@ def _check(fn: str, status: int) -> None:
         raise GnnError(fn, status)
 
 
+def _call_allocating(fn: str, call) -> None:
+    """Library calls that hipMalloc can fail only because torch's caching allocator is
+    sitting on freed blocks: hand those back to the driver and try once more."""
+    status = call()
+    if status == GNN_ERR_ALLOC:
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
+        status = call()
+    _check(fn, status)
+
+
 def _is64(indptr: torch.Tensor) -> int:
     if indptr.dtype == torch.int64:
         return 1
@@ -164,11 +175,11 @@ class Plan:
         return int(load_library().gnn_plan_workspace_bytes(self.handle, int(F)))
 
     def reserve(self, F: int) -> None:
-        _check("gnn_plan_reserve", load_library().gnn_plan_reserve(self.handle, int(F)))
+        _call_allocating("gnn_plan_reserve", lambda: load_library().gnn_plan_reserve(self.handle, int(F)))
 
     def prepare(self, indices: torch.Tensor, op: int, backward: bool, F: int, stream=None) -> None:
-        _check("gnn_plan_prepare", load_library().gnn_plan_prepare(self.handle, _ptr(indices), int(op),
-                                                                   1 if backward else 0, int(F), _stream(stream)))
+        _call_allocating("gnn_plan_prepare", lambda: load_library().gnn_plan_prepare(
+            self.handle, _ptr(indices), int(op), 1 if backward else 0, int(F), _stream(stream)))
 
 
 def gnn_plan_default_params() -> GnnPlanParams:
@@ -189,10 +200,9 @@ def make_plan_params(thresholds: Sequence[int], hub_chunk: int) -> GnnPlanParams
 def gnn_plan_create(indptr: torch.Tensor, indices: torch.Tensor, N: int,
                     params: Optional[GnnPlanParams] = None, stream=None) -> Plan:
     out = ctypes.c_void_p()
-    st = load_library().gnn_plan_create(_ptr(indptr), _ptr(indices), int(N), _is64(indptr),
-                                        ctypes.byref(params) if params is not None else None,
-                                        _stream(stream), ctypes.byref(out))
-    _check("gnn_plan_create", st)
+    _call_allocating("gnn_plan_create", lambda: load_library().gnn_plan_create(
+        _ptr(indptr), _ptr(indices), int(N), _is64(indptr), ctypes.byref(params) if params is not None else None,
+        _stream(stream), ctypes.byref(out)))
     k = params.n_thresholds if params is not None else gnn_plan_default_params().n_thresholds
     return Plan(out.value, k)
 
@@ -212,9 +222,8 @@ def _aggregate(fn_name, indptr, indices, edge_w, X, Y, N, F, op, plan, stream, w
     if workspace is not None:
         o.workspace = workspace.data_ptr()
         o.workspace_bytes = workspace.numel() * workspace.element_size()
-    st = getattr(lib, fn_name)(_ptr(indptr), _ptr(indices), _ptr(edge_w), _ptr(X), _ptr(Y),
-                               int(N), int(F), int(op), ctypes.byref(o))
-    _check(fn_name, st)
+    _call_allocating(fn_name, lambda: getattr(lib, fn_name)(_ptr(indptr), _ptr(indices), _ptr(edge_w), _ptr(X), _ptr(Y),
+                                                            int(N), int(F), int(op), ctypes.byref(o)))
 
 
 def gnn_aggregate_fwd(indptr, indices, edge_w, X, Y, N, F, op, plan: Optional[Plan] = None, stream=None,
@@ -240,9 +249,9 @@ def gnn_transpose_csr(indptr, indices, edge_w, N, indptr_t, indices_t, perm=None
         raise TypeError("indptr_t must have the dtype of indptr")
     if perm is not None and perm.dtype != torch.int64:
         raise TypeError("perm must be int64")
-    st = load_library().gnn_transpose_csr(_ptr(indptr), _ptr(indices), _ptr(edge_w), int(N), _is64(indptr),
-                                          _ptr(indptr_t), _ptr(indices_t), _ptr(perm), _ptr(edge_w_t), _stream(stream))
-    _check("gnn_transpose_csr", st)
+    _call_allocating("gnn_transpose_csr", lambda: load_library().gnn_transpose_csr(
+        _ptr(indptr), _ptr(indices), _ptr(edge_w), int(N), _is64(indptr), _ptr(indptr_t), _ptr(indices_t), _ptr(perm),
+        _ptr(edge_w_t), _stream(stream)))
 
 
 def gnn_validate_csr(indptr, indices, N, E, stream=None) -> int:

@@ -415,6 +415,7 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
     if (reinterpret_cast<uintptr_t>(gathered) % esz || reinterpret_cast<uintptr_t>(out) % esz) return GNN_ERR_INVALID_ARG;
 
     hipStream_t stream = static_cast<hipStream_t>(o.stream);
+    (void)hipGetLastError();  // a stale error of an earlier, failed call must not be blamed on this one
 
     // hub scratch
     float *partial = nullptr;

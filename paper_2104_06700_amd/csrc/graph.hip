@@ -100,6 +100,7 @@ extern "C" GNN_API int gnn_csr_from_sorted_coo(const int32_t *dst_sorted, int64_
     if (N < 0 || E < 0 || !indptr_out || (E > 0 && !dst_sorted)) return GNN_ERR_INVALID_ARG;
     if (!indptr_is_64 && E > INT32_MAX) return GNN_ERR_INVALID_ARG;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    (void)hipGetLastError();  // a stale error of an earlier, failed call must not be blamed on this one
     if (indptr_is_64)
         indptr_from_sorted_kernel<int64_t><<<grid_for(E + 1, 256), 256, 0, stream>>>(dst_sorted, E, N, static_cast<int64_t *>(indptr_out));
     else
@@ -114,6 +115,7 @@ extern "C" GNN_API int gnn_transpose_csr(const void *indptr, const int32_t *indi
     if (N < 0 || N > INT32_MAX || !indptr || !indptr_t) return GNN_ERR_INVALID_ARG;
     if (edge_w && !edge_w_t) return GNN_ERR_INVALID_ARG;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    (void)hipGetLastError();
     int64_t E = 0;
     int rc = read_edge_count(indptr, N, indptr_is_64, stream, &E);
     if (rc != GNN_OK) return rc;
@@ -172,6 +174,7 @@ extern "C" GNN_API int gnn_validate_csr(const void *indptr, const int32_t *indic
                                 void *stream_v) {
     if (N < 0 || E < 0 || !indptr || (E > 0 && !indices)) return GNN_ERR_INVALID_ARG;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    (void)hipGetLastError();
     int *bad = nullptr;
     if (hipMalloc(&bad, sizeof(int)) != hipSuccess) return GNN_ERR_ALLOC;
     int host_bad = 0;

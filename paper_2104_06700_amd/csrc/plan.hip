@@ -169,6 +169,7 @@ int gnn_plan_edge_scale(gnn_plan *plan, const int32_t *indices, int mode, hipStr
     float *&arr = plan->edge_scale[mode - 1];
     if (!arr && plan->n_edges > 0) {
         if (!indices) return GNN_ERR_INVALID_ARG;
+        (void)hipGetLastError();
         if (hipMalloc(&arr, sizeof(float) * plan->n_edges) != hipSuccess) { arr = nullptr; return GNN_ERR_ALLOC; }
         edge_scale_kernel<<<grid_for(plan->n_edges, 256, 1 << 16), 256, 0, stream>>>(indices, plan->n_edges, plan->col_counts, mode, arr);
         if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
@@ -214,6 +215,7 @@ extern "C" GNN_API int gnn_plan_create(const void *indptr, const int32_t *indice
         if (i > 0 && prm.thresholds[i] <= prm.thresholds[i - 1]) return GNN_ERR_INVALID_ARG;
     }
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    (void)hipGetLastError();  // a stale error of an earlier, failed call must not be blamed on this one
     gnn_plan *plan = new (std::nothrow) gnn_plan();
     if (!plan) return GNN_ERR_ALLOC;
     plan->n_rows = N;
@@ -325,6 +327,7 @@ extern "C" GNN_API int gnn_plan_reserve(gnn_plan *plan, int64_t F) {
     if (!plan || F < 0) return GNN_ERR_INVALID_ARG;
     const int64_t need = gnn_plan_workspace_bytes(plan, F);
     if (need <= plan->scratch_bytes) return GNN_OK;
+    (void)hipGetLastError();
     (void)hipFree(plan->scratch);
     plan->scratch = nullptr;
     plan->scratch_bytes = 0;
