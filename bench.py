@@ -171,8 +171,9 @@ def main():
     t_plan = time.perf_counter() - t0
     n, e = el.n, el.e
     fmax = max(widths)
-    dg.plan_fwd.prepare(dg.indices, op, False, fmax)
-    dg.plan_bwd.prepare(dg.indices_t, op, True, fmax)
+    for f in sorted(set(widths)):
+        dg.plan_fwd.prepare(dg.indices, op, False, f, dtype)
+        dg.plan_bwd.prepare(dg.indices_t, op, True, f, dtype)
 
     bufs = []  # one fresh set of inputs per layer of the stack
     for layer, f in enumerate(widths):

@@ -66,11 +66,16 @@ typedef struct gnn_opts {
                               scratch, grown (allocation!) on the first call that needs more */
     int64_t workspace_bytes;
     int32_t flags;         /* bit set of GNN_FLAG_*; 0 = defaults */
-    int32_t reserved;      /* must be 0 */
+    int32_t max_slices;    /* upper bound on the number of XCD column slices (1, 2, 4 or 8); 0 = automatic */
 } gnn_opts;
 
 /* Do not spread column slices of line-aligned rows over the XCDs (for A/B measurements). */
 #define GNN_FLAG_NO_COLUMN_SLICES 1
+/* Gather from the caller's matrix even when its rows are not whole 128-byte lines (default: a
+ * call with a plan copies such a matrix into plan-owned padded rows first, when it is large). */
+#define GNN_FLAG_NO_PADDED_COPY 2
+/* Take the padded-copy route whenever a plan is given, whatever the size and alignment (tests). */
+#define GNN_FLAG_FORCE_PADDED_COPY 4
 
 /* Degree-binning parameters.  thresholds t[0] < ... < t[k-1], all > 0, cut the
  * row-length axis into k+1 bins, bin(v) = #{i : t[i] <= deg(v)}.  If
@@ -170,10 +175,12 @@ GNN_API int gnn_plan_reserve(gnn_plan *plan, int64_t F);
 /* Everything a later hot call with (op, direction, F) would otherwise allocate on its first
  * use: the scratch of gnn_plan_reserve, and the plan-owned per-edge factor stream (4 bytes per
  * edge: 1/din or 1/sqrt(deg) of the gathered vertex) that MEAN backward and weight-less
- * GCN_SYM read instead of one random count lookup per edge.  `indices` is the index array
+ * GCN_SYM read instead of one random count lookup per edge, and -- for widths whose rows are
+ * not whole 128-byte lines -- the plan-owned copy of the gathered matrix with padded rows
+ * (N x roundup(F) elements of `dtype`) that the hot call fills and gathers from.  `indices` is the index array
  * of the plan's graph.  backward: 0 for gnn_aggregate_fwd, 1 for gnn_aggregate_bwd. */
 GNN_API int gnn_plan_prepare(gnn_plan *plan, const int32_t *indices, int op, int backward, int64_t F,
-                             void *stream);
+                             int dtype, void *stream);
 
 /* ---------------------------------------------------------------- utilities */
 GNN_API const char *gnn_status_string(int status);

@@ -20,6 +20,8 @@ GNN_SUM, GNN_MEAN, GNN_GCN_SYM = 0, 1, 2
 GNN_F32, GNN_BF16 = 0, 1
 GNN_MAX_THRESHOLDS = 15
 GNN_FLAG_NO_COLUMN_SLICES = 1
+GNN_FLAG_NO_PADDED_COPY = 2
+GNN_FLAG_FORCE_PADDED_COPY = 4
 
 EXPORTED_SYMBOLS = (
     "gnn_aggregate_fwd", "gnn_aggregate_bwd", "gnn_csr_from_sorted_coo", "gnn_transpose_csr",
@@ -35,7 +37,7 @@ class GnnOpts(ctypes.Structure):
         ("ldx", ctypes.c_int64), ("ldy", ctypes.c_int64),
         ("stream", ctypes.c_void_p), ("plan", ctypes.c_void_p),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_int64),
-        ("flags", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("flags", ctypes.c_int32), ("max_slices", ctypes.c_int32),
     ]
 
 
@@ -80,7 +82,7 @@ def load_library() -> ctypes.CDLL:
         lib.gnn_plan_workspace_bytes.argtypes = [vp, i64]
         lib.gnn_plan_workspace_bytes.restype = i64
         lib.gnn_plan_reserve.argtypes = [vp, i64]
-        lib.gnn_plan_prepare.argtypes = [vp, vp, i32, i32, i64, vp]
+        lib.gnn_plan_prepare.argtypes = [vp, vp, i32, i32, i64, i32, vp]
         lib.gnn_status_string.argtypes = [i32]
         lib.gnn_status_string.restype = ctypes.c_char_p
         lib.gnn_calib_copy.argtypes = [vp, vp, i64, vp]
@@ -177,9 +179,10 @@ class Plan:
     def reserve(self, F: int) -> None:
         _call_allocating("gnn_plan_reserve", lambda: load_library().gnn_plan_reserve(self.handle, int(F)))
 
-    def prepare(self, indices: torch.Tensor, op: int, backward: bool, F: int, stream=None) -> None:
+    def prepare(self, indices: torch.Tensor, op: int, backward: bool, F: int, dtype=torch.float32, stream=None) -> None:
+        code = GNN_BF16 if dtype == torch.bfloat16 else GNN_F32
         _call_allocating("gnn_plan_prepare", lambda: load_library().gnn_plan_prepare(
-            self.handle, _ptr(indices), int(op), 1 if backward else 0, int(F), _stream(stream)))
+            self.handle, _ptr(indices), int(op), 1 if backward else 0, int(F), code, _stream(stream)))
 
 
 def gnn_plan_default_params() -> GnnPlanParams:

@@ -5,7 +5,8 @@
 // counter readings calibrate FETCH_SIZE / WRITE_SIZE.
 //
 // usage: agg_profile DIR OP(0|1|2) REPS [noslice] F [F ...]      (fp32 features)
-// "noslice" switches the XCD column slicing off for the widths that follow it.
+// "noslice" switches the XCD column slicing off for the widths that follow it; "flags=N" sets
+// gnn_opts.flags (GNN_FLAG_* bits) for the widths that follow it.
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
@@ -71,9 +72,11 @@ int main(int argc, char **argv) {
     GCHECK(gnn_plan_create(indptr, (const int32_t *)indices, N, ip64, nullptr, nullptr, &pf));
     GCHECK(gnn_plan_create(indptr_t, (const int32_t *)indices_t, N, ip64, nullptr, nullptr, &pb));
 
-    int flags = 0;
+    int flags = 0, max_slices = 0;
     for (int a = 4; a < argc; ++a) {
         if (std::string(argv[a]) == "noslice") { flags = GNN_FLAG_NO_COLUMN_SLICES; continue; }
+        if (std::string(argv[a]).rfind("flags=", 0) == 0) { flags = atoi(argv[a] + 6); continue; }
+        if (std::string(argv[a]).rfind("slices=", 0) == 0) { max_slices = atoi(argv[a] + 7); continue; }
         const long long F = atoll(argv[a]);
         const size_t bytes = (size_t)N * F * 4;
         void *X = nullptr, *Y = nullptr;
@@ -82,6 +85,7 @@ int main(int argc, char **argv) {
         gnn_opts o{};
         o.indptr_is_64 = ip64;
         o.flags = flags;
+        o.max_slices = max_slices;
         o.plan = pf;
         hipEvent_t e0, e1;
         CHECK(hipEventCreate(&e0)); CHECK(hipEventCreate(&e1));
@@ -98,7 +102,7 @@ int main(int argc, char **argv) {
         CHECK(hipEventRecord(e1, nullptr));
         CHECK(hipEventSynchronize(e1));
         float ms_b = 0; CHECK(hipEventElapsedTime(&ms_b, e0, e1));
-        printf("N=%lld E=%lld F=%lld op=%d flags=%d fwd %.4f ms  bwd %.4f ms  (%.1f / %.1f GEF/s)\n", N, E, F, op, flags, ms_f / reps,
+        printf("N=%lld E=%lld F=%lld op=%d flags=%d slices<=%d fwd %.4f ms  bwd %.4f ms  (%.1f / %.1f GEF/s)\n", N, E, F, op, flags, max_slices, ms_f / reps,
                ms_b / reps, E * F / (ms_f / reps) / 1e6, E * F / (ms_b / reps) / 1e6);
         CHECK(hipFree(X)); CHECK(hipFree(Y));
     }

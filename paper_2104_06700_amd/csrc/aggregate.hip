@@ -59,7 +59,7 @@ struct AggArgs {
     int32_t n_bins;
     int32_t log2_slices;  // column slices; workgroup b serves slice b % n_slices (see run_aggregate)
     int32_t slice_cols;   // columns per slice
-    int32_t pad;
+    int32_t store_vec;    // widest store the output rows allow (elements, <= VEC)
     BinDesc bins[GNN_MAX_BINS + 1];
 };
 
@@ -152,6 +152,33 @@ __device__ __forceinline__ void store_f32(float *p, const float (&v)[VEC]) {
     }
 }
 
+// Output strip: one vector store when the output rows allow it, else narrower pieces; a
+// partial last strip (padded gather source) writes only its valid columns.
+template <typename T, int VEC>
+__device__ __forceinline__ void store_strip(T *y, const float (&o)[VEC], int ncols, int store_vec) {
+    if (ncols == VEC && store_vec == VEC) {
+        VecIO<T, VEC>::store(y, o);
+        return;
+    }
+    if constexpr (VEC >= 2) {
+        if (ncols == VEC && store_vec * 2 == VEC) {
+            float lo[VEC / 2], hi[VEC / 2];
+#pragma unroll
+            for (int i = 0; i < VEC / 2; ++i) { lo[i] = o[i]; hi[i] = o[VEC / 2 + i]; }
+            VecIO<T, VEC / 2>::store(y, lo);
+            VecIO<T, VEC / 2>::store(y + VEC / 2, hi);
+            return;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+        if (i < ncols) {
+            float one[1] = {o[i]};
+            VecIO<T, 1>::store(y + i, one);
+        }
+    }
+}
+
 __device__ __forceinline__ int64_t load_ip(const void *indptr, int ip64, int64_t i) {
     return ip64 ? static_cast<const int64_t *>(indptr)[i]
                 : static_cast<int64_t>(static_cast<const int32_t *>(indptr)[i]);
@@ -223,11 +250,14 @@ __global__ void __launch_bounds__(kBlockThreads) aggregate_kernel(const AggArgs 
 
     const T *__restrict__ X = static_cast<const T *>(a.X);
     int col[NPASS];
+    int ncols[NPASS];  // valid columns of the strip (< VEC only for the last strip of a padded matrix)
     bool col_ok[NPASS];
 #pragma unroll
     for (int p = 0; p < NPASS; ++p) {
-        col[p] = col_base + (p * C + c) * VEC;
-        col_ok[p] = (p * C + c) * VEC < Fk;
+        const int lc = (p * C + c) * VEC;
+        col[p] = col_base + lc;
+        col_ok[p] = lc < Fk;
+        ncols[p] = Fk - lc < VEC ? Fk - lc : VEC;
     }
 
     // Neighbour ids (and coefficients) travel one coalesced tile of G edges per group at a
@@ -315,7 +345,7 @@ __global__ void __launch_bounds__(kBlockThreads) aggregate_kernel(const AggArgs 
         float o[VEC];
 #pragma unroll
         for (int i = 0; i < VEC; ++i) o[i] = acc[p][i] * ds;
-        VecIO<T, VEC>::store(y + col[p], o);
+        store_strip<T, VEC>(y + col[p], o, ncols[p], a.store_vec);
     }
 }
 
@@ -325,7 +355,7 @@ __global__ void __launch_bounds__(256) hub_finalize_kernel(const int32_t *__rest
                                                            const int64_t *__restrict__ piece_offsets,
                                                            const float *__restrict__ partial, const void *indptr,
                                                            int ip64, int dst_mode, T *__restrict__ Y, int64_t ldy,
-                                                           int F) {
+                                                           int F, int64_t ldp) {
     const int64_t i = blockIdx.x;
     if (i >= n_hub) return;
     const int64_t row = hub_rows[i];
@@ -333,9 +363,23 @@ __global__ void __launch_bounds__(256) hub_finalize_kernel(const int32_t *__rest
     const float ds = scale_of(dst_mode, load_ip(indptr, ip64, row + 1) - load_ip(indptr, ip64, row));
     for (int colx = threadIdx.x; colx < F; colx += blockDim.x) {
         float sum = 0.0f;
-        for (int64_t p = p0; p < p1; ++p) sum += partial[p * F + colx];
+        for (int64_t p = p0; p < p1; ++p) sum += partial[p * ldp + colx];
         float o[1] = {sum * ds};
         VecIO<T, 1>::store(Y + row * ldy + colx, o);
+    }
+}
+
+// Copies the gathered matrix into rows of whole 128-byte lines (plan-owned buffer), so that
+// 16-byte loads and XCD column slices apply to widths like 100 or 602.  One wavefront per row.
+template <typename E>
+__global__ void __launch_bounds__(256) pad_rows_kernel(const E *__restrict__ src, int64_t ld_src, E *__restrict__ dst,
+                                                       int64_t ld_dst, int64_t N, int F) {
+    const int lane = threadIdx.x & 63;
+    const int64_t n_waves = (int64_t(gridDim.x) * blockDim.x) >> 6;
+    for (int64_t row = (int64_t(blockIdx.x) * blockDim.x + threadIdx.x) >> 6; row < N; row += n_waves) {
+        const E *s = src + row * ld_src;
+        E *d = dst + row * ld_dst;
+        for (int c = lane; c < F; c += 64) d[c] = s[c];
     }
 }
 
@@ -402,20 +446,52 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
     }
     const bool coef = (w != nullptr) || src_mode != kScaleNone;
 
-    // widest load the strides and base addresses allow
     const int esz = o.dtype == GNN_BF16 ? 2 : 4;
-    const int max_vec = 16 / esz;
-    int vec = max_vec;
-    auto aligned = [&](int v) {
-        const uintptr_t bytes = uintptr_t(v) * esz;
-        return F % v == 0 && ldx % v == 0 && ldy % v == 0 && reinterpret_cast<uintptr_t>(gathered) % bytes == 0 &&
-               reinterpret_cast<uintptr_t>(out) % bytes == 0;
-    };
-    while (vec > 1 && !aligned(vec)) vec >>= 1;
     if (reinterpret_cast<uintptr_t>(gathered) % esz || reinterpret_cast<uintptr_t>(out) % esz) return GNN_ERR_INVALID_ARG;
+    const int max_vec = 16 / esz;
+    const int64_t line_elems = 128 / esz;
 
     hipStream_t stream = static_cast<hipStream_t>(o.stream);
     (void)hipGetLastError();  // a stale error of an earlier, failed call must not be blamed on this one
+
+    // Gathered rows that are not whole 128-byte lines (F = 100, 602, or a misaligned base) are
+    // first copied into a plan-owned matrix of padded rows: one streaming pass over N*F elements,
+    // small next to the E*F gather, buys 16-byte loads and the XCD column slices below.
+    int64_t ldg = ldx;  // row stride of the matrix the kernel gathers from
+    bool padded = false;
+    {
+        const bool lines_ok = (ldx % line_elems == 0) && reinterpret_cast<uintptr_t>(gathered) % 128 == 0;
+        const int64_t row_bytes = F * esz;
+        const bool worth_it = !lines_ok && row_bytes >= 192 && N * row_bytes >= (int64_t(32) << 20);
+        if (plan && !(o.flags & GNN_FLAG_NO_PADDED_COPY) && (worth_it || (o.flags & GNN_FLAG_FORCE_PADDED_COPY))) {
+            const int64_t ld_pad = (F + line_elems - 1) / line_elems * line_elems;
+            int rc = gnn_plan_padded(plan, N * ld_pad * esz);
+            if (rc != GNN_OK) return rc;
+            int64_t blocks = (N + 3) / 4;
+            if (blocks > (int64_t(1) << 20)) blocks = int64_t(1) << 20;
+            if (esz == 4)
+                pad_rows_kernel<uint32_t><<<static_cast<unsigned>(blocks), 256, 0, stream>>>(
+                    static_cast<const uint32_t *>(gathered), ldx, static_cast<uint32_t *>(plan->padded), ld_pad, N, int(F));
+            else
+                pad_rows_kernel<uint16_t><<<static_cast<unsigned>(blocks), 256, 0, stream>>>(
+                    static_cast<const uint16_t *>(gathered), ldx, static_cast<uint16_t *>(plan->padded), ld_pad, N, int(F));
+            if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
+            gathered = plan->padded;
+            ldg = ld_pad;
+            padded = true;
+        }
+    }
+
+    // Widest load the gathered rows allow.  Only the padded copy may be read past column F (its
+    // rows end in padding that belongs to the buffer); a caller's matrix needs F % vec == 0.
+    int vec = max_vec;
+    while (vec > 1 && !(ldg % vec == 0 && reinterpret_cast<uintptr_t>(gathered) % (uintptr_t(vec) * esz) == 0 &&
+                        (padded || F % vec == 0)))
+        vec >>= 1;
+    // Widest store the output rows allow (partial strips fall back to single elements).
+    int store_vec = vec;
+    while (store_vec > 1 && !(ldy % store_vec == 0 && reinterpret_cast<uintptr_t>(out) % (uintptr_t(store_vec) * esz) == 0))
+        store_vec >>= 1;
 
     // hub scratch
     float *partial = nullptr;
@@ -442,12 +518,15 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
     int log2_slices = 0;
     int64_t slice_cols_all = 0;
     {
-        const int64_t line_elems = 128 / esz;
-        const bool lines_ok = (ldx % line_elems == 0) && reinterpret_cast<uintptr_t>(gathered) % 128 == 0;
+        const bool lines_ok = (ldg % line_elems == 0) && reinterpret_cast<uintptr_t>(gathered) % 128 == 0;
         const int64_t lines = (F + line_elems - 1) / line_elems;
         if (lines_ok && lines >= 2 && !(o.flags & GNN_FLAG_NO_COLUMN_SLICES)) {
+            // Measured: 4 slices (XCD k and k+4 share one) beat 8 on every width tried -- the index
+            // stream is re-read once per slice and one-line slices cost DRAM burst locality.
+            const int64_t s_max = o.max_slices > 0 ? o.max_slices : 4;
             for (int ls = 3; ls >= 1; --ls) {
                 const int64_t S = int64_t(1) << ls;
+                if (S > s_max) continue;
                 const int64_t per = (lines + S - 1) / S;
                 if (per * (S - 1) < lines && S * per * 5 <= lines * 6) { log2_slices = ls; slice_cols_all = per * line_elems; break; }
             }
@@ -480,7 +559,7 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         a.w = w;
         a.X = static_cast<const char *>(gathered) + f0 * esz;
         a.Y = static_cast<char *>(out) + f0 * esz;
-        a.ldx = ldx;
+        a.ldx = ldg;
         a.ldy = ldy;
         a.F = int32_t(fw);
         a.ip64 = o.indptr_is_64 ? 1 : 0;
@@ -488,6 +567,7 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         a.dst_mode = dst_mode;
         a.log2_slices = log2_s;
         a.slice_cols = int32_t(slice_cols);
+        a.store_vec = store_vec;
         int64_t next_block = 0;
         int nb = 0;
         auto add_bin = [&](int kind, int64_t begin, int64_t n_items, int log2_sr) {
@@ -507,7 +587,7 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
             a.chunks = plan->chunks;
             // The scratch rows are F wide for every slab; point at this slab's columns.
             a.partial = partial ? partial + f0 : nullptr;
-            a.ldp = F;
+            a.ldp = gnn_partial_ld(F);
             const int last = plan->n_bins - 1;
             // heaviest work first: hub pieces, then bins from long rows to short rows
             if (has_hub) add_bin(kKindHubPieces, 0, plan->n_chunks, max_log2_sr);
@@ -551,11 +631,11 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         if (o.dtype == GNN_F32)
             hub_finalize_kernel<float><<<grid, 256, 0, stream>>>(plan->row_perm + hub_begin, plan->n_hub_rows, plan->hub_chunk_offsets,
                                                                  partial, indptr, o.indptr_is_64 ? 1 : 0, dst_mode,
-                                                                 static_cast<float *>(out), ldy, int(F));
+                                                                 static_cast<float *>(out), ldy, int(F), gnn_partial_ld(F));
         else
             hub_finalize_kernel<bf16_t><<<grid, 256, 0, stream>>>(plan->row_perm + hub_begin, plan->n_hub_rows, plan->hub_chunk_offsets,
                                                                   partial, indptr, o.indptr_is_64 ? 1 : 0, dst_mode,
-                                                                  static_cast<bf16_t *>(out), ldy, int(F));
+                                                                  static_cast<bf16_t *>(out), ldy, int(F), gnn_partial_ld(F));
         if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
     }
     return GNN_OK;

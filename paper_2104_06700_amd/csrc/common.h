@@ -37,7 +37,17 @@ struct gnn_plan {
     // per-edge factor of the gathered vertex, streamed by the hot kernels:
     // [0] 1/max(col_counts[indices[e]],1)   [1] 1/sqrt(max(col_counts[indices[e]],1)); built on first use
     float *edge_scale[2] = {nullptr, nullptr};
+    // copy of the gathered matrix with rows padded to whole 128-byte lines (grown on first use)
+    void *padded = nullptr;
+    int64_t padded_bytes = 0;
 };
+
+// Row stride (floats) of the hub partial-sum scratch for width F: whole 32-byte groups, so that
+// vector stores of a last, partial strip stay inside the row.
+static inline int64_t gnn_partial_ld(int64_t F) { return (F + 7) / 8 * 8; }
+
+// Makes plan->padded at least `bytes` large (allocation on growth).
+int gnn_plan_padded(gnn_plan *plan, int64_t bytes);
 
 // mode: 1 = reciprocal, 2 = reciprocal square root.  Builds the array on first use (allocation).
 int gnn_plan_edge_scale(gnn_plan *plan, const int32_t *indices, int mode, hipStream_t stream, const float **out);

@@ -178,11 +178,31 @@ int gnn_plan_edge_scale(gnn_plan *plan, const int32_t *indices, int mode, hipStr
     return GNN_OK;
 }
 
+int gnn_plan_padded(gnn_plan *plan, int64_t bytes) {
+    if (!plan || bytes < 0) return GNN_ERR_INVALID_ARG;
+    if (bytes <= plan->padded_bytes) return GNN_OK;
+    (void)hipGetLastError();
+    (void)hipFree(plan->padded);
+    plan->padded = nullptr;
+    plan->padded_bytes = 0;
+    if (hipMalloc(&plan->padded, bytes) != hipSuccess) return GNN_ERR_ALLOC;
+    // padding columns are never written again; clear them once so that they hold finite values
+    if (hipMemset(plan->padded, 0, bytes) != hipSuccess) return GNN_ERR_LAUNCH;
+    plan->padded_bytes = bytes;
+    return GNN_OK;
+}
+
 extern "C" GNN_API int gnn_plan_prepare(gnn_plan *plan, const int32_t *indices, int op, int backward, int64_t F,
-                                        void *stream) {
+                                        int dtype, void *stream) {
     if (!plan || F < 0 || op < GNN_SUM || op > GNN_GCN_SYM) return GNN_ERR_INVALID_ARG;
+    if (dtype != GNN_F32 && dtype != GNN_BF16) return GNN_ERR_INVALID_ARG;
     int rc = gnn_plan_reserve(plan, F);
     if (rc != GNN_OK) return rc;
+    const int64_t esz = dtype == GNN_BF16 ? 2 : 4, line_elems = 128 / esz;
+    if (F % line_elems != 0) {  // dense rows of this width cannot be whole lines: the padded copy will be used
+        rc = gnn_plan_padded(plan, plan->n_rows * ((F + line_elems - 1) / line_elems * line_elems) * esz);
+        if (rc != GNN_OK) return rc;
+    }
     const float *unused = nullptr;
     if (op == GNN_MEAN && backward) rc = gnn_plan_edge_scale(plan, indices, 1, static_cast<hipStream_t>(stream), &unused);
     if (op == GNN_GCN_SYM) rc = gnn_plan_edge_scale(plan, indices, 2, static_cast<hipStream_t>(stream), &unused);
@@ -193,6 +213,7 @@ extern "C" GNN_API void gnn_plan_destroy(gnn_plan *plan) {
     if (!plan) return;
     (void)hipFree(plan->edge_scale[0]);
     (void)hipFree(plan->edge_scale[1]);
+    (void)hipFree(plan->padded);
     (void)hipFree(plan->row_perm);
     (void)hipFree(plan->col_counts);
     (void)hipFree(plan->chunks);
@@ -320,7 +341,7 @@ extern "C" GNN_API int gnn_plan_export(const gnn_plan *plan, int64_t *bin_offset
 
 extern "C" GNN_API int64_t gnn_plan_workspace_bytes(const gnn_plan *plan, int64_t F) {
     if (!plan || F < 0) return 0;
-    return plan->n_chunks * F * int64_t(sizeof(float));
+    return plan->n_chunks * gnn_partial_ld(F) * int64_t(sizeof(float));
 }
 
 extern "C" GNN_API int gnn_plan_reserve(gnn_plan *plan, int64_t F) {

@@ -170,6 +170,43 @@ def test_column_slices_over_xcds_on_and_off(f, dtype):
         outs.append(Y)
 
 
+@pytest.mark.parametrize("f,dtype", [(100, torch.float32), (602, torch.float32), (30, torch.float32), (7, torch.float32),
+                                     (129, torch.float32), (2052, torch.float32), (100, torch.bfloat16),
+                                     (602, torch.bfloat16), (9, torch.bfloat16), (1000, torch.bfloat16)])
+@pytest.mark.parametrize("hubs", [False, True])
+def test_padded_copy_route(f, dtype, hubs):
+    """Widths whose rows are not whole 128-byte lines are gathered from a plan-owned padded
+    copy (forced here; automatic for large matrices).  Loads run past column F into the
+    padding, stores must not: the output is poisoned and checked column by column."""
+    el = synth.make_graph("rmat_sparse_stack", scale=0.003, seed=81)
+    params = gnn.make_plan_params([2, 16], 24) if hubs else None
+    dg = device_graph(el, plan_params=params)
+    indptr, indices, indptr_t, indices_t, _ = host_csr(el)
+    X = synth.normal_features(el.n, f, 10, dtype=dtype)
+    bf16 = dtype == torch.bfloat16
+    for op, oop in ((gnn.GNN_MEAN, oracle.OP_MEAN), (gnn.GNN_GCN_SYM, oracle.OP_GCN_SYM)):
+        Yo, S = oracle.aggregate_fwd(indptr, indices, X.float().numpy(), op=oop, dout=np.diff(indptr_t), nthreads=8,
+                                     want_scale=True)
+        dXo, St = oracle.aggregate_bwd(indptr_t, indices_t, X.float().numpy(), op=oop, din=np.diff(indptr), nthreads=8,
+                                       want_scale=True)
+        # output with a wider stride: the columns between F and ld must stay untouched
+        ld = f + 5
+        out = torch.full((el.n, ld), float("nan"), dtype=dtype, device=DEV)
+        Y = out[:, :f]
+        Xd = X.to(DEV)
+        gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, None, Xd, Y, el.n, f, op, plan=dg.plan_fwd,
+                              flags=gnn.GNN_FLAG_FORCE_PADDED_COPY, ldy=ld)
+        torch.cuda.synchronize()
+        assert_close(Y, Yo, S, bf16, f"padded fwd F={f} op={op}")
+        assert torch.isnan(out[:, f:]).all()
+        out.fill_(float("nan"))
+        gnn.gnn_aggregate_bwd(dg.indptr_t, dg.indices_t, None, Xd, Y, el.n, f, op, plan=dg.plan_bwd,
+                              flags=gnn.GNN_FLAG_FORCE_PADDED_COPY, ldy=ld)
+        torch.cuda.synchronize()
+        assert_close(Y, dXo, St, bf16, f"padded bwd F={f} op={op}")
+        assert torch.isnan(out[:, f:]).all()
+
+
 # -------------------------------------------------------------- integer parts
 @pytest.mark.parametrize("name,scale,ip64", [("er_tiny", 1.0, False), ("rmat_sparse_stack", 0.02, False),
                                              ("rmat_dense_wide", 0.01, True), ("rmat_capacity", 0.0005, True)])
