@@ -42,8 +42,12 @@ typedef enum gnn_status {
  *   MEAN     SUM divided by the row length din[v] (stored edges; empty row -> 0)
  *   GCN_SYM  c_e = 1/sqrt(max(dout[u],1) * max(din[v],1)) when edge_w == NULL;
  *            with edge_w the weights are taken as given (same as SUM).
- * (The paper's own runs use sum plus a degree normalisation, Section 6.1.) */
-typedef enum gnn_op { GNN_SUM = 0, GNN_MEAN = 1, GNN_GCN_SYM = 2 } gnn_op;
+ *   SAGE_GCN the aggregator of the paper's own runs (Section 6.1): the sum, plus the
+ *            vertex's own vector, divided by din[v] + 1:
+ *            Y[v] = (sum_e c_e X[u_e] + X[v]) / (din[v] + 1); the backward call computes the
+ *            adjoint dX[u] = sum_{e'} c_e' dY[v_e'] / (din[v_e'] + 1) + dY[u] / (din[u] + 1)
+ *            and needs a plan (for din). */
+typedef enum gnn_op { GNN_SUM = 0, GNN_MEAN = 1, GNN_GCN_SYM = 2, GNN_SAGE_GCN = 3 } gnn_op;
 
 typedef enum gnn_dtype { GNN_F32 = 0, GNN_BF16 = 1 } gnn_dtype;
 
@@ -185,13 +189,10 @@ GNN_API int gnn_plan_prepare(gnn_plan *plan, const int32_t *indices, int op, int
 /* ---------------------------------------------------------------- utilities */
 GNN_API const char *gnn_status_string(int status);
 
-/* Bandwidth calibration kernels used by the bench to print measured ceilings
- * next to each result: a streaming copy of n_bytes (multiple of 16), and a
- * gather of n_rows_out rows of row_bytes (multiple of 16) from a table of
- * n_rows_table rows at pseudo-random row ids, written to a stream. */
+/* Streaming copy of n_bytes (multiple of 16; both pointers 16-byte aligned): the kernel of
+ * known traffic that the bench prints as a measured ceiling and that the profiler runs use to
+ * calibrate the FETCH_SIZE / WRITE_SIZE counters. */
 GNN_API int gnn_calib_copy(const void *src, void *dst, int64_t n_bytes, void *stream);
-GNN_API int gnn_calib_gather(const void *table, int64_t n_rows_table, int64_t row_bytes,
-                     void *out, int64_t n_rows_out, uint64_t seed, void *stream);
 
 #ifdef __cplusplus
 }

@@ -4,11 +4,11 @@ Only tests, the smoke check and the bench's cpu_baseline leg may import this
 package.  It never imports the HIP package and shares nothing with it.
 """
 from .cpu_oracle import (
-    OP_SUM, OP_MEAN, OP_GCN_SYM,
+    OP_SUM, OP_MEAN, OP_GCN_SYM, OP_SAGE_GCN,
     build_oracle, compile_c, use_library, aggregate_fwd, aggregate_bwd, csr_indptr, transpose, plan, max_threads,
 )
 
 __all__ = [
-    "OP_SUM", "OP_MEAN", "OP_GCN_SYM", "build_oracle", "compile_c", "use_library", "aggregate_fwd", "aggregate_bwd",
+    "OP_SUM", "OP_MEAN", "OP_GCN_SYM", "OP_SAGE_GCN", "build_oracle", "compile_c", "use_library", "aggregate_fwd", "aggregate_bwd",
     "csr_indptr", "transpose", "plan", "max_threads",
 ]

@@ -13,7 +13,7 @@ from typing import Optional
 
 import numpy as np
 
-OP_SUM, OP_MEAN, OP_GCN_SYM = 0, 1, 2
+OP_SUM, OP_MEAN, OP_GCN_SYM, OP_SAGE_GCN = 0, 1, 2, 3
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "oracle.c")

@@ -39,7 +39,7 @@
 #include <omp.h>
 #endif
 
-enum { OP_SUM = 0, OP_MEAN = 1, OP_GCN_SYM = 2 };
+enum { OP_SUM = 0, OP_MEAN = 1, OP_GCN_SYM = 2, OP_SAGE_GCN = 3 };
 
 static int64_t at_least_one(int64_t d) { return d > 0 ? d : 1; }
 
@@ -62,6 +62,10 @@ int oracle_max_threads(void) {
  * GCN_SYM without explicit weights: c_e = 1/sqrt(max(dout[u],1)*max(din[v],1))
  *       with dout[u] the number of edges leaving u.  With explicit weights the
  *       weights are used as given (they already carry the normalisation).
+ * SAGE_GCN: the aggregator of the paper's own runs (Section 6.1): the row sum,
+ *       plus the vertex's own feature vector, divided by din[v] + 1 (the number
+ *       of vectors added up; the paper says "normalizes with respect to the
+ *       in-degree", and its Table 8 counts 51.5 = 50.5 + 1 vectors per vertex).
  *
  * rows == NULL: compute all N rows, Y is [N, F].  Otherwise compute only
  * rows[0..nrows), Y is [nrows, F] in that order (rows are independent in the
@@ -73,7 +77,7 @@ int oracle_aggregate_fwd(const int64_t *indptr, const int32_t *indices, const fl
                          const float *X, int64_t ldx, double *Y, double *S,
                          int64_t N, int64_t F, int op, const int64_t *dout,
                          const int64_t *rows, int64_t nrows, int nthreads) {
-    if (op < 0 || op > 2) return 1;
+    if (op < 0 || op > 3) return 1;
     if (op == OP_GCN_SYM && !w && !dout) return 2;
     int64_t count = rows ? nrows : N;
     if (nthreads < 1) nthreads = 1;
@@ -102,6 +106,13 @@ int oracle_aggregate_fwd(const int64_t *indptr, const int32_t *indices, const fl
             for (int64_t j = 0; j < F; ++j) acc[j] /= (double)din;
             if (mag) for (int64_t j = 0; j < F; ++j) mag[j] /= (double)din;
         }
+        if (op == OP_SAGE_GCN) {
+            const float *self = X + v * ldx;
+            for (int64_t j = 0; j < F; ++j) {
+                acc[j] = (acc[j] + (double)self[j]) / (double)(din + 1);
+                if (mag) mag[j] = (mag[j] + fabs((double)self[j])) / (double)(din + 1);
+            }
+        }
     }
     return 0;
 }
@@ -116,15 +127,17 @@ int oracle_aggregate_fwd(const int64_t *indptr, const int32_t *indices, const fl
  * SUM: c = wt or 1.  MEAN: additionally divided by din[v] of the GATHERED
  * vertex v (the forward pass divided output row v by din[v]).  GCN_SYM without
  * weights: the same 1/sqrt(max(dout[u],1)*max(din[v],1)) as forward, where
- * dout[u] is this row's length.  din is the forward in-degree vector, needed
- * for MEAN and for GCN_SYM without weights.
+ * dout[u] is this row's length.  SAGE_GCN: every edge term is divided by
+ * din[v] + 1 of the gathered vertex, and the row's own gradient enters as
+ * dY[u] / (din[u] + 1) (the transpose of adding the self vector).  din is the
+ * forward in-degree vector, needed for MEAN, SAGE_GCN and weight-less GCN_SYM.
  */
 int oracle_aggregate_bwd(const int64_t *indptr_t, const int32_t *indices_t, const float *wt,
                          const float *dY, int64_t ldy, double *dX, double *S,
                          int64_t N, int64_t F, int op, const int64_t *din,
                          const int64_t *rows, int64_t nrows, int nthreads) {
-    if (op < 0 || op > 2) return 1;
-    if (op == OP_MEAN && !din) return 2;
+    if (op < 0 || op > 3) return 1;
+    if ((op == OP_MEAN || op == OP_SAGE_GCN) && !din) return 2;
     if (op == OP_GCN_SYM && !wt && !din) return 2;
     int64_t count = rows ? nrows : N;
     if (nthreads < 1) nthreads = 1;
@@ -143,9 +156,18 @@ int oracle_aggregate_bwd(const int64_t *indptr_t, const int32_t *indices_t, cons
             else if (op == OP_GCN_SYM)
                 c = 1.0 / sqrt((double)at_least_one(dout) * (double)at_least_one(din[v]));
             if (op == OP_MEAN) c /= (double)din[v]; /* v has at least this edge, so din[v] >= 1 */
+            if (op == OP_SAGE_GCN) c /= (double)(din[v] + 1);
             const float *g = dY + v * ldy;
             for (int64_t j = 0; j < F; ++j) {
                 double t = c * (double)g[j];
+                acc[j] += t;
+                if (mag) mag[j] += fabs(t);
+            }
+        }
+        if (op == OP_SAGE_GCN) {
+            const float *self = dY + u * ldy;
+            for (int64_t j = 0; j < F; ++j) {
+                double t = (double)self[j] / (double)(din[u] + 1);
                 acc[j] += t;
                 if (mag) mag[j] += fabs(t);
             }

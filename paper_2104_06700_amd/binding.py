@@ -16,7 +16,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libgnnagg.so")
 
 GNN_OK, GNN_ERR_INVALID_ARG, GNN_ERR_UNSUPPORTED, GNN_ERR_ALLOC, GNN_ERR_LAUNCH, GNN_ERR_INVALID_GRAPH = range(6)
-GNN_SUM, GNN_MEAN, GNN_GCN_SYM = 0, 1, 2
+GNN_SUM, GNN_MEAN, GNN_GCN_SYM, GNN_SAGE_GCN = 0, 1, 2, 3
 GNN_F32, GNN_BF16 = 0, 1
 GNN_MAX_THRESHOLDS = 15
 GNN_FLAG_NO_COLUMN_SLICES = 1
@@ -27,7 +27,7 @@ EXPORTED_SYMBOLS = (
     "gnn_aggregate_fwd", "gnn_aggregate_bwd", "gnn_csr_from_sorted_coo", "gnn_transpose_csr",
     "gnn_validate_csr", "gnn_plan_default_params", "gnn_plan_create", "gnn_plan_destroy",
     "gnn_plan_sizes", "gnn_plan_export", "gnn_plan_workspace_bytes", "gnn_plan_reserve", "gnn_plan_prepare",
-    "gnn_status_string", "gnn_calib_copy", "gnn_calib_gather",
+    "gnn_status_string", "gnn_calib_copy",
 )
 
 
@@ -86,7 +86,6 @@ def load_library() -> ctypes.CDLL:
         lib.gnn_status_string.argtypes = [i32]
         lib.gnn_status_string.restype = ctypes.c_char_p
         lib.gnn_calib_copy.argtypes = [vp, vp, i64, vp]
-        lib.gnn_calib_gather.argtypes = [vp, i64, i64, vp, i64, ctypes.c_uint64, vp]
         _lib = lib
     return _lib
 
@@ -268,9 +267,3 @@ def gnn_validate_csr(indptr, indices, N, E, stream=None) -> int:
 def gnn_calib_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
     st = load_library().gnn_calib_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), _stream(stream))
     _check("gnn_calib_copy", st)
-
-
-def gnn_calib_gather(table: torch.Tensor, out: torch.Tensor, seed: int = 1, stream=None) -> None:
-    row_bytes = table.shape[1] * table.element_size()
-    st = load_library().gnn_calib_gather(_ptr(table), table.shape[0], row_bytes, _ptr(out), out.shape[0], seed, _stream(stream))
-    _check("gnn_calib_gather", st)

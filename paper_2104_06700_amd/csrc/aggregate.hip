@@ -27,7 +27,8 @@ namespace {
 constexpr int kBlockThreads = 256;
 constexpr int kWavesPerBlock = kBlockThreads / 64;
 
-enum ScaleMode : int { kScaleNone = 0, kScaleInv = 1, kScaleRsqrt = 2 };
+enum ScaleMode : int { kScaleNone = 0, kScaleInv = 1, kScaleRsqrt = 2, kScaleInvPlus1 = 3 };
+enum SelfMode : int { kSelfNone = 0, kSelfPlain = 1, kSelfInvPlus1 = 2 };  // own row added to the sum
 enum BinKind : int { kKindRows = 0, kKindHubPieces = 1 };
 
 struct BinDesc {
@@ -52,7 +53,8 @@ struct AggArgs {
     const int32_t *row_perm;    // nullptr: identity
     const float *edge_scale;    // per-edge factor 1/deg or 1/sqrt(deg) of the gathered vertex, or nullptr
     int32_t dst_mode;
-    int32_t pad0;
+    int32_t self_mode;          // SelfMode: add the row's own gathered vector (GraphSAGE-GCN aggregator)
+    const int32_t *col_counts;  // per-vertex column counts of the plan (self term of the backward pass)
     const int64_t *chunks;      // hub pieces (row, e_begin, e_end)
     float *partial;             // [n_chunks, ldp] fp32
     int64_t ldp;
@@ -185,6 +187,7 @@ __device__ __forceinline__ int64_t load_ip(const void *indptr, int ip64, int64_t
 }
 
 __device__ __forceinline__ float scale_of(int mode, int64_t deg) {
+    if (mode == kScaleInvPlus1) return 1.0f / static_cast<float>(deg + 1);
     float d = static_cast<float>(deg > 1 ? deg : 1);
     if (mode == kScaleInv) return 1.0f / d;
     if (mode == kScaleRsqrt) return 1.0f / sqrtf(d);
@@ -338,10 +341,17 @@ __global__ void __launch_bounds__(kBlockThreads) aggregate_kernel(const AggArgs 
         return;
     }
     const float ds = scale_of(a.dst_mode, row_len);
+    const float self_cf = a.self_mode == kSelfInvPlus1 ? scale_of(kScaleInvPlus1, a.col_counts[row]) : 1.0f;
     T *__restrict__ y = static_cast<T *>(a.Y) + row * a.ldy;
 #pragma unroll
     for (int p = 0; p < NPASS; ++p) {
         if (!col_ok[p]) continue;
+        if (a.self_mode != kSelfNone) {  // Section 6.1: the vertex's own vector joins the sum
+            float xs[VEC];
+            VecIO<T, VEC>::load(X + row * a.ldx + col[p], xs);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[p][i] = fmaf(self_cf, xs[i], acc[p][i]);
+        }
         float o[VEC];
 #pragma unroll
         for (int i = 0; i < VEC; ++i) o[i] = acc[p][i] * ds;
@@ -355,7 +365,9 @@ __global__ void __launch_bounds__(256) hub_finalize_kernel(const int32_t *__rest
                                                            const int64_t *__restrict__ piece_offsets,
                                                            const float *__restrict__ partial, const void *indptr,
                                                            int ip64, int dst_mode, T *__restrict__ Y, int64_t ldy,
-                                                           int F, int64_t ldp) {
+                                                           int F, int64_t ldp, int self_mode,
+                                                           const T *__restrict__ G, int64_t ldg,
+                                                           const int32_t *__restrict__ col_counts) {
     const int64_t i = blockIdx.x;
     if (i >= n_hub) return;
     const int64_t row = hub_rows[i];
@@ -364,23 +376,41 @@ __global__ void __launch_bounds__(256) hub_finalize_kernel(const int32_t *__rest
     for (int colx = threadIdx.x; colx < F; colx += blockDim.x) {
         float sum = 0.0f;
         for (int64_t p = p0; p < p1; ++p) sum += partial[p * ldp + colx];
+        if (self_mode != kSelfNone) {
+            float xs[1];
+            VecIO<T, 1>::load(G + row * ldg + colx, xs);
+            sum = fmaf(self_mode == kSelfInvPlus1 ? scale_of(kScaleInvPlus1, col_counts[row]) : 1.0f, xs[0], sum);
+        }
         float o[1] = {sum * ds};
         VecIO<T, 1>::store(Y + row * ldy + colx, o);
     }
 }
 
 // Copies the gathered matrix into rows of whole 128-byte lines (plan-owned buffer), so that
-// 16-byte loads and XCD column slices apply to widths like 100 or 602.  One wavefront per row.
-template <typename E>
-__global__ void __launch_bounds__(256) pad_rows_kernel(const E *__restrict__ src, int64_t ld_src, E *__restrict__ dst,
-                                                       int64_t ld_dst, int64_t N, int F) {
-    const int lane = threadIdx.x & 63;
-    const int64_t n_waves = (int64_t(gridDim.x) * blockDim.x) >> 6;
-    for (int64_t row = (int64_t(blockIdx.x) * blockDim.x + threadIdx.x) >> 6; row < N; row += n_waves) {
-        const E *s = src + row * ld_src;
-        E *d = dst + row * ld_dst;
-        for (int c = lane; c < F; c += 64) d[c] = s[c];
+// 16-byte loads and XCD column slices apply to widths like 100 or 602.  One thread per chunk of
+// sizeof(V) bytes; V is the widest type the source rows allow.
+template <typename V>
+__global__ void __launch_bounds__(256) pad_rows_kernel(const V *__restrict__ src, int64_t ld_src, V *__restrict__ dst,
+                                                       int64_t ld_dst, int64_t N, int chunks_per_row) {
+    const int64_t total = N * chunks_per_row;
+    const int64_t stride = int64_t(gridDim.x) * blockDim.x;
+    for (int64_t g = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; g < total; g += stride) {
+        const int64_t row = g / chunks_per_row;
+        const int c = int(g - row * chunks_per_row);
+        dst[row * ld_dst + c] = src[row * ld_src + c];
     }
+}
+
+template <typename V>
+hipError_t launch_pad(const void *src, int64_t ld_src_bytes, void *dst, int64_t ld_dst_bytes, int64_t N,
+                      int64_t row_bytes, hipStream_t stream) {
+    const int cpr = int(row_bytes / sizeof(V));
+    int64_t blocks = (N * cpr + 255) / 256;
+    if (blocks > (int64_t(1) << 17)) blocks = int64_t(1) << 17;
+    pad_rows_kernel<V><<<static_cast<unsigned>(blocks), 256, 0, stream>>>(
+        static_cast<const V *>(src), ld_src_bytes / int64_t(sizeof(V)), static_cast<V *>(dst),
+        ld_dst_bytes / int64_t(sizeof(V)), N, cpr);
+    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------- host side
@@ -417,7 +447,7 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
     gnn_opts o{};
     if (opts_in) o = *opts_in;
     if (N < 0 || F < 0) return GNN_ERR_INVALID_ARG;
-    if (op != GNN_SUM && op != GNN_MEAN && op != GNN_GCN_SYM) return GNN_ERR_INVALID_ARG;
+    if (op != GNN_SUM && op != GNN_MEAN && op != GNN_GCN_SYM && op != GNN_SAGE_GCN) return GNN_ERR_INVALID_ARG;
     if (o.dtype != GNN_F32 && o.dtype != GNN_BF16) return GNN_ERR_INVALID_ARG;
     if (N == 0 || F == 0) return GNN_OK;
     if (!indptr || !gathered || !out) return GNN_ERR_INVALID_ARG;
@@ -436,7 +466,12 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         src_mode = kScaleRsqrt;
         dst_mode = kScaleRsqrt;
     }
-    if (src_mode != kScaleNone && !plan) return GNN_ERR_UNSUPPORTED;  // needs the column counts a plan holds
+    int self_mode = kSelfNone;
+    if (op == GNN_SAGE_GCN) {  // (sum + own vector) / (din + 1) and its adjoint
+        if (backward) { src_mode = kScaleInvPlus1; self_mode = kSelfInvPlus1; }
+        else { dst_mode = kScaleInvPlus1; self_mode = kSelfPlain; }
+    }
+    if ((src_mode != kScaleNone || self_mode == kSelfInvPlus1) && !plan) return GNN_ERR_UNSUPPORTED;  // needs the column counts a plan holds
     const float *edge_scale = nullptr;
     if (src_mode != kScaleNone && plan->n_edges > 0) {
         // streamed per-edge factors (built once per plan and mode) instead of a random 4-byte
@@ -467,15 +502,19 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
             const int64_t ld_pad = (F + line_elems - 1) / line_elems * line_elems;
             int rc = gnn_plan_padded(plan, N * ld_pad * esz);
             if (rc != GNN_OK) return rc;
-            int64_t blocks = (N + 3) / 4;
-            if (blocks > (int64_t(1) << 20)) blocks = int64_t(1) << 20;
-            if (esz == 4)
-                pad_rows_kernel<uint32_t><<<static_cast<unsigned>(blocks), 256, 0, stream>>>(
-                    static_cast<const uint32_t *>(gathered), ldx, static_cast<uint32_t *>(plan->padded), ld_pad, N, int(F));
+            // widest chunk the source rows allow
+            const int64_t src_ld_bytes = ldx * esz, dst_ld_bytes = ld_pad * esz;
+            const uintptr_t src_addr = reinterpret_cast<uintptr_t>(gathered);
+            hipError_t err;
+            if (row_bytes % 16 == 0 && src_ld_bytes % 16 == 0 && src_addr % 16 == 0)
+                err = launch_pad<uint4>(gathered, src_ld_bytes, plan->padded, dst_ld_bytes, N, row_bytes, stream);
+            else if (row_bytes % 8 == 0 && src_ld_bytes % 8 == 0 && src_addr % 8 == 0)
+                err = launch_pad<uint2>(gathered, src_ld_bytes, plan->padded, dst_ld_bytes, N, row_bytes, stream);
+            else if (row_bytes % 4 == 0 && src_ld_bytes % 4 == 0 && src_addr % 4 == 0)
+                err = launch_pad<uint32_t>(gathered, src_ld_bytes, plan->padded, dst_ld_bytes, N, row_bytes, stream);
             else
-                pad_rows_kernel<uint16_t><<<static_cast<unsigned>(blocks), 256, 0, stream>>>(
-                    static_cast<const uint16_t *>(gathered), ldx, static_cast<uint16_t *>(plan->padded), ld_pad, N, int(F));
-            if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
+                err = launch_pad<uint16_t>(gathered, src_ld_bytes, plan->padded, dst_ld_bytes, N, row_bytes, stream);
+            if (err != hipSuccess) return GNN_ERR_LAUNCH;
             gathered = plan->padded;
             ldg = ld_pad;
             padded = true;
@@ -565,6 +604,8 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         a.ip64 = o.indptr_is_64 ? 1 : 0;
         a.edge_scale = edge_scale;
         a.dst_mode = dst_mode;
+        a.self_mode = self_mode;
+        a.col_counts = plan ? plan->col_counts : nullptr;
         a.log2_slices = log2_s;
         a.slice_cols = int32_t(slice_cols);
         a.store_vec = store_vec;
@@ -631,11 +672,13 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         if (o.dtype == GNN_F32)
             hub_finalize_kernel<float><<<grid, 256, 0, stream>>>(plan->row_perm + hub_begin, plan->n_hub_rows, plan->hub_chunk_offsets,
                                                                  partial, indptr, o.indptr_is_64 ? 1 : 0, dst_mode,
-                                                                 static_cast<float *>(out), ldy, int(F), gnn_partial_ld(F));
+                                                                 static_cast<float *>(out), ldy, int(F), gnn_partial_ld(F), self_mode,
+                                                                 static_cast<const float *>(gathered), ldg, plan->col_counts);
         else
             hub_finalize_kernel<bf16_t><<<grid, 256, 0, stream>>>(plan->row_perm + hub_begin, plan->n_hub_rows, plan->hub_chunk_offsets,
                                                                   partial, indptr, o.indptr_is_64 ? 1 : 0, dst_mode,
-                                                                  static_cast<bf16_t *>(out), ldy, int(F), gnn_partial_ld(F));
+                                                                  static_cast<bf16_t *>(out), ldy, int(F), gnn_partial_ld(F), self_mode,
+                                                                  static_cast<const bf16_t *>(gathered), ldg, plan->col_counts);
         if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
     }
     return GNN_OK;

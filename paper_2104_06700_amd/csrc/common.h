@@ -35,8 +35,8 @@ struct gnn_plan {
     int64_t scratch_bytes = 0;
     const void *indptr_seen = nullptr;  // the indptr the plan was built from (sanity check only)
     // per-edge factor of the gathered vertex, streamed by the hot kernels:
-    // [0] 1/max(col_counts[indices[e]],1)   [1] 1/sqrt(max(col_counts[indices[e]],1)); built on first use
-    float *edge_scale[2] = {nullptr, nullptr};
+    // [0] 1/max(c,1)   [1] 1/sqrt(max(c,1))   [2] 1/(c+1), c = col_counts[indices[e]]; built on first use
+    float *edge_scale[3] = {nullptr, nullptr, nullptr};
     // copy of the gathered matrix with rows padded to whole 128-byte lines (grown on first use)
     void *padded = nullptr;
     int64_t padded_bytes = 0;
@@ -49,7 +49,8 @@ static inline int64_t gnn_partial_ld(int64_t F) { return (F + 7) / 8 * 8; }
 // Makes plan->padded at least `bytes` large (allocation on growth).
 int gnn_plan_padded(gnn_plan *plan, int64_t bytes);
 
-// mode: 1 = reciprocal, 2 = reciprocal square root.  Builds the array on first use (allocation).
+// mode: 1 = reciprocal, 2 = reciprocal square root, 3 = reciprocal of (count + 1).
+// Builds the array on first use (allocation).
 int gnn_plan_edge_scale(gnn_plan *plan, const int32_t *indices, int mode, hipStream_t stream, const float **out);
 
 static inline int gnn_ilog2_ceil(int64_t x) {

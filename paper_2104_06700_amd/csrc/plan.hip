@@ -142,7 +142,7 @@ __global__ void __launch_bounds__(256) edge_scale_kernel(const int32_t *__restri
     for (int64_t e = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; e < E; e += stride) {
         int c = col_counts[indices[e]];
         float d = static_cast<float>(c > 1 ? c : 1);
-        out[e] = mode == 1 ? 1.0f / d : 1.0f / sqrtf(d);
+        out[e] = mode == 3 ? 1.0f / static_cast<float>(c + 1) : (mode == 1 ? 1.0f / d : 1.0f / sqrtf(d));
     }
 }
 
@@ -165,7 +165,7 @@ extern "C" GNN_API void gnn_plan_default_params(gnn_plan_params *p) {
 }
 
 int gnn_plan_edge_scale(gnn_plan *plan, const int32_t *indices, int mode, hipStream_t stream, const float **out) {
-    if (!plan || !out || (mode != 1 && mode != 2)) return GNN_ERR_INVALID_ARG;
+    if (!plan || !out || mode < 1 || mode > 3) return GNN_ERR_INVALID_ARG;
     float *&arr = plan->edge_scale[mode - 1];
     if (!arr && plan->n_edges > 0) {
         if (!indices) return GNN_ERR_INVALID_ARG;
@@ -194,7 +194,7 @@ int gnn_plan_padded(gnn_plan *plan, int64_t bytes) {
 
 extern "C" GNN_API int gnn_plan_prepare(gnn_plan *plan, const int32_t *indices, int op, int backward, int64_t F,
                                         int dtype, void *stream) {
-    if (!plan || F < 0 || op < GNN_SUM || op > GNN_GCN_SYM) return GNN_ERR_INVALID_ARG;
+    if (!plan || F < 0 || op < GNN_SUM || op > GNN_SAGE_GCN) return GNN_ERR_INVALID_ARG;
     if (dtype != GNN_F32 && dtype != GNN_BF16) return GNN_ERR_INVALID_ARG;
     int rc = gnn_plan_reserve(plan, F);
     if (rc != GNN_OK) return rc;
@@ -206,6 +206,7 @@ extern "C" GNN_API int gnn_plan_prepare(gnn_plan *plan, const int32_t *indices, 
     const float *unused = nullptr;
     if (op == GNN_MEAN && backward) rc = gnn_plan_edge_scale(plan, indices, 1, static_cast<hipStream_t>(stream), &unused);
     if (op == GNN_GCN_SYM) rc = gnn_plan_edge_scale(plan, indices, 2, static_cast<hipStream_t>(stream), &unused);
+    if (op == GNN_SAGE_GCN && backward) rc = gnn_plan_edge_scale(plan, indices, 3, static_cast<hipStream_t>(stream), &unused);
     return rc;
 }
 
@@ -213,6 +214,7 @@ extern "C" GNN_API void gnn_plan_destroy(gnn_plan *plan) {
     if (!plan) return;
     (void)hipFree(plan->edge_scale[0]);
     (void)hipFree(plan->edge_scale[1]);
+    (void)hipFree(plan->edge_scale[2]);
     (void)hipFree(plan->padded);
     (void)hipFree(plan->row_perm);
     (void)hipFree(plan->col_counts);

@@ -181,3 +181,14 @@ def small_random_multigraph(n: int, e: int, seed: int, allow_dups: bool = True) 
 def to_csr_numpy(el: EdgeList):
     """(dst, src) int32 numpy arrays of an EdgeList, for host-side consumers."""
     return el.dst.cpu().numpy().astype(np.int32), el.src.cpu().numpy().astype(np.int32)
+
+
+def regular_random_neighbours(n_rows: int, degree: int, table_rows: int, seed: int, device="cpu"):
+    """(indptr int32[n_rows+1], indices int32[n_rows*degree]) of a bipartite-like gather
+    pattern: every row has `degree` neighbours drawn uniformly from [0, table_rows).
+    Used to measure what a gather achieves when the gathered table has a given size."""
+    key = stream_key(seed, 71)
+    ctr = torch.arange(n_rows * degree, dtype=torch.int64, device=device)
+    idx = ((hash_counter(key, ctr) >> 33) & 0x7FFFFFFF) % table_rows
+    indptr = torch.arange(n_rows + 1, dtype=torch.int64, device=device) * degree
+    return indptr.to(torch.int32), idx.to(torch.int32)

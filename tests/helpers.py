@@ -18,7 +18,7 @@ import synth
 RTOL_F32 = 1e-5
 RTOL_BF16 = 2e-2
 
-OP_CODE = {"sum": gnn.GNN_SUM, "mean": gnn.GNN_MEAN, "gcn": gnn.GNN_GCN_SYM}
+OP_CODE = {"sum": gnn.GNN_SUM, "mean": gnn.GNN_MEAN, "gcn": gnn.GNN_GCN_SYM, "sage": gnn.GNN_SAGE_GCN}
 
 
 def device_graph(el: synth.EdgeList, weights=None, indptr64=False, plan_params=None, want_perm=False, with_plans=True):

@@ -56,6 +56,7 @@ def test_argument_checks_that_need_no_device():
     assert lib.gnn_aggregate_fwd(one, one, None, one, one, 4, 4, 0, ctypes.byref(o)) == gnn.GNN_ERR_INVALID_ARG
     o.ldx = 0
     assert lib.gnn_aggregate_bwd(one, one, None, one, one, 4, 4, 1, ctypes.byref(o)) == gnn.GNN_ERR_UNSUPPORTED
+    assert lib.gnn_aggregate_bwd(one, one, None, one, one, 4, 4, 3, ctypes.byref(o)) == gnn.GNN_ERR_UNSUPPORTED
     assert lib.gnn_plan_create(None, None, 5, 0, None, None, ctypes.byref(ctypes.c_void_p())) == gnn.GNN_ERR_INVALID_ARG
     assert lib.gnn_csr_from_sorted_coo(None, 5, 5, one, 0, None) == gnn.GNN_ERR_INVALID_ARG
     assert lib.gnn_calib_copy(one, one, 7, None) == gnn.GNN_ERR_INVALID_ARG

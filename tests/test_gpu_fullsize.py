@@ -93,6 +93,11 @@ def test_fullsize_sparse_stack_f256():
     _fullsize("rmat_sparse_stack", 256, "mean")
 
 
+def test_fullsize_sparse_stack_f100_sage_gcn():
+    """The aggregator of the paper's own runs (sum + own vector, over in-degree + 1), full size."""
+    _fullsize("rmat_sparse_stack", 100, "sage")
+
+
 def test_fullsize_dense_wide_f602():
     """232,965 vertices / 114,615,892 edges, F=602, MEAN."""
     _fullsize("rmat_dense_wide", 602, "mean")

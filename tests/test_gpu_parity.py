@@ -98,7 +98,7 @@ def test_widths_bf16(f):
     _check_both_directions(el, f, "sum", dtype=torch.bfloat16, seed=f)
 
 
-@pytest.mark.parametrize("op_name", ["sum", "mean", "gcn"])
+@pytest.mark.parametrize("op_name", ["sum", "mean", "gcn", "sage"])
 @pytest.mark.parametrize("weighted", [False, True])
 @pytest.mark.parametrize("use_plan", [False, True])
 def test_ops_weights_plan(op_name, weighted, use_plan):
@@ -111,15 +111,15 @@ def test_ops_weights_plan(op_name, weighted, use_plan):
     w = None
     if weighted:
         w = torch.from_numpy(np.random.default_rng(4).uniform(0.1, 2.0, el.e).astype(np.float32))
-    if not use_plan and op_name == "mean":
-        # backward MEAN needs a plan; check forward only
+    if not use_plan and op_name in ("mean", "sage"):
+        # the backward pass of these ops needs a plan; check forward only
         dg = device_graph(el, weights=w, with_plans=False)
         indptr, indices, *_ = host_csr(el)
         X = synth.normal_features(el.n, 40, 5)
-        Y = run_fwd(dg, X.to(DEV), OP_CODE["mean"], plan=None)
-        Yo, S = oracle.aggregate_fwd(indptr, indices, X.numpy(), op=oracle.OP_MEAN,
+        Y = run_fwd(dg, X.to(DEV), OP_CODE[op_name], plan=None)
+        Yo, S = oracle.aggregate_fwd(indptr, indices, X.numpy(), op=OP_CODE[op_name],
                                      w=None if w is None else w.numpy(), want_scale=True)
-        assert_close(Y, Yo, S, False, "fwd mean no plan")
+        assert_close(Y, Yo, S, False, f"fwd {op_name} no plan")
         return
     _check_both_directions(el, 40, op_name, weights=w, use_plan=use_plan)
 
@@ -146,6 +146,7 @@ def test_every_kernel_family_gives_the_same_answer(variant, f):
     params = None if pv is None else gnn.make_plan_params(*pv)
     _check_both_directions(el, f, "mean", plan_params=params)
     _check_both_directions(el, f, "gcn", plan_params=params)
+    _check_both_directions(el, f, "sage", plan_params=params)
 
 
 @pytest.mark.parametrize("f,dtype", [(64, torch.float32), (256, torch.float32), (640, torch.float32),
@@ -184,7 +185,7 @@ def test_padded_copy_route(f, dtype, hubs):
     indptr, indices, indptr_t, indices_t, _ = host_csr(el)
     X = synth.normal_features(el.n, f, 10, dtype=dtype)
     bf16 = dtype == torch.bfloat16
-    for op, oop in ((gnn.GNN_MEAN, oracle.OP_MEAN), (gnn.GNN_GCN_SYM, oracle.OP_GCN_SYM)):
+    for op, oop in ((gnn.GNN_MEAN, oracle.OP_MEAN), (gnn.GNN_GCN_SYM, oracle.OP_GCN_SYM), (gnn.GNN_SAGE_GCN, oracle.OP_SAGE_GCN)):
         Yo, S = oracle.aggregate_fwd(indptr, indices, X.float().numpy(), op=oop, dout=np.diff(indptr_t), nthreads=8,
                                      want_scale=True)
         dXo, St = oracle.aggregate_bwd(indptr_t, indices_t, X.float().numpy(), op=oop, din=np.diff(indptr), nthreads=8,
@@ -263,12 +264,14 @@ def test_empty_and_degenerate_inputs():
         assert not run_fwd(dg, X, op).any()
         assert not run_bwd(dg, X, op).any()
         assert not run_fwd(dg, X, gnn.GNN_SUM, plan=None).any()
+    # the GraphSAGE-GCN aggregator of an edgeless graph is the vertex's own vector (divided by 0 + 1)
+    assert torch.equal(run_fwd(dg, X, gnn.GNN_SAGE_GCN), X) and torch.equal(run_bwd(dg, X, gnn.GNN_SAGE_GCN), X)
     gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, None, X[:, :0], X[:, :0].clone(), n, 0, gnn.GNN_SUM)
     # one vertex with a self-loop, and a multigraph with duplicates and self-loops
     el = synth.EdgeList(1, torch.zeros(1, dtype=torch.int32), torch.zeros(1, dtype=torch.int32))
     _check_both_directions(el, 5, "mean")
     el = synth.small_random_multigraph(37, 500, 3)
-    for op_name in ("sum", "mean", "gcn"):
+    for op_name in ("sum", "mean", "gcn", "sage"):
         _check_both_directions(el, 9, op_name)
     # a star: one row with N-1 neighbours, N-1 rows with one
     n = 5000
@@ -277,6 +280,7 @@ def test_empty_and_degenerate_inputs():
     el = synth.EdgeList(n, torch.cat([leaves, zeros]), torch.cat([zeros, leaves]))
     _check_both_directions(el, 100, "mean")
     _check_both_directions(el, 100, "gcn", plan_params=gnn.make_plan_params([64], 256))
+    _check_both_directions(el, 100, "sage", plan_params=gnn.make_plan_params([64], 256))
 
 
 def test_strided_and_misaligned_rows():
@@ -319,6 +323,7 @@ def test_errors():
     assert status(gnn.gnn_aggregate_fwd, dg.indptr, dg.indices, None, X, Y, el.n + 1, 8, 0, plan=dg.plan_fwd) == gnn.GNN_ERR_INVALID_ARG
     assert status(gnn.gnn_aggregate_bwd, dg.indptr_t, dg.indices_t, None, X, Y, el.n, 8, gnn.GNN_MEAN) == gnn.GNN_ERR_UNSUPPORTED
     assert status(gnn.gnn_aggregate_fwd, dg.indptr, dg.indices, None, X, Y, el.n, 8, gnn.GNN_GCN_SYM) == gnn.GNN_ERR_UNSUPPORTED
+    assert status(gnn.gnn_aggregate_bwd, dg.indptr_t, dg.indices_t, None, X, Y, el.n, 8, gnn.GNN_SAGE_GCN) == gnn.GNN_ERR_UNSUPPORTED
     assert status(gnn.gnn_plan_create, dg.indptr, dg.indices, el.n, gnn.make_plan_params([4, 2], 0)) == gnn.GNN_ERR_INVALID_ARG
     # a workspace that is too small is rejected, one that is large enough is used
     params = gnn.make_plan_params([8], 4)

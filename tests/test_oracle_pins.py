@@ -16,7 +16,7 @@ import pytest
 import oracle
 import synth
 
-OPS = (oracle.OP_SUM, oracle.OP_MEAN, oracle.OP_GCN_SYM)
+OPS = (oracle.OP_SUM, oracle.OP_MEAN, oracle.OP_GCN_SYM, oracle.OP_SAGE_GCN)
 
 
 # ---------------------------------------------------------------- helpers
@@ -40,6 +40,8 @@ def dense_operator(dst, src, n, op, w=None):
         A = A / np.maximum(din, 1.0)[:, None]
     elif op == oracle.OP_GCN_SYM and w is None:
         A = A / np.sqrt(np.maximum(din, 1.0))[:, None] / np.sqrt(np.maximum(dout, 1.0))[None, :]
+    elif op == oracle.OP_SAGE_GCN:                       # (A + I) scaled by 1/(din+1): Section 6.1
+        A = (A + np.eye(n)) / (din + 1.0)[:, None]
     return A, din.astype(np.int64), dout.astype(np.int64)
 
 
@@ -139,6 +141,9 @@ def pin_closed_forms():
     assert np.array_equal(Y[1:], np.repeat(X[:1].astype(np.float64), n - 1, axis=0))
     Ym = oracle.aggregate_fwd(indptr, indices, X, op=oracle.OP_MEAN)
     np.testing.assert_allclose(Ym[0], X[1:].astype(np.float64).mean(axis=0), rtol=1e-13)
+    Ys = oracle.aggregate_fwd(indptr, indices, X, op=oracle.OP_SAGE_GCN)
+    np.testing.assert_allclose(Ys[0], X.astype(np.float64).mean(axis=0), rtol=1e-13)          # hub: mean of all n rows
+    np.testing.assert_allclose(Ys[1:], (X[1:].astype(np.float64) + X[0].astype(np.float64)) / 2.0, rtol=1e-13)
     # d-regular circulant graph with all-ones features under GCN_SYM: every entry is 1.
     n, offs = 30, (1, 2, 5)
     s = np.repeat(np.arange(n), 2 * len(offs))
@@ -148,11 +153,13 @@ def pin_closed_forms():
     Yg = oracle.aggregate_fwd(indptr, indices, np.ones((n, f), np.float32), op=oracle.OP_GCN_SYM,
                               dout=np.bincount(s, minlength=n))
     np.testing.assert_allclose(Yg, 1.0, rtol=1e-14)
-    # no edges at all: zeros for every op, rows present.
+    # no edges at all: zeros for every op (SAGE_GCN: the vertex's own vector over 1), rows present.
     indptr = np.zeros(8, dtype=np.int64); indices = np.zeros(0, dtype=np.int32)
+    X0 = rand((7, f), 6)
     for op in OPS:
-        Y0 = oracle.aggregate_fwd(indptr, indices, rand((7, f), 6), op=op, dout=np.zeros(7, np.int64))
-        assert Y0.shape == (7, f) and not Y0.any()
+        Y0 = oracle.aggregate_fwd(indptr, indices, X0, op=op, dout=np.zeros(7, np.int64))
+        assert Y0.shape == (7, f)
+        assert np.array_equal(Y0, X0.astype(np.float64)) if op == oracle.OP_SAGE_GCN else not Y0.any()
 
 
 def pin_relabel_equivariance():
@@ -278,6 +285,10 @@ MUTATIONS = [
      "c = 1.0 / sqrt((double)at_least_one(dout) * (double)at_least_one(dout));"),
     ("bwd_sign", "const float *g = dY + v * ldy;\n            for (int64_t j = 0; j < F; ++j) {\n                double t = c * (double)g[j];\n                acc[j] += t;",
      "const float *g = dY + v * ldy;\n            for (int64_t j = 0; j < F; ++j) {\n                double t = c * (double)g[j];\n                acc[j] -= t;"),
+    ("sage_self_term_dropped", "acc[j] = (acc[j] + (double)self[j]) / (double)(din + 1);", "acc[j] = acc[j] / (double)(din + 1);"),
+    ("sage_divides_by_din", "acc[j] = (acc[j] + (double)self[j]) / (double)(din + 1);", "acc[j] = (acc[j] + (double)self[j]) / (double)at_least_one(din);"),
+    ("sage_bwd_self_uses_dout", "double t = (double)self[j] / (double)(din[u] + 1);", "double t = (double)self[j] / (double)(dout + 1);"),
+    ("sage_bwd_edge_unscaled", "if (op == OP_SAGE_GCN) c /= (double)(din[v] + 1);", ""),
     ("transpose_not_stable", "int64_t pos = cursor[u]++;", "int64_t pos = indptr_t[u + 1] - 1 - (cursor[u]++ - indptr_t[u]);"),
     ("transpose_perm_off", "perm[pos] = e;", "perm[pos] = e - indptr[v];"),
     ("indptr_off_by_one", "indptr[v + 1] += 1;\n    }\n    for (int64_t v = 0; v < N; ++v) indptr[v + 1] += indptr[v];",
