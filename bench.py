@@ -107,7 +107,7 @@ def cpu_baseline(el, widths, op_name, target_seconds=20.0):
     # probe for speed at the first width, then size the row sample to the time target
     f0 = widths[0]
     X0 = synth.normal_features(el.n, f0, 1).numpy()
-    probe = rng.choice(el.n, size=min(el.n, 20000), replace=False)
+    probe = rng.choice(el.n, size=min(el.n, 200000), replace=False)
     t0 = time.perf_counter()
     oracle.aggregate_fwd(indptr, src, X0, op=op, rows=probe, nthreads=threads, dout=dout)
     dt = max(time.perf_counter() - t0, 1e-4)
@@ -131,6 +131,127 @@ def cpu_baseline(el, widths, op_name, target_seconds=20.0):
                       f"{secs:.1f} s of CPU time, fp64 scalar loops, OpenMP dynamic over rows"}
 
 
+def measure(workload, steps, warmup, scale, dev, dump_graph=None):
+    """Setup + warm-up + the timed region for one workload; returns (result dict, host edge list factory)."""
+    w = synth.WORKLOADS[workload]
+    widths = list(w["widths"])
+    op_names = w["op"].split("+")
+    dtype = torch.bfloat16 if w["dtype"] == "bf16" else torch.float32
+    esz = 2 if dtype == torch.bfloat16 else 4
+
+    # ---- setup (not timed as part of a step) ----
+    t0 = time.perf_counter()
+    el = synth.make_graph(workload, device=dev, scale=scale)
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t0
+    weights = synth.gcn_sym_edge_weights(el.dst, el.src, el.n) if w.get("weighted") else None
+    t0 = time.perf_counter()
+    dg = gnn.build_device_graph(el.dst, el.src, el.n, edge_w=weights, indptr64=w["indptr64"], with_plans=False)
+    torch.cuda.synchronize()
+    t_csr = time.perf_counter() - t0
+    if dump_graph:
+        os.makedirs(dump_graph, exist_ok=True)
+        for name_, t in (("indptr", dg.indptr), ("indices", dg.indices), ("indptr_t", dg.indptr_t), ("indices_t", dg.indices_t)):
+            t.cpu().numpy().tofile(os.path.join(dump_graph, name_ + ".bin"))
+        with open(os.path.join(dump_graph, "meta.txt"), "w") as fh:
+            fh.write(f"{el.n} {el.e} {1 if w['indptr64'] else 0}\n")
+        print(f"dumped {workload} to {dump_graph}", file=sys.stderr)
+        return None, None
+    t0 = time.perf_counter()
+    dg.plan_fwd = gnn.gnn_plan_create(dg.indptr, dg.indices, el.n)
+    dg.plan_bwd = gnn.gnn_plan_create(dg.indptr_t, dg.indices_t, el.n)
+    torch.cuda.synchronize()
+    t_plan = time.perf_counter() - t0
+    n, e = el.n, el.e
+    fmax = max(widths)
+    for op_name in op_names:
+        for f in sorted(set(widths)):
+            dg.plan_fwd.prepare(dg.indices, OPS[op_name], False, f, dtype)
+            dg.plan_bwd.prepare(dg.indices_t, OPS[op_name], True, f, dtype)
+
+    bufs = []  # one fresh set of inputs per layer of the stack
+    for layer, f in enumerate(widths):
+        X = synth.normal_features(n, f, 100 + layer, device=dev, dtype=dtype)
+        dY = synth.normal_features(n, f, 200 + layer, device=dev, dtype=dtype)
+        bufs.append((X, torch.empty_like(X), dY, torch.empty_like(dY)))
+    torch.cuda.synchronize()
+
+    calls = [(op_name, d, layer) for op_name in op_names for layer in range(len(widths)) for d in ("fwd", "bwd")]
+
+    def one_call(op_name, d, layer):
+        X, Y, dY, dX = bufs[layer]
+        f = widths[layer]
+        op = OPS[op_name]
+        if d == "fwd":
+            gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, dg.edge_w, X, Y, n, f, op, plan=dg.plan_fwd)
+        else:
+            gnn.gnn_aggregate_bwd(dg.indptr_t, dg.indices_t, dg.edge_w_t, dY, dX, n, f, op, plan=dg.plan_bwd)
+
+    for _ in range(warmup):
+        for op_name, d, layer in calls:
+            one_call(op_name, d, layer)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps; events on the launch stream bracket every call ----
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in calls]
+          for _ in range(steps)]
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for k in range(steps):
+        for i, (op_name, d, layer) in enumerate(calls):
+            ev[k][i][0].record()
+            one_call(op_name, d, layer)
+            ev[k][i][1].record()
+    torch.cuda.synchronize()
+    t_total = time.perf_counter() - t_start
+
+    per_call_ms = [float(np.mean([ev[k][i][0].elapsed_time(ev[k][i][1]) for k in range(steps)]))
+                   for i in range(len(calls))]
+    ef_step = sum(2 * e * f for f in widths) * len(op_names)
+    ms_per_step = t_total / steps * 1e3
+    value = ef_step / (t_total / steps) / 1e9
+
+    ip_bytes = 8 if w["indptr64"] else 4
+    weighted = weights is not None
+    call_rows = []
+    for i, (op_name, d, layer) in enumerate(calls):
+        f = widths[layer]
+        src_scaled = (op_name in ("mean", "sage") and d == "bwd") or (op_name == "gcn" and not weighted)
+        b = algorithmic_bytes(n, e, f, esz, ip_bytes, weighted, src_scaled)
+        s = per_call_ms[i] * 1e-3
+        call_rows.append({"op": op_name, "dir": d, "F": f, "ms": round(per_call_ms[i], 4), "GEF_per_s": round(e * f / s / 1e9, 2),
+                          "algorithmic_GB": round(b / 1e9, 4), "algorithmic_GBs": round(b / s / 1e9, 1),
+                          "frac_of_hbm_peak": round(b / s / 1e9 / HBM_PEAK_GBS, 4),
+                          "gathered_TBs": round(e * f * esz / s / 1e12, 2)})
+    # Dominant kernel = the forward aggregation kernel (one template instantiation serves all
+    # widths of this workload); its launches are the "fwd" calls of a step.
+    fwd = [r for r in call_rows if r["dir"] == "fwd"]
+    fwd_bytes = sum(r["algorithmic_GB"] for r in fwd)
+    fwd_s = sum(r["ms"] for r in fwd) * 1e-3
+    achieved = fwd_bytes / fwd_s
+    traffic = read_traffic_note(workload) if scale == 1.0 else None
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "traffic_GBs": None if traffic is None else round(traffic / (fwd_s / len(fwd)) / 1e9, 1),
+                "kernel": "aggregate_kernel (forward launches of one step)",
+                "launches_per_step": len(fwd), "avg_launch_ms": round(fwd_s * 1e3 / len(fwd), 4)}
+
+    result = {
+        "metric": "aggregation GEdge-features/s (edges*F/s) fwd+bwd; % of HBM peak GB/s",
+        "value": round(value, 2), "unit": "GEF/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if dtype == torch.bfloat16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{workload}: R-MAT/ER graph N={n} E={e}, op={w['op']}, widths={widths}, "
+                               f"fwd+bwd per width" + ("" if scale == 1.0 else f" (SCALED x{scale}: not a result)"),
+                   "N": n, "E": e, "widths": widths, "op": w["op"], "indptr_bits": ip_bytes * 8, "parallelism": "1 GPU"},
+        "roofline": roofline,
+        "calls": call_rows,
+        "setup_ms": {"graph_generation": round(t_gen * 1e3, 1), "csr_and_transpose": round(t_csr * 1e3, 1),
+                     "plans_fwd_and_bwd": round(t_plan * 1e3, 1)},
+    }
+    return result, (el, widths, op_names)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -140,6 +261,8 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the graph (debugging only; invalid as a result)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-calibration", action="store_true")
+    ap.add_argument("--secondary", default="rmat_dense_wide",
+                    help="a second workload measured briefly in the same run and reported under 'secondary' ('' = none)")
     ap.add_argument("--dump-graph", default=None, metavar="DIR",
                     help="write the CSR and transposed CSR as raw arrays for the stand-alone profiling driver, then exit")
     args = ap.parse_args()
@@ -151,127 +274,22 @@ def main():
     torch.cuda.set_device(dev)
     gnn.load_library()
 
-    w = synth.WORKLOADS[args.workload]
-    widths = list(w["widths"])
-    op_name = w["op"].split("+")[0]
-    op = OPS[op_name]
-    dtype = torch.bfloat16 if w["dtype"] == "bf16" else torch.float32
-    esz = 2 if dtype == torch.bfloat16 else 4
-
-    # ---- setup (not timed as part of a step) ----
-    t0 = time.perf_counter()
-    el = synth.make_graph(args.workload, device=dev, scale=args.scale)
-    torch.cuda.synchronize()
-    t_gen = time.perf_counter() - t0
-    weights = synth.gcn_sym_edge_weights(el.dst, el.src, el.n) if w.get("weighted") else None
-    t0 = time.perf_counter()
-    dg = gnn.build_device_graph(el.dst, el.src, el.n, edge_w=weights, indptr64=w["indptr64"], with_plans=False)
-    torch.cuda.synchronize()
-    t_csr = time.perf_counter() - t0
-    if args.dump_graph:
-        os.makedirs(args.dump_graph, exist_ok=True)
-        for name_, t in (("indptr", dg.indptr), ("indices", dg.indices), ("indptr_t", dg.indptr_t), ("indices_t", dg.indices_t)):
-            t.cpu().numpy().tofile(os.path.join(args.dump_graph, name_ + ".bin"))
-        with open(os.path.join(args.dump_graph, "meta.txt"), "w") as fh:
-            fh.write(f"{el.n} {el.e} {1 if w['indptr64'] else 0}\n")
-        print(f"dumped {args.workload} to {args.dump_graph}", file=sys.stderr)
+    result, ctx = measure(args.workload, args.steps, args.warmup, args.scale, dev, args.dump_graph)
+    if result is None:
         return
-    t0 = time.perf_counter()
-    dg.plan_fwd = gnn.gnn_plan_create(dg.indptr, dg.indices, el.n)
-    dg.plan_bwd = gnn.gnn_plan_create(dg.indptr_t, dg.indices_t, el.n)
-    torch.cuda.synchronize()
-    t_plan = time.perf_counter() - t0
-    n, e = el.n, el.e
-    fmax = max(widths)
-    for f in sorted(set(widths)):
-        dg.plan_fwd.prepare(dg.indices, op, False, f, dtype)
-        dg.plan_bwd.prepare(dg.indices_t, op, True, f, dtype)
-
-    bufs = []  # one fresh set of inputs per layer of the stack
-    for layer, f in enumerate(widths):
-        X = synth.normal_features(n, f, 100 + layer, device=dev, dtype=dtype)
-        dY = synth.normal_features(n, f, 200 + layer, device=dev, dtype=dtype)
-        bufs.append((X, torch.empty_like(X), dY, torch.empty_like(dY)))
-    torch.cuda.synchronize()
-
-    calls = [(d, layer) for layer in range(len(widths)) for d in ("fwd", "bwd")]
-
-    def one_call(d, layer):
-        X, Y, dY, dX = bufs[layer]
-        f = widths[layer]
-        if d == "fwd":
-            gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, dg.edge_w, X, Y, n, f, op, plan=dg.plan_fwd)
-        else:
-            gnn.gnn_aggregate_bwd(dg.indptr_t, dg.indices_t, dg.edge_w_t, dY, dX, n, f, op, plan=dg.plan_bwd)
-
-    for _ in range(args.warmup):
-        for d, layer in calls:
-            one_call(d, layer)
-    torch.cuda.synchronize()
-
-    # ---- timed region: exactly K steps; events on the launch stream bracket every call ----
-    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in calls]
-          for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t_start = time.perf_counter()
-    for k in range(args.steps):
-        for i, (d, layer) in enumerate(calls):
-            ev[k][i][0].record()
-            one_call(d, layer)
-            ev[k][i][1].record()
-    torch.cuda.synchronize()
-    t_total = time.perf_counter() - t_start
-
-    per_call_ms = [float(np.mean([ev[k][i][0].elapsed_time(ev[k][i][1]) for k in range(args.steps)]))
-                   for i in range(len(calls))]
-    ef_step = sum(2 * e * f for f in widths)
-    ms_per_step = t_total / args.steps * 1e3
-    value = ef_step / (t_total / args.steps) / 1e9
-
-    ip_bytes = 8 if w["indptr64"] else 4
-    weighted = weights is not None
-    call_rows = []
-    for i, (d, layer) in enumerate(calls):
-        f = widths[layer]
-        src_scaled = (op_name == "mean" and d == "bwd") or (op_name == "gcn" and not weighted)
-        b = algorithmic_bytes(n, e, f, esz, ip_bytes, weighted, src_scaled)
-        s = per_call_ms[i] * 1e-3
-        call_rows.append({"dir": d, "F": f, "ms": round(per_call_ms[i], 4), "GEF_per_s": round(e * f / s / 1e9, 2),
-                          "algorithmic_GB": round(b / 1e9, 4), "algorithmic_GBs": round(b / s / 1e9, 1),
-                          "frac_of_hbm_peak": round(b / s / 1e9 / HBM_PEAK_GBS, 4),
-                          "gathered_TBs": round(e * f * esz / s / 1e12, 2)})
-    # Dominant kernel = the forward aggregation kernel (one template instantiation serves all
-    # widths of this workload); its launches are the "fwd" calls of a step.
-    fwd = [r for r in call_rows if r["dir"] == "fwd"]
-    fwd_bytes = sum(r["algorithmic_GB"] for r in fwd)
-    fwd_s = sum(r["ms"] for r in fwd) * 1e-3
-    achieved = fwd_bytes / fwd_s
-    traffic = read_traffic_note(args.workload)
-    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                "traffic_GBs": None if traffic is None else round(traffic / (fwd_s / len(fwd)) / 1e9, 1),
-                "kernel": "aggregate_kernel (forward launches of one step)",
-                "launches_per_step": len(fwd), "avg_launch_ms": round(fwd_s * 1e3 / len(fwd), 4)}
-
-    result = {
-        "metric": "aggregation GEdge-features/s (edges*F/s) fwd+bwd; % of HBM peak GB/s",
-        "value": round(value, 2), "unit": "GEF/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if dtype == torch.bfloat16 else "f32", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: R-MAT/ER graph N={n} E={e}, op={w['op']}, widths={widths}, "
-                               f"fwd+bwd per width" + ("" if args.scale == 1.0 else f" (SCALED x{args.scale}: not a result)"),
-                   "N": n, "E": e, "widths": widths, "op": w["op"], "indptr_bits": ip_bytes * 8, "parallelism": "1 GPU"},
-        "roofline": roofline,
-        "calls": call_rows,
-        "setup_ms": {"graph_generation": round(t_gen * 1e3, 1), "csr_and_transpose": round(t_csr * 1e3, 1),
-                     "plans_fwd_and_bwd": round(t_plan * 1e3, 1)},
-    }
+    el, widths, op_names = ctx
+    e = el.e
+    if args.secondary and args.secondary != args.workload:
+        # one more workload in the same run, for context (not the headline value): fewer steps
+        torch.cuda.empty_cache()
+        sec, _ = measure(args.secondary, max(3, args.steps // 4), 1, 1.0, dev)
+        result["secondary"] = {k: sec[k] for k in ("value", "unit", "ms_per_step", "steps", "config", "calls", "setup_ms")}
     if not args.no_calibration:
         result["ceilings"] = calibrate(dev)
     if not args.no_cpu_baseline and e > 500_000_000:
         result["cpu_baseline"] = None  # the host copy of this workload alone is > 60 GB; see tests/test_gpu_capacity.py
     elif not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(synth.EdgeList(el.n, el.src.cpu(), el.dst.cpu(), el.meta), widths, op_name)
+        result["cpu_baseline"] = cpu_baseline(synth.EdgeList(el.n, el.src.cpu(), el.dst.cpu(), el.meta), widths, op_names[0])
     else:
         result["cpu_baseline"] = None
     print(json.dumps(result))
