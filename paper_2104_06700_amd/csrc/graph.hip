@@ -5,10 +5,6 @@
 // The paper takes the CSR as given (Section 4.1) and builds extra CSRs as
 // preprocessing (Section 4.2); the transposed graph is what the implied
 // backward pass needs.
-#include <cstring>
-
-#include <rocprim/device/device_radix_sort.hpp>
-
 #include "common.h"
 
 namespace {
@@ -73,6 +69,167 @@ __global__ void __launch_bounds__(256) validate_kernel(const IP *__restrict__ in
     if (err) atomicOr(bad, 1);
 }
 
+// ---------------------------------------------------------------- stable radix sort
+// LSD radix sort of (key, value) pairs of 32-bit words, 8 bits per pass, stable.  One wavefront
+// owns a tile of kSortTile consecutive pairs.  Per pass: (1) every tile counts its digits,
+// (2) the [digit][tile] table is prefix-summed (digit-major, so equal digits of earlier tiles come
+// first), (3) every tile walks its pairs in order, 64 at a time, and places each behind the
+// equal-digit pairs that precede it (lanes with the same digit are found with eight ballots).
+constexpr int kSortRounds = 64;
+constexpr int kSortTile = 64 * kSortRounds;
+
+__device__ __forceinline__ unsigned long long same_digit_lanes(unsigned digit, bool valid) {
+    unsigned long long peers = __ballot(valid);
+#pragma unroll
+    for (int bit = 0; bit < 8; ++bit) {
+        const bool one = (digit >> bit) & 1u;
+        const unsigned long long b = __ballot(one);
+        peers &= one ? b : ~b;
+    }
+    return peers;
+}
+
+__global__ void __launch_bounds__(64) sort_count_kernel(const uint32_t *__restrict__ keys, int64_t n, int shift,
+                                                        int64_t n_tiles, uint32_t *__restrict__ table) {
+    __shared__ uint32_t hist[256];
+    const int lane = threadIdx.x;
+    for (int d = lane; d < 256; d += 64) hist[d] = 0;
+    __syncthreads();
+    const int64_t tile0 = int64_t(blockIdx.x) * kSortTile;
+    for (int r = 0; r < kSortRounds; ++r) {
+        const int64_t i = tile0 + int64_t(r) * 64 + lane;
+        const bool valid = i < n;
+        const unsigned digit = valid ? (keys[i] >> shift) & 255u : 0u;
+        const unsigned long long peers = same_digit_lanes(digit, valid);
+        if (valid && (peers & ((1ull << lane) - 1ull)) == 0) hist[digit] += __popcll(peers);  // one leader per digit
+        __syncthreads();
+    }
+    for (int d = lane; d < 256; d += 64) table[int64_t(d) * n_tiles + blockIdx.x] = hist[d];
+}
+
+__global__ void __launch_bounds__(64) sort_scatter_kernel(const uint32_t *__restrict__ keys_in,
+                                                          const uint32_t *__restrict__ vals_in, int64_t n, int shift,
+                                                          int64_t n_tiles, const uint32_t *__restrict__ table,
+                                                          uint32_t *__restrict__ keys_out,
+                                                          uint32_t *__restrict__ vals_out) {
+    __shared__ uint32_t base[256];
+    const int lane = threadIdx.x;
+    for (int d = lane; d < 256; d += 64) base[d] = table[int64_t(d) * n_tiles + blockIdx.x];
+    __syncthreads();
+    const int64_t tile0 = int64_t(blockIdx.x) * kSortTile;
+    for (int r = 0; r < kSortRounds; ++r) {
+        const int64_t i = tile0 + int64_t(r) * 64 + lane;
+        const bool valid = i < n;
+        const uint32_t key = valid ? keys_in[i] : 0u;
+        const unsigned digit = (key >> shift) & 255u;
+        const unsigned long long peers = same_digit_lanes(digit, valid);
+        const unsigned long long before = peers & ((1ull << lane) - 1ull);
+        uint32_t pos = 0;
+        if (valid) pos = base[digit] + __popcll(before);
+        __syncthreads();
+        if (valid) {
+            keys_out[pos] = key;
+            vals_out[pos] = vals_in[i];
+            if (before == 0) base[digit] += __popcll(peers);
+        }
+        __syncthreads();
+    }
+}
+
+// Exclusive prefix sum of a uint32 table in three steps (block sums, scan of the sums, local scans).
+constexpr int kScanItems = 16;
+constexpr int kScanChunk = 256 * kScanItems;
+
+__global__ void __launch_bounds__(256) scan_block_sums_kernel(const uint32_t *__restrict__ data, int64_t n,
+                                                              uint32_t *__restrict__ sums) {
+    __shared__ uint32_t red[256];
+    const int64_t lo = int64_t(blockIdx.x) * kScanChunk + int64_t(threadIdx.x) * kScanItems;
+    uint32_t s = 0;
+    for (int k = 0; k < kScanItems; ++k) if (lo + k < n) s += data[lo + k];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if (int(threadIdx.x) < off) red[threadIdx.x] += red[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) sums[blockIdx.x] = red[0];
+}
+
+__global__ void __launch_bounds__(1024) scan_sums_kernel(uint32_t *__restrict__ sums, int64_t n) {
+    __shared__ uint32_t part[1024];
+    const int t = threadIdx.x;
+    const int64_t chunk = (n + 1023) / 1024;
+    const int64_t lo = chunk * t < n ? chunk * t : n;
+    const int64_t hi = lo + chunk < n ? lo + chunk : n;
+    uint32_t s = 0;
+    for (int64_t i = lo; i < hi; ++i) s += sums[i];
+    part[t] = s;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {
+        uint32_t add = t >= off ? part[t - off] : 0;
+        __syncthreads();
+        part[t] += add;
+        __syncthreads();
+    }
+    uint32_t run = part[t] - s;
+    for (int64_t i = lo; i < hi; ++i) {
+        uint32_t x = sums[i];
+        sums[i] = run;
+        run += x;
+    }
+}
+
+__global__ void __launch_bounds__(256) scan_local_kernel(uint32_t *__restrict__ data, int64_t n,
+                                                         const uint32_t *__restrict__ sums_scanned) {
+    __shared__ uint32_t part[256];
+    const int t = threadIdx.x;
+    const int64_t lo = int64_t(blockIdx.x) * kScanChunk + int64_t(t) * kScanItems;
+    uint32_t v[kScanItems];
+    uint32_t s = 0;
+    for (int k = 0; k < kScanItems; ++k) {
+        v[k] = lo + k < n ? data[lo + k] : 0;
+        s += v[k];
+    }
+    part[t] = s;
+    __syncthreads();
+    for (int off = 1; off < 256; off <<= 1) {
+        uint32_t add = t >= off ? part[t - off] : 0;
+        __syncthreads();
+        part[t] += add;
+        __syncthreads();
+    }
+    uint32_t run = sums_scanned[blockIdx.x] + part[t] - s;
+    for (int k = 0; k < kScanItems; ++k) {
+        if (lo + k < n) data[lo + k] = run;
+        run += v[k];
+    }
+}
+
+// Sorts n pairs by the low `bits` bits of the key.  buf_k[0]/buf_v[0] hold the input and are
+// overwritten; the result ends in buf_k[*out]/buf_v[*out].  `first_keys` (optional) replaces
+// buf_k[0] as the read-only input of the first pass.
+int radix_sort_pairs(const uint32_t *first_keys, uint32_t *buf_k[2], uint32_t *buf_v[2], int64_t n, int bits,
+                     uint32_t *table, uint32_t *sums, hipStream_t stream, int *out) {
+    const int64_t n_tiles = (n + kSortTile - 1) / kSortTile;
+    const int64_t n_table = n_tiles * 256;
+    const int64_t n_sums = (n_table + kScanChunk - 1) / kScanChunk;
+    if (n_tiles > INT32_MAX || n_sums > INT32_MAX) return GNN_ERR_UNSUPPORTED;
+    int cur = 0;
+    for (int shift = 0; shift < bits; shift += 8) {
+        const uint32_t *kin = (shift == 0 && first_keys) ? first_keys : buf_k[cur];
+        sort_count_kernel<<<static_cast<unsigned>(n_tiles), 64, 0, stream>>>(kin, n, shift, n_tiles, table);
+        scan_block_sums_kernel<<<static_cast<unsigned>(n_sums), 256, 0, stream>>>(table, n_table, sums);
+        scan_sums_kernel<<<1, 1024, 0, stream>>>(sums, n_sums);
+        scan_local_kernel<<<static_cast<unsigned>(n_sums), 256, 0, stream>>>(table, n_table, sums);
+        sort_scatter_kernel<<<static_cast<unsigned>(n_tiles), 64, 0, stream>>>(kin, buf_v[cur], n, shift, n_tiles, table,
+                                                                             buf_k[cur ^ 1], buf_v[cur ^ 1]);
+        if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
+        cur ^= 1;
+    }
+    *out = cur;
+    return GNN_OK;
+}
+
 int grid_for(int64_t n, int block, int64_t cap = (int64_t(1) << 16)) {
     int64_t g = (n + block - 1) / block;
     if (g < 1) g = 1;
@@ -127,38 +284,39 @@ extern "C" GNN_API int gnn_transpose_csr(const void *indptr, const int32_t *indi
         return GNN_OK;
     }
 
-    int32_t *row_of = nullptr, *keys_sorted = nullptr;
-    uint32_t *pos = nullptr, *pos_sorted = nullptr;
-    void *temp = nullptr;
-    size_t temp_bytes = 0;
+    int32_t *row_of = nullptr;
+    uint32_t *buf_k[2] = {nullptr, nullptr}, *buf_v[2] = {nullptr, nullptr}, *table = nullptr, *sums = nullptr;
     auto cleanup = [&]() {
-        (void)hipFree(row_of); (void)hipFree(keys_sorted); (void)hipFree(pos); (void)hipFree(pos_sorted); (void)hipFree(temp);
+        (void)hipFree(row_of); (void)hipFree(buf_k[0]); (void)hipFree(buf_k[1]); (void)hipFree(buf_v[0]);
+        (void)hipFree(buf_v[1]); (void)hipFree(table); (void)hipFree(sums);
     };
     auto fail = [&](int s) { (void)hipStreamSynchronize(stream); cleanup(); return s; };
 
+    const int64_t n_tiles = (E + kSortTile - 1) / kSortTile;
+    const int64_t n_table = n_tiles * 256;
+    const int64_t n_sums = (n_table + kScanChunk - 1) / kScanChunk;
     if (hipMalloc(&row_of, sizeof(int32_t) * E) != hipSuccess) return fail(GNN_ERR_ALLOC);
-    if (hipMalloc(&keys_sorted, sizeof(int32_t) * E) != hipSuccess) return fail(GNN_ERR_ALLOC);
-    if (hipMalloc(&pos, sizeof(uint32_t) * E) != hipSuccess) return fail(GNN_ERR_ALLOC);
-    if (hipMalloc(&pos_sorted, sizeof(uint32_t) * E) != hipSuccess) return fail(GNN_ERR_ALLOC);
+    for (int i = 0; i < 2; ++i) {
+        if (hipMalloc(&buf_k[i], sizeof(uint32_t) * E) != hipSuccess) return fail(GNN_ERR_ALLOC);
+        if (hipMalloc(&buf_v[i], sizeof(uint32_t) * E) != hipSuccess) return fail(GNN_ERR_ALLOC);
+    }
+    if (hipMalloc(&table, sizeof(uint32_t) * n_table) != hipSuccess) return fail(GNN_ERR_ALLOC);
+    if (hipMalloc(&sums, sizeof(uint32_t) * (n_sums + 1)) != hipSuccess) return fail(GNN_ERR_ALLOC);
 
     if (indptr_is_64)
         expand_rows_kernel<int64_t><<<grid_for(N * 64, 256), 256, 0, stream>>>(static_cast<const int64_t *>(indptr), N, row_of);
     else
         expand_rows_kernel<int32_t><<<grid_for(N * 64, 256), 256, 0, stream>>>(static_cast<const int32_t *>(indptr), N, row_of);
-    iota_kernel<<<grid_for(E, 256), 256, 0, stream>>>(pos, E);
+    iota_kernel<<<grid_for(E, 256), 256, 0, stream>>>(buf_v[0], E);
     if (hipGetLastError() != hipSuccess) return fail(GNN_ERR_LAUNCH);
 
-    // Stable LSD radix sort of (source id, CSR position) on the bits a vertex id can occupy.
-    const unsigned end_bit = static_cast<unsigned>(gnn_ilog2_ceil(N > 1 ? N : 2));
-    const uint32_t *keys_in = reinterpret_cast<const uint32_t *>(indices);
-    uint32_t *keys_out = reinterpret_cast<uint32_t *>(keys_sorted);
-    if (rocprim::radix_sort_pairs(nullptr, temp_bytes, keys_in, keys_out, pos, pos_sorted, static_cast<size_t>(E), 0u,
-                                  end_bit, stream) != hipSuccess)
-        return fail(GNN_ERR_LAUNCH);
-    if (hipMalloc(&temp, temp_bytes > 0 ? temp_bytes : 16) != hipSuccess) return fail(GNN_ERR_ALLOC);
-    if (rocprim::radix_sort_pairs(temp, temp_bytes, keys_in, keys_out, pos, pos_sorted, static_cast<size_t>(E), 0u,
-                                  end_bit, stream) != hipSuccess)
-        return fail(GNN_ERR_LAUNCH);
+    // Stable sort of (source id, CSR position) on the bits a vertex id can occupy.
+    const int bits = gnn_ilog2_ceil(N > 1 ? N : 2);
+    int where = 0;
+    rc = radix_sort_pairs(reinterpret_cast<const uint32_t *>(indices), buf_k, buf_v, E, bits, table, sums, stream, &where);
+    if (rc != GNN_OK) return fail(rc);
+    const int32_t *keys_sorted = reinterpret_cast<const int32_t *>(buf_k[where]);
+    const uint32_t *pos_sorted = buf_v[where];
 
     rc = gnn_csr_from_sorted_coo(keys_sorted, E, N, indptr_t, indptr_is_64, stream);
     if (rc != GNN_OK) return fail(rc);
