@@ -61,9 +61,10 @@ def read_traffic_note(workload):
 
 def calibrate(dev):
     """Measured ceilings printed next to the result: a streaming copy, and the aggregation
-    kernel itself on synthetic gather patterns (1 M rows x 50 uniformly random neighbours,
-    400-byte rows, no padded copy, no plan) whose source table is L2-resident (2 MB), too large for L2 but
-    inside the Infinity Cache (120 MB), or HBM-resident (980 MB)."""
+    kernel itself (no plan, rows gathered as they are) on synthetic gather patterns -- 2,449,029
+    rows x 50 uniformly random neighbours, 400-byte rows -- whose neighbours all lie in the first
+    5,000 rows of X (2 MB: L2-resident), the first 300,000 (120 MB: misses L2, fits the Infinity
+    Cache), or anywhere (980 MB: HBM-resident)."""
     out = {}
 
     def timed(fn, reps=5):
@@ -81,14 +82,15 @@ def calibrate(dev):
     s = timed(lambda: gnn.gnn_calib_copy(src, dst))
     out["stream_copy_read_plus_write_GBs"] = round(2 * src.numel() * 4 / s / 1e9, 1)
     del dst
-    n_rows, degree, f = 1_000_000, 50, 100
-    table = src[: 2_449_029 * f].view(2_449_029, f)
+    n_rows, degree, f = 2_449_029, 50, 100
+    x = src[: n_rows * f].view(n_rows, f)
     y = torch.empty((n_rows, f), dtype=torch.float32, device=dev)
     for label, rows in (("gather_L2_resident_GBs", 5_000), ("gather_L2_miss_infinity_cache_GBs", 300_000),
-                        ("gather_L2_miss_hbm_GBs", 2_449_029)):
+                        ("gather_L2_miss_hbm_GBs", n_rows)):
         indptr, idx = synth.regular_random_neighbours(n_rows, degree, rows, seed=rows, device=dev)
-        s = timed(lambda: gnn.gnn_aggregate_fwd(indptr, idx, None, table[:n_rows], y, n_rows, f, gnn.GNN_SUM))
+        s = timed(lambda: gnn.gnn_aggregate_fwd(indptr, idx, None, x, y, n_rows, f, gnn.GNN_SUM), reps=3)
         out[label] = round(n_rows * degree * f * 4 / s / 1e9, 1)  # gathered bytes per second
+        del indptr, idx
     return out
 
 
