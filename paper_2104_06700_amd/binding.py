@@ -209,7 +209,7 @@ def gnn_plan_create(indptr: torch.Tensor, indices: torch.Tensor, N: int,
     return Plan(out.value, k)
 
 
-def _aggregate(fn_name, indptr, indices, edge_w, X, Y, N, F, op, plan, stream, workspace, ldx, ldy, flags=0):
+def _aggregate(fn_name, indptr, indices, edge_w, X, Y, N, F, op, plan, stream, workspace, ldx, ldy, flags=0, max_slices=0):
     lib = load_library()
     if X.dtype != Y.dtype:
         raise TypeError("input and output features must have the same dtype")
@@ -221,6 +221,7 @@ def _aggregate(fn_name, indptr, indices, edge_w, X, Y, N, F, op, plan, stream, w
     o.stream = _stream(stream)
     o.plan = plan.handle if plan is not None else None
     o.flags = int(flags)
+    o.max_slices = int(max_slices)
     if workspace is not None:
         o.workspace = workspace.data_ptr()
         o.workspace_bytes = workspace.numel() * workspace.element_size()
@@ -229,15 +230,17 @@ def _aggregate(fn_name, indptr, indices, edge_w, X, Y, N, F, op, plan, stream, w
 
 
 def gnn_aggregate_fwd(indptr, indices, edge_w, X, Y, N, F, op, plan: Optional[Plan] = None, stream=None,
-                      workspace=None, ldx=None, ldy=None, flags=0) -> None:
+                      workspace=None, ldx=None, ldy=None, flags=0, max_slices=0) -> None:
     """Y[v] = scale_v * sum_e c_e X[indices[e]] over the CSR by destination (see include/gnnagg.h)."""
-    _aggregate("gnn_aggregate_fwd", indptr, indices, edge_w, X, Y, N, F, op, plan, stream, workspace, ldx, ldy, flags)
+    _aggregate("gnn_aggregate_fwd", indptr, indices, edge_w, X, Y, N, F, op, plan, stream, workspace, ldx, ldy, flags,
+               max_slices)
 
 
 def gnn_aggregate_bwd(indptr_t, indices_t, edge_w_t, dY, dX, N, F, op, plan: Optional[Plan] = None, stream=None,
-                      workspace=None, ldx=None, ldy=None, flags=0) -> None:
+                      workspace=None, ldx=None, ldy=None, flags=0, max_slices=0) -> None:
     """dX = adjoint of the forward map, over the transposed graph (see include/gnnagg.h)."""
-    _aggregate("gnn_aggregate_bwd", indptr_t, indices_t, edge_w_t, dY, dX, N, F, op, plan, stream, workspace, ldx, ldy, flags)
+    _aggregate("gnn_aggregate_bwd", indptr_t, indices_t, edge_w_t, dY, dX, N, F, op, plan, stream, workspace, ldx, ldy, flags,
+               max_slices)
 
 
 def gnn_csr_from_sorted_coo(dst_sorted: torch.Tensor, N: int, indptr_out: torch.Tensor, stream=None) -> None:

@@ -151,23 +151,25 @@ def test_every_kernel_family_gives_the_same_answer(variant, f):
 
 @pytest.mark.parametrize("f,dtype", [(64, torch.float32), (256, torch.float32), (640, torch.float32),
                                      (160, torch.float32), (128, torch.bfloat16), (1024, torch.bfloat16)])
-def test_column_slices_over_xcds_on_and_off(f, dtype):
+@pytest.mark.parametrize("hubs", [False, True])
+def test_column_slices_over_xcds_on_and_off(f, dtype, hubs):
     """Line-aligned rows are gathered slice by slice (one slice per XCD); with the
     slicing switched off the same rows go through the whole-row path.  Both must
-    match the oracle."""
+    match the oracle, with and without hub rows cut into pieces."""
     el = synth.make_graph("rmat_sparse_stack", scale=0.004, seed=71)
-    dg = device_graph(el)
+    dg = device_graph(el, plan_params=gnn.make_plan_params([1, 4, 32], 48) if hubs else None)
     indptr, indices, *_ = host_csr(el)
     X = synth.normal_features(el.n, f, 9, dtype=dtype)
     Yo, S = oracle.aggregate_fwd(indptr, indices, X.float().numpy(), op=oracle.OP_MEAN, nthreads=8, want_scale=True)
     Xd = X.to(DEV)
     assert Xd.data_ptr() % 128 == 0
     outs = []
-    for flags in (0, gnn.GNN_FLAG_NO_COLUMN_SLICES):
+    for flags, max_slices in ((0, 0), (0, 8), (0, 2), (gnn.GNN_FLAG_NO_COLUMN_SLICES, 0)):
         Y = torch.full_like(Xd, float("nan"))
-        gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, None, Xd, Y, el.n, f, gnn.GNN_MEAN, plan=dg.plan_fwd, flags=flags)
+        gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, None, Xd, Y, el.n, f, gnn.GNN_MEAN, plan=dg.plan_fwd, flags=flags,
+                              max_slices=max_slices)
         torch.cuda.synchronize()
-        assert_close(Y, Yo, S, dtype == torch.bfloat16, f"slices flags={flags} F={f}")
+        assert_close(Y, Yo, S, dtype == torch.bfloat16, f"slices flags={flags} max={max_slices} F={f}")
         outs.append(Y)
 
 

@@ -322,3 +322,21 @@ def test_pins_catch_planted_mistakes(mutation):
             assert caught, f"no pin noticed the planted mistake '{name}'"
         finally:
             oracle.use_library(None)
+
+
+def test_pins_under_undefined_behaviour_sanitizer():
+    """The oracle is rebuilt with -fsanitize=undefined (no recovery: any finding aborts the
+    process) and the pins run against that build in a child process."""
+    import subprocess
+    import sys
+    src_path = os.path.join(os.path.dirname(oracle.__file__), "oracle.c")
+    with tempfile.TemporaryDirectory() as tmp:
+        so_path = os.path.join(tmp, "oracle_ubsan.so")
+        subprocess.check_call(["gcc", "-O1", "-g", "-fopenmp", "-shared", "-fPIC", "-std=c11", "-fsanitize=undefined",
+                               "-fno-sanitize-recover=all", "-o", so_path, src_path, "-lm"])
+        code = ("import sys; sys.path.insert(0, %r); sys.path.insert(0, %r); import oracle; oracle.use_library(%r); "
+                "import test_oracle_pins as t; [p() for p in t.PINS]; print('pins ok under ubsan')"
+                % (os.path.dirname(os.path.dirname(os.path.abspath(__file__))), os.path.dirname(os.path.abspath(__file__)), so_path))
+        out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=600)
+        assert out.returncode == 0, out.stderr[-2000:]
+        assert "pins ok under ubsan" in out.stdout
