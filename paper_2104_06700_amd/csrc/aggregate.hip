@@ -60,7 +60,7 @@ struct AggArgs {
     int64_t ldp;
     int32_t n_bins;
     int32_t log2_slices;  // column slices; workgroup b serves slice b % n_slices (see run_aggregate)
-    int32_t slice_cols;   // columns per slice
+    int32_t slice_cols;   // columns per slice (the last slice of a launch may hold fewer)
     int32_t store_vec;    // widest store the output rows allow (elements, <= VEC)
     BinDesc bins[GNN_MAX_BINS + 1];
 };
@@ -401,6 +401,39 @@ __global__ void __launch_bounds__(256) pad_rows_kernel(const V *__restrict__ src
     }
 }
 
+// Same copy for fp32 rows, with row v multiplied by the factor its vertex carries as a gathered
+// row (1/din, 1/sqrt(deg) or 1/(din+1)): folding the factor into the copy that happens anyway
+// saves the per-edge factor stream and the per-edge multiply of MEAN / SAGE_GCN backward and GCN.
+template <int W>
+__global__ void __launch_bounds__(256) pad_scale_rows_kernel(const float *__restrict__ src, int64_t ld_src,
+                                                             float *__restrict__ dst, int64_t ld_dst, int64_t N,
+                                                             int chunks_per_row, int mode,
+                                                             const int32_t *__restrict__ counts) {
+    const int64_t total = N * chunks_per_row;
+    const int64_t stride = int64_t(gridDim.x) * blockDim.x;
+    for (int64_t g = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; g < total; g += stride) {
+        const int64_t row = g / chunks_per_row;
+        const int c = int(g - row * chunks_per_row);
+        const float f = scale_of(mode, counts[row]);
+        float v[W];
+        VecIO<float, W>::load(src + row * ld_src + int64_t(c) * W, v);
+#pragma unroll
+        for (int i = 0; i < W; ++i) v[i] *= f;
+        VecIO<float, W>::store(dst + row * ld_dst + int64_t(c) * W, v);
+    }
+}
+
+template <int W>
+hipError_t launch_pad_scale(const void *src, int64_t ld_src, void *dst, int64_t ld_dst, int64_t N, int64_t F, int mode,
+                            const int32_t *counts, hipStream_t stream) {
+    const int cpr = int(F / W);
+    int64_t blocks = (N * cpr + 255) / 256;
+    if (blocks > (int64_t(1) << 17)) blocks = int64_t(1) << 17;
+    pad_scale_rows_kernel<W><<<static_cast<unsigned>(blocks), 256, 0, stream>>>(
+        static_cast<const float *>(src), ld_src, static_cast<float *>(dst), ld_dst, N, cpr, mode, counts);
+    return hipGetLastError();
+}
+
 template <typename V>
 hipError_t launch_pad(const void *src, int64_t ld_src_bytes, void *dst, int64_t ld_dst_bytes, int64_t N,
                       int64_t row_bytes, hipStream_t stream) {
@@ -473,13 +506,6 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
     }
     if ((src_mode != kScaleNone || self_mode == kSelfInvPlus1) && !plan) return GNN_ERR_UNSUPPORTED;  // needs the column counts a plan holds
     const float *edge_scale = nullptr;
-    if (src_mode != kScaleNone && plan->n_edges > 0) {
-        // streamed per-edge factors (built once per plan and mode) instead of a random 4-byte
-        // lookup per edge, which would cost a 128-byte line each
-        int rc = gnn_plan_edge_scale(plan, indices, src_mode, static_cast<hipStream_t>(o.stream), &edge_scale);
-        if (rc != GNN_OK) return rc;
-    }
-    const bool coef = (w != nullptr) || src_mode != kScaleNone;
 
     const int esz = o.dtype == GNN_BF16 ? 2 : 4;
     if (reinterpret_cast<uintptr_t>(gathered) % esz || reinterpret_cast<uintptr_t>(out) % esz) return GNN_ERR_INVALID_ARG;
@@ -497,16 +523,37 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
     {
         const bool lines_ok = (ldx % line_elems == 0) && reinterpret_cast<uintptr_t>(gathered) % 128 == 0;
         const int64_t row_bytes = F * esz;
-        const bool worth_it = !lines_ok && row_bytes >= 192 && N * row_bytes >= (int64_t(32) << 20);
+        // Column slices make XCD k read the same lines (k, k+S, ...) of every row.  With a row
+        // stride of an even number of lines those addresses share their low line-index bits and
+        // crowd a few of the XCD's 16 L2 channels (measured at F=256, 8 slices: 15.4 ms with
+        // 8-line rows, 12.5 ms with 9-line rows).  An odd stride spreads them over all channels,
+        // so the padded copy always has one, and line-aligned rows with an even stride are copied
+        // too when the gather (E rows) dwarfs the copy (N rows).
+        const bool even_stride = lines_ok && (ldx / line_elems) % 2 == 0;
+        const bool big = N * row_bytes >= (int64_t(32) << 20);
+        const bool worth_it = row_bytes >= 192 && big &&
+                              (!lines_ok || (even_stride && row_bytes >= 768 && plan && plan->n_edges >= 16 * N));
         if (plan && !(o.flags & GNN_FLAG_NO_PADDED_COPY) && (worth_it || (o.flags & GNN_FLAG_FORCE_PADDED_COPY))) {
-            const int64_t ld_pad = (F + line_elems - 1) / line_elems * line_elems;
+            int64_t pad_lines = (F + line_elems - 1) / line_elems;
+            pad_lines |= 1;  // odd
+            const int64_t ld_pad = pad_lines * line_elems;
             int rc = gnn_plan_padded(plan, N * ld_pad * esz);
             if (rc != GNN_OK) return rc;
             // widest chunk the source rows allow
             const int64_t src_ld_bytes = ldx * esz, dst_ld_bytes = ld_pad * esz;
             const uintptr_t src_addr = reinterpret_cast<uintptr_t>(gathered);
             hipError_t err;
-            if (row_bytes % 16 == 0 && src_ld_bytes % 16 == 0 && src_addr % 16 == 0)
+            if (esz == 4 && src_mode != kScaleNone) {
+                // fp32: the factor of the gathered rows goes into the copy
+                if (row_bytes % 16 == 0 && src_ld_bytes % 16 == 0 && src_addr % 16 == 0)
+                    err = launch_pad_scale<4>(gathered, ldx, plan->padded, ld_pad, N, F, src_mode, plan->col_counts, stream);
+                else if (row_bytes % 8 == 0 && src_ld_bytes % 8 == 0 && src_addr % 8 == 0)
+                    err = launch_pad_scale<2>(gathered, ldx, plan->padded, ld_pad, N, F, src_mode, plan->col_counts, stream);
+                else
+                    err = launch_pad_scale<1>(gathered, ldx, plan->padded, ld_pad, N, F, src_mode, plan->col_counts, stream);
+                src_mode = kScaleNone;
+                if (self_mode == kSelfInvPlus1) self_mode = kSelfPlain;  // the own row is already scaled
+            } else if (row_bytes % 16 == 0 && src_ld_bytes % 16 == 0 && src_addr % 16 == 0)
                 err = launch_pad<uint4>(gathered, src_ld_bytes, plan->padded, dst_ld_bytes, N, row_bytes, stream);
             else if (row_bytes % 8 == 0 && src_ld_bytes % 8 == 0 && src_addr % 8 == 0)
                 err = launch_pad<uint2>(gathered, src_ld_bytes, plan->padded, dst_ld_bytes, N, row_bytes, stream);
@@ -520,6 +567,14 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
             padded = true;
         }
     }
+
+    if (src_mode != kScaleNone && plan->n_edges > 0) {
+        // streamed per-edge factors (built once per plan and mode) instead of a random 4-byte
+        // lookup per edge, which would cost a 128-byte line each
+        int rc = gnn_plan_edge_scale(plan, indices, src_mode, stream, &edge_scale);
+        if (rc != GNN_OK) return rc;
+    }
+    const bool coef = (w != nullptr) || src_mode != kScaleNone;
 
     // Widest load the gathered rows allow.  Only the padded copy may be read past column F (its
     // rows end in padding that belongs to the buffer); a caller's matrix needs F % vec == 0.
@@ -551,41 +606,61 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
 
     // Column slices over the XCDs.  Workgroups are handed to the 8 XCDs round-robin by
     // workgroup id, and every XCD has a private L2.  When the gathered rows are whole 128-byte
-    // lines, workgroup b gathers only column slice (b % S): an XCD's L2 then sees one slice of
-    // every gathered row instead of whole rows of an eighth of the destinations, so S times as
-    // many hot source rows stay resident.  The price is S reads of the index stream.
-    int log2_slices = 0;
-    int64_t slice_cols_all = 0;
+    // lines, workgroup b of a launch gathers only column slice (b % S): an XCD's L2 then sees one
+    // slice of every gathered row instead of whole rows of an eighth of the destinations, so many
+    // more hot source rows stay resident.  Slices are one line wide (wider when the row stride is a
+    // multiple of 8 lines: one-line slices would crowd too few L2 channels), and a row of more
+    // than 8 slices is covered by several launches of 8, 4, 2 or 1 slices (column slabs in time),
+    // so that every launch keeps all 8 XCDs equally busy.  The price is one read of the index
+    // stream per slice.
+    struct Segment { int64_t f0, fw; int log2_s; int64_t slice_cols; };
+    Segment segs[64];
+    int n_segs = 0;
     {
         const bool lines_ok = (ldg % line_elems == 0) && reinterpret_cast<uintptr_t>(gathered) % 128 == 0;
         const int64_t lines = (F + line_elems - 1) / line_elems;
-        if (lines_ok && lines >= 2 && !(o.flags & GNN_FLAG_NO_COLUMN_SLICES)) {
-            // Measured: 4 slices (XCD k and k+4 share one) beat 8 on every width tried -- the index
-            // stream is re-read once per slice and one-line slices cost DRAM burst locality.
-            const int64_t s_max = o.max_slices > 0 ? o.max_slices : 4;
-            for (int ls = 3; ls >= 1; --ls) {
-                const int64_t S = int64_t(1) << ls;
-                if (S > s_max) continue;
-                const int64_t per = (lines + S - 1) / S;
-                if (per * (S - 1) < lines && S * per * 5 <= lines * 6) { log2_slices = ls; slice_cols_all = per * line_elems; break; }
+        // Slice width: XCD k reads lines {k*w .. k*w+w-1} of rows L lines apart; with L a multiple
+        // of 8 (16) a one-line slice would land on 2 (1) of 16 line-interleaved L2 channels, so
+        // the slice is widened until it covers at least 4 (measured: L=8, w=2 beats w=1; L=4 and
+        // odd L are fastest with w=1).
+        int64_t g16 = 1;
+        while (g16 < 16 && (ldg / line_elems) % (g16 * 2) == 0) g16 *= 2;
+        const int64_t unit_lines = g16 >= 8 ? g16 / 4 : 1;
+        const int64_t units = (lines + unit_lines - 1) / unit_lines;
+        const int64_t s_max = o.max_slices > 0 ? o.max_slices : 8;
+        if (lines_ok && units >= 2 && units <= 256 && s_max >= 2 && !(o.flags & GNN_FLAG_NO_COLUMN_SLICES)) {
+            int64_t u0 = 0;
+            while (u0 < units) {
+                int ls = 3;
+                while (ls > 0 && ((int64_t(1) << ls) > units - u0 || (int64_t(1) << ls) > s_max)) --ls;
+                Segment &g = segs[n_segs++];
+                g.f0 = u0 * unit_lines * line_elems;
+                g.slice_cols = unit_lines * line_elems;
+                g.log2_s = ls;
+                const int64_t end = g.f0 + (g.slice_cols << ls);
+                g.fw = (end < F ? end : F) - g.f0;
+                u0 += int64_t(1) << ls;
             }
+        } else {
+            // no slices: slabs of up to 64 lanes * vec * kMaxPass columns
+            const int64_t slab = int64_t(64) * vec * kMaxPass;
+            for (int64_t f0 = 0; f0 < F && n_segs < 64; f0 += slab) {
+                Segment &g = segs[n_segs++];
+                g.f0 = f0;
+                g.fw = F - f0 < slab ? F - f0 : slab;
+                g.log2_s = 0;
+                g.slice_cols = g.fw;
+            }
+            if ((F + slab - 1) / slab > 64) return GNN_ERR_UNSUPPORTED;
         }
     }
 
     constexpr int sr_shift = 4;
 
-    // Feature slabs: one launch covers up to 64 lanes * vec * kMaxPass columns (per slice).
-    const int64_t slab = (int64_t(64) * vec * kMaxPass) << log2_slices;
-    for (int64_t f0 = 0; f0 < F; f0 += slab) {
-        const int64_t fw = F - f0 < slab ? F - f0 : slab;
-        // with slices, a workgroup's lanes span one slice; a wide slice may still need passes
-        int64_t slice_cols = fw;
-        int log2_s = 0;
-        if (log2_slices > 0) {
-            slice_cols = slice_cols_all < int64_t(64) * vec * kMaxPass ? slice_cols_all : int64_t(64) * vec * kMaxPass;
-            log2_s = log2_slices;
-            if (slice_cols << log2_s < fw) { slice_cols = fw; log2_s = 0; }  // does not tile this slab: fall back
-        }
+    for (int gi = 0; gi < n_segs; ++gi) {
+        const int64_t f0 = segs[gi].f0, fw = segs[gi].fw;
+        const int log2_s = segs[gi].log2_s;
+        const int64_t slice_cols = segs[gi].slice_cols;
         const int64_t strips = (slice_cols + vec - 1) / vec;
         const int log2_c = strips >= 64 ? 6 : gnn_ilog2_ceil(strips);
         const int C = 1 << log2_c;

@@ -199,8 +199,9 @@ extern "C" GNN_API int gnn_plan_prepare(gnn_plan *plan, const int32_t *indices, 
     int rc = gnn_plan_reserve(plan, F);
     if (rc != GNN_OK) return rc;
     const int64_t esz = dtype == GNN_BF16 ? 2 : 4, line_elems = 128 / esz;
-    if (F % line_elems != 0) {  // dense rows of this width cannot be whole lines: the padded copy will be used
-        rc = gnn_plan_padded(plan, plan->n_rows * ((F + line_elems - 1) / line_elems * line_elems) * esz);
+    {   // the padded copy (odd number of 128-byte lines per row) that a hot call may use
+        const int64_t pad_lines = ((F + line_elems - 1) / line_elems) | 1;
+        rc = gnn_plan_padded(plan, plan->n_rows * pad_lines * line_elems * esz);
         if (rc != GNN_OK) return rc;
     }
     const float *unused = nullptr;
