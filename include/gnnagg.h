@@ -172,6 +172,11 @@ GNN_API int gnn_plan_sizes(const gnn_plan *plan, int64_t *n_rows, int32_t *n_bin
  * as (row, e_begin, e_end), col_counts int32[n_rows].  Any may be NULL. */
 GNN_API int gnn_plan_export(const gnn_plan *plan, int64_t *bin_offsets, int32_t *row_perm,
                     int64_t *chunks, int32_t *col_counts);
+/* Share (0..1) of all gathers that goes to the K most-gathered vertices of the plan's graph
+ * (from a 256-bucket histogram of the column counts, so accurate to a few percent).  The hot
+ * calls use it to decide whether spreading column slices over the XCDs can keep more useful
+ * rows in the 4 MB L2 caches; exported for inspection. */
+GNN_API double gnn_plan_gather_share(const gnn_plan *plan, int64_t K);
 /* Bytes of scratch a hot call with this plan and width F needs (hub partials). */
 GNN_API int64_t gnn_plan_workspace_bytes(const gnn_plan *plan, int64_t F);
 /* Grow the plan-owned scratch now, so later hot calls do not allocate. */

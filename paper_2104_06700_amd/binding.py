@@ -26,7 +26,8 @@ GNN_FLAG_FORCE_PADDED_COPY = 4
 EXPORTED_SYMBOLS = (
     "gnn_aggregate_fwd", "gnn_aggregate_bwd", "gnn_csr_from_sorted_coo", "gnn_transpose_csr",
     "gnn_validate_csr", "gnn_plan_default_params", "gnn_plan_create", "gnn_plan_destroy",
-    "gnn_plan_sizes", "gnn_plan_export", "gnn_plan_workspace_bytes", "gnn_plan_reserve", "gnn_plan_prepare",
+    "gnn_plan_sizes", "gnn_plan_export", "gnn_plan_gather_share", "gnn_plan_workspace_bytes", "gnn_plan_reserve",
+    "gnn_plan_prepare",
     "gnn_status_string", "gnn_calib_copy",
 )
 
@@ -79,6 +80,8 @@ def load_library() -> ctypes.CDLL:
         lib.gnn_plan_destroy.restype = None
         lib.gnn_plan_sizes.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(i64)]
         lib.gnn_plan_export.argtypes = [vp, vp, vp, vp, vp]
+        lib.gnn_plan_gather_share.argtypes = [vp, i64]
+        lib.gnn_plan_gather_share.restype = ctypes.c_double
         lib.gnn_plan_workspace_bytes.argtypes = [vp, i64]
         lib.gnn_plan_workspace_bytes.restype = i64
         lib.gnn_plan_reserve.argtypes = [vp, i64]
@@ -171,6 +174,9 @@ class Plan:
             self.handle, bin_offsets.ctypes.data, row_perm.ctypes.data if n else None,
             chunks.ctypes.data if c else None, col_counts.ctypes.data if n else None))
         return bin_offsets, row_perm, chunks, col_counts
+
+    def gather_share(self, K: int) -> float:
+        return float(load_library().gnn_plan_gather_share(self.handle, int(K)))
 
     def workspace_bytes(self, F: int) -> int:
         return int(load_library().gnn_plan_workspace_bytes(self.handle, int(F)))

@@ -37,6 +37,12 @@ struct gnn_plan {
     // per-edge factor of the gathered vertex, streamed by the hot kernels:
     // [0] 1/max(c,1)   [1] 1/sqrt(max(c,1))   [2] 1/(c+1), c = col_counts[indices[e]]; built on first use
     float *edge_scale[3] = {nullptr, nullptr, nullptr};
+    // Histogram of the column counts in 256 roughly logarithmic buckets (host copies): how many
+    // vertices fall in each bucket and how many edges they are gathered by.  It answers "which
+    // share of the gathers goes to the K most-gathered vertices", the quantity that decides
+    // whether XCD column slices can keep more useful rows in L2.
+    int64_t bucket_vertices[256] = {0};
+    int64_t bucket_edges[256] = {0};
     // copy of the gathered matrix with rows padded to whole 128-byte lines (grown on first use)
     void *padded = nullptr;
     int64_t padded_bytes = 0;
@@ -45,6 +51,10 @@ struct gnn_plan {
 // Row stride (floats) of the hub partial-sum scratch for width F: whole 32-byte groups, so that
 // vector stores of a last, partial strip stay inside the row.
 static inline int64_t gnn_partial_ld(int64_t F) { return (F + 7) / 8 * 8; }
+
+// Share of all gathers that goes to the K most-gathered vertices (from the bucket histogram;
+// the boundary bucket is taken pro rata).
+double gnn_plan_top_share(const gnn_plan *plan, int64_t K);
 
 // Makes plan->padded at least `bytes` large (allocation on growth).
 int gnn_plan_padded(gnn_plan *plan, int64_t bytes);

@@ -37,6 +37,32 @@ __global__ void __launch_bounds__(256) count_cols_kernel(const int32_t *__restri
         atomicAdd(&col_counts[indices[e]], 1);
 }
 
+// 256 buckets over the count axis: counts below 16 one bucket each, then 8 buckets per octave.
+__device__ __forceinline__ int count_bucket(int c) {
+    if (c < 16) return c;
+    const int o = 31 - __clz(c);
+    return 16 + (o - 4) * 8 + ((c >> (o - 3)) & 7);
+}
+
+__global__ void __launch_bounds__(256) count_buckets_kernel(const int32_t *__restrict__ col_counts, int64_t N,
+                                                            unsigned long long *__restrict__ vertices,
+                                                            unsigned long long *__restrict__ edges) {
+    __shared__ unsigned long long sv[256], se[256];
+    sv[threadIdx.x] = 0;
+    se[threadIdx.x] = 0;
+    __syncthreads();
+    int64_t stride = int64_t(gridDim.x) * blockDim.x;
+    for (int64_t v = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; v < N; v += stride) {
+        const int c = col_counts[v];
+        const int b = count_bucket(c);
+        atomicAdd(&sv[b], 1ull);  // integer sums: the order of the additions does not matter
+        atomicAdd(&se[b], static_cast<unsigned long long>(c));
+    }
+    __syncthreads();
+    if (sv[threadIdx.x]) atomicAdd(&vertices[threadIdx.x], sv[threadIdx.x]);
+    if (se[threadIdx.x]) atomicAdd(&edges[threadIdx.x], se[threadIdx.x]);
+}
+
 // block_counts[b * n_blocks + blk] = rows of bin b among rows [blk*1024, blk*1024+1024)
 __global__ void __launch_bounds__(kSplitThreads) bin_count_kernel(const void *__restrict__ indptr, int ip64,
                                                                   int64_t N, Thresholds thr, int64_t n_blocks,
@@ -178,6 +204,26 @@ int gnn_plan_edge_scale(gnn_plan *plan, const int32_t *indices, int mode, hipStr
     return GNN_OK;
 }
 
+double gnn_plan_top_share(const gnn_plan *plan, int64_t K) {
+    if (!plan || plan->n_edges <= 0 || K <= 0) return 0.0;
+    double edges = 0.0;
+    int64_t left = K;
+    for (int b = 255; b >= 0 && left > 0; --b) {
+        const int64_t nv = plan->bucket_vertices[b];
+        if (nv <= 0) continue;
+        if (nv <= left) {
+            edges += static_cast<double>(plan->bucket_edges[b]);
+            left -= nv;
+        } else {
+            edges += static_cast<double>(plan->bucket_edges[b]) * static_cast<double>(left) / static_cast<double>(nv);
+            left = 0;
+        }
+    }
+    return edges / static_cast<double>(plan->n_edges);
+}
+
+extern "C" GNN_API double gnn_plan_gather_share(const gnn_plan *plan, int64_t K) { return gnn_plan_top_share(plan, K); }
+
 int gnn_plan_padded(gnn_plan *plan, int64_t bytes) {
     if (!plan || bytes < 0) return GNN_ERR_INVALID_ARG;
     if (bytes <= plan->padded_bytes) return GNN_OK;
@@ -282,6 +328,23 @@ extern "C" GNN_API int gnn_plan_create(const void *indptr, const int32_t *indice
     // column counts.  The zero fill is a kernel-free memset outside any graph capture.
     if (hipMemsetAsync(plan->col_counts, 0, sizeof(int32_t) * N, stream) != hipSuccess) return fail(GNN_ERR_LAUNCH);
     if (E > 0) count_cols_kernel<<<grid_for(E, 256, 1 << 16), 256, 0, stream>>>(indices, E, plan->col_counts);
+    {   // bucket histogram of the column counts (for gnn_plan_top_share)
+        unsigned long long *buckets = nullptr;
+        if (hipMalloc(&buckets, sizeof(unsigned long long) * 512) != hipSuccess) return fail(GNN_ERR_ALLOC);
+        bool ok = hipMemsetAsync(buckets, 0, sizeof(unsigned long long) * 512, stream) == hipSuccess;
+        if (ok) {
+            count_buckets_kernel<<<grid_for(N, 256, 2048), 256, 0, stream>>>(plan->col_counts, N, buckets, buckets + 256);
+            unsigned long long host[512];
+            ok = hipMemcpyAsync(host, buckets, sizeof(host), hipMemcpyDeviceToHost, stream) == hipSuccess &&
+                 hipStreamSynchronize(stream) == hipSuccess;
+            for (int b = 0; ok && b < 256; ++b) {
+                plan->bucket_vertices[b] = static_cast<int64_t>(host[b]);
+                plan->bucket_edges[b] = static_cast<int64_t>(host[256 + b]);
+            }
+        }
+        (void)hipFree(buckets);
+        if (!ok) return fail(GNN_ERR_LAUNCH);
+    }
 
     // stable multi-way split of the rows by bin
     bin_count_kernel<<<static_cast<int>(n_blocks), kSplitThreads, 0, stream>>>(indptr, plan->indptr_is_64, N, thr, n_blocks, block_counts);

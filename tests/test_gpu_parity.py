@@ -249,6 +249,19 @@ def test_plan_bit_exact(variant):
         assert np.array_equal(cc, np.bincount(ix, minlength=el.n).astype(np.int32))
 
 
+def test_gather_share_of_the_most_gathered_vertices():
+    """The plan's bucket histogram answers 'which share of the gathers goes to the K
+    most-gathered vertices' to within the bucket width (12 %)."""
+    el = synth.make_graph("rmat_sparse_stack", scale=0.05, seed=91)
+    dg = device_graph(el)
+    counts = np.sort(np.bincount(el.src.numpy(), minlength=el.n))[::-1].astype(np.float64)
+    for k in (1, 10, 300, 4096, 32768, el.n, 10 * el.n):
+        exact = counts[:k].sum() / el.e
+        got = dg.plan_fwd.gather_share(k)
+        assert abs(got - exact) <= 0.02 + 0.06 * exact, (k, got, exact)
+    assert dg.plan_fwd.gather_share(0) == 0.0
+
+
 # ------------------------------------------------------------------ edge cases
 def test_empty_and_degenerate_inputs():
     dev = torch.device(DEV)
