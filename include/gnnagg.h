@@ -58,7 +58,11 @@ typedef struct gnn_opts {
     int32_t dtype;         /* gnn_dtype of X and Y (same for both).  Accumulation is always fp32;
                               BF16 output is rounded to nearest-even once, at the store. */
     int32_t indptr_is_64;  /* 0: indptr is int32_t[N+1];  1: int64_t[N+1] */
-    int64_t ldx;           /* row stride of the gathered matrix in elements; 0 means F */
+    int64_t ldx;           /* row stride of the gathered matrix in elements; 0 means F.  Fastest: a
+                              128-byte-aligned base and a stride that is an ODD multiple of 128 bytes
+                              (e.g. 288 floats for F = 256): rows are then gathered in place, slice by
+                              slice, with all L2 channels in use; other layouts of large matrices are
+                              first copied into such rows (plan-owned buffer) when a plan is given */
     int64_t ldy;           /* row stride of the output matrix in elements; 0 means F */
     void *stream;          /* hipStream_t to enqueue on; NULL = the null stream */
     gnn_plan *plan;        /* degree-binning plan OF THE GRAPH PASSED IN THE SAME CALL (forward plan
