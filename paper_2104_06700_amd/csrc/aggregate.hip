@@ -520,34 +520,13 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
     // small next to the E*F gather, buys 16-byte loads and the XCD column slices below.
     int64_t ldg = ldx;  // row stride of the matrix the kernel gathers from
     bool padded = false;
-    // Do column slices pay?  Unsliced, an XCD's 4 MB L2 holds whole rows (32768 / lines of them);
-    // sliced, one line each of 32768 rows.  Slicing is used when that wins at least 8 points of
-    // the gathers (a power-law graph of a few million vertices: +20..30 points; a 111 M-vertex
-    // graph with 2-line rows: ~+2 points, where the extra index reads and the loss of burst
-    // locality cost more than the hits bring: 103.8 -> 94.4 ms without slices).
-    bool slices_wanted = !(o.flags & GNN_FLAG_NO_COLUMN_SLICES);
-    if (slices_wanted && plan && plan->n_edges > 0 && o.max_slices == 0) {
-        const int64_t lines = (F * esz + 127) / 128;
-        const double gain = gnn_plan_top_share(plan, 32768) - gnn_plan_top_share(plan, 32768 / (lines > 0 ? lines : 1));
-        slices_wanted = gain >= 0.08;
-    }
+    const gnn_layout layout = gnn_choose_layout(plan, N, F, esz, ldx, reinterpret_cast<uintptr_t>(gathered) % 128 == 0,
+                                                o.flags, o.max_slices);
+    const bool slices_wanted = layout.slices_wanted;
     {
-        const bool lines_ok = (ldx % line_elems == 0) && reinterpret_cast<uintptr_t>(gathered) % 128 == 0;
         const int64_t row_bytes = F * esz;
-        // Column slices make XCD k read the same lines (k, k+S, ...) of every row.  With a row
-        // stride of an even number of lines those addresses share their low line-index bits and
-        // crowd a few of the XCD's 16 L2 channels (measured at F=256, 8 slices: 15.4 ms with
-        // 8-line rows, 12.5 ms with 9-line rows).  An odd stride spreads them over all channels,
-        // so the padded copy always has one, and line-aligned rows with an even stride are copied
-        // too when the gather (E rows) dwarfs the copy (N rows).
-        const bool even_stride = lines_ok && (ldx / line_elems) % 2 == 0;
-        const bool big = N * row_bytes >= (int64_t(32) << 20);
-        const bool worth_it = row_bytes >= 192 && big && slices_wanted &&
-                              (!lines_ok || (even_stride && row_bytes >= 768 && plan && plan->n_edges >= 16 * N));
-        if (plan && !(o.flags & GNN_FLAG_NO_PADDED_COPY) && (worth_it || (o.flags & GNN_FLAG_FORCE_PADDED_COPY))) {
-            int64_t pad_lines = (F + line_elems - 1) / line_elems;
-            pad_lines |= 1;  // odd
-            const int64_t ld_pad = pad_lines * line_elems;
+        if (layout.padded_copy) {
+            const int64_t ld_pad = layout.ld_pad;
             int rc = gnn_plan_padded(plan, N * ld_pad * esz);
             if (rc != GNN_OK) return rc;
             // widest chunk the source rows allow

@@ -56,6 +56,46 @@ static inline int64_t gnn_partial_ld(int64_t F) { return (F + 7) / 8 * 8; }
 // the boundary bucket is taken pro rata).
 double gnn_plan_top_share(const gnn_plan *plan, int64_t K);
 
+// Layout decisions shared by the hot calls and gnn_plan_prepare (which must reserve exactly what
+// a later call will use).
+struct gnn_layout {
+    bool slices_wanted;   // spread column slices over the XCDs
+    bool padded_copy;     // gather from a plan-owned copy with rows of an odd number of lines
+    int64_t ld_pad;       // row stride of that copy in elements
+};
+
+static inline gnn_layout gnn_choose_layout(const gnn_plan *plan, int64_t N, int64_t F, int esz, int64_t ldx,
+                                           bool base_line_aligned, int flags, int max_slices) {
+    gnn_layout L{};
+    const int64_t line_elems = 128 / esz;
+    const int64_t lines = (F + line_elems - 1) / line_elems;
+    const int64_t row_bytes = F * esz;
+    // Do column slices pay?  Unsliced, an XCD's 4 MB L2 holds whole rows (32768 / lines of them);
+    // sliced, one line each of 32768 rows.  Slicing is used when that wins at least 8 points of
+    // the gathers (a power-law graph of a few million vertices: +20..30 points; a 111 M-vertex
+    // graph with 2-line rows: ~+2 points, where the extra index reads and the loss of burst
+    // locality cost more than the hits bring: 103.8 -> 94.4 ms without slices).
+    L.slices_wanted = !(flags & GNN_FLAG_NO_COLUMN_SLICES);
+    if (L.slices_wanted && plan && plan->n_edges > 0 && max_slices == 0) {
+        const double gain = gnn_plan_top_share(plan, 32768) - gnn_plan_top_share(plan, 32768 / (lines > 0 ? lines : 1));
+        L.slices_wanted = gain >= 0.08;
+    }
+    // Column slices make XCD k read the same lines (k, k+S, ...) of every row.  With a row stride
+    // of an even number of lines those addresses share their low line-index bits and crowd a few
+    // of the XCD's 16 L2 channels (measured at F=256, 8 slices: 15.4 ms with 8-line rows, 12.5 ms
+    // with 9-line rows).  An odd stride spreads them over all channels, so the padded copy always
+    // has one; rows that are not whole lines, and line-aligned rows of >= 768 bytes with an even
+    // stride when the gather (E rows) dwarfs the copy (N rows), are copied when slices are wanted.
+    const bool lines_ok = (ldx % line_elems == 0) && base_line_aligned;
+    const bool even_stride = lines_ok && (ldx / line_elems) % 2 == 0;
+    const bool big = N * row_bytes >= (int64_t(32) << 20);
+    const bool worth_it = row_bytes >= 192 && big && L.slices_wanted &&
+                          (!lines_ok || (even_stride && row_bytes >= 768 && plan && plan->n_edges >= 16 * N));
+    L.padded_copy = plan && !(flags & GNN_FLAG_NO_PADDED_COPY) && (worth_it || (flags & GNN_FLAG_FORCE_PADDED_COPY));
+    L.ld_pad = (lines | 1) * line_elems;
+    return L;
+}
+
 // Makes plan->padded at least `bytes` large (allocation on growth).
 int gnn_plan_padded(gnn_plan *plan, int64_t bytes);
 

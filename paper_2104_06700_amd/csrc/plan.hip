@@ -244,11 +244,13 @@ extern "C" GNN_API int gnn_plan_prepare(gnn_plan *plan, const int32_t *indices, 
     if (dtype != GNN_F32 && dtype != GNN_BF16) return GNN_ERR_INVALID_ARG;
     int rc = gnn_plan_reserve(plan, F);
     if (rc != GNN_OK) return rc;
-    const int64_t esz = dtype == GNN_BF16 ? 2 : 4, line_elems = 128 / esz;
-    {   // the padded copy (odd number of 128-byte lines per row) that a hot call may use
-        const int64_t pad_lines = ((F + line_elems - 1) / line_elems) | 1;
-        rc = gnn_plan_padded(plan, plan->n_rows * pad_lines * line_elems * esz);
-        if (rc != GNN_OK) return rc;
+    const int esz = dtype == GNN_BF16 ? 2 : 4;
+    {   // the padded copy a hot call on a dense, line-aligned matrix (ld = F) would use, if any
+        const gnn_layout layout = gnn_choose_layout(plan, plan->n_rows, F, esz, F, true, 0, 0);
+        if (layout.padded_copy) {
+            rc = gnn_plan_padded(plan, plan->n_rows * layout.ld_pad * esz);
+            if (rc != GNN_OK) return rc;
+        }
     }
     const float *unused = nullptr;
     if (op == GNN_MEAN && backward) rc = gnn_plan_edge_scale(plan, indices, 1, static_cast<hipStream_t>(stream), &unused);
