@@ -84,13 +84,14 @@ static inline gnn_layout gnn_choose_layout(const gnn_plan *plan, int64_t N, int6
     // of an even number of lines those addresses share their low line-index bits and crowd a few
     // of the XCD's 16 L2 channels (measured at F=256, 8 slices: 15.4 ms with 8-line rows, 12.5 ms
     // with 9-line rows).  An odd stride spreads them over all channels, so the padded copy always
-    // has one; rows that are not whole lines, and line-aligned rows of >= 768 bytes with an even
-    // stride when the gather (E rows) dwarfs the copy (N rows), are copied when slices are wanted.
+    // has one; rows that are not whole lines, and line-aligned rows with an even stride when the
+    // gather (E rows) dwarfs the copy (N rows: >= 16 edges per vertex for rows of >= 768 bytes,
+    // >= 128 for shorter ones), are copied when slices are wanted.
     const bool lines_ok = (ldx % line_elems == 0) && base_line_aligned;
     const bool even_stride = lines_ok && (ldx / line_elems) % 2 == 0;
     const bool big = N * row_bytes >= (int64_t(32) << 20);
     const bool worth_it = row_bytes >= 192 && big && L.slices_wanted &&
-                          (!lines_ok || (even_stride && row_bytes >= 768 && plan && plan->n_edges >= 16 * N));
+                          (!lines_ok || (even_stride && plan && plan->n_edges >= (row_bytes >= 768 ? 16 : 128) * N));
     L.padded_copy = plan && !(flags & GNN_FLAG_NO_PADDED_COPY) && (worth_it || (flags & GNN_FLAG_FORCE_PADDED_COPY));
     L.ld_pad = (lines | 1) * line_elems;
     return L;

@@ -376,3 +376,74 @@ def test_stream_and_repeatability():
         s.synchronize()
         outs.append(Y)
     assert torch.equal(outs[0], outs[1])
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_randomised_shapes_and_options(seed):
+    """Seeded random draws over graph shape, width, dtype, op, weights, bin thresholds, hub
+    piece size, row strides, base offsets and the layout switches; every draw must match the
+    oracle in both directions."""
+    rng = np.random.default_rng(1000 + seed)
+    n = int(rng.integers(1, 6000))
+    e = int(rng.integers(0, 40 * n + 1))
+    kind = rng.choice(["multi", "rmat", "star"])
+    if kind == "multi" or n < 64:
+        el = synth.small_random_multigraph(n, max(e, 1), seed) if e > 0 else synth.EdgeList(
+            n, torch.zeros(0, dtype=torch.int32), torch.zeros(0, dtype=torch.int32))
+    elif kind == "rmat":
+        e = min(e - e % 2, n * (n - 1) // 4 * 2)
+        el = synth.rmat_symmetric(n, max(e, 2), (0.57, 0.19, 0.19, 0.05), seed)
+    else:
+        leaves = torch.arange(1, n, dtype=torch.int32)
+        zeros = torch.zeros(n - 1, dtype=torch.int32)
+        el = synth.EdgeList(n, torch.cat([leaves, zeros]), torch.cat([zeros, leaves]))
+    f = int(rng.choice([1, 2, 3, 5, 8, 17, 32, 33, 64, 96, 100, 128, 160, 255, 256, 288, 602, 640, 1024, 1100]))
+    dtype = torch.bfloat16 if rng.random() < 0.35 else torch.float32
+    op_name = str(rng.choice(["sum", "mean", "gcn", "sage"]))
+    weights = None
+    if rng.random() < 0.4 and el.e > 0:
+        weights = torch.from_numpy(rng.uniform(0.1, 2.0, el.e).astype(np.float32))
+    k = int(rng.integers(0, 6))
+    thr = sorted(set(int(t) for t in rng.integers(1, 200, size=k)))
+    params = gnn.make_plan_params(thr, int(rng.choice([0, 3, 16, 64, 1024])))
+    flags = int(rng.choice([0, gnn.GNN_FLAG_FORCE_PADDED_COPY, gnn.GNN_FLAG_NO_COLUMN_SLICES, gnn.GNN_FLAG_NO_PADDED_COPY]))
+    max_slices = int(rng.choice([0, 0, 2, 4, 8]))
+    ld = f + int(rng.choice([0, 0, 1, 3, 32, 96]))
+    off = int(rng.choice([0, 0, 1, 4, 32]))
+
+    op = OP_CODE[op_name]
+    bf16 = dtype == torch.bfloat16
+    dg = device_graph(el, weights=weights, plan_params=params)
+    indptr, indices, indptr_t, indices_t, perm = host_csr(el)
+    din, dout = np.diff(indptr), np.diff(indptr_t)
+    w = None if weights is None else weights.numpy()
+    wt = None if w is None else w[perm]
+    what = f"seed={seed} n={el.n} e={el.e} f={f} {dtype} {op_name} w={w is not None} thr={thr} flags={flags} S<={max_slices} ld={ld} off={off}"
+    print(what, flush=True)
+
+    def strided(seed_):
+        base = synth.normal_features(el.n, ld + 1, seed_, dtype=dtype).to(DEV).view(-1)
+        need = off + (el.n - 1) * ld + f
+        assert base.numel() >= need
+        return base, torch.as_strided(base, (el.n, f), (ld, 1), storage_offset=off)
+
+    _, X = strided(1)
+    _, dY = strided(2)
+    out_buf = torch.full((el.n * ld + off + 8,), float("nan"), dtype=dtype, device=DEV)
+    out = torch.as_strided(out_buf, (el.n, f), (ld, 1), storage_offset=off)
+    gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, dg.edge_w, X, out, el.n, f, op, plan=dg.plan_fwd, ldx=ld, ldy=ld,
+                          flags=flags, max_slices=max_slices)
+    torch.cuda.synchronize()
+    Yo, S = oracle.aggregate_fwd(indptr, indices, X.float().cpu().numpy(), op=op, w=w, dout=dout, nthreads=8, want_scale=True)
+    assert_close(out, Yo, S, bf16, "fwd " + what)
+    written = torch.zeros(out_buf.numel(), dtype=torch.bool, device=DEV)
+    torch.as_strided(written, (el.n, f), (ld, 1), storage_offset=off).fill_(True)
+    assert torch.isnan(out_buf[~written]).all(), "stores outside the output rows: " + what
+    out_buf.fill_(float("nan"))
+    gnn.gnn_aggregate_bwd(dg.indptr_t, dg.indices_t, dg.edge_w_t, dY, out, el.n, f, op, plan=dg.plan_bwd, ldx=ld, ldy=ld,
+                          flags=flags, max_slices=max_slices)
+    torch.cuda.synchronize()
+    dXo, St = oracle.aggregate_bwd(indptr_t, indices_t, dY.float().cpu().numpy(), op=op, wt=wt, din=din, nthreads=8,
+                                   want_scale=True)
+    assert_close(out, dXo, St, bf16, "bwd " + what)
+    assert torch.isnan(out_buf[~written]).all(), "stores outside the output rows: " + what
