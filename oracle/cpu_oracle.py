@@ -17,20 +17,23 @@ OP_SUM, OP_MEAN, OP_GCN_SYM, OP_SAGE_GCN = 0, 1, 2, 3
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "oracle.c")
+_SRC_AP = os.path.join(_HERE, "ap_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
 _lib = None
 _lib_path = _LIB
 
 
-def compile_c(src: str, out: str) -> None:
-    subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-std=c11",
-                           "-Wall", "-Wextra", "-o", out, src, "-lm"])
+def compile_c(src, out: str) -> None:
+    srcs = [src] if isinstance(src, str) else list(src)
+    subprocess.check_call(["gcc", "-O2", "-fopenmp", "-ffp-contract=off", "-shared", "-fPIC", "-std=c11",
+                           "-Wall", "-Wextra", "-o", out, *srcs, "-lm"])
 
 
 def build_oracle(force: bool = False) -> str:
-    """Compile oracle.c with gcc (-O2, OpenMP, no fast-math)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        compile_c(_SRC, _LIB)
+    """Compile oracle.c and ap_oracle.c with gcc (-O2, OpenMP, no fast-math, no contraction)."""
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_AP))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
+        compile_c([_SRC, _SRC_AP], _LIB)
     return _LIB
 
 
@@ -38,8 +41,9 @@ def _open(path: str):
     lib = ctypes.CDLL(path)
     lib.oracle_max_threads.restype = ctypes.c_int
     for name in ("oracle_aggregate_fwd", "oracle_aggregate_bwd", "oracle_csr_indptr",
-                 "oracle_transpose", "oracle_plan"):
-        getattr(lib, name).restype = ctypes.c_int
+                 "oracle_transpose", "oracle_plan", "oracle_ap_fwd", "oracle_ap_bwd"):
+        if hasattr(lib, name):  # a mutated single-file build holds only its own functions
+            getattr(lib, name).restype = ctypes.c_int
     return lib
 
 
@@ -166,3 +170,69 @@ def plan(indptr, thresholds, hub_chunk: int):
     if rc != 0:
         raise ValueError(f"oracle_plan failed (code {rc})")
     return bin_offsets, row_perm, chunks
+
+
+# ---------------------------------------------------------------- general primitive (Table 1)
+BIN_ADD, BIN_SUB, BIN_MUL, BIN_DIV, BIN_COPY_LHS, BIN_COPY_RHS = range(6)
+RED_SUM, RED_MAX, RED_MIN = range(3)
+
+
+def _ap_common(indptr, indices, fV, fE, d, eid):
+    indptr = _i64(indptr)
+    indices = _i32(indices)
+    fV = None if fV is None else _f32(fV)
+    fE = None if fE is None else _f32(fE)
+    if fE is not None and fE.ndim == 1:
+        fE = fE.reshape(-1, 1)
+    eid = None if eid is None else _i64(eid)
+    ldv = 0 if fV is None else fV.shape[1]
+    lde = 0 if fE is None else fE.shape[1]
+    ewidth = d if fE is None else fE.shape[1]
+    assert indices.shape[0] == indptr[-1]
+    if fV is not None:
+        assert fV.shape[1] == d
+        assert indices.size == 0 or (indices.min() >= 0 and indices.max() < fV.shape[0])
+    if fE is not None:
+        rows = indices if eid is None else eid
+        assert rows.size == 0 or (eid is None and fE.shape[0] >= indices.shape[0]) or \
+            (eid is not None and eid.min() >= 0 and eid.max() < fE.shape[0])
+    return indptr, indices, fV, fE, eid, ldv, lde, ewidth
+
+
+def ap_fwd(indptr, indices, fV, fE, d, binop, reduce, eid=None):
+    """(O float64[N, d], S float64[N, d]) for the sum reducer, (O, arg int64[N, d]) for max / min."""
+    lib = _load()
+    indptr, indices, fV, fE, eid, ldv, lde, ewidth = _ap_common(indptr, indices, fV, fE, d, eid)
+    n = indptr.shape[0] - 1
+    O = np.empty((n, d), dtype=np.float64)
+    S = np.empty((n, d), dtype=np.float64) if reduce == RED_SUM else None
+    arg = np.empty((n, d), dtype=np.int64) if reduce != RED_SUM else None
+    rc = lib.oracle_ap_fwd(_p(indptr), _p(indices), _p(eid), _p(fV), ctypes.c_int64(ldv), _p(fE), ctypes.c_int64(lde),
+                           ctypes.c_int64(ewidth), _p(O), _p(S), _p(arg), ctypes.c_int64(n), ctypes.c_int64(d),
+                           ctypes.c_int(binop), ctypes.c_int(reduce))
+    if rc != 0:
+        raise ValueError(f"oracle_ap_fwd rejected its arguments (code {rc})")
+    return O, (S if reduce == RED_SUM else arg)
+
+
+def ap_bwd(indptr, indices, fV, fE, dO, d, binop, reduce, eid=None, arg=None, n_vertex_rows=None, n_edge_rows=None):
+    """((dV, SV), (dE, SE)): gradients with respect to f_V and f_E and their magnitude sums."""
+    lib = _load()
+    indptr, indices, fV, fE, eid, ldv, lde, ewidth = _ap_common(indptr, indices, fV, fE, d, eid)
+    n = indptr.shape[0] - 1
+    dO = _f32(dO)
+    assert dO.shape == (n, d)
+    arg = None if arg is None else _i64(arg)
+    nv = n_vertex_rows if n_vertex_rows is not None else (fV.shape[0] if fV is not None else n)
+    ne = n_edge_rows if n_edge_rows is not None else (fE.shape[0] if fE is not None else indices.shape[0])
+    dV = np.empty((nv, d), dtype=np.float64)
+    SV = np.empty((nv, d), dtype=np.float64)
+    dE = np.empty((ne, ewidth), dtype=np.float64)
+    SE = np.empty((ne, ewidth), dtype=np.float64)
+    rc = lib.oracle_ap_bwd(_p(indptr), _p(indices), _p(eid), _p(fV), ctypes.c_int64(ldv), _p(fE), ctypes.c_int64(lde),
+                           ctypes.c_int64(ewidth), _p(dO), ctypes.c_int64(d), _p(arg), _p(dV), _p(SV), ctypes.c_int64(nv),
+                           _p(dE), _p(SE), ctypes.c_int64(ne), ctypes.c_int64(n), ctypes.c_int64(d),
+                           ctypes.c_int(binop), ctypes.c_int(reduce))
+    if rc != 0:
+        raise ValueError(f"oracle_ap_bwd rejected its arguments (code {rc})")
+    return (dV, SV), (dE, SE)
