@@ -130,6 +130,75 @@ GNN_API int gnn_aggregate_fwd(const void *indptr, const int32_t *indices, const 
 GNN_API int gnn_aggregate_bwd(const void *indptr_t, const int32_t *indices_t, const float *edge_w_t,
                       const void *dY, void *dX, int64_t N, int64_t F, int op, const gnn_opts *opts);
 
+/* ------------------------------------- general aggregation primitive (fp32) */
+
+/* The operator table of Section 4.1 (Table 1).  x = f_V[u, j] of the source vertex, y = f_E[e, j]
+ * of the edge; copylhs ignores y, copyrhs ignores x. */
+typedef enum gnn_binop {
+    GNN_BIN_ADD = 0, GNN_BIN_SUB = 1, GNN_BIN_MUL = 2, GNN_BIN_DIV = 3, GNN_BIN_COPY_LHS = 4, GNN_BIN_COPY_RHS = 5
+} gnn_binop;
+typedef enum gnn_reduce { GNN_RED_SUM = 0, GNN_RED_MAX = 1, GNN_RED_MIN = 2 } gnn_reduce;
+
+/* Options of the gnn_ap_* calls.  Zero-initialise, then set what differs. */
+typedef struct gnn_ap_opts {
+    int32_t indptr_is_64;     /* as in gnn_opts */
+    int32_t edge_width;       /* columns of f_E in use: 0 or d = one per feature column; 1 = one scalar
+                                 per edge that serves every column */
+    int64_t ldv, lde, ldo;    /* row strides in floats of f_V, f_E and f_O (and of their gradients);
+                                 0 = d, edge_width, d */
+    const int64_t *edge_ids;  /* [E] device, or NULL: the row of f_E that the edge at CSR position e
+                                 uses (NULL: row e).  A transposed graph passes the `perm` of
+                                 gnn_transpose_csr here to keep addressing the original edge rows.
+                                 Must not name a row twice when an edge gradient is written. */
+    void *stream;
+    gnn_plan *plan;           /* plan of the graph passed in the same call, or NULL (no binning) */
+    int32_t flags;            /* reserved, 0 */
+    int32_t reserved;
+} gnn_ap_opts;
+
+/* Algorithm 1 with any operator pair of Table 1:
+ *     f_O[v, j] = reduce over the edges e = (u -> v) of row v of  binop(f_V[u, j], f_E[e, j])
+ * f_V [*, ldv] (not read by copyrhs, may be NULL then), f_E [*, lde] (not read by copylhs),
+ * f_O [N, ldo] is overwritten.  The reduction starts from the identity of `reduce`; a row without
+ * edges yields 0.  sum accumulates in fp32.  max / min: every message is one correctly rounded
+ * fp32 operation, so the result is exact; arg_e (optional, int32 [N, d], dense) receives the CSR
+ * position of the winning edge of every (v, j) -- the lowest position among equals, -1 for an
+ * empty row -- and must be NULL for sum.  NaN inputs give an unspecified winner.  max / min need
+ * E <= INT32_MAX.  16-byte loads are used when d, the strides and the base addresses allow,
+ * scalar ones otherwise.  Hub rows use plan-owned scratch (grown on first use: allocation).
+ * Asynchronous on opts->stream. */
+GNN_API int gnn_ap_fwd(const void *indptr, const int32_t *indices, const float *fV, const float *fE,
+                       float *fO, int32_t *arg_e, int64_t N, int64_t d, int binop, int reduce,
+                       const gnn_ap_opts *opts);
+
+/* Gradient of sum_{v,j} dO[v,j] f_O[v,j] with respect to f_V for reduce = sum (the paper does not
+ * spell out backward passes; this is the derivative of the definition above).  It is the same
+ * primitive over the TRANSPOSED graph, gathering dO: copylhs for add / sub / copylhs, mul by f_E
+ * for mul, div by f_E for div, zero for copyrhs.  indptr_t / indices_t / opts (plan, edge_ids =
+ * perm, or perm composed with the forward edge_ids) describe the transposed graph.  dfV [N, ldv]
+ * is overwritten. */
+GNN_API int gnn_ap_bwd_vertex(const void *indptr_t, const int32_t *indices_t, const float *dO, const float *fE,
+                              float *dfV, int64_t N, int64_t d, int binop, const gnn_ap_opts *opts);
+
+/* The same gradient for reduce = max / min, where only the winning edge of each (v, j) carries
+ * gradient: dfV[indices[arg_e[v,j]], j] += dO[v,j] * d(binop)/dx.  Runs over the FORWARD graph's
+ * `indices` and the arg_e that gnn_ap_fwd wrote; N*d fp32 atomic adds into dfV [n_vertex_rows, ldv]
+ * (zero-filled first), so the summation order, and with it the last bits, vary from run to run. */
+GNN_API int gnn_ap_bwd_vertex_arg(const int32_t *indices, const int32_t *arg_e, const float *dO, const float *fE,
+                                  float *dfV, int64_t n_vertex_rows, int64_t N, int64_t d, int binop,
+                                  const gnn_ap_opts *opts);
+
+/* Gradient with respect to f_E, one output row per edge (the sampled dense-dense product of
+ * Section 2.2 when edge_width = 1 and binop = mul: dfE[e] = <dO[v, :], f_V[u, :]>):
+ *     dfE[r(e), j] = dO[v, j] * d(binop)/dy          add: 1, sub: -1, mul: x, div: -x / y^2, copyrhs: 1
+ * summed over j when edge_width = 1; for max / min (arg_e != NULL) only where arg_e[v, j] == e,
+ * zero elsewhere.  Runs over the forward graph; r(e) = edge_ids[e] or e; dfE has f_E's layout
+ * (lde) and every row an edge names is overwritten.  copylhs has no edge operand:
+ * GNN_ERR_INVALID_ARG. */
+GNN_API int gnn_ap_bwd_edge(const void *indptr, const int32_t *indices, const int32_t *arg_e, const float *fV,
+                            const float *fE, const float *dO, float *dfE, int64_t N, int64_t d, int binop,
+                            const gnn_ap_opts *opts);
+
 /* ------------------------------------------------------- once-per-graph setup */
 
 /* Row pointers of the destination-indexed CSR (Section 4.1 requires the graph

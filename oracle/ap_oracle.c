@@ -78,6 +78,8 @@ int oracle_ap_fwd(const int64_t *indptr, const int32_t *indices, const int64_t *
     if (ewidth != d && ewidth != 1) return 2;
     if (bin != BIN_COPY_RHS && !fV) return 3;
     if (bin != BIN_COPY_LHS && !fE) return 4;
+    /* rows are independent, so threads over rows change nothing in the results */
+#pragma omp parallel for schedule(dynamic, 64)
     for (int64_t v = 0; v < N; ++v) {
         for (int64_t j = 0; j < d; ++j) {
             double acc = 0.0, mag = 0.0;

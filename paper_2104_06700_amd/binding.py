@@ -22,12 +22,15 @@ GNN_MAX_THRESHOLDS = 15
 GNN_FLAG_NO_COLUMN_SLICES = 1
 GNN_FLAG_NO_PADDED_COPY = 2
 GNN_FLAG_FORCE_PADDED_COPY = 4
+GNN_BIN_ADD, GNN_BIN_SUB, GNN_BIN_MUL, GNN_BIN_DIV, GNN_BIN_COPY_LHS, GNN_BIN_COPY_RHS = range(6)
+GNN_RED_SUM, GNN_RED_MAX, GNN_RED_MIN = range(3)
 
 EXPORTED_SYMBOLS = (
     "gnn_aggregate_fwd", "gnn_aggregate_bwd", "gnn_csr_from_sorted_coo", "gnn_transpose_csr",
     "gnn_validate_csr", "gnn_plan_default_params", "gnn_plan_create", "gnn_plan_destroy",
     "gnn_plan_sizes", "gnn_plan_export", "gnn_plan_gather_share", "gnn_plan_workspace_bytes", "gnn_plan_reserve",
     "gnn_plan_prepare",
+    "gnn_ap_fwd", "gnn_ap_bwd_vertex", "gnn_ap_bwd_vertex_arg", "gnn_ap_bwd_edge",
     "gnn_status_string", "gnn_calib_copy",
 )
 
@@ -39,6 +42,15 @@ class GnnOpts(ctypes.Structure):
         ("stream", ctypes.c_void_p), ("plan", ctypes.c_void_p),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_int64),
         ("flags", ctypes.c_int32), ("max_slices", ctypes.c_int32),
+    ]
+
+
+class GnnApOpts(ctypes.Structure):
+    _fields_ = [
+        ("indptr_is_64", ctypes.c_int32), ("edge_width", ctypes.c_int32),
+        ("ldv", ctypes.c_int64), ("lde", ctypes.c_int64), ("ldo", ctypes.c_int64),
+        ("edge_ids", ctypes.c_void_p), ("stream", ctypes.c_void_p), ("plan", ctypes.c_void_p),
+        ("flags", ctypes.c_int32), ("reserved", ctypes.c_int32),
     ]
 
 
@@ -86,6 +98,11 @@ def load_library() -> ctypes.CDLL:
         lib.gnn_plan_workspace_bytes.restype = i64
         lib.gnn_plan_reserve.argtypes = [vp, i64]
         lib.gnn_plan_prepare.argtypes = [vp, vp, i32, i32, i64, i32, vp]
+        ap = ctypes.POINTER(GnnApOpts)
+        lib.gnn_ap_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i32, i32, ap]
+        lib.gnn_ap_bwd_vertex.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, ap]
+        lib.gnn_ap_bwd_vertex_arg.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, ap]
+        lib.gnn_ap_bwd_edge.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i32, ap]
         lib.gnn_status_string.argtypes = [i32]
         lib.gnn_status_string.restype = ctypes.c_char_p
         lib.gnn_calib_copy.argtypes = [vp, vp, i64, vp]
@@ -247,6 +264,85 @@ def gnn_aggregate_bwd(indptr_t, indices_t, edge_w_t, dY, dX, N, F, op, plan: Opt
     """dX = adjoint of the forward map, over the transposed graph (see include/gnnagg.h)."""
     _aggregate("gnn_aggregate_bwd", indptr_t, indices_t, edge_w_t, dY, dX, N, F, op, plan, stream, workspace, ldx, ldy, flags,
                max_slices)
+
+
+def _row_stride(t: Optional[torch.Tensor]) -> int:
+    if t is None or t.dim() != 2 or t.shape[0] <= 1:
+        return 0
+    if t.stride(1) != 1:
+        raise ValueError("feature matrices must have unit column stride")
+    return int(t.stride(0))
+
+
+def _ap_opts(indptr, plan, stream, edge_ids, edge_width, ldv, lde, ldo) -> GnnApOpts:
+    o = GnnApOpts()
+    o.indptr_is_64 = 0 if indptr is None else _is64(indptr)
+    o.edge_width = int(edge_width)
+    o.ldv, o.lde, o.ldo = int(ldv), int(lde), int(ldo)
+    if edge_ids is not None:
+        if edge_ids.dtype != torch.int64:
+            raise TypeError("edge_ids must be int64")
+        o.edge_ids = _ptr(edge_ids)
+    o.stream = _stream(stream)
+    o.plan = plan.handle if plan is not None else None
+    return o
+
+
+def _edge_width(fE: Optional[torch.Tensor], d: int) -> int:
+    if fE is None:
+        return 0
+    return 1 if (fE.dim() == 1 or fE.shape[1] == 1) and d != 1 else 0
+
+
+def _f32(*tensors) -> None:
+    for t in tensors:
+        if t is not None and t.dtype != torch.float32:
+            raise TypeError("the general primitive takes float32 features")
+
+
+def gnn_ap_fwd(indptr, indices, fV, fE, fO, arg_e, N, d, binop, reduce, plan: Optional[Plan] = None, edge_ids=None,
+               stream=None) -> None:
+    """f_O[v] = reduce_e binop(f_V[u_e], f_E[e]) with any operator pair of Table 1 (see include/gnnagg.h).
+    f_E may be [E, d] or [E] / [E, 1] (one scalar per edge)."""
+    _f32(fV, fE, fO)
+    if arg_e is not None and (arg_e.dtype != torch.int32 or not arg_e.is_contiguous()):
+        raise TypeError("arg_e must be a contiguous int32 tensor")
+    o = _ap_opts(indptr, plan, stream, edge_ids, _edge_width(fE, d), _row_stride(fV), _row_stride(fE) if fE is not None and fE.dim() == 2 else 0,
+                 _row_stride(fO))
+    _call_allocating("gnn_ap_fwd", lambda: load_library().gnn_ap_fwd(
+        _ptr(indptr), _ptr(indices), _ptr(fV), _ptr(fE), _ptr(fO), _ptr(arg_e), int(N), int(d), int(binop), int(reduce),
+        ctypes.byref(o)))
+
+
+def gnn_ap_bwd_vertex(indptr_t, indices_t, dO, fE, dfV, N, d, binop, plan: Optional[Plan] = None, edge_ids=None,
+                      stream=None) -> None:
+    """Gradient with respect to f_V for the sum reducer, over the transposed graph (see include/gnnagg.h)."""
+    _f32(dO, fE, dfV)
+    o = _ap_opts(indptr_t, plan, stream, edge_ids, _edge_width(fE, d), _row_stride(dfV),
+                 _row_stride(fE) if fE is not None and fE.dim() == 2 else 0, _row_stride(dO))
+    _call_allocating("gnn_ap_bwd_vertex", lambda: load_library().gnn_ap_bwd_vertex(
+        _ptr(indptr_t), _ptr(indices_t), _ptr(dO), _ptr(fE), _ptr(dfV), int(N), int(d), int(binop), ctypes.byref(o)))
+
+
+def gnn_ap_bwd_vertex_arg(indices, arg_e, dO, fE, dfV, n_vertex_rows, N, d, binop, edge_ids=None, stream=None) -> None:
+    """Gradient with respect to f_V for max / min: scatter to the winners (see include/gnnagg.h)."""
+    _f32(dO, fE, dfV)
+    o = _ap_opts(None, None, stream, edge_ids, _edge_width(fE, d), _row_stride(dfV),
+                 _row_stride(fE) if fE is not None and fE.dim() == 2 else 0, _row_stride(dO))
+    _check("gnn_ap_bwd_vertex_arg", load_library().gnn_ap_bwd_vertex_arg(
+        _ptr(indices), _ptr(arg_e), _ptr(dO), _ptr(fE), _ptr(dfV), int(n_vertex_rows), int(N), int(d), int(binop),
+        ctypes.byref(o)))
+
+
+def gnn_ap_bwd_edge(indptr, indices, arg_e, fV, fE, dO, dfE, N, d, binop, plan: Optional[Plan] = None, edge_ids=None,
+                    stream=None) -> None:
+    """Gradient with respect to f_E, one row per edge (see include/gnnagg.h).  dfE has f_E's shape."""
+    _f32(fV, fE, dO, dfE)
+    o = _ap_opts(indptr, plan, stream, edge_ids, _edge_width(dfE, d), _row_stride(fV),
+                 _row_stride(dfE) if dfE.dim() == 2 else 0, _row_stride(dO))
+    _check("gnn_ap_bwd_edge", load_library().gnn_ap_bwd_edge(
+        _ptr(indptr), _ptr(indices), _ptr(arg_e), _ptr(fV), _ptr(fE), _ptr(dO), _ptr(dfE), int(N), int(d), int(binop),
+        ctypes.byref(o)))
 
 
 def gnn_csr_from_sorted_coo(dst_sorted: torch.Tensor, N: int, indptr_out: torch.Tensor, stream=None) -> None:

@@ -698,7 +698,7 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
             // heaviest work first: hub pieces, then bins from long rows to short rows
             if (has_hub) add_bin(kKindHubPieces, 0, plan->n_chunks, max_log2_sr);
             for (int bi = last; bi >= 0; --bi) {
-                if (bi == last && plan->params.hub_chunk > 0) continue;  // handled as pieces (+ finalize)
+                if (bi == last && has_hub) continue;  // handled as pieces (+ finalize)
                 const int64_t lo = bi == 0 ? 0 : plan->params.thresholds[bi - 1];
                 // Edge slots per row: enough that the shortest row of the bin still takes ~16
                 // steps (several batches of loads per group), so short rows share a wavefront

@@ -38,6 +38,8 @@ def test_struct_layout_matches_header():
     # gnn_opts: 2 x int32, 2 x int64, 3 pointers, int64, 2 x int32; gnn_plan_params: int32 (+pad), 15 x int64, int64
     assert ctypes.sizeof(gnn.GnnOpts) == 8 + 16 + 24 + 8 + 8
     assert ctypes.sizeof(gnn.GnnPlanParams) == 8 + 15 * 8 + 8
+    # gnn_ap_opts: 2 x int32, 3 x int64, 3 pointers, 2 x int32
+    assert ctypes.sizeof(gnn.GnnApOpts) == 8 + 24 + 24 + 8
 
 
 def test_argument_checks_that_need_no_device():
@@ -61,3 +63,23 @@ def test_argument_checks_that_need_no_device():
     assert lib.gnn_csr_from_sorted_coo(None, 5, 5, one, 0, None) == gnn.GNN_ERR_INVALID_ARG
     assert lib.gnn_calib_copy(one, one, 7, None) == gnn.GNN_ERR_INVALID_ARG
     assert gnn.load_library().gnn_plan_workspace_bytes(None, 4) == 0
+    # general primitive
+    a = gnn.GnnApOpts()
+    bad, ok = gnn.GNN_ERR_INVALID_ARG, gnn.GNN_OK
+    assert lib.gnn_ap_fwd(one, one, one, one, one, None, 4, 4, 9, 0, ctypes.byref(a)) == bad       # unknown binop
+    assert lib.gnn_ap_fwd(one, one, one, one, one, None, 4, 4, 0, 7, ctypes.byref(a)) == bad       # unknown reduce
+    assert lib.gnn_ap_fwd(one, one, one, one, one, one, 4, 4, 0, 0, ctypes.byref(a)) == bad        # winners asked of a sum
+    assert lib.gnn_ap_fwd(one, one, one, one, one, None, 0, 4, 0, 0, None) == ok
+    assert lib.gnn_ap_fwd(one, one, None, one, one, None, 4, 4, 0, 0, None) == bad                 # add needs f_V
+    assert lib.gnn_ap_fwd(one, one, one, None, one, None, 4, 4, 2, 1, None) == bad                 # mul needs f_E
+    a.edge_width = 3
+    assert lib.gnn_ap_fwd(one, one, one, one, one, None, 4, 4, 0, 0, ctypes.byref(a)) == bad       # width neither d nor 1
+    a.edge_width = 0
+    a.ldo = 2
+    assert lib.gnn_ap_fwd(one, one, one, one, one, None, 4, 4, 0, 0, ctypes.byref(a)) == bad       # stride below d
+    a.ldo = 0
+    assert lib.gnn_ap_bwd_edge(one, one, None, one, one, one, one, 4, 4, gnn.GNN_BIN_COPY_LHS, ctypes.byref(a)) == bad
+    assert lib.gnn_ap_bwd_edge(one, one, None, None, one, one, one, 4, 4, gnn.GNN_BIN_MUL, ctypes.byref(a)) == bad
+    assert lib.gnn_ap_bwd_vertex(one, one, one, one, None, 4, 4, 0, ctypes.byref(a)) == bad
+    assert lib.gnn_ap_bwd_vertex(one, one, one, one, one, 4, 0, 0, ctypes.byref(a)) == ok
+    assert lib.gnn_ap_bwd_vertex_arg(one, one, one, one, one, -1, 4, 4, 0, ctypes.byref(a)) == bad

@@ -1,0 +1,203 @@
+"""GPU parity of the general aggregation primitive (operator table of Table 1) and its
+gradients against the CPU oracle: exact for max / min (values and winners), within
+1e-5 of the magnitude sum for everything summed."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2104_06700_amd as gnn
+import synth
+from helpers import RTOL_F32, device_graph, host_csr
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+BINOPS = {"add": 0, "sub": 1, "mul": 2, "div": 3, "copylhs": 4, "copyrhs": 5}
+REDUCES = {"sum": 0, "max": 1, "min": 2}
+
+
+def _graph(kind):
+    if kind == "multi":       # duplicates and self-loops, light rows
+        return synth.small_random_multigraph(700, 9000, 3), None
+    if kind == "rmat_hubs":   # power law; tiny hub pieces so that hub rows are cut into many
+        el = synth.rmat_symmetric(3000, 90000, (0.57, 0.19, 0.19, 0.05), 5)
+        return el, gnn.make_plan_params([2, 8, 32, 128], 48)
+    if kind == "star":        # one row with every edge, everything else empty
+        n = 5000
+        leaves = torch.arange(1, n, dtype=torch.int32)
+        return synth.EdgeList(n, leaves, torch.zeros(n - 1, dtype=torch.int32)), gnn.make_plan_params([4, 64], 100)
+    raise KeyError(kind)
+
+
+def _inputs(rng, n, e_rows, d, ewidth, ties):
+    if ties:  # few distinct values: many equal extrema, exact sums
+        fV = rng.integers(-2, 3, size=(n, d)).astype(np.float32)
+        fE = rng.choice(np.array([-2.0, -1.0, 1.0, 2.0], dtype=np.float32), size=(e_rows, ewidth))
+    else:
+        fV = rng.normal(size=(n, d)).astype(np.float32)
+        fE = rng.normal(size=(e_rows, ewidth)).astype(np.float32)
+        fE = (np.sign(fE) * (0.25 + np.abs(fE))).astype(np.float32)
+        fE[fE == 0] = 0.25
+    return fV, fE
+
+
+def _close(g, ref, S, what):
+    g = g.detach().cpu().numpy().astype(np.float64)
+    assert g.shape == ref.shape, (g.shape, ref.shape)
+    assert np.isfinite(g).all(), what
+    err = np.abs(g - ref)
+    bound = RTOL_F32 * S
+    bad = err > bound
+    if bad.any():
+        i = np.unravel_index(np.argmax(err - bound), err.shape)
+        raise AssertionError(f"{what}: {bad.sum()} of {bad.size} out of tolerance; worst at {i}: gpu={g[i]!r} "
+                             f"oracle={ref[i]!r} err={err[i]:.3e} bound={bound[i]:.3e}")
+    assert not g[S == 0].any(), what
+
+
+def _check_all(el, params, d, ewidth, use_eid, ties, seed, binops=BINOPS, reduces=REDUCES, use_plan=True):
+    rng = np.random.default_rng(seed)
+    dg = device_graph(el, plan_params=params, want_perm=True, with_plans=use_plan)
+    indptr, indices, indptr_t, indices_t, perm = host_csr(el)
+    n, E = el.n, el.e
+    e_rows = E + 5
+    eid = rng.permutation(e_rows)[:E].astype(np.int64) if use_eid else None
+    fV, fE = _inputs(rng, n, e_rows, d, ewidth, ties)
+    dO = rng.normal(size=(n, d)).astype(np.float32)
+    fV_d, fE_d, dO_d = (torch.from_numpy(a).to(DEV) for a in (fV, fE, dO))
+    eid_d = None if eid is None else torch.from_numpy(eid).to(DEV)
+    # edge ids of the transposed graph: CSR position, then the caller's row map
+    eid_t = dg.perm if eid is None else eid_d[dg.perm]
+    for bname, b in binops.items():
+        fv_arg = None if bname == "copyrhs" else fV_d
+        fe_arg = None if bname == "copylhs" else fE_d
+        for rname, r in reduces.items():
+            what = f"n={n} E={E} d={d} ewidth={ewidth} eid={use_eid} ties={ties} {bname}/{rname}"
+            print(what, flush=True)
+            out = torch.full((n, d), float("nan"), device=DEV)
+            arg = torch.full((n, d), -7, dtype=torch.int32, device=DEV) if r else None
+            gnn.gnn_ap_fwd(dg.indptr, dg.indices, fv_arg, fe_arg, out, arg, n, d, b, r, plan=dg.plan_fwd, edge_ids=eid_d)
+            torch.cuda.synchronize()
+            O, aux = oracle.ap_fwd(indptr, indices, None if bname == "copyrhs" else fV, None if bname == "copylhs" else fE,
+                                   d, b, r, eid=eid)
+            if rname == "sum":
+                _close(out, O, aux, "fwd " + what)
+            else:
+                assert np.array_equal(out.cpu().numpy().astype(np.float64), O), "fwd values " + what
+                assert np.array_equal(arg.cpu().numpy().astype(np.int64), aux), "fwd winners " + what
+            # gradients
+            arg_h = None if rname == "sum" else aux
+            (dV, SV), (dE, SE) = oracle.ap_bwd(indptr, indices, None if bname == "copyrhs" else fV,
+                                               None if bname == "copylhs" else fE, dO, d, b, r, eid=eid, arg=arg_h,
+                                               n_vertex_rows=n, n_edge_rows=e_rows)
+            dfV = torch.full((n, d), float("nan"), device=DEV)
+            if rname == "sum":
+                gnn.gnn_ap_bwd_vertex(dg.indptr_t, dg.indices_t, dO_d, fe_arg, dfV, n, d, b, plan=dg.plan_bwd, edge_ids=eid_t)
+            else:
+                gnn.gnn_ap_bwd_vertex_arg(dg.indices, arg, dO_d, fe_arg, dfV, n, n, d, b, edge_ids=eid_d)
+            torch.cuda.synchronize()
+            _close(dfV, dV, SV, "vertex gradient " + what)
+            if bname != "copylhs":
+                dfE = torch.full((e_rows, ewidth), float("nan"), device=DEV)
+                gnn.gnn_ap_bwd_edge(dg.indptr, dg.indices, arg, fv_arg, fe_arg, dO_d, dfE, n, d, b, plan=dg.plan_fwd, edge_ids=eid_d)
+                torch.cuda.synchronize()
+                g = dfE.cpu().numpy()
+                used = np.zeros(e_rows, dtype=bool)
+                used[np.arange(E) if eid is None else eid] = True
+                assert np.isnan(g[~used]).all(), "edge gradient wrote rows no edge names: " + what
+                _close(dfE[torch.from_numpy(used).to(DEV)], dE[used], SE[used], "edge gradient " + what)
+
+
+@pytest.mark.parametrize("kind", ["multi", "rmat_hubs", "star"])
+@pytest.mark.parametrize("d,ewidth", [(1, 1), (5, 5), (5, 1), (32, 32), (32, 1), (100, 100), (100, 1)])
+def test_every_operator_pair(kind, d, ewidth):
+    el, params = _graph(kind)
+    _check_all(el, params, d, ewidth, use_eid=False, ties=False, seed=d * 7 + ewidth)
+
+
+@pytest.mark.parametrize("kind", ["multi", "rmat_hubs"])
+@pytest.mark.parametrize("d,ewidth", [(8, 8), (8, 1), (36, 36)])
+def test_equal_values_pick_the_lowest_edge_position(kind, d, ewidth):
+    el, params = _graph(kind)
+    _check_all(el, params, d, ewidth, use_eid=False, ties=True, seed=11)
+
+
+@pytest.mark.parametrize("d,ewidth", [(4, 4), (12, 1), (64, 64)])
+def test_edge_ids_remap_the_edge_rows(d, ewidth):
+    el, params = _graph("rmat_hubs")
+    _check_all(el, params, d, ewidth, use_eid=True, ties=False, seed=13)
+
+
+def test_without_a_plan():
+    el, _ = _graph("multi")
+    _check_all(el, None, 16, 16, use_eid=False, ties=False, seed=17, use_plan=False)
+    _check_all(el, None, 7, 1, use_eid=True, ties=True, seed=18, use_plan=False)
+
+
+def test_wide_rows_span_several_column_slabs():
+    el = synth.small_random_multigraph(300, 4000, 21)
+    _check_all(el, gnn.make_plan_params([4, 16], 8), 520, 520, False, False, 23, binops={"mul": 2, "div": 3}, reduces=REDUCES)
+    _check_all(el, gnn.make_plan_params([4, 16], 8), 301, 1, False, False, 24, binops={"add": 0, "copylhs": 4}, reduces=REDUCES)
+
+
+def test_strided_and_misaligned_operands():
+    """Row strides larger than d and bases off the 16-byte grid take the scalar-access kernels."""
+    el, params = _graph("rmat_hubs")
+    rng = np.random.default_rng(31)
+    dg = device_graph(el, plan_params=params, want_perm=True)
+    indptr, indices, *_ = host_csr(el)
+    n, E, d = el.n, el.e, 12
+    for ldv, lde, ldo, off in ((12, 12, 12, 1), (13, 15, 17, 0), (16, 16, 16, 4)):
+        bufV = torch.randn(n * ldv + 8, device=DEV)
+        bufE = torch.randn(E * lde + 8, device=DEV).abs() + 0.5
+        bufO = torch.full((n * ldo + 8,), float("nan"), device=DEV)
+        fV = torch.as_strided(bufV, (n, d), (ldv, 1), off)
+        fE = torch.as_strided(bufE, (E, d), (lde, 1), off)
+        fO = torch.as_strided(bufO, (n, d), (ldo, 1), off)
+        for b, r in ((2, 0), (3, 1), (0, 2)):
+            bufO.fill_(float("nan"))
+            gnn.gnn_ap_fwd(dg.indptr, dg.indices, fV, fE, fO, None, n, d, b, r, plan=dg.plan_fwd)
+            torch.cuda.synchronize()
+            O, aux = oracle.ap_fwd(indptr, indices, fV.cpu().numpy(), fE.cpu().numpy(), d, b, r)
+            if r == 0:
+                _close(fO, O, aux, f"strided {ldv}/{lde}/{ldo}+{off} sum")
+            else:
+                assert np.array_equal(fO.cpu().numpy().astype(np.float64), O)
+            written = torch.zeros_like(bufO, dtype=torch.bool)
+            torch.as_strided(written, (n, d), (ldo, 1), off).fill_(True)
+            assert torch.isnan(bufO[~written]).all(), "stores outside the output rows"
+
+
+def test_argument_errors_on_the_device():
+    el, params = _graph("multi")
+    dg = device_graph(el, plan_params=params)
+    n, d = el.n, 8
+    fV = torch.randn(n, d, device=DEV)
+    fE = torch.randn(el.e, d, device=DEV)
+    fO = torch.empty(n, d, device=DEV)
+    arg = torch.empty(n, d, dtype=torch.int32, device=DEV)
+    with pytest.raises(gnn.GnnError):   # winners only exist for max / min
+        gnn.gnn_ap_fwd(dg.indptr, dg.indices, fV, fE, fO, arg, n, d, 0, 0, plan=dg.plan_fwd)
+    with pytest.raises(gnn.GnnError):   # a plan of another graph size
+        gnn.gnn_ap_fwd(dg.indptr, dg.indices, fV, fE, fO, None, n - 1, d, 0, 0, plan=dg.plan_fwd)
+    with pytest.raises(gnn.GnnError):   # copylhs has no edge operand to differentiate
+        gnn.gnn_ap_bwd_edge(dg.indptr, dg.indices, None, fV, fE, fO, torch.empty_like(fE), n, d, 4, plan=dg.plan_fwd)
+    with pytest.raises(TypeError):
+        gnn.gnn_ap_fwd(dg.indptr, dg.indices, fV.double(), fE, fO, None, n, d, 0, 0, plan=dg.plan_fwd)
+
+
+def test_sum_copylhs_equals_the_hot_path():
+    """The general kernel and the tuned sum kernel compute the same aggregation."""
+    el = synth.make_graph("rmat_sparse_stack", scale=0.02)
+    dg = device_graph(el)
+    X = synth.normal_features(el.n, 100, 5).to(DEV)
+    Y1 = torch.empty_like(X)
+    Y2 = torch.empty_like(X)
+    gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, None, X, Y1, el.n, 100, gnn.GNN_SUM, plan=dg.plan_fwd)
+    gnn.gnn_ap_fwd(dg.indptr, dg.indices, X, None, Y2, None, el.n, 100, gnn.GNN_BIN_COPY_LHS, gnn.GNN_RED_SUM, plan=dg.plan_fwd)
+    torch.cuda.synchronize()
+    indptr, indices, *_ = host_csr(el)
+    O, S = oracle.ap_fwd(indptr, indices, X.cpu().numpy(), None, 100, 4, 0)
+    _close(Y2, O, S, "general kernel")
+    _close(Y1, O, S, "hot kernel")
