@@ -255,6 +255,64 @@ def measure(workload, steps, warmup, scale, dev, dump_graph=None):
     return result, (el, widths, op_names)
 
 
+def measure_general_primitive(workload, dev, reps=5):
+    """The general primitive (operator table, Table 1) and its gradients on the same graph: a
+    few representative calls, each timed with events on the launch stream.  Not part of `value`."""
+    w = synth.WORKLOADS[workload]
+    el = synth.make_graph(workload, device=dev)
+    n, e = el.n, el.e
+    dg = gnn.build_device_graph(el.dst, el.src, n, indptr64=w["indptr64"], want_perm=True)
+    ip = 8 if w["indptr64"] else 4
+    rows = []
+
+    def timed(name, d, bytes_, fn):
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / reps
+        rows.append({"call": name, "d": d, "ms": round(ms, 4), "GEF_per_s": round(e * d / ms / 1e6, 2),
+                     "algorithmic_GB": round(bytes_ / 1e9, 4), "frac_of_hbm_peak": round(bytes_ / ms / 1e6 / HBM_PEAK_GBS, 4)})
+
+    for d in (100, 32):
+        fV = synth.normal_features(n, d, 301, device=dev)
+        dO = synth.normal_features(n, d, 302, device=dev)
+        fO = torch.empty_like(fV)
+        dfV = torch.empty_like(fV)
+        arg = torch.empty((n, d), dtype=torch.int32, device=dev)
+        ws = synth.gcn_sym_edge_weights(el.dst, el.src, n).to(dev) + 0.5
+        dws = torch.empty_like(ws)
+        base = 2 * n * d * 4 + 4 * e + (n + 1) * ip
+        B, R = gnn, gnn
+        timed("fwd copylhs/max + winners", d, base + n * d * 4,
+              lambda: gnn.gnn_ap_fwd(dg.indptr, dg.indices, fV, None, fO, arg, n, d, B.GNN_BIN_COPY_LHS, R.GNN_RED_MAX, plan=dg.plan_fwd))
+        timed("vertex gradient of max (scatter to winners)", d, 4 * n * d * 4 + 4 * n * d,
+              lambda: gnn.gnn_ap_bwd_vertex_arg(dg.indices, arg, dO, None, dfV, n, n, d, B.GNN_BIN_COPY_LHS))
+        timed("fwd mul(scalar edge feature)/sum", d, base + 4 * e,
+              lambda: gnn.gnn_ap_fwd(dg.indptr, dg.indices, fV, ws, fO, None, n, d, B.GNN_BIN_MUL, R.GNN_RED_SUM, plan=dg.plan_fwd))
+        timed("edge gradient of mul(scalar)/sum (sampled dense-dense product)", d, 2 * n * d * 4 + 8 * e + (n + 1) * ip,
+              lambda: gnn.gnn_ap_bwd_edge(dg.indptr, dg.indices, None, fV, ws, dO, dws, n, d, B.GNN_BIN_MUL, plan=dg.plan_fwd))
+        if d == 32:
+            fE = torch.rand((e, d), device=dev) + 0.5
+            dfE = torch.empty_like(fE)
+            timed("fwd mul(full-width edge features)/sum", d, base + e * d * 4,
+                  lambda: gnn.gnn_ap_fwd(dg.indptr, dg.indices, fV, fE, fO, None, n, d, B.GNN_BIN_MUL, R.GNN_RED_SUM, plan=dg.plan_fwd))
+            timed("fwd copyrhs/max + winners", d, n * d * 8 + 4 * e + e * d * 4 + (n + 1) * ip,
+                  lambda: gnn.gnn_ap_fwd(dg.indptr, dg.indices, None, fE, fO, arg, n, d, B.GNN_BIN_COPY_RHS, R.GNN_RED_MAX, plan=dg.plan_fwd))
+            timed("edge gradient of mul(full-width)/sum", d, 2 * n * d * 4 + 4 * e + e * d * 4 + (n + 1) * ip,
+                  lambda: gnn.gnn_ap_bwd_edge(dg.indptr, dg.indices, None, fV, fE, dO, dfE, n, d, B.GNN_BIN_MUL, plan=dg.plan_fwd))
+            timed("vertex gradient of mul(full-width)/sum (transposed graph, edge rows through perm)", d,
+                  base + e * d * 4 + 8 * e,
+                  lambda: gnn.gnn_ap_bwd_vertex(dg.indptr_t, dg.indices_t, dO, fE, dfV, n, d, B.GNN_BIN_MUL, plan=dg.plan_bwd, edge_ids=dg.perm))
+            del fE, dfE
+    return {"workload": workload, "reps": reps, "calls": rows,
+            "note": "algorithmic_GB = operands read once + results written once; frac_of_hbm_peak = that / time / 8 TB/s"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -266,6 +324,8 @@ def main():
     ap.add_argument("--no-calibration", action="store_true")
     ap.add_argument("--secondary", default="rmat_dense_wide",
                     help="a second workload measured briefly in the same run and reported under 'secondary' ('' = none)")
+    ap.add_argument("--no-general-primitive", action="store_true",
+                    help="skip the operator-table calls (gnn_ap_*) reported under 'general_primitive'")
     ap.add_argument("--dump-graph", default=None, metavar="DIR",
                     help="write the CSR and transposed CSR as raw arrays for the stand-alone profiling driver, then exit")
     args = ap.parse_args()
@@ -287,6 +347,10 @@ def main():
         torch.cuda.empty_cache()
         sec, _ = measure(args.secondary, max(3, args.steps // 4), 1, 1.0, dev)
         result["secondary"] = {k: sec[k] for k in ("value", "unit", "ms_per_step", "steps", "config", "calls", "setup_ms")}
+    if not args.no_general_primitive and args.scale == 1.0 and e <= 500_000_000:
+        torch.cuda.empty_cache()
+        result["general_primitive"] = measure_general_primitive(args.workload, dev)
+        torch.cuda.empty_cache()
     if not args.no_calibration:
         result["ceilings"] = calibrate(dev)
     if not args.no_cpu_baseline and e > 500_000_000:

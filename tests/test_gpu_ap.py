@@ -201,3 +201,78 @@ def test_sum_copylhs_equals_the_hot_path():
     O, S = oracle.ap_fwd(indptr, indices, X.cpu().numpy(), None, 100, 4, 0)
     _close(Y2, O, S, "general kernel")
     _close(Y1, O, S, "hot kernel")
+
+
+# ------------------------------------------------------------------ full size
+def _sub_csr(indptr, indices, rows):
+    """CSR holding only `rows` of a larger CSR, plus the global edge positions of its edges."""
+    lens = (indptr[rows + 1] - indptr[rows]).astype(np.int64)
+    sub_ptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    pos = np.concatenate([np.arange(indptr[r], indptr[r + 1], dtype=np.int64) for r in rows]) if len(rows) else np.zeros(0, np.int64)
+    return sub_ptr, indices[pos], pos
+
+
+@pytest.mark.timeout(900)
+def test_fullsize_sparse_workload_sampled_rows():
+    """2,449,029 vertices / 123,718,280 edges, d = 100, default plans: sampled rows of the forward
+    results (max with winners, weighted sum), of the vertex gradient (transposed graph, edge rows
+    through perm) and the edge gradient of the sampled rows' edges against the oracle; the
+    winner scatter is checked through what it conserves."""
+    name, d = "rmat_sparse_stack", 100
+    print(f"[fullsize general primitive] {name} d={d}", flush=True)
+    el = synth.make_graph(name, device=DEV)
+    n, E = el.n, el.e
+    dg = gnn.build_device_graph(el.dst, el.src, n, want_perm=True)
+    fV = synth.normal_features(n, d, 1, device=DEV)
+    dO = synth.normal_features(n, d, 2, device=DEV)
+    w = synth.gcn_sym_edge_weights(el.dst, el.src, n).to(DEV) * 50.0 + 0.25
+    fO = torch.full((n, d), float("nan"), device=DEV)
+    arg = torch.full((n, d), -7, dtype=torch.int32, device=DEV)
+
+    dst_h, src_h = synth.to_csr_numpy(el)
+    indptr = oracle.csr_indptr(dst_h, n)
+    deg = np.diff(indptr)
+    rng = np.random.default_rng(3)
+    rows = np.unique(np.concatenate([np.argsort(deg)[-32:], rng.choice(n, 4000, replace=False), np.flatnonzero(deg == 0)[:8]]))
+    sub_ptr, sub_idx, pos = _sub_csr(indptr, src_h, rows)
+    rows_d = torch.from_numpy(rows).to(DEV)
+    fV_h, dO_h, w_h = fV.cpu().numpy(), dO.cpu().numpy(), w.cpu().numpy()
+
+    # forward, max with winners
+    gnn.gnn_ap_fwd(dg.indptr, dg.indices, fV, None, fO, arg, n, d, gnn.GNN_BIN_COPY_LHS, gnn.GNN_RED_MAX, plan=dg.plan_fwd)
+    torch.cuda.synchronize()
+    O, won = oracle.ap_fwd(sub_ptr, sub_idx, fV_h, None, d, oracle.BIN_COPY_LHS, oracle.RED_MAX)
+    assert np.array_equal(fO[rows_d].cpu().numpy().astype(np.float64), O)
+    won_global = np.where(won >= 0, pos[np.maximum(won, 0)], -1)
+    assert np.array_equal(arg[rows_d].cpu().numpy().astype(np.int64), won_global)
+    # winner scatter: every non-empty (v, j) hands its dO to exactly one vertex
+    dfV = torch.empty(n, d, device=DEV)
+    gnn.gnn_ap_bwd_vertex_arg(dg.indices, arg, dO, None, dfV, n, n, d, gnn.GNN_BIN_COPY_LHS)
+    torch.cuda.synchronize()
+    nonempty = torch.from_numpy(deg > 0).to(DEV)
+    want = dO[nonempty].double().sum(0)
+    scale = dO[nonempty].double().abs().sum(0)
+    assert bool(((dfV.double().sum(0) - want).abs() <= 1e-6 * scale).all())
+    never_won = torch.ones(n, dtype=torch.bool, device=DEV)
+    never_won[dg.indices[arg[arg >= 0].long()].long()] = False
+    assert not dfV[never_won].any()
+
+    # forward, sum of scalar-weighted rows; its edge gradient on the sampled rows' edges
+    gnn.gnn_ap_fwd(dg.indptr, dg.indices, fV, w, fO, None, n, d, gnn.GNN_BIN_MUL, gnn.GNN_RED_SUM, plan=dg.plan_fwd)
+    dw = torch.full((E,), float("nan"), device=DEV)
+    gnn.gnn_ap_bwd_edge(dg.indptr, dg.indices, None, fV, w, dO, dw, n, d, gnn.GNN_BIN_MUL, plan=dg.plan_fwd)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(dw).all())
+    O, S = oracle.ap_fwd(sub_ptr, sub_idx, fV_h, w_h, d, oracle.BIN_MUL, oracle.RED_SUM, eid=pos)
+    _close(fO[rows_d], O, S, "fullsize mul/sum")
+    (_, _), (dE, SE) = oracle.ap_bwd(sub_ptr, sub_idx, fV_h, w_h[pos], dO_h[rows], d, oracle.BIN_MUL, oracle.RED_SUM)
+    _close(dw[torch.from_numpy(pos).to(DEV)].reshape(-1, 1), dE, SE, "fullsize edge gradient")
+
+    # vertex gradient of the same: the primitive over the transposed graph, weights through perm
+    gnn.gnn_ap_bwd_vertex(dg.indptr_t, dg.indices_t, dO, w, dfV, n, d, gnn.GNN_BIN_MUL, plan=dg.plan_bwd, edge_ids=dg.perm)
+    torch.cuda.synchronize()
+    indptr_t, indices_t, perm = oracle.transpose(indptr, src_h)
+    rows_t = np.unique(np.concatenate([np.argsort(np.diff(indptr_t))[-32:], rng.choice(n, 4000, replace=False)]))
+    subt_ptr, subt_idx, pos_t = _sub_csr(indptr_t, indices_t, rows_t)
+    dV, SV = oracle.ap_fwd(subt_ptr, subt_idx, dO_h, w_h, d, oracle.BIN_MUL, oracle.RED_SUM, eid=perm[pos_t])
+    _close(dfV[torch.from_numpy(rows_t).to(DEV)], dV, SV, "fullsize vertex gradient")
