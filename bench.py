@@ -128,9 +128,17 @@ def cpu_baseline(el, widths, op_name, target_seconds=20.0):
         secs += time.perf_counter() - t0
         ef += f * float((din.sum() + dout.sum()) if rows is None else (din[rows].sum() + dout[rows].sum()))
     what = "all rows" if rows is None else f"{n_rows} uniformly sampled rows per direction"
+    # the same loops on ONE core, on a sample sized to a few seconds (forward at the first width)
+    one_rows = np.sort(rng.choice(el.n, size=max(1000, min(el.n, int(el.n * min(1.0, rate / threads * 4.0 / (el.e * f0))))), replace=False))
+    t0 = time.perf_counter()
+    oracle.aggregate_fwd(indptr, src, X0, op=op, rows=one_rows, nthreads=1, dout=dout)
+    one_secs = max(time.perf_counter() - t0, 1e-6)
+    one_core = din[one_rows].sum() * f0 / one_secs / 1e9
     return {"value": round(ef / secs / 1e9, 4), "unit": "GEF/s", "cores": threads, "kind": "oracle",
             "sample": f"the same step (forward + backward {op_name}, widths {list(widths)}) on {what} of the same graph, "
-                      f"{secs:.1f} s of CPU time, fp64 scalar loops, OpenMP dynamic over rows"}
+                      f"{secs:.1f} s of CPU time, fp64 scalar loops, OpenMP dynamic over rows",
+            "one_core_GEFs": round(float(one_core), 4),
+            "one_core_sample": f"forward {op_name} at F={f0} on {len(one_rows)} sampled rows, {one_secs:.1f} s"}
 
 
 def measure(workload, steps, warmup, scale, dev, dump_graph=None):
@@ -207,8 +215,8 @@ def measure(workload, steps, warmup, scale, dev, dump_graph=None):
     torch.cuda.synchronize()
     t_total = time.perf_counter() - t_start
 
-    per_call_ms = [float(np.mean([ev[k][i][0].elapsed_time(ev[k][i][1]) for k in range(steps)]))
-                   for i in range(len(calls))]
+    samples = [[ev[k][i][0].elapsed_time(ev[k][i][1]) for k in range(steps)] for i in range(len(calls))]
+    per_call_ms = [float(np.mean(x)) for x in samples]
     ef_step = sum(2 * e * f for f in widths) * len(op_names)
     ms_per_step = t_total / steps * 1e3
     value = ef_step / (t_total / steps) / 1e9
@@ -221,7 +229,9 @@ def measure(workload, steps, warmup, scale, dev, dump_graph=None):
         src_scaled = (op_name in ("mean", "sage") and d == "bwd") or (op_name == "gcn" and not weighted)
         b = algorithmic_bytes(n, e, f, esz, ip_bytes, weighted, src_scaled)
         s = per_call_ms[i] * 1e-3
-        call_rows.append({"op": op_name, "dir": d, "F": f, "ms": round(per_call_ms[i], 4), "GEF_per_s": round(e * f / s / 1e9, 2),
+        call_rows.append({"op": op_name, "dir": d, "F": f, "ms": round(per_call_ms[i], 4),
+                          "ms_median": round(float(np.median(samples[i])), 4), "ms_min": round(float(np.min(samples[i])), 4),
+                          "GEF_per_s": round(e * f / s / 1e9, 2),
                           "algorithmic_GB": round(b / 1e9, 4), "algorithmic_GBs": round(b / s / 1e9, 1),
                           "frac_of_hbm_peak": round(b / s / 1e9 / HBM_PEAK_GBS, 4),
                           "gathered_TBs": round(e * f * esz / s / 1e12, 2)})

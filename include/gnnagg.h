@@ -199,6 +199,23 @@ GNN_API int gnn_ap_bwd_edge(const void *indptr, const int32_t *indices, const in
                             const float *fE, const float *dO, float *dfE, int64_t N, int64_t d, int binop,
                             const gnn_ap_opts *opts);
 
+/* ------------------------------------------------ dense update of a layer (fp32) */
+
+/* The MLP step that follows the aggregation in every layer (Section 6.3, "Memory": weight
+ * matrices f x h1, h1 x h2, h2 x l), on the matrix cores with exact fp32 products:
+ *     C[m, n] = act( sum_k opA(A)[m, k] * opB(B)[k, n] + bias[n] ),   act = max(., 0) if relu
+ * A is stored [M, K] with row stride lda, or [K, M] when trans_a; B is stored [K, N] with row
+ * stride ldb, or [N, K] when trans_b; C [M, ldc] is overwritten; bias [N] or NULL.  All device
+ * pointers.  A long reduction with few output tiles (the weight gradient: K = number of vertices)
+ * is split into partial products that are added in a fixed order; that needs `workspace` of
+ * gnn_matmul_workspace_bytes(M, N, K) bytes (0 for most shapes); without it the call still
+ * works, unsplit.  16-byte loads are used when the leading dimensions and bases allow.
+ * Asynchronous on `stream`; allocates nothing. */
+GNN_API int gnn_matmul(const float *A, int64_t lda, int trans_a, const float *B, int64_t ldb, int trans_b,
+                       float *C, int64_t ldc, int64_t M, int64_t N, int64_t K, const float *bias, int relu,
+                       void *workspace, int64_t workspace_bytes, void *stream);
+GNN_API int64_t gnn_matmul_workspace_bytes(int64_t M, int64_t N, int64_t K);
+
 /* ------------------------------------------------------- once-per-graph setup */
 
 /* Row pointers of the destination-indexed CSR (Section 4.1 requires the graph

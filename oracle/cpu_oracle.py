@@ -18,6 +18,8 @@ OP_SUM, OP_MEAN, OP_GCN_SYM, OP_SAGE_GCN = 0, 1, 2, 3
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "oracle.c")
 _SRC_AP = os.path.join(_HERE, "ap_oracle.c")
+_SRC_LAYER = os.path.join(_HERE, "layer_oracle.c")
+SOURCES = (_SRC, _SRC_AP, _SRC_LAYER)
 _LIB = os.path.join(_HERE, "liboracle.so")
 _lib = None
 _lib_path = _LIB
@@ -30,10 +32,10 @@ def compile_c(src, out: str) -> None:
 
 
 def build_oracle(force: bool = False) -> str:
-    """Compile oracle.c and ap_oracle.c with gcc (-O2, OpenMP, no fast-math, no contraction)."""
-    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_AP))
+    """Compile the oracle's C files with gcc (-O2, OpenMP, no fast-math, no contraction)."""
+    newest = max(os.path.getmtime(p) for p in SOURCES)
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
-        compile_c([_SRC, _SRC_AP], _LIB)
+        compile_c(list(SOURCES), _LIB)
     return _LIB
 
 
@@ -41,7 +43,8 @@ def _open(path: str):
     lib = ctypes.CDLL(path)
     lib.oracle_max_threads.restype = ctypes.c_int
     for name in ("oracle_aggregate_fwd", "oracle_aggregate_bwd", "oracle_csr_indptr",
-                 "oracle_transpose", "oracle_plan", "oracle_ap_fwd", "oracle_ap_bwd"):
+                 "oracle_transpose", "oracle_plan", "oracle_ap_fwd", "oracle_ap_bwd", "oracle_matmul",
+                 "oracle_sage_layer_fwd", "oracle_sage_layer_bwd"):
         if hasattr(lib, name):  # a mutated single-file build holds only its own functions
             getattr(lib, name).restype = ctypes.c_int
     return lib
@@ -236,3 +239,58 @@ def ap_bwd(indptr, indices, fV, fE, dO, d, binop, reduce, eid=None, arg=None, n_
     if rc != 0:
         raise ValueError(f"oracle_ap_bwd rejected its arguments (code {rc})")
     return (dV, SV), (dE, SE)
+
+
+# ---------------------------------------------------------------- one GraphSAGE layer
+def matmul(A, B, trans_a=False, trans_b=False, bias=None, relu=False):
+    """(C, S) float64: C = act(opA(A) @ opB(B) + bias), S = sum_k |a b| + |bias|."""
+    lib = _load()
+    A, B = _f32(A), _f32(B)
+    M, K = (A.shape[1], A.shape[0]) if trans_a else A.shape
+    Kb, N = (B.shape[1], B.shape[0]) if trans_b else B.shape
+    assert K == Kb
+    bias = None if bias is None else _f32(bias)
+    C = np.empty((M, N), dtype=np.float64)
+    S = np.empty((M, N), dtype=np.float64)
+    rc = lib.oracle_matmul(_p(A), ctypes.c_int64(A.shape[1]), ctypes.c_int(1 if trans_a else 0), _p(B),
+                           ctypes.c_int64(B.shape[1]), ctypes.c_int(1 if trans_b else 0), _p(C), _p(S),
+                           ctypes.c_int64(M), ctypes.c_int64(N), ctypes.c_int64(K), _p(bias), ctypes.c_int(1 if relu else 0))
+    if rc != 0:
+        raise ValueError(f"oracle_matmul rejected its arguments (code {rc})")
+    return C, S
+
+
+def sage_layer_fwd(indptr, indices, X, W, bias=None, relu=True):
+    """(Z, H, SH) float64 of one layer: aggregated input, output, magnitude sums of the output."""
+    lib = _load()
+    indptr, indices, X, W = _i64(indptr), _i32(indices), _f32(X), _f32(W)
+    n, fi = X.shape
+    fo = W.shape[1]
+    assert W.shape[0] == fi and indptr.shape[0] == n + 1
+    bias = None if bias is None else _f32(bias)
+    Z = np.empty((n, fi), dtype=np.float64)
+    H = np.empty((n, fo), dtype=np.float64)
+    SH = np.empty((n, fo), dtype=np.float64)
+    rc = lib.oracle_sage_layer_fwd(_p(indptr), _p(indices), _p(X), _p(W), _p(bias), _p(Z), _p(H), _p(SH),
+                                   ctypes.c_int64(n), ctypes.c_int64(fi), ctypes.c_int64(fo), ctypes.c_int(1 if relu else 0))
+    if rc != 0:
+        raise ValueError(f"oracle_sage_layer_fwd failed (code {rc})")
+    return Z, H, SH
+
+
+def sage_layer_bwd(indptr, indices, X, W, H_saved, dH, relu=True):
+    """{"dX": (value, scale), "dW": ..., "db": ...} float64 gradients of one layer."""
+    lib = _load()
+    indptr, indices, X, W, H_saved, dH = _i64(indptr), _i32(indices), _f32(X), _f32(W), _f32(H_saved), _f32(dH)
+    n, fi = X.shape
+    fo = W.shape[1]
+    assert H_saved.shape == (n, fo) and dH.shape == (n, fo)
+    out = {k: (np.empty(shape, dtype=np.float64), np.empty(shape, dtype=np.float64))
+           for k, shape in (("dX", (n, fi)), ("dW", (fi, fo)), ("db", (fo,)))}
+    rc = lib.oracle_sage_layer_bwd(_p(indptr), _p(indices), _p(X), _p(W), _p(H_saved), _p(dH),
+                                   _p(out["dX"][0]), _p(out["dX"][1]), _p(out["dW"][0]), _p(out["dW"][1]),
+                                   _p(out["db"][0]), _p(out["db"][1]),
+                                   ctypes.c_int64(n), ctypes.c_int64(fi), ctypes.c_int64(fo), ctypes.c_int(1 if relu else 0))
+    if rc != 0:
+        raise ValueError(f"oracle_sage_layer_bwd failed (code {rc})")
+    return out

@@ -31,6 +31,7 @@ EXPORTED_SYMBOLS = (
     "gnn_plan_sizes", "gnn_plan_export", "gnn_plan_gather_share", "gnn_plan_workspace_bytes", "gnn_plan_reserve",
     "gnn_plan_prepare",
     "gnn_ap_fwd", "gnn_ap_bwd_vertex", "gnn_ap_bwd_vertex_arg", "gnn_ap_bwd_edge",
+    "gnn_matmul", "gnn_matmul_workspace_bytes",
     "gnn_status_string", "gnn_calib_copy",
 )
 
@@ -103,6 +104,9 @@ def load_library() -> ctypes.CDLL:
         lib.gnn_ap_bwd_vertex.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, ap]
         lib.gnn_ap_bwd_vertex_arg.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, ap]
         lib.gnn_ap_bwd_edge.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i32, ap]
+        lib.gnn_matmul.argtypes = [vp, i64, i32, vp, i64, i32, vp, i64, i64, i64, i64, vp, i32, vp, i64, vp]
+        lib.gnn_matmul_workspace_bytes.argtypes = [i64, i64, i64]
+        lib.gnn_matmul_workspace_bytes.restype = i64
         lib.gnn_status_string.argtypes = [i32]
         lib.gnn_status_string.restype = ctypes.c_char_p
         lib.gnn_calib_copy.argtypes = [vp, vp, i64, vp]
@@ -343,6 +347,28 @@ def gnn_ap_bwd_edge(indptr, indices, arg_e, fV, fE, dO, dfE, N, d, binop, plan: 
     _check("gnn_ap_bwd_edge", load_library().gnn_ap_bwd_edge(
         _ptr(indptr), _ptr(indices), _ptr(arg_e), _ptr(fV), _ptr(fE), _ptr(dO), _ptr(dfE), int(N), int(d), int(binop),
         ctypes.byref(o)))
+
+
+def gnn_matmul_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(load_library().gnn_matmul_workspace_bytes(int(M), int(N), int(K)))
+
+
+def gnn_matmul(A, B, C, trans_a=False, trans_b=False, bias=None, relu=False, workspace=None, stream=None) -> None:
+    """C = act(opA(A) @ opB(B) + bias) on the matrix cores (see include/gnnagg.h).  A, B, C are 2-D
+    float32 tensors with unit column stride; shapes follow torch.matmul after the transposes."""
+    _f32(A, B, C, bias)
+    for t in (A, B, C):
+        if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+            raise ValueError("matrices must be 2-D with unit column stride")
+    M, K = (A.shape[1], A.shape[0]) if trans_a else (A.shape[0], A.shape[1])
+    Kb, N = (B.shape[1], B.shape[0]) if trans_b else (B.shape[0], B.shape[1])
+    if K != Kb or tuple(C.shape) != (M, N):
+        raise ValueError("shape mismatch")
+    ld = lambda t: int(t.stride(0)) if t.shape[0] > 1 else int(t.shape[1])  # noqa: E731
+    _check("gnn_matmul", load_library().gnn_matmul(
+        _ptr(A), ld(A), 1 if trans_a else 0, _ptr(B), ld(B), 1 if trans_b else 0, _ptr(C), ld(C), int(M), int(N), int(K),
+        _ptr(bias), 1 if relu else 0, _ptr(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def gnn_csr_from_sorted_coo(dst_sorted: torch.Tensor, N: int, indptr_out: torch.Tensor, stream=None) -> None:
