@@ -358,13 +358,13 @@ def gnn_matmul(A, B, C, trans_a=False, trans_b=False, bias=None, relu=False, wor
     float32 tensors with unit column stride; shapes follow torch.matmul after the transposes."""
     _f32(A, B, C, bias)
     for t in (A, B, C):
-        if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        if t.dim() != 2 or (t.numel() > 0 and t.shape[1] > 1 and t.stride(1) != 1):
             raise ValueError("matrices must be 2-D with unit column stride")
     M, K = (A.shape[1], A.shape[0]) if trans_a else (A.shape[0], A.shape[1])
     Kb, N = (B.shape[1], B.shape[0]) if trans_b else (B.shape[0], B.shape[1])
     if K != Kb or tuple(C.shape) != (M, N):
         raise ValueError("shape mismatch")
-    ld = lambda t: int(t.stride(0)) if t.shape[0] > 1 else int(t.shape[1])  # noqa: E731
+    ld = lambda t: max(1, int(t.stride(0)) if t.shape[0] > 1 and t.numel() > 0 else int(t.shape[1]))  # noqa: E731
     _check("gnn_matmul", load_library().gnn_matmul(
         _ptr(A), ld(A), 1 if trans_a else 0, _ptr(B), ld(B), 1 if trans_b else 0, _ptr(C), ld(C), int(M), int(N), int(K),
         _ptr(bias), 1 if relu else 0, _ptr(workspace),
