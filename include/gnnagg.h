@@ -216,6 +216,47 @@ GNN_API int gnn_matmul(const float *A, int64_t lda, int trans_a, const float *B,
                        void *workspace, int64_t workspace_bytes, void *stream);
 GNN_API int64_t gnn_matmul_workspace_bytes(int64_t M, int64_t N, int64_t K);
 
+/* ------------------------------------------- one GraphSAGE layer (fp32) */
+
+/* Options of the layer calls.  Zero-initialise, then set what differs. */
+typedef struct gnn_layer_opts {
+    int32_t indptr_is_64;
+    int32_t relu;        /* 1: rectifier after the bias; 0: identity (a last layer) */
+    int32_t order;       /* 0: aggregate first iff F_in <= F_out, else transform first (the two linear
+                            steps commute; the narrower rows are gathered); 1 / 2 force either */
+    int32_t reserved;
+    void *stream;
+    gnn_plan *plan;      /* REQUIRED: plan of the graph passed in the same call (forward plan for _fwd,
+                            plan of the transposed graph for _bwd) */
+    void *workspace;     /* _bwd only: device scratch of gnn_sage_layer_workspace_bytes(), 16-byte aligned */
+    int64_t workspace_bytes;
+} gnn_layer_opts;
+
+/* One layer of the paper's model: the aggregation (Section 6.1: sum of the in-neighbours' vectors
+ * plus the vertex's own, divided by in-degree + 1) followed by the dense update (Section 6.3,
+ * "Memory": one weight matrix per layer), with a bias and an optional rectifier (not stated in
+ * the paper; the usual GraphSAGE layer):
+ *     H[v, :] = act( ((sum_{u->v} X[u, :] + X[v, :]) / (din[v] + 1)) W + b )
+ * X [N, F_in], W [F_in, F_out] row-major, bias [F_out] or NULL, H [N, F_out], all dense fp32.
+ * `saved` receives what the chosen order materialises, gnn_sage_layer_saved_elems() floats: the
+ * aggregated input Z [N, F_in] (aggregate first; the backward call needs it) or the transformed
+ * input X W [N, F_out] (transform first; only a temporary).  Asynchronous on opts->stream; the
+ * aggregation may grow plan-owned buffers on first use (gnn_plan_prepare with GNN_SAGE_GCN). */
+GNN_API int gnn_sage_layer_fwd(const void *indptr, const int32_t *indices, const float *X, const float *W,
+                               const float *bias, float *saved, float *H, int64_t N, int64_t F_in, int64_t F_out,
+                               const gnn_layer_opts *opts);
+/* Gradients of sum_{v,j} dH[v,j] H[v,j]: dW [F_in, F_out], db [F_out] (may be NULL), dX [N, F_in] (may
+ * be NULL: a first layer needs none).  The rectifier passes gradient where the stored forward
+ * output H is > 0.  indptr_t / indices_t / opts->plan describe the TRANSPOSED graph; `saved` is
+ * what the forward call wrote (needed when aggregating first; may be NULL otherwise).  opts->relu
+ * and opts->order must be those of the forward call.  Sums over vertices (dW, db) are formed in a
+ * fixed order: results are reproducible run to run. */
+GNN_API int gnn_sage_layer_bwd(const void *indptr_t, const int32_t *indices_t, const float *X, const float *W,
+                               const float *saved, const float *H, const float *dH, float *dX, float *dW,
+                               float *db, int64_t N, int64_t F_in, int64_t F_out, const gnn_layer_opts *opts);
+GNN_API int64_t gnn_sage_layer_saved_elems(int64_t N, int64_t F_in, int64_t F_out, int order);
+GNN_API int64_t gnn_sage_layer_workspace_bytes(int64_t N, int64_t F_in, int64_t F_out, int relu, int order);
+
 /* ------------------------------------------------------- once-per-graph setup */
 
 /* Row pointers of the destination-indexed CSR (Section 4.1 requires the graph

@@ -32,6 +32,7 @@ EXPORTED_SYMBOLS = (
     "gnn_plan_prepare",
     "gnn_ap_fwd", "gnn_ap_bwd_vertex", "gnn_ap_bwd_vertex_arg", "gnn_ap_bwd_edge",
     "gnn_matmul", "gnn_matmul_workspace_bytes",
+    "gnn_sage_layer_fwd", "gnn_sage_layer_bwd", "gnn_sage_layer_saved_elems", "gnn_sage_layer_workspace_bytes",
     "gnn_status_string", "gnn_calib_copy",
 )
 
@@ -52,6 +53,14 @@ class GnnApOpts(ctypes.Structure):
         ("ldv", ctypes.c_int64), ("lde", ctypes.c_int64), ("ldo", ctypes.c_int64),
         ("edge_ids", ctypes.c_void_p), ("stream", ctypes.c_void_p), ("plan", ctypes.c_void_p),
         ("flags", ctypes.c_int32), ("reserved", ctypes.c_int32),
+    ]
+
+
+class GnnLayerOpts(ctypes.Structure):
+    _fields_ = [
+        ("indptr_is_64", ctypes.c_int32), ("relu", ctypes.c_int32), ("order", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("stream", ctypes.c_void_p), ("plan", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
+        ("workspace_bytes", ctypes.c_int64),
     ]
 
 
@@ -107,6 +116,13 @@ def load_library() -> ctypes.CDLL:
         lib.gnn_matmul.argtypes = [vp, i64, i32, vp, i64, i32, vp, i64, i64, i64, i64, vp, i32, vp, i64, vp]
         lib.gnn_matmul_workspace_bytes.argtypes = [i64, i64, i64]
         lib.gnn_matmul_workspace_bytes.restype = i64
+        lp = ctypes.POINTER(GnnLayerOpts)
+        lib.gnn_sage_layer_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, lp]
+        lib.gnn_sage_layer_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, lp]
+        lib.gnn_sage_layer_saved_elems.argtypes = [i64, i64, i64, i32]
+        lib.gnn_sage_layer_saved_elems.restype = i64
+        lib.gnn_sage_layer_workspace_bytes.argtypes = [i64, i64, i64, i32, i32]
+        lib.gnn_sage_layer_workspace_bytes.restype = i64
         lib.gnn_status_string.argtypes = [i32]
         lib.gnn_status_string.restype = ctypes.c_char_p
         lib.gnn_calib_copy.argtypes = [vp, vp, i64, vp]
@@ -369,6 +385,54 @@ def gnn_matmul(A, B, C, trans_a=False, trans_b=False, bias=None, relu=False, wor
         _ptr(A), ld(A), 1 if trans_a else 0, _ptr(B), ld(B), 1 if trans_b else 0, _ptr(C), ld(C), int(M), int(N), int(K),
         _ptr(bias), 1 if relu else 0, _ptr(workspace),
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def _dense(*tensors) -> None:
+    for t in tensors:
+        if t is not None and not t.is_contiguous():
+            raise ValueError("the layer calls take dense (contiguous) tensors")
+
+
+def gnn_sage_layer_saved_elems(N, F_in, F_out, order=0) -> int:
+    return int(load_library().gnn_sage_layer_saved_elems(int(N), int(F_in), int(F_out), int(order)))
+
+
+def gnn_sage_layer_workspace_bytes(N, F_in, F_out, relu=True, order=0) -> int:
+    return int(load_library().gnn_sage_layer_workspace_bytes(int(N), int(F_in), int(F_out), 1 if relu else 0, int(order)))
+
+
+def _layer_opts(indptr, plan, relu, order, stream, workspace=None) -> GnnLayerOpts:
+    o = GnnLayerOpts()
+    o.indptr_is_64 = _is64(indptr)
+    o.relu = 1 if relu else 0
+    o.order = int(order)
+    o.stream = _stream(stream)
+    o.plan = plan.handle if plan is not None else None
+    if workspace is not None:
+        o.workspace = workspace.data_ptr()
+        o.workspace_bytes = workspace.numel() * workspace.element_size()
+    return o
+
+
+def gnn_sage_layer_fwd(indptr, indices, X, W, bias, saved, H, plan: Plan, relu=True, order=0, stream=None) -> None:
+    """H = act(aggregate(X) W + b), one GraphSAGE layer (see include/gnnagg.h)."""
+    _f32(X, W, bias, saved, H)
+    _dense(X, W, bias, saved, H)
+    o = _layer_opts(indptr, plan, relu, order, stream)
+    _call_allocating("gnn_sage_layer_fwd", lambda: load_library().gnn_sage_layer_fwd(
+        _ptr(indptr), _ptr(indices), _ptr(X), _ptr(W), _ptr(bias), _ptr(saved), _ptr(H), int(X.shape[0]), int(W.shape[0]),
+        int(W.shape[1]), ctypes.byref(o)))
+
+
+def gnn_sage_layer_bwd(indptr_t, indices_t, X, W, saved, H, dH, dX, dW, db, plan: Plan, workspace, relu=True, order=0,
+                       stream=None) -> None:
+    """Gradients of one layer over the transposed graph (see include/gnnagg.h)."""
+    _f32(X, W, saved, H, dH, dX, dW, db)
+    _dense(X, W, saved, H, dH, dX, dW, db)
+    o = _layer_opts(indptr_t, plan, relu, order, stream, workspace)
+    _call_allocating("gnn_sage_layer_bwd", lambda: load_library().gnn_sage_layer_bwd(
+        _ptr(indptr_t), _ptr(indices_t), _ptr(X), _ptr(W), _ptr(saved), _ptr(H), _ptr(dH), _ptr(dX), _ptr(dW), _ptr(db),
+        int(X.shape[0]), int(W.shape[0]), int(W.shape[1]), ctypes.byref(o)))
 
 
 def gnn_csr_from_sorted_coo(dst_sorted: torch.Tensor, N: int, indptr_out: torch.Tensor, stream=None) -> None:

@@ -62,6 +62,8 @@ struct AggArgs {
     int32_t log2_slices;  // column slices; workgroup b serves slice b % n_slices (see run_aggregate)
     int32_t slice_cols;   // columns per slice (the last slice of a launch may hold fewer)
     int32_t store_vec;    // widest store the output rows allow (elements, <= VEC)
+    const float *bias;    // fused layer epilogue: per-column bias added to the scaled row, or nullptr
+    int32_t relu;         // fused layer epilogue: rectifier after the bias
     BinDesc bins[GNN_MAX_BINS + 1];
 };
 
@@ -355,6 +357,15 @@ __global__ void __launch_bounds__(kBlockThreads) aggregate_kernel(const AggArgs 
         float o[VEC];
 #pragma unroll
         for (int i = 0; i < VEC; ++i) o[i] = acc[p][i] * ds;
+        if (a.bias) {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i)
+                if (i < ncols[p]) o[i] += a.bias[col[p] + i];
+        }
+        if (a.relu) {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) o[i] = o[i] > 0.0f ? o[i] : 0.0f;
+        }
         store_strip<T, VEC>(y + col[p], o, ncols[p], a.store_vec);
     }
 }
@@ -367,7 +378,8 @@ __global__ void __launch_bounds__(256) hub_finalize_kernel(const int32_t *__rest
                                                            int ip64, int dst_mode, T *__restrict__ Y, int64_t ldy,
                                                            int F, int64_t ldp, int self_mode,
                                                            const T *__restrict__ G, int64_t ldg,
-                                                           const int32_t *__restrict__ col_counts) {
+                                                           const int32_t *__restrict__ col_counts,
+                                                           const float *__restrict__ bias, int relu) {
     const int64_t i = blockIdx.x;
     if (i >= n_hub) return;
     const int64_t row = hub_rows[i];
@@ -382,6 +394,8 @@ __global__ void __launch_bounds__(256) hub_finalize_kernel(const int32_t *__rest
             sum = fmaf(self_mode == kSelfInvPlus1 ? scale_of(kScaleInvPlus1, col_counts[row]) : 1.0f, xs[0], sum);
         }
         float o[1] = {sum * ds};
+        if (bias) o[0] += bias[colx];
+        if (relu) o[0] = o[0] > 0.0f ? o[0] : 0.0f;
         VecIO<T, 1>::store(Y + row * ldy + colx, o);
     }
 }
@@ -474,9 +488,11 @@ hipError_t launch_coef(bool coef, int npass, dim3 grid, hipStream_t stream, cons
 
 constexpr int kMaxPass = 8;
 
-// One direction of the aggregation.  `gathered` is X (forward) or dY (backward).
+// One direction of the aggregation.  `gathered` is X (forward) or dY (backward).  bias / relu:
+// the epilogue of a fused layer (out = act(aggregate + bias)), or nullptr / 0.
 int run_aggregate(const void *indptr, const int32_t *indices, const float *w, const void *gathered, void *out,
-                  int64_t N, int64_t F, int op, const gnn_opts *opts_in, bool backward) {
+                  int64_t N, int64_t F, int op, const gnn_opts *opts_in, bool backward, const float *bias = nullptr,
+                  int relu = 0) {
     gnn_opts o{};
     if (opts_in) o = *opts_in;
     if (N < 0 || F < 0) return GNN_ERR_INVALID_ARG;
@@ -674,6 +690,8 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         a.log2_slices = log2_s;
         a.slice_cols = int32_t(slice_cols);
         a.store_vec = store_vec;
+        a.bias = bias ? bias + f0 : nullptr;
+        a.relu = relu;
         int64_t next_block = 0;
         int nb = 0;
         auto add_bin = [&](int kind, int64_t begin, int64_t n_items, int log2_sr) {
@@ -738,18 +756,24 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
             hub_finalize_kernel<float><<<grid, 256, 0, stream>>>(plan->row_perm + hub_begin, plan->n_hub_rows, plan->hub_chunk_offsets,
                                                                  partial, indptr, o.indptr_is_64 ? 1 : 0, dst_mode,
                                                                  static_cast<float *>(out), ldy, int(F), gnn_partial_ld(F), self_mode,
-                                                                 static_cast<const float *>(gathered), ldg, plan->col_counts);
+                                                                 static_cast<const float *>(gathered), ldg, plan->col_counts, bias, relu);
         else
             hub_finalize_kernel<bf16_t><<<grid, 256, 0, stream>>>(plan->row_perm + hub_begin, plan->n_hub_rows, plan->hub_chunk_offsets,
                                                                   partial, indptr, o.indptr_is_64 ? 1 : 0, dst_mode,
                                                                   static_cast<bf16_t *>(out), ldy, int(F), gnn_partial_ld(F), self_mode,
-                                                                  static_cast<const bf16_t *>(gathered), ldg, plan->col_counts);
+                                                                  static_cast<const bf16_t *>(gathered), ldg, plan->col_counts, bias, relu);
         if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
     }
     return GNN_OK;
 }
 
 }  // namespace
+
+// Forward aggregation with the epilogue of a fused layer (used by layer.hip).
+int gnn_aggregate_fwd_epilogue(const void *indptr, const int32_t *indices, const void *X, void *Y, int64_t N, int64_t F,
+                               int op, const gnn_opts *opts, const float *bias, int relu) {
+    return run_aggregate(indptr, indices, nullptr, X, Y, N, F, op, opts, /*backward=*/false, bias, relu);
+}
 
 extern "C" GNN_API int gnn_aggregate_fwd(const void *indptr, const int32_t *indices, const float *edge_w, const void *X,
                                  void *Y, int64_t N, int64_t F, int op, const gnn_opts *opts) {

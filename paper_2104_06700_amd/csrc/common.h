@@ -104,6 +104,15 @@ int gnn_plan_padded(gnn_plan *plan, int64_t bytes);
 // Builds the array on first use (allocation).
 int gnn_plan_edge_scale(gnn_plan *plan, const int32_t *indices, int mode, hipStream_t stream, const float **out);
 
+// gnn_aggregate_fwd with a fused epilogue: Y = act(aggregate(X) + bias), act = rectifier if relu.
+int gnn_aggregate_fwd_epilogue(const void *indptr, const int32_t *indices, const void *X, void *Y, int64_t N, int64_t F,
+                               int op, const gnn_opts *opts, const float *bias, int relu);
+
+// gnn_matmul on a typed stream (shared by the C entry point and the layer calls).
+int gnn_matmul_impl(const float *A, int64_t lda, int trans_a, const float *B, int64_t ldb, int trans_b, float *C, int64_t ldc,
+                    int64_t M, int64_t N, int64_t K, const float *bias, int relu, void *workspace, int64_t workspace_bytes,
+                    hipStream_t stream);
+
 static inline int gnn_ilog2_ceil(int64_t x) {
     int l = 0;
     while ((int64_t(1) << l) < x) ++l;

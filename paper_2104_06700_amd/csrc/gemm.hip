@@ -4,18 +4,19 @@
 //
 // fp32 in, fp32 out, on the matrix cores: v_mfma_f32_32x32x2_f32 multiplies exact fp32 products and
 // accumulates in fp32, so the result meets the same tolerance as the aggregation.  A workgroup of
-// four wavefronts owns a 128 x 128 tile of C; each wavefront a 64 x 64 quarter as 2 x 2 MFMA
-// tiles.  A and B tiles of 16 k-steps are staged through LDS k-major ([k][m] and [k][n]), so that
-// the 32 lanes of an MFMA operand read consecutive words; the global loads follow whichever
-// direction of the operand is contiguous.  The reduction over a very long k (the weight gradient:
+// four wavefronts owns a 128 x 128 tile of C, each wavefront a 64 x 64 quarter as 2 x 2 MFMA
+// tiles (256 x 64 or 256 x 32 tiles for narrow outputs).  A and B tiles of 16 k-steps are staged
+// through LDS k-major ([k][m] and [k][n]), so that the 32 lanes of an MFMA operand read
+// consecutive words; the global loads follow whichever direction of the operand is contiguous
+// and are issued one tile ahead, so they fly while the matrix cores work on the current tile.  The reduction over a very long k (the weight gradient:
 // k = number of vertices) is split over blockIdx.z into partial tiles that a second kernel adds in
 // order (deterministic, no atomics).
 #include "common.h"
 
 namespace {
 
-constexpr int BM = 128, BN = 128, BK = 16;
-constexpr int PAD = 4;  // row stride BM + PAD: k-rows start 4 banks apart
+constexpr int BK = 16;
+constexpr int PAD = 4;  // row stride rows + PAD: k-rows start 4 banks apart
 constexpr int kThreads = 256;
 
 typedef float float16v __attribute__((ext_vector_type(16)));
@@ -34,91 +35,122 @@ struct GemmArgs {
     int32_t n_split;
 };
 
-// Stages a [rows x BK] tile of an operand into LDS as tile[k][r].  X(r, k) = base[r * sr + k * sk].
-// K_CONTIG: sk == 1 (threads run along k with 16-byte loads when aligned), else sr == 1.
-template <bool K_CONTIG>
-__device__ __forceinline__ void stage_tile(float (*tile)[BM + PAD], const float *__restrict__ base, int64_t sr, int64_t sk,
-                                           int64_t r0, int64_t r_end, int64_t k0, int64_t k_end, bool vec_ok) {
-    const int t = threadIdx.x;
-    if (K_CONTIG) {
-        // 128 rows x 16 k = 512 quads of 4 k; thread t takes quads t and t + 256
+// One [ROWS x BK] tile of an operand on its way from global memory to LDS (stored k-major as
+// tile[k][r]).  X(r, k) = base[r * sr + k * sk].  K_CONTIG: sk == 1 (threads run along k), else
+// sr == 1 (threads run along the rows); 16-byte loads when aligned.  load() and store() are
+// separate so that the loads of the next tile are in flight while the matrix cores work.
+template <bool K_CONTIG, int ROWS>
+struct Stager {
+    static constexpr int QUADS = ROWS * BK / 4;
+    static constexpr int PER_THREAD = (QUADS + kThreads - 1) / kThreads;
+    float v[PER_THREAD][4];
+
+    __device__ __forceinline__ void load(const float *__restrict__ base, int64_t sr, int64_t sk, int64_t r0, int64_t r_end,
+                                         int64_t k0, int64_t k_end, bool vec_ok) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int q = t + h * kThreads;
-            const int r = q >> 2, kq = (q & 3) * 4;
-            const int64_t gr = r0 + r, gk = k0 + kq;
-            float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-            if (gr < r_end) {
-                const float *p = base + gr * sr + gk;
-                if (vec_ok && gk + 3 < k_end) {
-                    const float4 x = *reinterpret_cast<const float4 *>(p);
-                    v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
-                } else {
+        for (int h = 0; h < PER_THREAD; ++h) {
+            const int q = int(threadIdx.x) + h * kThreads;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if (gk + i < k_end) v[i] = p[i];
+            for (int i = 0; i < 4; ++i) v[h][i] = 0.0f;
+            if (QUADS % kThreads != 0 && q >= QUADS) continue;
+            if (K_CONTIG) {
+                const int r = q >> 2, kq = (q & 3) * 4;
+                const int64_t gr = r0 + r, gk = k0 + kq;
+                if (gr < r_end) {
+                    const float *p = base + gr * sr + gk;
+                    if (vec_ok && gk + 3 < k_end) {
+                        const float4 x = *reinterpret_cast<const float4 *>(p);
+                        v[h][0] = x.x; v[h][1] = x.y; v[h][2] = x.z; v[h][3] = x.w;
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (gk + i < k_end) v[h][i] = p[i];
+                    }
+                }
+            } else {
+                const int k = q / (ROWS / 4), rq = (q % (ROWS / 4)) * 4;
+                const int64_t gk = k0 + k, gr = r0 + rq;
+                if (gk < k_end) {
+                    const float *p = base + gk * sk + gr;
+                    if (vec_ok && gr + 3 < r_end) {
+                        const float4 x = *reinterpret_cast<const float4 *>(p);
+                        v[h][0] = x.x; v[h][1] = x.y; v[h][2] = x.z; v[h][3] = x.w;
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (gr + i < r_end) v[h][i] = p[i];
+                    }
                 }
             }
-#pragma unroll
-            for (int i = 0; i < 4; ++i) tile[kq + i][r] = v[i];
-        }
-    } else {
-        // rows contiguous: 16 k x 32 quads of 4 rows; thread t takes quads t and t + 256
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int q = t + h * kThreads;
-            const int k = q >> 5, rq = (q & 31) * 4;
-            const int64_t gk = k0 + k, gr = r0 + rq;
-            float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-            if (gk < k_end) {
-                const float *p = base + gk * sk + gr;
-                if (vec_ok && gr + 3 < r_end) {
-                    const float4 x = *reinterpret_cast<const float4 *>(p);
-                    v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if (gr + i < r_end) v[i] = p[i];
-                }
-            }
-            *reinterpret_cast<float4 *>(&tile[k][rq]) = make_float4(v[0], v[1], v[2], v[3]);
         }
     }
-}
 
-template <bool A_K_CONTIG, bool B_K_CONTIG>
+    __device__ __forceinline__ void store(float (*tile)[ROWS + PAD]) const {
+#pragma unroll
+        for (int h = 0; h < PER_THREAD; ++h) {
+            const int q = int(threadIdx.x) + h * kThreads;
+            if (QUADS % kThreads != 0 && q >= QUADS) continue;
+            if (K_CONTIG) {
+                const int r = q >> 2, kq = (q & 3) * 4;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) tile[kq + i][r] = v[h][i];
+            } else {
+                const int k = q / (ROWS / 4), rq = (q % (ROWS / 4)) * 4;
+                *reinterpret_cast<float4 *>(&tile[k][rq]) = make_float4(v[h][0], v[h][1], v[h][2], v[h][3]);
+            }
+        }
+    }
+};
+
+// Workgroup tile (WM * TI * 32) x (WN * TJ * 32): WM x WN wavefronts, each TI x TJ MFMA tiles.
+template <bool A_K_CONTIG, bool B_K_CONTIG, int WM, int WN, int TI, int TJ>
 __global__ void __launch_bounds__(kThreads) gemm_kernel(const GemmArgs g, int a_vec_ok, int b_vec_ok) {
+    static_assert(WM * WN == kThreads / 64, "four wavefronts");
+    constexpr int BM = WM * TI * 32, BN = WN * TJ * 32;
     __shared__ __attribute__((aligned(16))) float As[BK][BM + PAD];
     __shared__ __attribute__((aligned(16))) float Bs[BK][BN + PAD];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;  // this wavefront's quarter of the tile
+    const int wm = (wave / WN) * TI * 32, wn = (wave % WN) * TJ * 32;  // this wavefront's part of the tile
     const int64_t m0 = int64_t(blockIdx.x) * BM, n0 = int64_t(blockIdx.y) * BN;
     const int64_t k_begin = int64_t(blockIdx.z) * g.k_per_split;
     const int64_t k_end = k_begin + g.k_per_split < g.K ? k_begin + g.k_per_split : g.K;
 
-    float16v acc[2][2];
+    float16v acc[TI][TJ];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < TJ; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
+    Stager<A_K_CONTIG, BM> sa;
+    Stager<B_K_CONTIG, BN> sb;
+    if (k_begin < k_end) {
+        sa.load(g.A, g.sam, g.sak, m0, g.M, k_begin, k_end, a_vec_ok != 0);
+        sb.load(g.B, g.sbn, g.sbk, n0, g.N, k_begin, k_end, b_vec_ok != 0);
+    }
     const int l32 = lane & 31, lk = lane >> 5;
     for (int64_t k0 = k_begin; k0 < k_end; k0 += BK) {
-        stage_tile<A_K_CONTIG>(As, g.A, g.sam, g.sak, m0, g.M, k0, k_end, a_vec_ok != 0);
-        stage_tile<B_K_CONTIG>(Bs, g.B, g.sbn, g.sbk, n0, g.N, k0, k_end, b_vec_ok != 0);
+        sa.store(As);
+        sb.store(Bs);
         __syncthreads();
+        if (k0 + BK < k_end) {  // next tile's loads fly while this tile is multiplied
+            sa.load(g.A, g.sam, g.sak, m0, g.M, k0 + BK, k_end, a_vec_ok != 0);
+            sb.load(g.B, g.sbn, g.sbk, n0, g.N, k0 + BK, k_end, b_vec_ok != 0);
+        }
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
             // operand layout of the 32x32x2 instruction: lane l holds A[l % 32][l / 32] and B[l / 32][l % 32]
-            const float a0 = As[kk + lk][wm + l32], a1 = As[kk + lk][wm + 32 + l32];
-            const float b0 = Bs[kk + lk][wn + l32], b1 = Bs[kk + lk][wn + 32 + l32];
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+            float a[TI], b[TJ];
+#pragma unroll
+            for (int i = 0; i < TI; ++i) a[i] = As[kk + lk][wm + i * 32 + l32];
+#pragma unroll
+            for (int j = 0; j < TJ; ++j) b[j] = Bs[kk + lk][wn + j * 32 + l32];
+#pragma unroll
+            for (int i = 0; i < TI; ++i)
+#pragma unroll
+                for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
         }
         __syncthreads();
     }
@@ -127,9 +159,9 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(const GemmArgs g, int a_
     float *out = g.C;
     if (g.n_split > 1) out += int64_t(blockIdx.z) * g.M * g.ldc;  // partial planes of M x ldc
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+        for (int j = 0; j < TJ; ++j) {
             const int64_t n = n0 + wn + j * 32 + l32;
             if (n >= g.N) continue;
             const float bv = (g.bias && g.n_split == 1) ? g.bias[n] : 0.0f;
@@ -142,6 +174,14 @@ __global__ void __launch_bounds__(kThreads) gemm_kernel(const GemmArgs g, int a_
                 out[m * g.ldc + n] = r;
             }
         }
+}
+
+template <int WM, int WN, int TI, int TJ>
+void launch_gemm(bool a_k, bool b_k, dim3 grid, hipStream_t stream, const GemmArgs &g, int a_vec, int b_vec) {
+    if (a_k && !b_k) gemm_kernel<true, false, WM, WN, TI, TJ><<<grid, kThreads, 0, stream>>>(g, a_vec, b_vec);
+    else if (a_k && b_k) gemm_kernel<true, true, WM, WN, TI, TJ><<<grid, kThreads, 0, stream>>>(g, a_vec, b_vec);
+    else if (!a_k && !b_k) gemm_kernel<false, false, WM, WN, TI, TJ><<<grid, kThreads, 0, stream>>>(g, a_vec, b_vec);
+    else gemm_kernel<false, true, WM, WN, TI, TJ><<<grid, kThreads, 0, stream>>>(g, a_vec, b_vec);
 }
 
 // C = act(sum over the partial planes + bias)
@@ -163,7 +203,16 @@ __global__ void __launch_bounds__(256) gemm_reduce_kernel(const float *__restric
 }  // namespace
 
 // How many partial planes the reduction over k is split into.
+// Tile width: 128 columns, or 64 / 32 (with 256 rows) for narrow outputs such as class scores.
+static void choose_tile(int64_t N, int64_t *bm, int64_t *bn) {
+    if (N > 64) { *bm = 128; *bn = 128; }
+    else if (N > 32) { *bm = 256; *bn = 64; }
+    else { *bm = 256; *bn = 32; }
+}
+
 static int64_t choose_split(int64_t M, int64_t N, int64_t K) {
+    int64_t BM, BN;
+    choose_tile(N, &BM, &BN);
     const int64_t tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
     if (tiles >= 512 || K < 4096) return 1;
     int64_t split = (1024 + tiles - 1) / tiles;           // aim at ~4 workgroups per compute unit
@@ -181,7 +230,14 @@ extern "C" GNN_API int64_t gnn_matmul_workspace_bytes(int64_t M, int64_t N, int6
 
 extern "C" GNN_API int gnn_matmul(const float *A, int64_t lda, int trans_a, const float *B, int64_t ldb, int trans_b,
                                   float *C, int64_t ldc, int64_t M, int64_t N, int64_t K, const float *bias, int relu,
-                                  void *workspace, int64_t workspace_bytes, void *stream_) {
+                                  void *workspace, int64_t workspace_bytes, void *stream) {
+    return gnn_matmul_impl(A, lda, trans_a, B, ldb, trans_b, C, ldc, M, N, K, bias, relu, workspace, workspace_bytes,
+                           static_cast<hipStream_t>(stream));
+}
+
+int gnn_matmul_impl(const float *A, int64_t lda, int trans_a, const float *B, int64_t ldb, int trans_b, float *C, int64_t ldc,
+                    int64_t M, int64_t N, int64_t K, const float *bias, int relu, void *workspace, int64_t workspace_bytes,
+                    hipStream_t stream) {
     if (M < 0 || N < 0 || K < 0) return GNN_ERR_INVALID_ARG;
     if (M == 0 || N == 0) return GNN_OK;
     if (!C || ldc < N) return GNN_ERR_INVALID_ARG;
@@ -190,7 +246,6 @@ extern "C" GNN_API int gnn_matmul(const float *A, int64_t lda, int trans_a, cons
     if (K > 0 && (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N))) return GNN_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(C) % 4 || reinterpret_cast<uintptr_t>(A) % 4 || reinterpret_cast<uintptr_t>(B) % 4)
         return GNN_ERR_INVALID_ARG;
-    hipStream_t stream = static_cast<hipStream_t>(stream_);
     (void)hipGetLastError();
 
     GemmArgs g{};
@@ -207,15 +262,17 @@ extern "C" GNN_API int gnn_matmul(const float *A, int64_t lda, int trans_a, cons
         g.C = static_cast<float *>(workspace);
         g.ldc = N;
     }
+    int64_t BM, BN;
+    choose_tile(N, &BM, &BN);
     const int64_t gx = (M + BM - 1) / BM, gy = (N + BN - 1) / BN;
     if (gx > INT32_MAX || gy > 65535 || split > 65535) return GNN_ERR_UNSUPPORTED;
     dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy), static_cast<unsigned>(split));
     const int a_vec = (lda % 4 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0) ? 1 : 0;
     const int b_vec = (ldb % 4 == 0 && reinterpret_cast<uintptr_t>(B) % 16 == 0) ? 1 : 0;
-    if (!trans_a && !trans_b) gemm_kernel<true, false><<<grid, kThreads, 0, stream>>>(g, a_vec, b_vec);
-    else if (!trans_a && trans_b) gemm_kernel<true, true><<<grid, kThreads, 0, stream>>>(g, a_vec, b_vec);
-    else if (trans_a && !trans_b) gemm_kernel<false, false><<<grid, kThreads, 0, stream>>>(g, a_vec, b_vec);
-    else gemm_kernel<false, true><<<grid, kThreads, 0, stream>>>(g, a_vec, b_vec);
+    const bool a_k = !trans_a, b_k = trans_b != 0;  // is k the contiguous direction of the operand?
+    if (BN == 128) launch_gemm<2, 2, 2, 2>(a_k, b_k, grid, stream, g, a_vec, b_vec);
+    else if (BN == 64) launch_gemm<4, 1, 2, 2>(a_k, b_k, grid, stream, g, a_vec, b_vec);
+    else launch_gemm<4, 1, 2, 1>(a_k, b_k, grid, stream, g, a_vec, b_vec);
     if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
     if (split > 1) {
         int64_t blocks = (M * N + 255) / 256;

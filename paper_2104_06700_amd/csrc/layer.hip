@@ -1,0 +1,191 @@
+// One GraphSAGE layer: neighbourhood aggregation followed by the dense update (Section 6.3,
+// "Memory": every layer is the aggregation step followed by the MLP operation with one weight
+// matrix), with the aggregator of the paper's runs (Section 6.1: sum of the in-neighbours plus the
+// vertex's own vector, over in-degree + 1):
+//
+//     H = act( A^ X W + b ),     A^ = D^-1 (A + I),  D = diag(din + 1)
+//
+// Both steps are linear, so the cheaper order is taken: aggregate first when F_in <= F_out
+// (gather rows of width F_in), transform first otherwise (gather rows of width F_out: the class
+// scores of a last layer, or 16 hidden units after 602 input features); in the second case bias
+// and rectifier are the epilogue of the aggregation kernel, in the first of the matrix product.
+// The backward pass mirrors the order taken:
+//     G  = dH where H > 0 (rectifier; the stored forward output decides), db = column sums of G
+//     aggregate first:  dW = Z^T G,  dZ = G W^T,  dX = A^^T dZ          (Z = A^ X, stored by forward)
+//     transform first:  dP = A^^T G, dW = X^T dP, dX = dP W^T
+#include "common.h"
+
+namespace {
+
+constexpr int kRowsPerBlock = 128;
+
+// G = dH where H > 0 (else 0) for a block of rows, plus the block's column sums of G.
+// One thread per column (strided), rows walked in order: deterministic.
+__global__ void __launch_bounds__(256) mask_colsum_kernel(const float *__restrict__ H, const float *__restrict__ dH,
+                                                          float *__restrict__ G, float *__restrict__ partial, int64_t N,
+                                                          int F, int relu) {
+    const int64_t r0 = int64_t(blockIdx.x) * kRowsPerBlock;
+    const int64_t r1 = r0 + kRowsPerBlock < N ? r0 + kRowsPerBlock : N;
+    for (int j = threadIdx.x; j < F; j += blockDim.x) {
+        float s = 0.0f;
+        for (int64_t r = r0; r < r1; ++r) {
+            float g = dH[r * F + j];
+            if (relu) {
+                g = H[r * F + j] > 0.0f ? g : 0.0f;
+                G[r * F + j] = g;
+            }
+            s += g;
+        }
+        partial[int64_t(blockIdx.x) * F + j] = s;
+    }
+}
+
+// db[j] = sum of the block partials, in block order, two levels (chunks of 256 blocks).
+__global__ void __launch_bounds__(256) colsum_reduce_kernel(const float *__restrict__ partial, int64_t n_blocks, int F,
+                                                            float *__restrict__ out, int chunk) {
+    const int64_t b0 = int64_t(blockIdx.x) * chunk;
+    const int64_t b1 = b0 + chunk < n_blocks ? b0 + chunk : n_blocks;
+    for (int j = threadIdx.x; j < F; j += blockDim.x) {
+        float s = 0.0f;
+        for (int64_t b = b0; b < b1; ++b) s += partial[b * F + j];
+        out[int64_t(blockIdx.x) * F + j] = s;
+    }
+}
+
+__global__ void __launch_bounds__(256) zero_kernel(float *__restrict__ p, int64_t n) {
+    const int64_t stride = int64_t(gridDim.x) * blockDim.x;
+    for (int64_t t = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; t < n; t += stride) p[t] = 0.0f;
+}
+
+int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+bool aggregate_first(int order, int64_t Fi, int64_t Fo) { return order == 1 || (order == 0 && Fi <= Fo); }
+
+struct BwdLayout {
+    int64_t g_off, t_off, part_off, part2_off, mm_off, total;
+};
+
+BwdLayout bwd_layout(int64_t N, int64_t Fi, int64_t Fo, bool agg_first, bool relu) {
+    BwdLayout L{};
+    int64_t off = 0;
+    L.g_off = off;
+    if (relu) off += round_up(N * Fo * 4, 256);
+    L.t_off = off;
+    off += round_up(N * (agg_first ? Fi : Fo) * 4, 256);
+    const int64_t n_blocks = (N + kRowsPerBlock - 1) / kRowsPerBlock;
+    L.part_off = off;
+    off += round_up(n_blocks * Fo * 4, 256);
+    L.part2_off = off;
+    off += round_up(((n_blocks + 255) / 256) * Fo * 4, 256);
+    L.mm_off = off;
+    off += round_up(gnn_matmul_workspace_bytes(Fi, Fo, N), 256);
+    L.total = off;
+    return L;
+}
+
+}  // namespace
+
+extern "C" GNN_API int64_t gnn_sage_layer_saved_elems(int64_t N, int64_t F_in, int64_t F_out, int order) {
+    if (N < 0 || F_in < 0 || F_out < 0) return 0;
+    return N * (aggregate_first(order, F_in, F_out) ? F_in : F_out);
+}
+
+extern "C" GNN_API int64_t gnn_sage_layer_workspace_bytes(int64_t N, int64_t F_in, int64_t F_out, int relu, int order) {
+    if (N <= 0 || F_in <= 0 || F_out <= 0) return 0;
+    return bwd_layout(N, F_in, F_out, aggregate_first(order, F_in, F_out), relu != 0).total;
+}
+
+static int check_layer(const gnn_layer_opts *opts, int64_t N, int64_t Fi, int64_t Fo, gnn_layer_opts &o) {
+    if (!opts) return GNN_ERR_INVALID_ARG;
+    o = *opts;
+    if (N < 0 || Fi < 0 || Fo < 0 || N > INT32_MAX || Fi > INT32_MAX || Fo > INT32_MAX) return GNN_ERR_INVALID_ARG;
+    if (o.order < 0 || o.order > 2) return GNN_ERR_INVALID_ARG;
+    if (!o.plan) return GNN_ERR_UNSUPPORTED;  // the aggregator needs the plan's degree counts
+    if (o.plan->n_rows != N || o.plan->indptr_is_64 != (o.indptr_is_64 ? 1 : 0)) return GNN_ERR_INVALID_ARG;
+    return GNN_OK;
+}
+
+extern "C" GNN_API int gnn_sage_layer_fwd(const void *indptr, const int32_t *indices, const float *X, const float *W,
+                                          const float *bias, float *saved, float *H, int64_t N, int64_t F_in, int64_t F_out,
+                                          const gnn_layer_opts *opts) {
+    gnn_layer_opts o;
+    int rc = check_layer(opts, N, F_in, F_out, o);
+    if (rc != GNN_OK) return rc;
+    if (N == 0 || F_out == 0) return GNN_OK;
+    if (F_in == 0) return GNN_ERR_INVALID_ARG;
+    if (!indptr || !X || !W || !saved || !H) return GNN_ERR_INVALID_ARG;
+    hipStream_t stream = static_cast<hipStream_t>(o.stream);
+    gnn_opts a{};
+    a.dtype = GNN_F32;
+    a.indptr_is_64 = o.indptr_is_64;
+    a.stream = o.stream;
+    a.plan = o.plan;
+    if (aggregate_first(o.order, F_in, F_out)) {
+        rc = gnn_aggregate_fwd(indptr, indices, nullptr, X, saved, N, F_in, GNN_SAGE_GCN, &a);
+        if (rc != GNN_OK) return rc;
+        return gnn_matmul_impl(saved, F_in, 0, W, F_out, 0, H, F_out, N, F_out, F_in, bias, o.relu, nullptr, 0, stream);
+    }
+    rc = gnn_matmul_impl(X, F_in, 0, W, F_out, 0, saved, F_out, N, F_out, F_in, nullptr, 0, nullptr, 0, stream);
+    if (rc != GNN_OK) return rc;
+    return gnn_aggregate_fwd_epilogue(indptr, indices, saved, H, N, F_out, GNN_SAGE_GCN, &a, bias, o.relu);
+}
+
+extern "C" GNN_API int gnn_sage_layer_bwd(const void *indptr_t, const int32_t *indices_t, const float *X, const float *W,
+                                          const float *saved, const float *H, const float *dH, float *dX, float *dW,
+                                          float *db, int64_t N, int64_t F_in, int64_t F_out, const gnn_layer_opts *opts) {
+    gnn_layer_opts o;
+    int rc = check_layer(opts, N, F_in, F_out, o);
+    if (rc != GNN_OK) return rc;
+    if (F_in == 0 || F_out == 0) return GNN_OK;
+    if (!W || !dH || !dW || (o.relu && !H)) return GNN_ERR_INVALID_ARG;
+    const bool agg_first = aggregate_first(o.order, F_in, F_out);
+    if (N > 0 && (!indptr_t || !X || (agg_first && !saved))) return GNN_ERR_INVALID_ARG;
+    const BwdLayout L = bwd_layout(N > 0 ? N : 1, F_in, F_out, agg_first, o.relu != 0);
+    if (N > 0 && (!o.workspace || o.workspace_bytes < L.total || reinterpret_cast<uintptr_t>(o.workspace) % 16))
+        return GNN_ERR_INVALID_ARG;
+    hipStream_t stream = static_cast<hipStream_t>(o.stream);
+    (void)hipGetLastError();
+    char *ws = static_cast<char *>(o.workspace);
+    if (N == 0) {
+        zero_kernel<<<64, 256, 0, stream>>>(dW, F_in * F_out);
+        if (db) zero_kernel<<<1, 256, 0, stream>>>(db, F_out);
+        return hipGetLastError() == hipSuccess ? GNN_OK : GNN_ERR_LAUNCH;
+    }
+    float *G = o.relu ? reinterpret_cast<float *>(ws + L.g_off) : nullptr;
+    float *T = reinterpret_cast<float *>(ws + L.t_off);
+    float *part = reinterpret_cast<float *>(ws + L.part_off);
+    float *part2 = reinterpret_cast<float *>(ws + L.part2_off);
+    void *mm_ws = ws + L.mm_off;
+    const int64_t mm_bytes = L.total - L.mm_off;
+
+    // rectifier mask and bias gradient
+    const int64_t n_blocks = (N + kRowsPerBlock - 1) / kRowsPerBlock;
+    if (o.relu || db) {
+        mask_colsum_kernel<<<static_cast<unsigned>(n_blocks), 256, 0, stream>>>(H, dH, G, part, N, int(F_out), o.relu ? 1 : 0);
+        if (db) {
+            const int64_t n2 = (n_blocks + 255) / 256;
+            colsum_reduce_kernel<<<static_cast<unsigned>(n2), 256, 0, stream>>>(part, n_blocks, int(F_out), part2, 256);
+            colsum_reduce_kernel<<<1, 256, 0, stream>>>(part2, n2, int(F_out), db, int(n2));
+        }
+        if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
+    }
+    const float *Gm = o.relu ? G : dH;
+
+    gnn_opts a{};
+    a.dtype = GNN_F32;
+    a.indptr_is_64 = o.indptr_is_64;
+    a.stream = o.stream;
+    a.plan = o.plan;
+    if (agg_first) {
+        rc = gnn_matmul_impl(saved, F_in, 1, Gm, F_out, 0, dW, F_out, F_in, F_out, N, nullptr, 0, mm_ws, mm_bytes, stream);
+        if (rc != GNN_OK || !dX) return rc;
+        rc = gnn_matmul_impl(Gm, F_out, 0, W, F_out, 1, T, F_in, N, F_in, F_out, nullptr, 0, nullptr, 0, stream);
+        if (rc != GNN_OK) return rc;
+        return gnn_aggregate_bwd(indptr_t, indices_t, nullptr, T, dX, N, F_in, GNN_SAGE_GCN, &a);
+    }
+    rc = gnn_aggregate_bwd(indptr_t, indices_t, nullptr, Gm, T, N, F_out, GNN_SAGE_GCN, &a);
+    if (rc != GNN_OK) return rc;
+    rc = gnn_matmul_impl(X, F_in, 1, T, F_out, 0, dW, F_out, F_in, F_out, N, nullptr, 0, mm_ws, mm_bytes, stream);
+    if (rc != GNN_OK || !dX) return rc;
+    return gnn_matmul_impl(T, F_out, 0, W, F_out, 1, dX, F_in, N, F_in, F_out, nullptr, 0, nullptr, 0, stream);
+}

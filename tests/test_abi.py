@@ -40,6 +40,8 @@ def test_struct_layout_matches_header():
     assert ctypes.sizeof(gnn.GnnPlanParams) == 8 + 15 * 8 + 8
     # gnn_ap_opts: 2 x int32, 3 x int64, 3 pointers, 2 x int32
     assert ctypes.sizeof(gnn.GnnApOpts) == 8 + 24 + 24 + 8
+    # gnn_layer_opts: 4 x int32, 3 pointers, int64
+    assert ctypes.sizeof(gnn.GnnLayerOpts) == 16 + 24 + 8
 
 
 def test_argument_checks_that_need_no_device():
@@ -83,3 +85,16 @@ def test_argument_checks_that_need_no_device():
     assert lib.gnn_ap_bwd_vertex(one, one, one, one, None, 4, 4, 0, ctypes.byref(a)) == bad
     assert lib.gnn_ap_bwd_vertex(one, one, one, one, one, 4, 0, 0, ctypes.byref(a)) == ok
     assert lib.gnn_ap_bwd_vertex_arg(one, one, one, one, one, -1, 4, 4, 0, ctypes.byref(a)) == bad
+    # dense update and layer
+    assert lib.gnn_matmul(one, 4, 0, one, 4, 0, one, 2, 4, 4, 4, None, 0, None, 0, None) == bad      # ldc < N
+    assert lib.gnn_matmul(None, 4, 0, one, 4, 0, one, 4, 4, 4, 4, None, 0, None, 0, None) == bad
+    assert lib.gnn_matmul(one, 4, 0, one, 4, 0, one, 4, 0, 4, 4, None, 0, None, 0, None) == ok
+    assert lib.gnn_matmul_workspace_bytes(100, 47, 2_000_000) > 0 and lib.gnn_matmul_workspace_bytes(2_000_000, 256, 100) == 0
+    lo = gnn.GnnLayerOpts()
+    assert lib.gnn_sage_layer_fwd(one, one, one, one, None, one, one, 4, 4, 4, None) == bad
+    assert lib.gnn_sage_layer_fwd(one, one, one, one, None, one, one, 4, 4, 4, ctypes.byref(lo)) == gnn.GNN_ERR_UNSUPPORTED
+    lo.order = 5
+    assert lib.gnn_sage_layer_bwd(one, one, one, one, one, one, one, one, one, one, 4, 4, 4, ctypes.byref(lo)) == bad
+    assert lib.gnn_sage_layer_saved_elems(10, 3, 5, 0) == 30 and lib.gnn_sage_layer_saved_elems(10, 5, 3, 0) == 30
+    assert lib.gnn_sage_layer_saved_elems(10, 5, 3, 1) == 50
+    assert lib.gnn_sage_layer_workspace_bytes(1000, 8, 4, 1, 0) >= 1000 * 4 * 4 * 2

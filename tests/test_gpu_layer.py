@@ -93,3 +93,104 @@ def test_matmul_long_reduction_is_split_and_deterministic():
     gnn.gnn_matmul(Zd, Gd, C, trans_a=True)  # no workspace: unsplit, still right
     torch.cuda.synchronize()
     _close(C, ref, S, "unsplit long reduction", rtol=2e-4)
+
+
+# ------------------------------------------------------------------ one layer
+def _graph(kind):
+    if kind == "multi":
+        return synth.small_random_multigraph(900, 7000, 3), None
+    if kind == "rmat_hubs":
+        return synth.rmat_symmetric(4000, 120000, (0.57, 0.19, 0.19, 0.05), 5), gnn.make_plan_params([2, 8, 32, 128], 64)
+    raise KeyError(kind)
+
+
+def _layer_case(el, params, fi, fo, relu, order, seed, use_bias=True, want_dx=True):
+    rng = np.random.default_rng(seed)
+    n = el.n
+    dg = device_graph(el, plan_params=params)
+    indptr, indices, *_ = host_csr(el)
+    X = rng.normal(size=(n, fi)).astype(np.float32)
+    W = (rng.normal(size=(fi, fo)) / np.sqrt(fi)).astype(np.float32)
+    b = rng.normal(size=fo).astype(np.float32) if use_bias else None
+    dH = rng.normal(size=(n, fo)).astype(np.float32)
+    what = f"n={n} E={el.e} {fi}->{fo} relu={relu} order={order} bias={use_bias}"
+    print(what, flush=True)
+    Xd, Wd, dHd = (torch.from_numpy(a).to(DEV) for a in (X, W, dH))
+    bd = None if b is None else torch.from_numpy(b).to(DEV)
+    saved = torch.full((gnn.gnn_sage_layer_saved_elems(n, fi, fo, order),), float("nan"), device=DEV)
+    H = torch.full((n, fo), float("nan"), device=DEV)
+    gnn.gnn_sage_layer_fwd(dg.indptr, dg.indices, Xd, Wd, bd, saved, H, dg.plan_fwd, relu=relu, order=order)
+    torch.cuda.synchronize()
+    Z, Ho, SH = oracle.sage_layer_fwd(indptr, indices, X, W, b, relu)
+    _close(H, Ho, SH, "forward " + what)
+    # backward; the stored forward output that decides the rectifier's mask is the oracle's, for both sides
+    Hs = Ho.astype(np.float32)
+    ws = torch.empty(max(1, gnn.gnn_sage_layer_workspace_bytes(n, fi, fo, relu, order) // 4), device=DEV)
+    dX = torch.full((n, fi), float("nan"), device=DEV) if want_dx else None
+    dW = torch.full((fi, fo), float("nan"), device=DEV)
+    db = torch.full((fo,), float("nan"), device=DEV)
+    gnn.gnn_sage_layer_bwd(dg.indptr_t, dg.indices_t, Xd, Wd, saved, torch.from_numpy(Hs).to(DEV), dHd, dX, dW, db,
+                           dg.plan_bwd, ws, relu=relu, order=order)
+    torch.cuda.synchronize()
+    g = oracle.sage_layer_bwd(indptr, indices, X, W, Hs, dH, relu)
+    _close(dW, g["dW"][0], g["dW"][1], "dW " + what)
+    _close(db, g["db"][0], g["db"][1], "db " + what)
+    if want_dx:
+        _close(dX, g["dX"][0], g["dX"][1], "dX " + what)
+
+
+@pytest.mark.parametrize("kind", ["multi", "rmat_hubs"])
+@pytest.mark.parametrize("fi,fo", [(100, 256), (256, 47), (602, 16), (5, 3), (64, 64), (33, 130)])
+@pytest.mark.parametrize("relu", [True, False])
+def test_layer_forward_and_gradients(kind, fi, fo, relu):
+    el, params = _graph(kind)
+    _layer_case(el, params, fi, fo, relu, order=0, seed=fi + fo)
+
+
+@pytest.mark.parametrize("order", [1, 2])
+@pytest.mark.parametrize("fi,fo", [(100, 256), (256, 47)])
+def test_layer_either_order_gives_the_same_layer(order, fi, fo):
+    el, params = _graph("rmat_hubs")
+    _layer_case(el, params, fi, fo, True, order=order, seed=9)
+
+
+def test_layer_without_bias_and_without_input_gradient():
+    el, params = _graph("multi")
+    _layer_case(el, params, 40, 24, True, order=0, seed=10, use_bias=False, want_dx=False)
+    _layer_case(el, params, 24, 40, False, order=0, seed=11, use_bias=False, want_dx=False)
+
+
+def test_layer_gradients_are_reproducible():
+    el, params = _graph("rmat_hubs")
+    n, fi, fo = el.n, 100, 47
+    dg = device_graph(el, plan_params=params)
+    X = torch.randn(n, fi, device=DEV)
+    W = torch.randn(fi, fo, device=DEV)
+    H = torch.randn(n, fo, device=DEV)
+    dH = torch.randn(n, fo, device=DEV)
+    ws = torch.empty(gnn.gnn_sage_layer_workspace_bytes(n, fi, fo, True, 0) // 4, device=DEV)
+    outs = []
+    for _ in range(2):
+        dX, dW, db = torch.empty(n, fi, device=DEV), torch.empty(fi, fo, device=DEV), torch.empty(fo, device=DEV)
+        gnn.gnn_sage_layer_bwd(dg.indptr_t, dg.indices_t, X, W, None, H, dH, dX, dW, db, dg.plan_bwd, ws)
+        torch.cuda.synchronize()
+        outs.append((dX, dW, db))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
+def test_layer_argument_errors():
+    el, params = _graph("multi")
+    dg = device_graph(el, plan_params=params)
+    n = el.n
+    X = torch.randn(n, 8, device=DEV)
+    W = torch.randn(8, 4, device=DEV)
+    H = torch.empty(n, 4, device=DEV)
+    saved = torch.empty(n * 8, device=DEV)
+    with pytest.raises(gnn.GnnError):   # no plan
+        gnn.gnn_sage_layer_fwd(dg.indptr, dg.indices, X, W, None, saved, H, None)
+    with pytest.raises(gnn.GnnError):   # workspace too small
+        gnn.gnn_sage_layer_bwd(dg.indptr_t, dg.indices_t, X, W, saved, H, H, torch.empty_like(X), torch.empty_like(W), None,
+                               dg.plan_bwd, torch.empty(16, device=DEV))
+    with pytest.raises(ValueError):
+        gnn.gnn_sage_layer_fwd(dg.indptr, dg.indices, X[:, ::2], W, None, saved, H, dg.plan_fwd)
