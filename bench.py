@@ -323,6 +323,59 @@ def measure_general_primitive(workload, dev, reps=5):
             "note": "algorithmic_GB = operands read once + results written once; frac_of_hbm_peak = that / time / 8 TB/s"}
 
 
+MODELS = {  # layer widths of the paper's GraphSAGE models (Section 6.1; Table 2 for inputs and classes)
+    "rmat_sparse_stack": (100, 256, 256, 47),
+    "rmat_dense_wide": (602, 16, 41),
+}
+
+
+def measure_layers(workload, dev, reps=5):
+    """Forward and backward of every layer of the paper's model for this graph shape (aggregation +
+    dense update, gnn_sage_layer_*), each timed with events on the launch stream.  Not part of `value`."""
+    dims = MODELS[workload]
+    w = synth.WORKLOADS[workload]
+    el = synth.make_graph(workload, device=dev)
+    n, e = el.n, el.e
+    dg = gnn.build_device_graph(el.dst, el.src, n, indptr64=w["indptr64"])
+    rows = []
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    for li in range(len(dims) - 1):
+        fi, fo = dims[li], dims[li + 1]
+        relu = li < len(dims) - 2
+        X = synth.normal_features(n, fi, 400 + li, device=dev)
+        W = synth.normal_features(fi, fo, 410 + li, device=dev) / fi ** 0.5
+        b = synth.normal_features(1, fo, 420 + li, device=dev).reshape(fo)
+        dH = synth.normal_features(n, fo, 430 + li, device=dev)
+        H = torch.empty((n, fo), device=dev)
+        dX = torch.empty((n, fi), device=dev) if li else None
+        dW, db = torch.empty((fi, fo), device=dev), torch.empty(fo, device=dev)
+        saved = torch.empty(gnn.gnn_sage_layer_saved_elems(n, fi, fo), device=dev)
+        ws = torch.empty(gnn.gnn_sage_layer_workspace_bytes(n, fi, fo, relu) // 4, device=dev)
+        tf = timed(lambda: gnn.gnn_sage_layer_fwd(dg.indptr, dg.indices, X, W, b, saved, H, dg.plan_fwd, relu=relu))
+        tb = timed(lambda: gnn.gnn_sage_layer_bwd(dg.indptr_t, dg.indices_t, X, W, saved, H, dH, dX, dW, db, dg.plan_bwd, ws,
+                                                  relu=relu))
+        rows.append({"layer": f"{fi}->{fo}", "order": "aggregate first" if fi <= fo else "transform first",
+                     "gathered_width": min(fi, fo), "fwd_ms": round(tf, 4), "bwd_ms": round(tb, 4),
+                     "dense_GFLOP_fwd": round(2.0 * n * fi * fo / 1e9, 2), "input_gradient": li > 0})
+        del X, W, H, dH, dX, saved, ws
+    return {"workload": workload, "widths": list(dims), "layers": rows,
+            "fwd_ms": round(sum(r["fwd_ms"] for r in rows), 4), "bwd_ms": round(sum(r["bwd_ms"] for r in rows), 4),
+            "note": "model compute of one full-batch epoch without loss and optimizer; the paper's epochs on one Xeon 8280 "
+                    "socket: 0.88 s (232,965-vertex dataset, widths 602-16-41) and 11 s (2,449,029-vertex dataset, "
+                    "widths 100-256-256-47), Sections 6.2 and 6.3 -- other hardware and real data, context only"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -336,6 +389,8 @@ def main():
                     help="a second workload measured briefly in the same run and reported under 'secondary' ('' = none)")
     ap.add_argument("--no-general-primitive", action="store_true",
                     help="skip the operator-table calls (gnn_ap_*) reported under 'general_primitive'")
+    ap.add_argument("--no-layers", action="store_true",
+                    help="skip the GraphSAGE layer calls (gnn_sage_layer_*) reported under 'layers'")
     ap.add_argument("--dump-graph", default=None, metavar="DIR",
                     help="write the CSR and transposed CSR as raw arrays for the stand-alone profiling driver, then exit")
     args = ap.parse_args()
@@ -360,6 +415,10 @@ def main():
     if not args.no_general_primitive and args.scale == 1.0 and e <= 500_000_000:
         torch.cuda.empty_cache()
         result["general_primitive"] = measure_general_primitive(args.workload, dev)
+        torch.cuda.empty_cache()
+    if not args.no_layers and args.scale == 1.0:
+        torch.cuda.empty_cache()
+        result["layers"] = [measure_layers(wl, dev) for wl in (args.workload, args.secondary) if wl in MODELS]
         torch.cuda.empty_cache()
     if not args.no_calibration:
         result["ceilings"] = calibrate(dev)

@@ -194,3 +194,56 @@ def test_layer_argument_errors():
                                dg.plan_bwd, torch.empty(16, device=DEV))
     with pytest.raises(ValueError):
         gnn.gnn_sage_layer_fwd(dg.indptr, dg.indices, X[:, ::2], W, None, saved, H, dg.plan_fwd)
+
+
+@pytest.mark.timeout(900)
+def test_layer_fullsize_sparse_workload():
+    """2,449,029 vertices / 123,718,280 edges, the first layer of the paper's model for this graph
+    (100 -> 256, aggregate first) and its last (256 -> 47, transform first), default plans.
+    Forward: sampled rows against the oracle on the compacted neighbourhood of the sample.
+    Backward: the identities that tie the gradients to the forward map, in fp64 on the whole output:
+    <G, H> = <dW, W> + <db, b> = <dX, X> + <db, b> with G = dH where H > 0."""
+    el = synth.make_graph("rmat_sparse_stack", device=DEV)
+    n = el.n
+    dg = gnn.build_device_graph(el.dst, el.src, n)
+    dst_h, src_h = synth.to_csr_numpy(el)
+    indptr = oracle.csr_indptr(dst_h, n)
+    deg = np.diff(indptr)
+    rng = np.random.default_rng(4)
+    rows = np.unique(np.concatenate([np.argsort(deg)[-16:], rng.choice(n, 1500, replace=False), np.flatnonzero(deg == 0)[:8]]))
+    # compacted problem: the sampled rows first (their own vectors are needed), then every neighbour
+    nbr = np.concatenate([src_h[indptr[r]:indptr[r + 1]] for r in rows]).astype(np.int64)
+    ids = np.concatenate([rows, np.setdiff1d(np.unique(nbr), rows)])
+    local = np.full(n, -1, dtype=np.int64)
+    local[ids] = np.arange(len(ids))
+    sub_ptr = np.zeros(len(ids) + 1, dtype=np.int64)
+    sub_ptr[1:len(rows) + 1] = np.cumsum(deg[rows])
+    sub_ptr[len(rows) + 1:] = sub_ptr[len(rows)]
+    sub_idx = local[nbr].astype(np.int32)
+    for fi, fo, relu in ((100, 256, True), (256, 47, False)):
+        print(f"[fullsize layer] {fi}->{fo} relu={relu}", flush=True)
+        X = synth.normal_features(n, fi, 1, device=DEV)
+        W = synth.normal_features(fi, fo, 2, device=DEV) / fi ** 0.5
+        b = synth.normal_features(1, fo, 3, device=DEV).reshape(fo)
+        dH = synth.normal_features(n, fo, 4, device=DEV)
+        saved = torch.empty(gnn.gnn_sage_layer_saved_elems(n, fi, fo), device=DEV)
+        H = torch.full((n, fo), float("nan"), device=DEV)
+        gnn.gnn_sage_layer_fwd(dg.indptr, dg.indices, X, W, b, saved, H, dg.plan_fwd, relu=relu)
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(H).all())
+        _, Ho, SH = oracle.sage_layer_fwd(sub_ptr, sub_idx, X[torch.from_numpy(ids).to(DEV)].cpu().numpy(), W.cpu().numpy(),
+                                          b.cpu().numpy(), relu)
+        k = len(rows)
+        _close(H[torch.from_numpy(rows).to(DEV)], Ho[:k], SH[:k], f"fullsize forward {fi}->{fo}")
+        ws = torch.empty(gnn.gnn_sage_layer_workspace_bytes(n, fi, fo, relu) // 4, device=DEV)
+        dX, dW, db = torch.empty((n, fi), device=DEV), torch.empty((fi, fo), device=DEV), torch.empty(fo, device=DEV)
+        gnn.gnn_sage_layer_bwd(dg.indptr_t, dg.indices_t, X, W, saved, H, dH, dX, dW, db, dg.plan_bwd, ws, relu=relu)
+        torch.cuda.synchronize()
+        G = torch.where(H > 0, dH, torch.zeros_like(dH)) if relu else dH
+        lhs = (G.double() * H.double()).sum().item()
+        scale = (G.double().abs() * H.double().abs()).sum().item() + (db.double().abs() * b.double().abs()).sum().item()
+        via_w = (dW.double() * W.double()).sum().item() + (db.double() * b.double()).sum().item()
+        via_x = (dX.double() * X.double()).sum().item() + (db.double() * b.double()).sum().item()
+        assert abs(lhs - via_w) <= 2e-6 * scale, (lhs, via_w, scale)
+        assert abs(lhs - via_x) <= 2e-6 * scale, (lhs, via_x, scale)
+        del X, dH, saved, H, ws, dX, G
