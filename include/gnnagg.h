@@ -85,6 +85,11 @@ typedef struct gnn_opts {
 /* Take the padded-copy route whenever a plan is given, whatever the size and alignment (tests). */
 #define GNN_FLAG_FORCE_PADDED_COPY 4
 
+/* The caller guarantees that elements F .. ldx-1 of every gathered row are readable (their values
+ * are ignored): wide loads may then be used for widths that are not a multiple of 4 (2 for bf16:
+ * 8) when ldx is. */
+#define GNN_FLAG_PADDED_ROWS 8
+
 /* Degree-binning parameters.  thresholds t[0] < ... < t[k-1], all > 0, cut the
  * row-length axis into k+1 bins, bin(v) = #{i : t[i] <= deg(v)}.  If
  * hub_chunk > 0 the rows of the LAST bin are "hub" rows: each is cut into
@@ -240,7 +245,7 @@ typedef struct gnn_layer_opts {
  * X [N, F_in], W [F_in, F_out] row-major, bias [F_out] or NULL, H [N, F_out], all dense fp32.
  * `saved` receives what the chosen order materialises, gnn_sage_layer_saved_elems() floats: the
  * aggregated input Z [N, F_in] (aggregate first; the backward call needs it) or the transformed
- * input X W [N, F_out] (transform first; only a temporary).  Asynchronous on opts->stream; the
+ * input X W with rows padded to a multiple of 4 floats (transform first; only a temporary).  Asynchronous on opts->stream; the
  * aggregation may grow plan-owned buffers on first use (gnn_plan_prepare with GNN_SAGE_GCN). */
 GNN_API int gnn_sage_layer_fwd(const void *indptr, const int32_t *indices, const float *X, const float *W,
                                const float *bias, float *saved, float *H, int64_t N, int64_t F_in, int64_t F_out,

@@ -583,10 +583,12 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
     const bool coef = (w != nullptr) || src_mode != kScaleNone;
 
     // Widest load the gathered rows allow.  Only the padded copy may be read past column F (its
-    // rows end in padding that belongs to the buffer); a caller's matrix needs F % vec == 0.
+    // rows end in padding that belongs to the buffer); a caller's matrix needs F % vec == 0 unless
+    // the caller vouches for the padding (GNN_FLAG_PADDED_ROWS).
     int vec = max_vec;
+    const bool rows_padded = padded || (o.flags & GNN_FLAG_PADDED_ROWS) != 0;  // then ldg % vec == 0 covers the over-read
     while (vec > 1 && !(ldg % vec == 0 && reinterpret_cast<uintptr_t>(gathered) % (uintptr_t(vec) * esz) == 0 &&
-                        (padded || F % vec == 0)))
+                        (rows_padded || F % vec == 0)))
         vec >>= 1;
     // Widest store the output rows allow (partial strips fall back to single elements).
     int store_vec = vec;

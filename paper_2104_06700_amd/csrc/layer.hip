@@ -19,24 +19,38 @@ namespace {
 
 constexpr int kRowsPerBlock = 128;
 
-// G = dH where H > 0 (else 0) for a block of rows, plus the block's column sums of G.
-// One thread per column (strided), rows walked in order: deterministic.
+// G = dH where H > 0 (else 0; plain copy without a rectifier) for a block of rows, written with row
+// stride ldg when G != nullptr, plus the block's column sums.  A thread owns one column and every
+// (256 / cols)-th row of the block; the row lanes are added through LDS in a fixed order, so the
+// sums are reproducible.  cols = power of two >= F, at most 256 (wider F: several column passes).
 __global__ void __launch_bounds__(256) mask_colsum_kernel(const float *__restrict__ H, const float *__restrict__ dH,
-                                                          float *__restrict__ G, float *__restrict__ partial, int64_t N,
-                                                          int F, int relu) {
+                                                          float *__restrict__ G, int64_t ldg, float *__restrict__ partial,
+                                                          int64_t N, int F, int relu, int log2_cols) {
+    __shared__ float red[256];
+    const int cols = 1 << log2_cols;
+    const int row_lanes = 256 >> log2_cols;
+    const int jl = threadIdx.x & (cols - 1), rl = threadIdx.x >> log2_cols;
     const int64_t r0 = int64_t(blockIdx.x) * kRowsPerBlock;
     const int64_t r1 = r0 + kRowsPerBlock < N ? r0 + kRowsPerBlock : N;
-    for (int j = threadIdx.x; j < F; j += blockDim.x) {
+    for (int j0 = 0; j0 < F; j0 += cols) {
+        const int j = j0 + jl;
         float s = 0.0f;
-        for (int64_t r = r0; r < r1; ++r) {
-            float g = dH[r * F + j];
-            if (relu) {
-                g = H[r * F + j] > 0.0f ? g : 0.0f;
-                G[r * F + j] = g;
+        if (j < F) {
+            for (int64_t r = r0 + rl; r < r1; r += row_lanes) {
+                float g = dH[r * F + j];
+                if (relu) g = H[r * F + j] > 0.0f ? g : 0.0f;
+                if (G) G[r * ldg + j] = g;
+                s += g;
             }
-            s += g;
         }
-        partial[int64_t(blockIdx.x) * F + j] = s;
+        red[threadIdx.x] = s;
+        __syncthreads();
+        if (rl == 0 && j < F) {
+            float t = 0.0f;
+            for (int k = 0; k < row_lanes; ++k) t += red[(k << log2_cols) + jl];
+            partial[int64_t(blockIdx.x) * F + j] = t;
+        }
+        __syncthreads();
     }
 }
 
@@ -61,6 +75,10 @@ int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
 bool aggregate_first(int order, int64_t Fi, int64_t Fo) { return order == 1 || (order == 0 && Fi <= Fo); }
 
+// Row stride of the matrices that the transform-first order gathers from (X W, and the masked
+// output gradient): whole 16-byte groups, so that 16-byte loads apply to widths like 47.
+int64_t gather_ld(int64_t Fo) { return round_up(Fo, 4); }
+
 struct BwdLayout {
     int64_t g_off, t_off, part_off, part2_off, mm_off, total;
 };
@@ -69,9 +87,9 @@ BwdLayout bwd_layout(int64_t N, int64_t Fi, int64_t Fo, bool agg_first, bool rel
     BwdLayout L{};
     int64_t off = 0;
     L.g_off = off;
-    if (relu) off += round_up(N * Fo * 4, 256);
+    if (relu || !agg_first) off += round_up(N * (agg_first ? Fo : gather_ld(Fo)) * 4, 256);
     L.t_off = off;
-    off += round_up(N * (agg_first ? Fi : Fo) * 4, 256);
+    off += round_up(N * (agg_first ? Fi : gather_ld(Fo)) * 4, 256);
     const int64_t n_blocks = (N + kRowsPerBlock - 1) / kRowsPerBlock;
     L.part_off = off;
     off += round_up(n_blocks * Fo * 4, 256);
@@ -87,7 +105,7 @@ BwdLayout bwd_layout(int64_t N, int64_t Fi, int64_t Fo, bool agg_first, bool rel
 
 extern "C" GNN_API int64_t gnn_sage_layer_saved_elems(int64_t N, int64_t F_in, int64_t F_out, int order) {
     if (N < 0 || F_in < 0 || F_out < 0) return 0;
-    return N * (aggregate_first(order, F_in, F_out) ? F_in : F_out);
+    return N * (aggregate_first(order, F_in, F_out) ? F_in : gather_ld(F_out));
 }
 
 extern "C" GNN_API int64_t gnn_sage_layer_workspace_bytes(int64_t N, int64_t F_in, int64_t F_out, int relu, int order) {
@@ -125,8 +143,13 @@ extern "C" GNN_API int gnn_sage_layer_fwd(const void *indptr, const int32_t *ind
         if (rc != GNN_OK) return rc;
         return gnn_matmul_impl(saved, F_in, 0, W, F_out, 0, H, F_out, N, F_out, F_in, bias, o.relu, nullptr, 0, stream);
     }
-    rc = gnn_matmul_impl(X, F_in, 0, W, F_out, 0, saved, F_out, N, F_out, F_in, nullptr, 0, nullptr, 0, stream);
+    // X W is written with padded rows (the padding is never written and never used: the gather
+    // reads it with 16-byte loads and drops it)
+    const int64_t ldp = gather_ld(F_out);
+    rc = gnn_matmul_impl(X, F_in, 0, W, F_out, 0, saved, ldp, N, F_out, F_in, nullptr, 0, nullptr, 0, stream);
     if (rc != GNN_OK) return rc;
+    a.ldx = ldp;
+    a.flags = GNN_FLAG_PADDED_ROWS;
     return gnn_aggregate_fwd_epilogue(indptr, indices, saved, H, N, F_out, GNN_SAGE_GCN, &a, bias, o.relu);
 }
 
@@ -151,7 +174,9 @@ extern "C" GNN_API int gnn_sage_layer_bwd(const void *indptr_t, const int32_t *i
         if (db) zero_kernel<<<1, 256, 0, stream>>>(db, F_out);
         return hipGetLastError() == hipSuccess ? GNN_OK : GNN_ERR_LAUNCH;
     }
-    float *G = o.relu ? reinterpret_cast<float *>(ws + L.g_off) : nullptr;
+    const bool need_g = o.relu || !agg_first;  // transform first gathers G: always the padded copy
+    const int64_t ldg = agg_first ? F_out : gather_ld(F_out);
+    float *G = need_g ? reinterpret_cast<float *>(ws + L.g_off) : nullptr;
     float *T = reinterpret_cast<float *>(ws + L.t_off);
     float *part = reinterpret_cast<float *>(ws + L.part_off);
     float *part2 = reinterpret_cast<float *>(ws + L.part2_off);
@@ -160,8 +185,11 @@ extern "C" GNN_API int gnn_sage_layer_bwd(const void *indptr_t, const int32_t *i
 
     // rectifier mask and bias gradient
     const int64_t n_blocks = (N + kRowsPerBlock - 1) / kRowsPerBlock;
-    if (o.relu || db) {
-        mask_colsum_kernel<<<static_cast<unsigned>(n_blocks), 256, 0, stream>>>(H, dH, G, part, N, int(F_out), o.relu ? 1 : 0);
+    if (need_g || db) {
+        int log2_cols = 0;
+        while ((1 << log2_cols) < F_out && log2_cols < 8) ++log2_cols;
+        mask_colsum_kernel<<<static_cast<unsigned>(n_blocks), 256, 0, stream>>>(H, dH, G, ldg, part, N, int(F_out),
+                                                                                o.relu ? 1 : 0, log2_cols);
         if (db) {
             const int64_t n2 = (n_blocks + 255) / 256;
             colsum_reduce_kernel<<<static_cast<unsigned>(n2), 256, 0, stream>>>(part, n_blocks, int(F_out), part2, 256);
@@ -169,7 +197,7 @@ extern "C" GNN_API int gnn_sage_layer_bwd(const void *indptr_t, const int32_t *i
         }
         if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
     }
-    const float *Gm = o.relu ? G : dH;
+    const float *Gm = need_g ? G : dH;
 
     gnn_opts a{};
     a.dtype = GNN_F32;
@@ -183,9 +211,12 @@ extern "C" GNN_API int gnn_sage_layer_bwd(const void *indptr_t, const int32_t *i
         if (rc != GNN_OK) return rc;
         return gnn_aggregate_bwd(indptr_t, indices_t, nullptr, T, dX, N, F_in, GNN_SAGE_GCN, &a);
     }
+    a.ldx = ldg;
+    a.ldy = ldg;
+    a.flags = GNN_FLAG_PADDED_ROWS;
     rc = gnn_aggregate_bwd(indptr_t, indices_t, nullptr, Gm, T, N, F_out, GNN_SAGE_GCN, &a);
     if (rc != GNN_OK) return rc;
-    rc = gnn_matmul_impl(X, F_in, 1, T, F_out, 0, dW, F_out, F_in, F_out, N, nullptr, 0, mm_ws, mm_bytes, stream);
+    rc = gnn_matmul_impl(X, F_in, 1, T, ldg, 0, dW, F_out, F_in, F_out, N, nullptr, 0, mm_ws, mm_bytes, stream);
     if (rc != GNN_OK || !dX) return rc;
-    return gnn_matmul_impl(T, F_out, 0, W, F_out, 1, dX, F_in, N, F_in, F_out, nullptr, 0, nullptr, 0, stream);
+    return gnn_matmul_impl(T, ldg, 0, W, F_out, 1, dX, F_in, N, F_in, F_out, nullptr, 0, nullptr, 0, stream);
 }

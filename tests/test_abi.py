@@ -95,6 +95,6 @@ def test_argument_checks_that_need_no_device():
     assert lib.gnn_sage_layer_fwd(one, one, one, one, None, one, one, 4, 4, 4, ctypes.byref(lo)) == gnn.GNN_ERR_UNSUPPORTED
     lo.order = 5
     assert lib.gnn_sage_layer_bwd(one, one, one, one, one, one, one, one, one, one, 4, 4, 4, ctypes.byref(lo)) == bad
-    assert lib.gnn_sage_layer_saved_elems(10, 3, 5, 0) == 30 and lib.gnn_sage_layer_saved_elems(10, 5, 3, 0) == 30
+    assert lib.gnn_sage_layer_saved_elems(10, 3, 5, 0) == 30 and lib.gnn_sage_layer_saved_elems(10, 5, 3, 0) == 40  # rows padded to 4 floats
     assert lib.gnn_sage_layer_saved_elems(10, 5, 3, 1) == 50
     assert lib.gnn_sage_layer_workspace_bytes(1000, 8, 4, 1, 0) >= 1000 * 4 * 4 * 2

@@ -447,3 +447,23 @@ def test_randomised_shapes_and_options(seed):
                                    want_scale=True)
     assert_close(out, dXo, St, bf16, "bwd " + what)
     assert torch.isnan(out_buf[~written]).all(), "stores outside the output rows: " + what
+
+
+@pytest.mark.parametrize("f,ld", [(47, 48), (5, 8), (101, 104)])
+def test_padded_rows_flag_allows_wide_loads(f, ld):
+    """With GNN_FLAG_PADDED_ROWS the padding of the gathered rows may be read (and must be ignored):
+    it is filled with NaN here."""
+    el = synth.rmat_symmetric(3000, 60000, (0.57, 0.19, 0.19, 0.05), 2)
+    dg = device_graph(el, plan_params=gnn.make_plan_params([4, 32], 64))
+    indptr, indices, indptr_t, indices_t, _ = host_csr(el)
+    buf = torch.full((el.n, ld), float("nan"), device=DEV)
+    X = synth.normal_features(el.n, f, 3)
+    buf[:, :f] = X.to(DEV)
+    out = torch.full((el.n, ld), float("nan"), device=DEV)
+    for op_name in ("sum", "sage"):
+        gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, None, buf[:, :f], out[:, :f], el.n, f, OP_CODE[op_name], plan=dg.plan_fwd,
+                              ldx=ld, ldy=ld, flags=gnn.GNN_FLAG_PADDED_ROWS)
+        torch.cuda.synchronize()
+        Yo, S = oracle.aggregate_fwd(indptr, indices, X.numpy(), op=OP_CODE[op_name], nthreads=8, want_scale=True)
+        assert_close(out[:, :f], Yo, S, False, f"padded rows {op_name} F={f}")
+        assert torch.isnan(out[:, f:]).all(), "the output padding must stay untouched"
