@@ -15,9 +15,24 @@
 //     transform first:  dP = A^^T G, dW = X^T dP, dX = dP W^T
 #include "common.h"
 
+#include <mutex>
+
 namespace {
 
 constexpr int kRowsPerBlock = 128;
+
+// A library-owned side stream per device (default priority, created on first use, kept until
+// the process ends): the weight-gradient product, which depends only on G, runs there while the
+// main stream does the input-gradient product and the gather-bound backward aggregation.
+hipStream_t side_stream() {
+    static std::mutex mu;
+    static hipStream_t streams[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!streams[dev] && hipStreamCreateWithFlags(&streams[dev], hipStreamNonBlocking) != hipSuccess) streams[dev] = nullptr;
+    return streams[dev];
+}
 
 // G = dH where H > 0 (else 0; plain copy without a rectifier) for a block of rows, written with row
 // stride ldg when G != nullptr, plus the block's column sums.  A thread owns one column and every
@@ -205,11 +220,33 @@ extern "C" GNN_API int gnn_sage_layer_bwd(const void *indptr_t, const int32_t *i
     a.stream = o.stream;
     a.plan = o.plan;
     if (agg_first) {
-        rc = gnn_matmul_impl(saved, F_in, 1, Gm, F_out, 0, dW, F_out, F_in, F_out, N, nullptr, 0, mm_ws, mm_bytes, stream);
-        if (rc != GNN_OK || !dX) return rc;
+        if (!dX) return gnn_matmul_impl(saved, F_in, 1, Gm, F_out, 0, dW, F_out, F_in, F_out, N, nullptr, 0, mm_ws, mm_bytes, stream);
+        // dZ = G W^T first; then fork: dW = Z^T G (matrix cores) on the side stream while the caller's
+        // stream runs the gather-bound backward aggregation
         rc = gnn_matmul_impl(Gm, F_out, 0, W, F_out, 1, T, F_in, N, F_in, F_out, nullptr, 0, nullptr, 0, stream);
         if (rc != GNN_OK) return rc;
-        return gnn_aggregate_bwd(indptr_t, indices_t, nullptr, T, dX, N, F_in, GNN_SAGE_GCN, &a);
+        hipStream_t side = side_stream();
+        hipEvent_t fork = nullptr, join = nullptr;
+        if (side && (hipEventCreateWithFlags(&fork, hipEventDisableTiming) != hipSuccess ||
+                     hipEventCreateWithFlags(&join, hipEventDisableTiming) != hipSuccess)) {
+            if (fork) (void)hipEventDestroy(fork);
+            fork = join = nullptr;
+            side = nullptr;
+            (void)hipGetLastError();
+        }
+        if (side && (hipEventRecord(fork, stream) != hipSuccess || hipStreamWaitEvent(side, fork, 0) != hipSuccess)) {
+            (void)hipEventDestroy(fork);
+            (void)hipEventDestroy(join);
+            return GNN_ERR_LAUNCH;
+        }
+        rc = gnn_matmul_impl(saved, F_in, 1, Gm, F_out, 0, dW, F_out, F_in, F_out, N, nullptr, 0, mm_ws, mm_bytes, side ? side : stream);
+        int rc2 = gnn_aggregate_bwd(indptr_t, indices_t, nullptr, T, dX, N, F_in, GNN_SAGE_GCN, &a);
+        if (side) {  // join, whatever happened above: the caller's stream must not run ahead of the side stream
+            if (hipEventRecord(join, side) != hipSuccess || hipStreamWaitEvent(stream, join, 0) != hipSuccess) rc = GNN_ERR_LAUNCH;
+            (void)hipEventDestroy(fork);  // released by the runtime once the recorded work has completed
+            (void)hipEventDestroy(join);
+        }
+        return rc != GNN_OK ? rc : rc2;
     }
     a.ldx = ldg;
     a.ldy = ldg;
