@@ -276,3 +276,32 @@ def test_fullsize_sparse_workload_sampled_rows():
     subt_ptr, subt_idx, pos_t = _sub_csr(indptr_t, indices_t, rows_t)
     dV, SV = oracle.ap_fwd(subt_ptr, subt_idx, dO_h, w_h, d, oracle.BIN_MUL, oracle.RED_SUM, eid=perm[pos_t])
     _close(dfV[torch.from_numpy(rows_t).to(DEV)], dV, SV, "fullsize vertex gradient")
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_randomised_graphs_widths_and_plans(seed):
+    """Seeded random draws over graph shape, width, edge-feature width, edge-id map and plan
+    parameters (bin thresholds, hub piece size, or no plan); three operator pairs per draw."""
+    rng = np.random.default_rng(500 + seed)
+    n = int(rng.integers(1, 3000))
+    e = int(rng.integers(0, 30 * n + 1))
+    if n < 64 or rng.random() < 0.5:
+        el = synth.small_random_multigraph(n, max(e, 1), seed) if e > 0 else synth.EdgeList(
+            n, torch.zeros(0, dtype=torch.int32), torch.zeros(0, dtype=torch.int32))
+    else:
+        e = min(e - e % 2, n * (n - 1) // 4 * 2)
+        el = synth.rmat_symmetric(n, max(e, 2), (0.57, 0.19, 0.19, 0.05), seed)
+    d = int(rng.choice([1, 2, 3, 4, 7, 8, 20, 33, 64, 100, 130, 260]))
+    ewidth = d if rng.random() < 0.5 else 1
+    use_plan = rng.random() < 0.8
+    params = None
+    if use_plan:
+        k = int(rng.integers(0, 5))
+        thr = sorted(set(int(t) for t in rng.integers(1, 100, size=k)))
+        params = gnn.make_plan_params(thr, int(rng.choice([0, 5, 32, 1024])))
+    names_b = list(BINOPS)
+    names_r = list(REDUCES)
+    picks = {(names_b[int(rng.integers(6))], names_r[int(rng.integers(3))]) for _ in range(3)}
+    for bname, rname in picks:
+        _check_all(el, params, d, ewidth, use_eid=bool(rng.random() < 0.4), ties=bool(rng.random() < 0.3), seed=seed,
+                   binops={bname: BINOPS[bname]}, reduces={rname: REDUCES[rname]}, use_plan=use_plan)

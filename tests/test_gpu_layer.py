@@ -247,3 +247,22 @@ def test_layer_fullsize_sparse_workload():
         assert abs(lhs - via_w) <= 2e-6 * scale, (lhs, via_w, scale)
         assert abs(lhs - via_x) <= 2e-6 * scale, (lhs, via_x, scale)
         del X, dH, saved, H, ws, dX, G
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_layer_randomised(seed):
+    rng = np.random.default_rng(700 + seed)
+    n = int(rng.integers(2, 3000))
+    e = int(rng.integers(1, 25 * n + 1))
+    if n < 64 or rng.random() < 0.5:
+        el = synth.small_random_multigraph(n, e, seed)
+    else:
+        e = min(e - e % 2, n * (n - 1) // 4 * 2)
+        el = synth.rmat_symmetric(n, max(e, 2), (0.57, 0.19, 0.19, 0.05), seed)
+    k = int(rng.integers(0, 5))
+    thr = sorted(set(int(t) for t in rng.integers(1, 100, size=k)))
+    params = gnn.make_plan_params(thr, int(rng.choice([0, 7, 64, 1024])))
+    fi = int(rng.choice([1, 3, 16, 31, 47, 100, 129, 300]))
+    fo = int(rng.choice([1, 2, 16, 41, 47, 64, 130, 256]))
+    _layer_case(el, params, fi, fo, relu=bool(rng.random() < 0.6), order=int(rng.integers(0, 3)), seed=seed,
+                use_bias=bool(rng.random() < 0.7), want_dx=bool(rng.random() < 0.8))
