@@ -157,8 +157,10 @@ typedef struct gnn_ap_opts {
                                  Must not name a row twice when an edge gradient is written. */
     void *stream;
     gnn_plan *plan;           /* plan of the graph passed in the same call, or NULL (no binning) */
-    int32_t flags;            /* reserved, 0 */
-    int32_t reserved;
+    int32_t flags;            /* GNN_FLAG_NO_COLUMN_SLICES / NO_PADDED_COPY / FORCE_PADDED_COPY, as in gnn_opts:
+                                 gather-bound forward calls (no full-width edge operand, d % 4 == 0, a plan)
+                                 use the layout of the sum-only hot path */
+    int32_t max_slices;       /* as in gnn_opts; 0 = automatic */
 } gnn_ap_opts;
 
 /* Algorithm 1 with any operator pair of Table 1:

@@ -53,7 +53,7 @@ class GnnApOpts(ctypes.Structure):
         ("indptr_is_64", ctypes.c_int32), ("edge_width", ctypes.c_int32),
         ("ldv", ctypes.c_int64), ("lde", ctypes.c_int64), ("ldo", ctypes.c_int64),
         ("edge_ids", ctypes.c_void_p), ("stream", ctypes.c_void_p), ("plan", ctypes.c_void_p),
-        ("flags", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("flags", ctypes.c_int32), ("max_slices", ctypes.c_int32),
     ]
 
 
@@ -295,8 +295,10 @@ def _row_stride(t: Optional[torch.Tensor]) -> int:
     return int(t.stride(0))
 
 
-def _ap_opts(indptr, plan, stream, edge_ids, edge_width, ldv, lde, ldo) -> GnnApOpts:
+def _ap_opts(indptr, plan, stream, edge_ids, edge_width, ldv, lde, ldo, flags=0, max_slices=0) -> GnnApOpts:
     o = GnnApOpts()
+    o.flags = int(flags)
+    o.max_slices = int(max_slices)
     o.indptr_is_64 = 0 if indptr is None else _is64(indptr)
     o.edge_width = int(edge_width)
     o.ldv, o.lde, o.ldo = int(ldv), int(lde), int(ldo)
@@ -322,14 +324,14 @@ def _f32(*tensors) -> None:
 
 
 def gnn_ap_fwd(indptr, indices, fV, fE, fO, arg_e, N, d, binop, reduce, plan: Optional[Plan] = None, edge_ids=None,
-               stream=None) -> None:
+               stream=None, flags=0, max_slices=0) -> None:
     """f_O[v] = reduce_e binop(f_V[u_e], f_E[e]) with any operator pair of Table 1 (see include/gnnagg.h).
     f_E may be [E, d] or [E] / [E, 1] (one scalar per edge)."""
     _f32(fV, fE, fO)
     if arg_e is not None and (arg_e.dtype != torch.int32 or not arg_e.is_contiguous()):
         raise TypeError("arg_e must be a contiguous int32 tensor")
     o = _ap_opts(indptr, plan, stream, edge_ids, _edge_width(fE, d), _row_stride(fV), _row_stride(fE) if fE is not None and fE.dim() == 2 else 0,
-                 _row_stride(fO))
+                 _row_stride(fO), flags, max_slices)
     _call_allocating("gnn_ap_fwd", lambda: load_library().gnn_ap_fwd(
         _ptr(indptr), _ptr(indices), _ptr(fV), _ptr(fE), _ptr(fO), _ptr(arg_e), int(N), int(d), int(binop), int(reduce),
         ctypes.byref(o)))

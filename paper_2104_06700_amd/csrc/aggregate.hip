@@ -771,6 +771,21 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
 
 }  // namespace
 
+// Copy of an fp32 matrix into rows of another stride (the plan-owned padded matrix), with the
+// widest chunks the source allows (used by ap.hip).
+int gnn_pad_rows_f32(const float *src, int64_t ld_src, float *dst, int64_t ld_dst, int64_t N, int64_t F, hipStream_t stream) {
+    const int64_t row_bytes = F * 4, src_ld_bytes = ld_src * 4, dst_ld_bytes = ld_dst * 4;
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(src);
+    hipError_t err;
+    if (row_bytes % 16 == 0 && src_ld_bytes % 16 == 0 && addr % 16 == 0)
+        err = launch_pad<uint4>(src, src_ld_bytes, dst, dst_ld_bytes, N, row_bytes, stream);
+    else if (row_bytes % 8 == 0 && src_ld_bytes % 8 == 0 && addr % 8 == 0)
+        err = launch_pad<uint2>(src, src_ld_bytes, dst, dst_ld_bytes, N, row_bytes, stream);
+    else
+        err = launch_pad<uint32_t>(src, src_ld_bytes, dst, dst_ld_bytes, N, row_bytes, stream);
+    return err == hipSuccess ? GNN_OK : GNN_ERR_LAUNCH;
+}
+
 // Forward aggregation with the epilogue of a fused layer (used by layer.hip).
 int gnn_aggregate_fwd_epilogue(const void *indptr, const int32_t *indices, const void *X, void *Y, int64_t N, int64_t F,
                                int op, const gnn_opts *opts, const float *bias, int relu) {

@@ -49,7 +49,12 @@ struct ApArgs {
     int32_t *parg;     // hub pieces: partial winners  [n_chunks, ldp]
     int64_t ldp;
     int32_t n_bins;
-    int32_t slab_cols;  // columns one workgroup row (blockIdx.y) covers
+    int32_t slab_cols;    // columns one workgroup covers
+    int32_t col0;         // first column of this launch
+    int32_t col_end;      // one past its last column
+    int32_t log2_slices;  // > 0: workgroup b serves column slab (b % n_slices) of the launch, so that an
+                          // XCD (workgroups go to the 8 XCDs round-robin) keeps gathering the same lines
+                          // of every row; 0: the slab is blockIdx.y
     ApBin bins[GNN_MAX_BINS + 1];
 };
 
@@ -111,11 +116,10 @@ struct Group {
     bool is_piece;
 };
 
-__device__ __forceinline__ Group locate_group(const ApArgs &a) {
+__device__ __forceinline__ Group locate_group(const ApArgs &a, int64_t vblock) {
     Group g;
     const int lane = threadIdx.x & 63;
     const int wave_in_block = threadIdx.x >> 6;
-    const int64_t vblock = blockIdx.x;
     int b = 0;
     for (int i = 1; i < a.n_bins; ++i)
         if (vblock >= a.bins[i].first_block) b = i;
@@ -158,10 +162,11 @@ __global__ void __launch_bounds__(kBlockThreads) ap_fwd_kernel(const ApArgs a) {
     constexpr bool USE_E = BIN != GNN_BIN_COPY_LHS;
     constexpr bool WIDE = USE_E && EWIDE;
     constexpr int U = (VEC == 4 && WIDE) ? 4 : 8;  // edges in flight per slot
-    const Group g = locate_group(a);
+    const int slab = a.log2_slices > 0 ? int(blockIdx.x) & ((1 << a.log2_slices) - 1) : int(blockIdx.y);
+    const Group g = locate_group(a, int64_t(blockIdx.x) >> a.log2_slices);
     const int G = g.G, SR = g.SR;
-    const int col = int(blockIdx.y) * a.slab_cols + g.c * VEC;
-    const bool col_ok = col < a.d && g.c * VEC < a.slab_cols;
+    const int col = a.col0 + slab * a.slab_cols + g.c * VEC;
+    const bool col_ok = col < a.col_end && g.c * VEC < a.slab_cols;
     const int64_t e0 = g.e0, e1 = g.e1;
 
     float acc[VEC];
@@ -306,7 +311,7 @@ __global__ void __launch_bounds__(kBlockThreads) ap_bwd_edge_kernel(const ApArgs
     constexpr bool NEED_X = BIN == GNN_BIN_MUL || BIN == GNN_BIN_DIV;
     constexpr bool NEED_Y = BIN == GNN_BIN_DIV;
     constexpr int U = 4;
-    const Group g = locate_group(a);
+    const Group g = locate_group(a, blockIdx.x);
     const int G = g.G, SR = g.SR, C = g.C;
     const int64_t e0 = g.e0, e1 = g.e1;
     const int64_t row = g.row < 0 ? 0 : g.row;
@@ -550,12 +555,6 @@ int run_ap_fwd(const void *indptr, const int32_t *indices, const float *fV, cons
     if (wide && (c.lde % 4 || !aligned16(fE))) vec = 1;
     if (arg_e && !aligned16(arg_e)) vec = 1;
 
-    const int64_t strips = (d + vec - 1) / vec;
-    const int log2_c = strips >= 64 ? 6 : gnn_ilog2_ceil(strips);
-    const int64_t slab_cols = (int64_t(1) << log2_c) * vec;
-    const int64_t n_slabs = (d + slab_cols - 1) / slab_cols;
-    if (n_slabs > 65535) return GNN_ERR_UNSUPPORTED;
-
     ApArgs a{};
     a.indptr = indptr;
     a.indices = indices;
@@ -569,7 +568,6 @@ int run_ap_fwd(const void *indptr, const int32_t *indices, const float *fV, cons
     a.ldo = c.ldo;
     a.d = int32_t(d);
     a.ip64 = c.o.indptr_is_64 ? 1 : 0;
-    a.slab_cols = int32_t(slab_cols);
     const bool has_hub = plan && plan->n_chunks > 0;
     if (has_hub) {
         a.ldp = gnn_partial_ld(d);
@@ -578,12 +576,73 @@ int run_ap_fwd(const void *indptr, const int32_t *indices, const float *fV, cons
         a.pval = static_cast<float *>(plan->scratch);
         a.parg = reinterpret_cast<int32_t *>(a.pval + plan->n_chunks * a.ldp);
     }
-    const int64_t blocks = make_bins(a, plan, N, log2_c, /*pieces=*/true);
-    if (blocks > INT32_MAX) return GNN_ERR_UNSUPPORTED;
-    if (blocks > 0) {
-        dim3 grid(static_cast<unsigned>(blocks), static_cast<unsigned>(n_slabs));
-        launch_fwd(binop, reduce, vec, c.ewide, grid, c.stream, a);
-        if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
+
+    // Gather-bound calls (no full-width edge operand) get the layout of the sum-only hot path:
+    // rows copied to an odd number of 128-byte lines when the plan says column slices pay, and
+    // one-line column slices spread over the XCD L2s, 8 / 4 / 2 / 1 slices per launch.
+    // Not with an edge-id map on a scalar edge operand (every slice would repeat the random 4-byte
+    // reads: measured 10.5 -> 16.6 ms at d = 100), nor for max / min with a scalar operand (the
+    // repeated weight stream and winner bookkeeping cost more than the hits bring: 8.4 -> 9.0 ms).
+    bool sliced = false;
+    const bool slice_ok = !use_e || (!wide && !c.o.edge_ids && reduce == GNN_RED_SUM) || c.o.max_slices > 1;
+    if (use_v && !wide && vec == 4 && plan && plan->n_edges > 0 && slice_ok) {
+        const gnn_layout L = gnn_choose_layout(plan, N, d, 4, c.ldv, reinterpret_cast<uintptr_t>(fV) % 128 == 0, c.o.flags,
+                                               c.o.max_slices);
+        if (L.padded_copy) {
+            rc = gnn_plan_padded(plan, N * L.ld_pad * 4);
+            if (rc != GNN_OK) return rc;
+            rc = gnn_pad_rows_f32(fV, c.ldv, static_cast<float *>(plan->padded), L.ld_pad, N, d, c.stream);
+            if (rc != GNN_OK) return rc;
+            a.fV = static_cast<const float *>(plan->padded);
+            a.ldv = L.ld_pad;
+        }
+        const int64_t line = 32;  // floats per 128-byte line
+        const bool lines_ok = a.ldv % line == 0 && reinterpret_cast<uintptr_t>(a.fV) % 128 == 0;
+        const int64_t lines = (d + line - 1) / line;
+        int64_t g16 = 1;
+        while (g16 < 16 && (a.ldv / line) % (g16 * 2) == 0) g16 *= 2;
+        const int64_t unit_lines = g16 >= 8 ? g16 / 4 : 1;  // even strides: wider slices (see aggregate.hip)
+        const int64_t units = (lines + unit_lines - 1) / unit_lines;
+        if (L.slices_wanted && lines_ok && units >= 2 && units <= 256 && c.o.max_slices != 1) {
+            sliced = true;
+            a.slab_cols = int32_t(unit_lines * line);
+            const int log2_c = gnn_ilog2_ceil(a.slab_cols / vec);
+            int64_t u0 = 0;
+            while (u0 < units) {
+                const int64_t s_max = c.o.max_slices > 0 ? c.o.max_slices : 8;
+                int ls = 3;
+                while (ls > 0 && ((int64_t(1) << ls) > units - u0 || (int64_t(1) << ls) > s_max)) --ls;
+                a.col0 = int32_t(u0 * a.slab_cols);
+                const int64_t end = int64_t(a.col0) + (int64_t(a.slab_cols) << ls);
+                a.col_end = int32_t(end < d ? end : d);
+                a.log2_slices = ls;
+                const int64_t blocks = make_bins(a, plan, N, log2_c, /*pieces=*/true) << ls;
+                if (blocks > INT32_MAX) return GNN_ERR_UNSUPPORTED;
+                if (blocks > 0) {
+                    launch_fwd(binop, reduce, vec, c.ewide, dim3(static_cast<unsigned>(blocks)), c.stream, a);
+                    if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
+                }
+                u0 += int64_t(1) << ls;
+            }
+        }
+    }
+    if (!sliced) {
+        const int64_t strips = (d + vec - 1) / vec;
+        const int log2_c = strips >= 64 ? 6 : gnn_ilog2_ceil(strips);
+        const int64_t slab_cols = (int64_t(1) << log2_c) * vec;
+        const int64_t n_slabs = (d + slab_cols - 1) / slab_cols;
+        if (n_slabs > 65535) return GNN_ERR_UNSUPPORTED;
+        a.slab_cols = int32_t(slab_cols);
+        a.col0 = 0;
+        a.col_end = int32_t(d);
+        a.log2_slices = 0;
+        const int64_t blocks = make_bins(a, plan, N, log2_c, /*pieces=*/true);
+        if (blocks > INT32_MAX) return GNN_ERR_UNSUPPORTED;
+        if (blocks > 0) {
+            dim3 grid(static_cast<unsigned>(blocks), static_cast<unsigned>(n_slabs));
+            launch_fwd(binop, reduce, vec, c.ewide, grid, c.stream, a);
+            if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
+        }
     }
     if (has_hub) {
         const int64_t hub_begin = plan->bin_offsets[plan->n_bins - 1];

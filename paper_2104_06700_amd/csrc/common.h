@@ -108,6 +108,9 @@ int gnn_plan_edge_scale(gnn_plan *plan, const int32_t *indices, int mode, hipStr
 int gnn_aggregate_fwd_epilogue(const void *indptr, const int32_t *indices, const void *X, void *Y, int64_t N, int64_t F,
                                int op, const gnn_opts *opts, const float *bias, int relu);
 
+// Copies an fp32 [N, F] matrix with row stride ld_src into rows of stride ld_dst (elements).
+int gnn_pad_rows_f32(const float *src, int64_t ld_src, float *dst, int64_t ld_dst, int64_t N, int64_t F, hipStream_t stream);
+
 // gnn_matmul on a typed stream (shared by the C entry point and the layer calls).
 int gnn_matmul_impl(const float *A, int64_t lda, int trans_a, const float *B, int64_t ldb, int trans_b, float *C, int64_t ldc,
                     int64_t M, int64_t N, int64_t K, const float *bias, int relu, void *workspace, int64_t workspace_bytes,

@@ -56,7 +56,8 @@ def _close(g, ref, S, what):
     assert not g[S == 0].any(), what
 
 
-def _check_all(el, params, d, ewidth, use_eid, ties, seed, binops=BINOPS, reduces=REDUCES, use_plan=True):
+def _check_all(el, params, d, ewidth, use_eid, ties, seed, binops=BINOPS, reduces=REDUCES, use_plan=True, flags=0,
+               max_slices=0):
     rng = np.random.default_rng(seed)
     dg = device_graph(el, plan_params=params, want_perm=True, with_plans=use_plan)
     indptr, indices, indptr_t, indices_t, perm = host_csr(el)
@@ -77,7 +78,8 @@ def _check_all(el, params, d, ewidth, use_eid, ties, seed, binops=BINOPS, reduce
             print(what, flush=True)
             out = torch.full((n, d), float("nan"), device=DEV)
             arg = torch.full((n, d), -7, dtype=torch.int32, device=DEV) if r else None
-            gnn.gnn_ap_fwd(dg.indptr, dg.indices, fv_arg, fe_arg, out, arg, n, d, b, r, plan=dg.plan_fwd, edge_ids=eid_d)
+            gnn.gnn_ap_fwd(dg.indptr, dg.indices, fv_arg, fe_arg, out, arg, n, d, b, r, plan=dg.plan_fwd, edge_ids=eid_d,
+                           flags=flags, max_slices=max_slices)
             torch.cuda.synchronize()
             O, aux = oracle.ap_fwd(indptr, indices, None if bname == "copyrhs" else fV, None if bname == "copylhs" else fE,
                                    d, b, r, eid=eid)
@@ -127,6 +129,19 @@ def test_equal_values_pick_the_lowest_edge_position(kind, d, ewidth):
 def test_edge_ids_remap_the_edge_rows(d, ewidth):
     el, params = _graph("rmat_hubs")
     _check_all(el, params, d, ewidth, use_eid=True, ties=False, seed=13)
+
+
+@pytest.mark.parametrize("d,ewidth", [(100, 1), (64, 1), (256, 1), (600, 1), (100, 100)])
+@pytest.mark.parametrize("max_slices", [8, 2])
+def test_padded_copy_and_column_slices(d, ewidth, max_slices):
+    """The layout of the sum-only hot path (rows copied to an odd line stride, one-line column
+    slices over the XCDs), forced on graphs small enough for the whole-output comparison."""
+    el, params = _graph("rmat_hubs")
+    ops = {"copylhs": 4, "mul": 2, "sub": 1}
+    _check_all(el, params, d, ewidth, use_eid=False, ties=False, seed=d + max_slices, binops=ops,
+               flags=gnn.GNN_FLAG_FORCE_PADDED_COPY, max_slices=max_slices)
+    _check_all(el, params, d, ewidth, use_eid=True, ties=True, seed=d, binops={"copylhs": 4}, reduces={"max": 1},
+               flags=gnn.GNN_FLAG_NO_PADDED_COPY, max_slices=max_slices)
 
 
 def test_without_a_plan():
