@@ -467,3 +467,48 @@ def test_padded_rows_flag_allows_wide_loads(f, ld):
         Yo, S = oracle.aggregate_fwd(indptr, indices, X.numpy(), op=OP_CODE[op_name], nthreads=8, want_scale=True)
         assert_close(out[:, :f], Yo, S, False, f"padded rows {op_name} F={f}")
         assert torch.isnan(out[:, f:]).all(), "the output padding must stay untouched"
+
+
+@pytest.mark.parametrize("case", ["er_tiny", "hubs_padded_sliced"])
+def test_graph_capture_replays_match_eager(case):
+    """The hot calls allocate nothing once the plan is prepared and record no memset, so a step can
+    be captured into a HIP graph; every replay (with eager work between replays) must reproduce
+    the eager result bit for bit."""
+    if case == "er_tiny":
+        el, f, params, flags, max_slices = synth.make_graph("er_tiny"), 64, None, 0, 0
+    else:
+        el = synth.rmat_symmetric(20000, 600000, (0.57, 0.19, 0.19, 0.05), 3)
+        f, params, flags, max_slices = 100, gnn.make_plan_params([4, 32, 256], 128), gnn.GNN_FLAG_FORCE_PADDED_COPY, 4
+    dg = device_graph(el, plan_params=params)
+    op = gnn.GNN_MEAN
+    X = synth.normal_features(el.n, f, 1).to(DEV)
+    dY = synth.normal_features(el.n, f, 2).to(DEV)
+    Y, dX = torch.empty_like(X), torch.empty_like(dY)
+
+    def step():
+        gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, None, X, Y, el.n, f, op, plan=dg.plan_fwd, flags=flags, max_slices=max_slices)
+        gnn.gnn_aggregate_bwd(dg.indptr_t, dg.indices_t, None, dY, dX, el.n, f, op, plan=dg.plan_bwd, flags=flags, max_slices=max_slices)
+
+    step()  # first use: plan-owned buffers are grown here, outside the capture
+    torch.cuda.synchronize()
+    want_Y, want_dX = Y.clone(), dX.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        Y.fill_(float("nan"))
+        dX.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y, want_Y) and torch.equal(dX, want_dX), f"replay {rep}"
+        # eager work between the replays, new inputs for the next one
+        X.mul_(1.5)
+        dY.add_(0.25)
+        step()
+        torch.cuda.synchronize()
+        want_Y, want_dX = Y.clone(), dX.clone()
