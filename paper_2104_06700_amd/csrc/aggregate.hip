@@ -29,17 +29,8 @@ constexpr int kWavesPerBlock = kBlockThreads / 64;
 
 enum ScaleMode : int { kScaleNone = 0, kScaleInv = 1, kScaleRsqrt = 2, kScaleInvPlus1 = 3 };
 enum SelfMode : int { kSelfNone = 0, kSelfPlain = 1, kSelfInvPlus1 = 2 };  // own row added to the sum
-enum BinKind : int { kKindRows = 0, kKindHubPieces = 1 };
-
-struct BinDesc {
-    int64_t first_block;  // first (slice-independent) workgroup index of this bin
-    int64_t item_begin;   // offset into row_perm (rows) or into the piece list (hub pieces)
-    int64_t n_items;      // rows or pieces
-    int32_t log2_g;       // lanes per row group
-    int32_t log2_sr;      // edge slots per group
-    int32_t kind;
-    int32_t pad;
-};
+constexpr int kKindHubPieces = GNN_BIN_HUB_PIECES;
+using BinDesc = gnn_bin_desc;
 
 struct AggArgs {
     const void *indptr;
@@ -461,12 +452,6 @@ hipError_t launch_pad(const void *src, int64_t ld_src_bytes, void *dst, int64_t 
 }
 
 // ---------------------------------------------------------------- host side
-int pow2_floor_log2(int64_t x) {
-    int l = 0;
-    while ((int64_t(2) << l) <= x) ++l;
-    return l;
-}
-
 template <typename T, int VEC, bool COEF>
 hipError_t launch_npass(int npass, dim3 grid, hipStream_t stream, const AggArgs &a) {
     switch (npass) {
@@ -663,8 +648,6 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         }
     }
 
-    constexpr int sr_shift = 4;
-
     for (int gi = 0; gi < n_segs; ++gi) {
         const int64_t f0 = segs[gi].f0, fw = segs[gi].fw;
         const int log2_s = segs[gi].log2_s;
@@ -673,7 +656,6 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         const int log2_c = strips >= 64 ? 6 : gnn_ilog2_ceil(strips);
         const int C = 1 << log2_c;
         const int npass = int((strips + C - 1) / C);
-        const int max_log2_sr = 6 - log2_c;
 
         AggArgs a{};
         a.indptr = indptr;
@@ -694,43 +676,15 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         a.store_vec = store_vec;
         a.bias = bias ? bias + f0 : nullptr;
         a.relu = relu;
-        int64_t next_block = 0;
-        int nb = 0;
-        auto add_bin = [&](int kind, int64_t begin, int64_t n_items, int log2_sr) {
-            if (n_items <= 0) return;
-            BinDesc &d = a.bins[nb++];
-            d.first_block = next_block;
-            d.item_begin = begin;
-            d.n_items = n_items;
-            d.kind = kind;
-            d.log2_sr = log2_sr;
-            d.log2_g = kind == kKindHubPieces ? 6 : log2_c + log2_sr;
-            const int64_t items_per_block = int64_t(kWavesPerBlock) * (64 >> d.log2_g);
-            next_block += (n_items + items_per_block - 1) / items_per_block;
-        };
         if (plan) {
             a.row_perm = plan->row_perm;
             a.chunks = plan->chunks;
             // The scratch rows are F wide for every slab; point at this slab's columns.
             a.partial = partial ? partial + f0 : nullptr;
             a.ldp = gnn_partial_ld(F);
-            const int last = plan->n_bins - 1;
-            // heaviest work first: hub pieces, then bins from long rows to short rows
-            if (has_hub) add_bin(kKindHubPieces, 0, plan->n_chunks, max_log2_sr);
-            for (int bi = last; bi >= 0; --bi) {
-                if (bi == last && has_hub) continue;  // handled as pieces (+ finalize)
-                const int64_t lo = bi == 0 ? 0 : plan->params.thresholds[bi - 1];
-                // Edge slots per row: enough that the shortest row of the bin still takes ~16
-                // steps (several batches of loads per group), so short rows share a wavefront
-                // (64/G rows each) and only long rows get a whole wavefront.
-                int lsr = lo <= 1 ? 0 : pow2_floor_log2(lo) - sr_shift;
-                if (lsr < 0) lsr = 0;
-                if (lsr > max_log2_sr) lsr = max_log2_sr;
-                add_bin(kKindRows, plan->bin_offsets[bi], plan->bin_offsets[bi + 1] - plan->bin_offsets[bi], lsr);
-            }
-        } else {
-            add_bin(kKindRows, 0, N, max_log2_sr);
         }
+        int32_t nb = 0;
+        int64_t next_block = gnn_fill_bins(a.bins, &nb, plan, N, log2_c);
         a.n_bins = nb;
         if (nb == 0 || next_block == 0) continue;
         next_block <<= log2_s;

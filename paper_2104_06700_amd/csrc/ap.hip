@@ -18,17 +18,8 @@ namespace {
 constexpr int kBlockThreads = 256;
 constexpr int kWavesPerBlock = kBlockThreads / 64;
 
-enum : int { kKindRows = 0, kKindHubPieces = 1 };
-
-struct ApBin {
-    int64_t first_block;
-    int64_t item_begin;
-    int64_t n_items;
-    int32_t log2_g;
-    int32_t log2_sr;
-    int32_t kind;
-    int32_t pad;
-};
+constexpr int kKindHubPieces = GNN_BIN_HUB_PIECES;
+using ApBin = gnn_bin_desc;
 
 struct ApArgs {
     const void *indptr;
@@ -426,12 +417,6 @@ __global__ void __launch_bounds__(256) fill_rows_kernel(float *__restrict__ p, i
 }
 
 // ---------------------------------------------------------------- host side
-int floor_log2(int64_t x) {
-    int l = 0;
-    while ((int64_t(2) << l) <= x) ++l;
-    return l;
-}
-
 bool aligned16(const void *p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; }
 bool aligned4(const void *p) { return reinterpret_cast<uintptr_t>(p) % 4 == 0; }
 
@@ -443,42 +428,12 @@ unsigned grid_1d(int64_t work, int64_t cap = int64_t(1) << 17) {
 }
 
 // Fills the bin table (heaviest work first) and returns the number of workgroups along x.
-int64_t make_bins(ApArgs &a, const gnn_plan *plan, int64_t N, int log2_c, bool pieces) {
-    const int max_log2_sr = 6 - log2_c;
-    int64_t next_block = 0;
-    int nb = 0;
-    auto add_bin = [&](int kind, int64_t begin, int64_t n_items, int log2_sr) {
-        if (n_items <= 0) return;
-        ApBin &b = a.bins[nb++];
-        b.first_block = next_block;
-        b.item_begin = begin;
-        b.n_items = n_items;
-        b.kind = kind;
-        b.log2_sr = log2_sr;
-        b.log2_g = kind == kKindHubPieces ? 6 : log2_c + log2_sr;
-        b.pad = 0;
-        const int64_t items_per_block = int64_t(kWavesPerBlock) * (64 >> b.log2_g);
-        next_block += (n_items + items_per_block - 1) / items_per_block;
-    };
+int64_t make_bins(ApArgs &a, const gnn_plan *plan, int64_t N, int log2_c) {
     if (plan) {
         a.row_perm = plan->row_perm;
         a.chunks = plan->chunks;
-        const int last = plan->n_bins - 1;
-        const bool has_hub = plan->n_chunks > 0;
-        if (has_hub && pieces) add_bin(kKindHubPieces, 0, plan->n_chunks, max_log2_sr);
-        for (int bi = last; bi >= 0; --bi) {
-            if (bi == last && has_hub && pieces) continue;  // handled as pieces (+ finalize)
-            const int64_t lo = bi == 0 ? 0 : plan->params.thresholds[bi - 1];
-            int lsr = lo <= 1 ? 0 : floor_log2(lo) - 4;
-            if (lsr < 0) lsr = 0;
-            if (lsr > max_log2_sr) lsr = max_log2_sr;
-            add_bin(kKindRows, plan->bin_offsets[bi], plan->bin_offsets[bi + 1] - plan->bin_offsets[bi], lsr);
-        }
-    } else {
-        add_bin(kKindRows, 0, N, max_log2_sr);
     }
-    a.n_bins = nb;
-    return next_block;
+    return gnn_fill_bins(a.bins, &a.n_bins, plan, N, log2_c);
 }
 
 struct Common {
@@ -616,7 +571,7 @@ int run_ap_fwd(const void *indptr, const int32_t *indices, const float *fV, cons
                 const int64_t end = int64_t(a.col0) + (int64_t(a.slab_cols) << ls);
                 a.col_end = int32_t(end < d ? end : d);
                 a.log2_slices = ls;
-                const int64_t blocks = make_bins(a, plan, N, log2_c, /*pieces=*/true) << ls;
+                const int64_t blocks = make_bins(a, plan, N, log2_c) << ls;
                 if (blocks > INT32_MAX) return GNN_ERR_UNSUPPORTED;
                 if (blocks > 0) {
                     launch_fwd(binop, reduce, vec, c.ewide, dim3(static_cast<unsigned>(blocks)), c.stream, a);
@@ -636,7 +591,7 @@ int run_ap_fwd(const void *indptr, const int32_t *indices, const float *fV, cons
         a.col0 = 0;
         a.col_end = int32_t(d);
         a.log2_slices = 0;
-        const int64_t blocks = make_bins(a, plan, N, log2_c, /*pieces=*/true);
+        const int64_t blocks = make_bins(a, plan, N, log2_c);
         if (blocks > INT32_MAX) return GNN_ERR_UNSUPPORTED;
         if (blocks > 0) {
             dim3 grid(static_cast<unsigned>(blocks), static_cast<unsigned>(n_slabs));
@@ -775,7 +730,7 @@ extern "C" GNN_API int gnn_ap_bwd_edge(const void *indptr, const int32_t *indice
     a.ldo = c.ldo;
     a.d = int32_t(d);
     a.ip64 = c.o.indptr_is_64 ? 1 : 0;
-    const int64_t blocks = make_bins(a, plan, N, log2_c, /*pieces=*/true);
+    const int64_t blocks = make_bins(a, plan, N, log2_c);
     if (blocks > INT32_MAX) return GNN_ERR_UNSUPPORTED;
     if (blocks == 0) return GNN_OK;
     dim3 grid(static_cast<unsigned>(blocks));

@@ -108,6 +108,69 @@ int gnn_plan_edge_scale(gnn_plan *plan, const int32_t *indices, int mode, hipStr
 int gnn_aggregate_fwd_epilogue(const void *indptr, const int32_t *indices, const void *X, void *Y, int64_t N, int64_t F,
                                int op, const gnn_opts *opts, const float *bias, int relu);
 
+// ---- work distribution shared by the aggregation kernels (aggregate.hip, ap.hip) ----
+// A launch serves all degree bins of a plan at once: the workgroup index is looked up in a small
+// table of bins (heaviest work first).  A bin holds rows (64 >> log2_g rows per wavefront, each row
+// group being 2^(log2_g - log2_sr) column lanes x 2^log2_sr edge slots) or hub pieces (one per
+// wavefront).
+enum gnn_bin_kind : int32_t { GNN_BIN_ROWS = 0, GNN_BIN_HUB_PIECES = 1 };
+
+struct gnn_bin_desc {
+    int64_t first_block;  // first workgroup index of this bin (before any slice interleaving)
+    int64_t item_begin;   // offset into row_perm (rows) or into the piece list (hub pieces)
+    int64_t n_items;      // rows or pieces
+    int32_t log2_g;       // lanes per row group
+    int32_t log2_sr;      // edge slots per group
+    int32_t kind;
+    int32_t pad;
+};
+
+constexpr int GNN_WAVES_PER_BLOCK = 4;  // 256-thread workgroups
+
+// Fills `bins` for a launch whose row groups have 2^log2_c column lanes; returns the number of
+// workgroups.  plan == nullptr: all N rows in one bin, whole wavefronts per row.
+static inline int64_t gnn_fill_bins(gnn_bin_desc *bins, int32_t *n_bins, const gnn_plan *plan, int64_t N, int log2_c) {
+    const int max_log2_sr = 6 - log2_c;
+    int64_t next_block = 0;
+    int nb = 0;
+    auto add_bin = [&](int kind, int64_t begin, int64_t n_items, int log2_sr) {
+        if (n_items <= 0) return;
+        gnn_bin_desc &d = bins[nb++];
+        d.first_block = next_block;
+        d.item_begin = begin;
+        d.n_items = n_items;
+        d.kind = kind;
+        d.log2_sr = log2_sr;
+        d.log2_g = kind == GNN_BIN_HUB_PIECES ? 6 : log2_c + log2_sr;
+        d.pad = 0;
+        const int64_t items_per_block = int64_t(GNN_WAVES_PER_BLOCK) * (64 >> d.log2_g);
+        next_block += (n_items + items_per_block - 1) / items_per_block;
+    };
+    if (plan) {
+        const int last = plan->n_bins - 1;
+        const bool has_hub = plan->n_chunks > 0;
+        // heaviest work first: hub pieces, then bins from long rows to short rows
+        if (has_hub) add_bin(GNN_BIN_HUB_PIECES, 0, plan->n_chunks, max_log2_sr);
+        for (int bi = last; bi >= 0; --bi) {
+            if (bi == last && has_hub) continue;  // handled as pieces (+ finalize)
+            const int64_t lo = bi == 0 ? 0 : plan->params.thresholds[bi - 1];
+            // Edge slots per row: enough that the shortest row of the bin still takes ~16 steps
+            // (several batches of loads per group), so short rows share a wavefront (64/G rows
+            // each) and only long rows get a whole wavefront.
+            int lsr = 0;
+            while (lo > 1 && (int64_t(2) << lsr) <= lo) ++lsr;  // floor(log2(lo))
+            lsr -= 4;
+            if (lsr < 0) lsr = 0;
+            if (lsr > max_log2_sr) lsr = max_log2_sr;
+            add_bin(GNN_BIN_ROWS, plan->bin_offsets[bi], plan->bin_offsets[bi + 1] - plan->bin_offsets[bi], lsr);
+        }
+    } else {
+        add_bin(GNN_BIN_ROWS, 0, N, max_log2_sr);
+    }
+    *n_bins = nb;
+    return next_block;
+}
+
 // Copies an fp32 [N, F] matrix with row stride ld_src into rows of stride ld_dst (elements).
 int gnn_pad_rows_f32(const float *src, int64_t ld_src, float *dst, int64_t ld_dst, int64_t N, int64_t F, hipStream_t stream);
 
