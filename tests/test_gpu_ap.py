@@ -320,3 +320,30 @@ def test_randomised_graphs_widths_and_plans(seed):
     for bname, rname in picks:
         _check_all(el, params, d, ewidth, use_eid=bool(rng.random() < 0.4), ties=bool(rng.random() < 0.3), seed=seed,
                    binops={bname: BINOPS[bname]}, reduces={rname: REDUCES[rname]}, use_plan=use_plan)
+
+
+def test_int64_row_pointers():
+    el, params = _graph("rmat_hubs")
+    rng = np.random.default_rng(41)
+    dg = device_graph(el, indptr64=True, plan_params=params, want_perm=True)
+    assert dg.indptr.dtype == torch.int64
+    indptr, indices, *_ = host_csr(el)
+    n, E, d = el.n, el.e, 20
+    fV, fE = _inputs(rng, n, E, d, 1, False)
+    dO = rng.normal(size=(n, d)).astype(np.float32)
+    fV_d, fE_d, dO_d = (torch.from_numpy(a).to(DEV) for a in (fV, fE, dO))
+    out = torch.empty((n, d), device=DEV)
+    arg = torch.empty((n, d), dtype=torch.int32, device=DEV)
+    gnn.gnn_ap_fwd(dg.indptr, dg.indices, fV_d, fE_d, out, arg, n, d, 2, 2, plan=dg.plan_fwd)
+    torch.cuda.synchronize()
+    O, won = oracle.ap_fwd(indptr, indices, fV, fE, d, 2, 2)
+    assert np.array_equal(out.cpu().numpy().astype(np.float64), O) and np.array_equal(arg.cpu().numpy().astype(np.int64), won)
+    dfE = torch.empty((E, 1), device=DEV)
+    gnn.gnn_ap_bwd_edge(dg.indptr, dg.indices, arg, fV_d, fE_d, dO_d, dfE, n, d, 2, plan=dg.plan_fwd)
+    dfV = torch.empty((n, d), device=DEV)
+    gnn.gnn_ap_bwd_vertex(dg.indptr_t, dg.indices_t, dO_d, fE_d, dfV, n, d, 2, plan=dg.plan_bwd, edge_ids=dg.perm)
+    torch.cuda.synchronize()
+    (_, _), (dE, SE) = oracle.ap_bwd(indptr, indices, fV, fE, dO, d, 2, 2, arg=won)
+    _close(dfE, dE, SE, "edge gradient, int64 row pointers")
+    (dV, SV), _ = oracle.ap_bwd(indptr, indices, fV, fE, dO, d, 2, 0)
+    _close(dfV, dV, SV, "vertex gradient, int64 row pointers")

@@ -266,3 +266,20 @@ def test_layer_randomised(seed):
     fo = int(rng.choice([1, 2, 16, 41, 47, 64, 130, 256]))
     _layer_case(el, params, fi, fo, relu=bool(rng.random() < 0.6), order=int(rng.integers(0, 3)), seed=seed,
                 use_bias=bool(rng.random() < 0.7), want_dx=bool(rng.random() < 0.8))
+
+
+def test_layer_int64_row_pointers():
+    el, params = _graph("rmat_hubs")
+    rng = np.random.default_rng(43)
+    n, fi, fo = el.n, 48, 20
+    dg = device_graph(el, indptr64=True, plan_params=params)
+    indptr, indices, *_ = host_csr(el)
+    X = rng.normal(size=(n, fi)).astype(np.float32)
+    W = rng.normal(size=(fi, fo)).astype(np.float32)
+    Xd, Wd = torch.from_numpy(X).to(DEV), torch.from_numpy(W).to(DEV)
+    saved = torch.empty(gnn.gnn_sage_layer_saved_elems(n, fi, fo), device=DEV)
+    H = torch.empty((n, fo), device=DEV)
+    gnn.gnn_sage_layer_fwd(dg.indptr, dg.indices, Xd, Wd, None, saved, H, dg.plan_fwd, relu=False)
+    torch.cuda.synchronize()
+    _, Ho, SH = oracle.sage_layer_fwd(indptr, indices, X, W, None, False)
+    _close(H, Ho, SH, "layer forward, int64 row pointers")
