@@ -90,6 +90,13 @@ typedef struct gnn_opts {
  * 8) when ldx is. */
 #define GNN_FLAG_PADDED_ROWS 8
 
+/* Cold hints: sliced launches on a large power-law graph fetch the rows of rarely gathered sources
+ * with non-temporal loads (the plan keeps a copy of the index array with those sources flagged,
+ * 4 bytes per edge, built on first use or by gnn_plan_prepare).  NO: never; FORCE: whatever the
+ * graph and layout (tests).  Results do not depend on it. */
+#define GNN_FLAG_NO_COLD_HINTS 16
+#define GNN_FLAG_FORCE_COLD_HINTS 32
+
 /* Degree-binning parameters.  thresholds t[0] < ... < t[k-1], all > 0, cut the
  * row-length axis into k+1 bins, bin(v) = #{i : t[i] <= deg(v)}.  If
  * hub_chunk > 0 the rows of the LAST bin are "hub" rows: each is cut into

@@ -73,9 +73,17 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
 
 template <typename T, int VEC> struct VecIO;
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
 template <> struct VecIO<float, 4> {
     static __device__ __forceinline__ void load(const float *p, float (&v)[4]) {
         float4 t = *reinterpret_cast<const float4 *>(p); v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    }
+    static __device__ __forceinline__ void load_nt(const float *p, float (&v)[4]) {
+        f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p)); v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
     }
     static __device__ __forceinline__ void store(float *p, const float (&v)[4]) {
         *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
@@ -85,20 +93,32 @@ template <> struct VecIO<float, 2> {
     static __device__ __forceinline__ void load(const float *p, float (&v)[2]) {
         float2 t = *reinterpret_cast<const float2 *>(p); v[0] = t.x; v[1] = t.y;
     }
+    static __device__ __forceinline__ void load_nt(const float *p, float (&v)[2]) {
+        f32x2 t = __builtin_nontemporal_load(reinterpret_cast<const f32x2 *>(p)); v[0] = t.x; v[1] = t.y;
+    }
     static __device__ __forceinline__ void store(float *p, const float (&v)[2]) {
         *reinterpret_cast<float2 *>(p) = make_float2(v[0], v[1]);
     }
 };
 template <> struct VecIO<float, 1> {
     static __device__ __forceinline__ void load(const float *p, float (&v)[1]) { v[0] = *p; }
+    static __device__ __forceinline__ void load_nt(const float *p, float (&v)[1]) { v[0] = __builtin_nontemporal_load(p); }
     static __device__ __forceinline__ void store(float *p, const float (&v)[1]) { *p = v[0]; }
 };
 template <> struct VecIO<bf16_t, 8> {
+    static __device__ __forceinline__ void unpack(const uint32_t (&w)[4], float (&v)[8]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { v[2 * i] = __uint_as_float(w[i] << 16); v[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u); }
+    }
     static __device__ __forceinline__ void load(const bf16_t *p, float (&v)[8]) {
         uint4 t = *reinterpret_cast<const uint4 *>(p);
         uint32_t w[4] = {t.x, t.y, t.z, t.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) { v[2 * i] = __uint_as_float(w[i] << 16); v[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u); }
+        unpack(w, v);
+    }
+    static __device__ __forceinline__ void load_nt(const bf16_t *p, float (&v)[8]) {
+        u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+        uint32_t w[4] = {t.x, t.y, t.z, t.w};
+        unpack(w, v);
     }
     static __device__ __forceinline__ void store(bf16_t *p, const float (&v)[8]) {
         uint32_t w[4];
@@ -110,6 +130,11 @@ template <> struct VecIO<bf16_t, 8> {
 template <> struct VecIO<bf16_t, 4> {
     static __device__ __forceinline__ void load(const bf16_t *p, float (&v)[4]) {
         uint2 t = *reinterpret_cast<const uint2 *>(p);
+        v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xFFFF0000u);
+        v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xFFFF0000u);
+    }
+    static __device__ __forceinline__ void load_nt(const bf16_t *p, float (&v)[4]) {
+        u32x2 t = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(p));
         v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xFFFF0000u);
         v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xFFFF0000u);
     }
@@ -125,12 +150,19 @@ template <> struct VecIO<bf16_t, 2> {
         uint32_t t = *reinterpret_cast<const uint32_t *>(p);
         v[0] = __uint_as_float(t << 16); v[1] = __uint_as_float(t & 0xFFFF0000u);
     }
+    static __device__ __forceinline__ void load_nt(const bf16_t *p, float (&v)[2]) {
+        uint32_t t = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(p));
+        v[0] = __uint_as_float(t << 16); v[1] = __uint_as_float(t & 0xFFFF0000u);
+    }
     static __device__ __forceinline__ void store(bf16_t *p, const float (&v)[2]) {
         *reinterpret_cast<uint32_t *>(p) = uint32_t(f32_to_bf16(v[0])) | (uint32_t(f32_to_bf16(v[1])) << 16);
     }
 };
 template <> struct VecIO<bf16_t, 1> {
     static __device__ __forceinline__ void load(const bf16_t *p, float (&v)[1]) { v[0] = bf16_to_f32(p->bits); }
+    static __device__ __forceinline__ void load_nt(const bf16_t *p, float (&v)[1]) {
+        v[0] = bf16_to_f32(__builtin_nontemporal_load(&p->bits));
+    }
     static __device__ __forceinline__ void store(bf16_t *p, const float (&v)[1]) { p->bits = f32_to_bf16(v[0]); }
 };
 
@@ -295,11 +327,16 @@ __global__ void __launch_bounds__(kBlockThreads) aggregate_kernel(const AggArgs 
             float x[U][NPASS][VEC];
 #pragma unroll
             for (int k = 0; k < U; ++k) {
-                const T *xr = X + int64_t(u[k]) * a.ldx;
+                // Bit 31 of an index marks a rarely gathered ("cold") source (plan-owned index copy):
+                // its row is fetched with a non-temporal load, so that it does not displace the
+                // warm rows of the L2.
+                const bool cold = u[k] < 0;
+                const T *xr = X + int64_t(u[k] & 0x7FFFFFFF) * a.ldx;
 #pragma unroll
                 for (int p = 0; p < NPASS; ++p) {
                     if (ok[k] && col_ok[p]) {
-                        VecIO<T, VEC>::load(xr + col[p], x[k][p]);
+                        if (cold) VecIO<T, VEC>::load_nt(xr + col[p], x[k][p]);
+                        else VecIO<T, VEC>::load(xr + col[p], x[k][p]);
                     } else {
 #pragma unroll
                         for (int i = 0; i < VEC; ++i) x[k][p][i] = 0.0f;
@@ -648,6 +685,17 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         }
     }
 
+    // Sliced launches of a large power-law graph gather their rarely used sources with
+    // non-temporal loads: the plan keeps a copy of the index array with those sources flagged.
+    const int32_t *gather_indices = indices;
+    if (plan && ((n_segs > 0 && segs[0].log2_s > 0 && !(o.flags & GNN_FLAG_NO_COLD_HINTS)) ||
+                 (o.flags & GNN_FLAG_FORCE_COLD_HINTS))) {
+        const int32_t *flagged = nullptr;
+        int rc = gnn_plan_cold_indices(plan, indices, (o.flags & GNN_FLAG_FORCE_COLD_HINTS) != 0, stream, &flagged);
+        if (rc != GNN_OK) return rc;
+        if (flagged) gather_indices = flagged;
+    }
+
     for (int gi = 0; gi < n_segs; ++gi) {
         const int64_t f0 = segs[gi].f0, fw = segs[gi].fw;
         const int log2_s = segs[gi].log2_s;
@@ -659,7 +707,7 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
 
         AggArgs a{};
         a.indptr = indptr;
-        a.indices = indices;
+        a.indices = gather_indices;
         a.w = w;
         a.X = static_cast<const char *>(gathered) + f0 * esz;
         a.Y = static_cast<char *>(out) + f0 * esz;

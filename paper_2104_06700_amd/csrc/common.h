@@ -46,6 +46,11 @@ struct gnn_plan {
     // copy of the gathered matrix with rows padded to whole 128-byte lines (grown on first use)
     void *padded = nullptr;
     int64_t padded_bytes = 0;
+    // copy of `indices` in which bit 31 marks the rarely gathered ("cold") sources; built on first
+    // use when the plan's graph is in the regime where non-temporal loads of cold rows pay
+    int32_t *cold_indices = nullptr;
+    int32_t cold_decided = 0;    // 0: not yet; 1: decided (cold_indices is null when it does not pay)
+    int32_t cold_threshold = 0;  // sources gathered fewer times than this are cold
 };
 
 // Row stride (floats) of the hub partial-sum scratch for width F: whole 32-byte groups, so that
@@ -99,6 +104,11 @@ static inline gnn_layout gnn_choose_layout(const gnn_plan *plan, int64_t N, int6
 
 // Makes plan->padded at least `bytes` large (allocation on growth).
 int gnn_plan_padded(gnn_plan *plan, int64_t bytes);
+
+// The plan's index copy with cold sources flagged in bit 31, or nullptr when cold hints do not pay
+// for this graph (see plan.hip).  force: build it whatever the graph (tests).  Builds on first use
+// (allocation).
+int gnn_plan_cold_indices(gnn_plan *plan, const int32_t *indices, bool force, hipStream_t stream, const int32_t **out);
 
 // mode: 1 = reciprocal, 2 = reciprocal square root, 3 = reciprocal of (count + 1).
 // Builds the array on first use (allocation).

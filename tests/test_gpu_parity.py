@@ -512,3 +512,33 @@ def test_graph_capture_replays_match_eager(case):
         step()
         torch.cuda.synchronize()
         want_Y, want_dX = Y.clone(), dX.clone()
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("f", [5, 64, 100, 256])
+def test_cold_hints_do_not_change_results(f, dtype):
+    """Sources flagged as cold are fetched with non-temporal loads; forced here on a small graph
+    (a quarter of the vertices stays warm), every layout, both directions, bit-identical output."""
+    el = synth.rmat_symmetric(6000, 150000, (0.57, 0.19, 0.19, 0.05), 8)
+    bf16 = dtype == torch.bfloat16
+    indptr, indices, indptr_t, indices_t, _ = host_csr(el)
+    X = synth.normal_features(el.n, f, 3, dtype=dtype)
+    Yo, S = oracle.aggregate_fwd(indptr, indices, X.float().numpy(), op=OP_CODE["mean"], nthreads=8, want_scale=True)
+    dXo, St = oracle.aggregate_bwd(indptr_t, indices_t, X.float().numpy(), op=OP_CODE["mean"], din=np.diff(indptr), nthreads=8,
+                                   want_scale=True)
+    Xd = X.to(DEV)
+    for layout_flags, max_slices in ((0, 0), (gnn.GNN_FLAG_FORCE_PADDED_COPY, 8), (gnn.GNN_FLAG_NO_PADDED_COPY, 2)):
+        outs = []
+        for hint in (gnn.GNN_FLAG_NO_COLD_HINTS, gnn.GNN_FLAG_FORCE_COLD_HINTS):
+            dg = device_graph(el, plan_params=gnn.make_plan_params([4, 32, 256], 64))
+            Y = torch.full((el.n, f), float("nan"), dtype=dtype, device=DEV)
+            dX = torch.full((el.n, f), float("nan"), dtype=dtype, device=DEV)
+            gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, None, Xd, Y, el.n, f, gnn.GNN_MEAN, plan=dg.plan_fwd,
+                                  flags=layout_flags | hint, max_slices=max_slices)
+            gnn.gnn_aggregate_bwd(dg.indptr_t, dg.indices_t, None, Xd, dX, el.n, f, gnn.GNN_MEAN, plan=dg.plan_bwd,
+                                  flags=layout_flags | hint, max_slices=max_slices)
+            torch.cuda.synchronize()
+            assert_close(Y, Yo, S, bf16, f"fwd hints={hint}")
+            assert_close(dX, dXo, St, bf16, f"bwd hints={hint}")
+            outs.append((Y, dX))
+        assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
