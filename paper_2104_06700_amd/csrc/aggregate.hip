@@ -85,8 +85,11 @@ template <> struct VecIO<float, 4> {
     static __device__ __forceinline__ void load_nt(const float *p, float (&v)[4]) {
         f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p)); v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
     }
+    // Output rows are written once and not read again by this kernel: non-temporal stores keep
+    // them from displacing gathered rows in the L2 (measured: +0.5..1 %).
     static __device__ __forceinline__ void store(float *p, const float (&v)[4]) {
-        *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+        f32x4 t = {v[0], v[1], v[2], v[3]};
+        __builtin_nontemporal_store(t, reinterpret_cast<f32x4 *>(p));
     }
 };
 template <> struct VecIO<float, 2> {
@@ -97,13 +100,14 @@ template <> struct VecIO<float, 2> {
         f32x2 t = __builtin_nontemporal_load(reinterpret_cast<const f32x2 *>(p)); v[0] = t.x; v[1] = t.y;
     }
     static __device__ __forceinline__ void store(float *p, const float (&v)[2]) {
-        *reinterpret_cast<float2 *>(p) = make_float2(v[0], v[1]);
+        f32x2 t = {v[0], v[1]};
+        __builtin_nontemporal_store(t, reinterpret_cast<f32x2 *>(p));
     }
 };
 template <> struct VecIO<float, 1> {
     static __device__ __forceinline__ void load(const float *p, float (&v)[1]) { v[0] = *p; }
     static __device__ __forceinline__ void load_nt(const float *p, float (&v)[1]) { v[0] = __builtin_nontemporal_load(p); }
-    static __device__ __forceinline__ void store(float *p, const float (&v)[1]) { *p = v[0]; }
+    static __device__ __forceinline__ void store(float *p, const float (&v)[1]) { __builtin_nontemporal_store(v[0], p); }
 };
 template <> struct VecIO<bf16_t, 8> {
     static __device__ __forceinline__ void unpack(const uint32_t (&w)[4], float (&v)[8]) {
@@ -124,7 +128,8 @@ template <> struct VecIO<bf16_t, 8> {
         uint32_t w[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) w[i] = uint32_t(f32_to_bf16(v[2 * i])) | (uint32_t(f32_to_bf16(v[2 * i + 1])) << 16);
-        *reinterpret_cast<uint4 *>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+        u32x4 t = {w[0], w[1], w[2], w[3]};
+        __builtin_nontemporal_store(t, reinterpret_cast<u32x4 *>(p));
     }
 };
 template <> struct VecIO<bf16_t, 4> {
@@ -139,10 +144,10 @@ template <> struct VecIO<bf16_t, 4> {
         v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xFFFF0000u);
     }
     static __device__ __forceinline__ void store(bf16_t *p, const float (&v)[4]) {
-        uint2 t;
+        u32x2 t;
         t.x = uint32_t(f32_to_bf16(v[0])) | (uint32_t(f32_to_bf16(v[1])) << 16);
         t.y = uint32_t(f32_to_bf16(v[2])) | (uint32_t(f32_to_bf16(v[3])) << 16);
-        *reinterpret_cast<uint2 *>(p) = t;
+        __builtin_nontemporal_store(t, reinterpret_cast<u32x2 *>(p));
     }
 };
 template <> struct VecIO<bf16_t, 2> {
@@ -155,7 +160,7 @@ template <> struct VecIO<bf16_t, 2> {
         v[0] = __uint_as_float(t << 16); v[1] = __uint_as_float(t & 0xFFFF0000u);
     }
     static __device__ __forceinline__ void store(bf16_t *p, const float (&v)[2]) {
-        *reinterpret_cast<uint32_t *>(p) = uint32_t(f32_to_bf16(v[0])) | (uint32_t(f32_to_bf16(v[1])) << 16);
+        __builtin_nontemporal_store(uint32_t(f32_to_bf16(v[0])) | (uint32_t(f32_to_bf16(v[1])) << 16), reinterpret_cast<uint32_t *>(p));
     }
 };
 template <> struct VecIO<bf16_t, 1> {
@@ -163,7 +168,7 @@ template <> struct VecIO<bf16_t, 1> {
     static __device__ __forceinline__ void load_nt(const bf16_t *p, float (&v)[1]) {
         v[0] = bf16_to_f32(__builtin_nontemporal_load(&p->bits));
     }
-    static __device__ __forceinline__ void store(bf16_t *p, const float (&v)[1]) { p->bits = f32_to_bf16(v[0]); }
+    static __device__ __forceinline__ void store(bf16_t *p, const float (&v)[1]) { __builtin_nontemporal_store(f32_to_bf16(v[0]), &p->bits); }
 };
 
 // fp32 store of VEC consecutive values (hub partial sums are fp32 whatever T is)
@@ -439,7 +444,7 @@ __global__ void __launch_bounds__(256) pad_rows_kernel(const V *__restrict__ src
     for (int64_t g = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; g < total; g += stride) {
         const int64_t row = g / chunks_per_row;
         const int c = int(g - row * chunks_per_row);
-        dst[row * ld_dst + c] = src[row * ld_src + c];
+        __builtin_nontemporal_store(src[row * ld_src + c], &dst[row * ld_dst + c]);
     }
 }
 
@@ -582,9 +587,9 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
                 src_mode = kScaleNone;
                 if (self_mode == kSelfInvPlus1) self_mode = kSelfPlain;  // the own row is already scaled
             } else if (row_bytes % 16 == 0 && src_ld_bytes % 16 == 0 && src_addr % 16 == 0)
-                err = launch_pad<uint4>(gathered, src_ld_bytes, plan->padded, dst_ld_bytes, N, row_bytes, stream);
+                err = launch_pad<u32x4>(gathered, src_ld_bytes, plan->padded, dst_ld_bytes, N, row_bytes, stream);
             else if (row_bytes % 8 == 0 && src_ld_bytes % 8 == 0 && src_addr % 8 == 0)
-                err = launch_pad<uint2>(gathered, src_ld_bytes, plan->padded, dst_ld_bytes, N, row_bytes, stream);
+                err = launch_pad<u32x2>(gathered, src_ld_bytes, plan->padded, dst_ld_bytes, N, row_bytes, stream);
             else if (row_bytes % 4 == 0 && src_ld_bytes % 4 == 0 && src_addr % 4 == 0)
                 err = launch_pad<uint32_t>(gathered, src_ld_bytes, plan->padded, dst_ld_bytes, N, row_bytes, stream);
             else
@@ -780,9 +785,9 @@ int gnn_pad_rows_f32(const float *src, int64_t ld_src, float *dst, int64_t ld_ds
     const uintptr_t addr = reinterpret_cast<uintptr_t>(src);
     hipError_t err;
     if (row_bytes % 16 == 0 && src_ld_bytes % 16 == 0 && addr % 16 == 0)
-        err = launch_pad<uint4>(src, src_ld_bytes, dst, dst_ld_bytes, N, row_bytes, stream);
+        err = launch_pad<u32x4>(src, src_ld_bytes, dst, dst_ld_bytes, N, row_bytes, stream);
     else if (row_bytes % 8 == 0 && src_ld_bytes % 8 == 0 && addr % 8 == 0)
-        err = launch_pad<uint2>(src, src_ld_bytes, dst, dst_ld_bytes, N, row_bytes, stream);
+        err = launch_pad<u32x2>(src, src_ld_bytes, dst, dst_ld_bytes, N, row_bytes, stream);
     else
         err = launch_pad<uint32_t>(src, src_ld_bytes, dst, dst_ld_bytes, N, row_bytes, stream);
     return err == hipSuccess ? GNN_OK : GNN_ERR_LAUNCH;
