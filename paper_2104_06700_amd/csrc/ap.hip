@@ -62,6 +62,16 @@ template <int VEC> __device__ __forceinline__ void load_f(const float *p, float 
         v[0] = *p;
     }
 }
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+// non-temporal variant for rows of rarely gathered ("cold") sources
+template <int VEC> __device__ __forceinline__ void load_f_nt(const float *p, float (&v)[VEC]) {
+    if constexpr (VEC == 4) {
+        const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    } else {
+        v[0] = __builtin_nontemporal_load(p);
+    }
+}
 template <int VEC> __device__ __forceinline__ void store_f(float *p, const float (&v)[VEC]) {
     if constexpr (VEC == 4) *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
     else *p = v[0];
@@ -208,7 +218,11 @@ __global__ void __launch_bounds__(kBlockThreads) ap_fwd_kernel(const ApArgs a) {
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) { x[k][i] = 0.0f; y[k][i] = ys[k]; }
                 if (ok[k]) {
-                    if (USE_V) load_f<VEC>(a.fV + int64_t(u[k]) * a.ldv + col, x[k]);
+                    if (USE_V) {  // bit 31 of an index flags a cold source (plan-owned index copy, see aggregate.hip)
+                        const float *xr = a.fV + int64_t(u[k] & 0x7FFFFFFF) * a.ldv + col;
+                        if (u[k] < 0) load_f_nt<VEC>(xr, x[k]);
+                        else load_f<VEC>(xr, x[k]);
+                    }
                     if (WIDE) load_f<VEC>(a.fE + r[k] * a.lde + col, y[k]);
                 } else {
 #pragma unroll
@@ -560,6 +574,12 @@ int run_ap_fwd(const void *indptr, const int32_t *indices, const float *fV, cons
         const int64_t units = (lines + unit_lines - 1) / unit_lines;
         if (L.slices_wanted && lines_ok && units >= 2 && units <= 256 && c.o.max_slices != 1) {
             sliced = true;
+            if (!(c.o.flags & GNN_FLAG_NO_COLD_HINTS)) {
+                const int32_t *flagged = nullptr;
+                rc = gnn_plan_cold_indices(plan, indices, (c.o.flags & GNN_FLAG_FORCE_COLD_HINTS) != 0, c.stream, &flagged);
+                if (rc != GNN_OK) return rc;
+                if (flagged) a.indices = flagged;
+            }
             a.slab_cols = int32_t(unit_lines * line);
             const int log2_c = gnn_ilog2_ceil(a.slab_cols / vec);
             int64_t u0 = 0;

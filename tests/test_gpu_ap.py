@@ -142,6 +142,9 @@ def test_padded_copy_and_column_slices(d, ewidth, max_slices):
                flags=gnn.GNN_FLAG_FORCE_PADDED_COPY, max_slices=max_slices)
     _check_all(el, params, d, ewidth, use_eid=True, ties=True, seed=d, binops={"copylhs": 4}, reduces={"max": 1},
                flags=gnn.GNN_FLAG_NO_PADDED_COPY, max_slices=max_slices)
+    # cold sources flagged in the plan's index copy and fetched with non-temporal loads
+    _check_all(el, params, d, ewidth, use_eid=False, ties=True, seed=d + 1, binops={"copylhs": 4, "mul": 2},
+               flags=gnn.GNN_FLAG_FORCE_PADDED_COPY | gnn.GNN_FLAG_FORCE_COLD_HINTS, max_slices=max_slices)
 
 
 def test_without_a_plan():
