@@ -96,6 +96,10 @@ typedef struct gnn_opts {
  * graph and layout (tests).  Results do not depend on it. */
 #define GNN_FLAG_NO_COLD_HINTS 16
 #define GNN_FLAG_FORCE_COLD_HINTS 32
+/* Keep the plan-owned padded copy in vertex order (default: rows stored by descending gather
+ * count, gathered through a rank-mapped copy of the index array; 4 bytes per edge and per vertex
+ * of plan memory).  For A/B measurements; results do not depend on it. */
+#define GNN_FLAG_NO_RANK_ORDER 64
 
 /* Degree-binning parameters.  thresholds t[0] < ... < t[k-1], all > 0, cut the
  * row-length axis into k+1 bins, bin(v) = #{i : t[i] <= deg(v)}.  If

@@ -53,6 +53,13 @@ struct AggArgs {
     int32_t log2_slices;  // column slices; workgroup b serves slice b % n_slices (see run_aggregate)
     int32_t slice_cols;   // columns per slice (the last slice of a launch may hold fewer)
     int32_t store_vec;    // widest store the output rows allow (elements, <= VEC)
+    const int32_t *row_map;  // row of the gathered table that holds vertex v (rank layout), or nullptr: v
+    const int64_t *p_indptr;  // rank layout: edge range of the row at position i of row_perm within `indices`
+    const int64_t *p_chunks;  // rank layout: hub pieces (row, begin, end, original - plan-order position)
+    int32_t cold_on;      // honour the cold flag (bit 31) of the indices
+    const void *X_tail;   // dense tail table (see gnn_layout), read by slice `tail_slice` of the launch
+    int64_t ld_tail;
+    int32_t tail_slice;   // -1: none
     const float *bias;    // fused layer epilogue: per-column bias added to the scaled row, or nullptr
     int32_t relu;         // fused layer epilogue: rectifier after the bias
     BinDesc bins[GNN_MAX_BINS + 1];
@@ -256,21 +263,33 @@ __global__ void __launch_bounds__(kBlockThreads) aggregate_kernel(const AggArgs 
     const int c = lane_in_g & (C - 1);  // feature strip of this lane
 
     // the row (or hub piece) this group owns
-    int64_t e0 = 0, e1 = 0, row = -1, row_len = 0;
+    // e0..e1 index `indices`; the per-edge streams of the caller (weights, factors) live at e + wdelta
+    int64_t e0 = 0, e1 = 0, row = -1, row_len = 0, wdelta = 0;
     float *partial_out = nullptr;
     if (bin.kind == kKindHubPieces) {
         const int64_t piece = wave_in_bin;  // G == 64: one piece per wavefront
         if (piece < bin.n_items) {
-            const int64_t *p = a.chunks + 3 * (bin.item_begin + piece);
-            row = p[0]; e0 = p[1]; e1 = p[2];
+            if (a.p_chunks) {
+                const int64_t *p = a.p_chunks + 4 * (bin.item_begin + piece);
+                row = p[0]; e0 = p[1]; e1 = p[2]; wdelta = p[3];
+            } else {
+                const int64_t *p = a.chunks + 3 * (bin.item_begin + piece);
+                row = p[0]; e0 = p[1]; e1 = p[2];
+            }
             partial_out = a.partial + (bin.item_begin + piece) * a.ldp;
         }
     } else {
         const int64_t item = wave_in_bin * (64 >> bin.log2_g) + (lane >> bin.log2_g);
         if (item < bin.n_items) {
             row = a.row_perm ? int64_t(a.row_perm[bin.item_begin + item]) : bin.item_begin + item;
-            e0 = load_ip(a.indptr, a.ip64, row);
-            e1 = load_ip(a.indptr, a.ip64, row + 1);
+            if (a.p_indptr) {
+                e0 = a.p_indptr[bin.item_begin + item];
+                e1 = a.p_indptr[bin.item_begin + item + 1];
+                if (COEF) wdelta = load_ip(a.indptr, a.ip64, row) - e0;
+            } else {
+                e0 = load_ip(a.indptr, a.ip64, row);
+                e1 = load_ip(a.indptr, a.ip64, row + 1);
+            }
             row_len = e1 - e0;
         }
     }
@@ -281,14 +300,19 @@ __global__ void __launch_bounds__(kBlockThreads) aggregate_kernel(const AggArgs 
 #pragma unroll
         for (int i = 0; i < VEC; ++i) acc[p][i] = 0.0f;
 
-    const T *__restrict__ X = static_cast<const T *>(a.X);
-    int col[NPASS];
+    // the slice that holds the last, short line of the rows gathers it from the dense tail table
+    const bool is_tail = slice == a.tail_slice;
+    const T *__restrict__ X = static_cast<const T *>(is_tail ? a.X_tail : a.X);
+    const int64_t ldx = is_tail ? a.ld_tail : a.ldx;
+    int col[NPASS];    // column in the output (and in a caller's matrix)
+    int lcol[NPASS];   // column in the table this slice gathers from
     int ncols[NPASS];  // valid columns of the strip (< VEC only for the last strip of a padded matrix)
     bool col_ok[NPASS];
 #pragma unroll
     for (int p = 0; p < NPASS; ++p) {
         const int lc = (p * C + c) * VEC;
         col[p] = col_base + lc;
+        lcol[p] = is_tail ? lc : col[p];
         col_ok[p] = lc < Fk;
         ncols[p] = Fk - lc < VEC ? Fk - lc : VEC;
     }
@@ -302,8 +326,8 @@ __global__ void __launch_bounds__(kBlockThreads) aggregate_kernel(const AggArgs 
         if (e < e1) {
             u_out = a.indices[e];
             if (COEF) {
-                cf_out = a.w ? a.w[e] : 1.0f;
-                if (a.edge_scale) cf_out *= a.edge_scale[e];
+                cf_out = a.w ? a.w[e + wdelta] : 1.0f;
+                if (a.edge_scale) cf_out *= a.edge_scale[e + wdelta];
             }
         }
     };
@@ -335,13 +359,13 @@ __global__ void __launch_bounds__(kBlockThreads) aggregate_kernel(const AggArgs 
                 // Bit 31 of an index marks a rarely gathered ("cold") source (plan-owned index copy):
                 // its row is fetched with a non-temporal load, so that it does not displace the
                 // warm rows of the L2.
-                const bool cold = u[k] < 0;
-                const T *xr = X + int64_t(u[k] & 0x7FFFFFFF) * a.ldx;
+                const bool cold = u[k] < 0 && a.cold_on;
+                const T *xr = X + int64_t(u[k] & 0x7FFFFFFF) * ldx;
 #pragma unroll
                 for (int p = 0; p < NPASS; ++p) {
                     if (ok[k] && col_ok[p]) {
-                        if (cold) VecIO<T, VEC>::load_nt(xr + col[p], x[k][p]);
-                        else VecIO<T, VEC>::load(xr + col[p], x[k][p]);
+                        if (cold) VecIO<T, VEC>::load_nt(xr + lcol[p], x[k][p]);
+                        else VecIO<T, VEC>::load(xr + lcol[p], x[k][p]);
                     } else {
 #pragma unroll
                         for (int i = 0; i < VEC; ++i) x[k][p][i] = 0.0f;
@@ -376,6 +400,7 @@ __global__ void __launch_bounds__(kBlockThreads) aggregate_kernel(const AggArgs 
         return;
     }
     const float ds = scale_of(a.dst_mode, row_len);
+    const int64_t self_row = (a.self_mode != kSelfNone && a.row_map) ? int64_t(a.row_map[row]) : row;
     const float self_cf = a.self_mode == kSelfInvPlus1 ? scale_of(kScaleInvPlus1, a.col_counts[row]) : 1.0f;
     T *__restrict__ y = static_cast<T *>(a.Y) + row * a.ldy;
 #pragma unroll
@@ -383,7 +408,7 @@ __global__ void __launch_bounds__(kBlockThreads) aggregate_kernel(const AggArgs 
         if (!col_ok[p]) continue;
         if (a.self_mode != kSelfNone) {  // Section 6.1: the vertex's own vector joins the sum
             float xs[VEC];
-            VecIO<T, VEC>::load(X + row * a.ldx + col[p], xs);
+            VecIO<T, VEC>::load(X + self_row * ldx + lcol[p], xs);
 #pragma unroll
             for (int i = 0; i < VEC; ++i) acc[p][i] = fmaf(self_cf, xs[i], acc[p][i]);
         }
@@ -438,13 +463,15 @@ __global__ void __launch_bounds__(256) hub_finalize_kernel(const int32_t *__rest
 // sizeof(V) bytes; V is the widest type the source rows allow.
 template <typename V>
 __global__ void __launch_bounds__(256) pad_rows_kernel(const V *__restrict__ src, int64_t ld_src, V *__restrict__ dst,
-                                                       int64_t ld_dst, int64_t N, int chunks_per_row) {
+                                                       int64_t ld_dst, int64_t N, int chunks_per_row,
+                                                       const int32_t *__restrict__ row_map) {
     const int64_t total = N * chunks_per_row;
     const int64_t stride = int64_t(gridDim.x) * blockDim.x;
     for (int64_t g = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; g < total; g += stride) {
         const int64_t row = g / chunks_per_row;
         const int c = int(g - row * chunks_per_row);
-        __builtin_nontemporal_store(src[row * ld_src + c], &dst[row * ld_dst + c]);
+        const int64_t drow = row_map ? int64_t(row_map[row]) : row;
+        __builtin_nontemporal_store(src[row * ld_src + c], &dst[drow * ld_dst + c]);
     }
 }
 
@@ -455,7 +482,8 @@ template <int W>
 __global__ void __launch_bounds__(256) pad_scale_rows_kernel(const float *__restrict__ src, int64_t ld_src,
                                                              float *__restrict__ dst, int64_t ld_dst, int64_t N,
                                                              int chunks_per_row, int mode,
-                                                             const int32_t *__restrict__ counts) {
+                                                             const int32_t *__restrict__ counts,
+                                                             const int32_t *__restrict__ row_map) {
     const int64_t total = N * chunks_per_row;
     const int64_t stride = int64_t(gridDim.x) * blockDim.x;
     for (int64_t g = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; g < total; g += stride) {
@@ -466,30 +494,31 @@ __global__ void __launch_bounds__(256) pad_scale_rows_kernel(const float *__rest
         VecIO<float, W>::load(src + row * ld_src + int64_t(c) * W, v);
 #pragma unroll
         for (int i = 0; i < W; ++i) v[i] *= f;
-        VecIO<float, W>::store(dst + row * ld_dst + int64_t(c) * W, v);
+        const int64_t drow = row_map ? int64_t(row_map[row]) : row;
+        VecIO<float, W>::store(dst + drow * ld_dst + int64_t(c) * W, v);
     }
 }
 
 template <int W>
 hipError_t launch_pad_scale(const void *src, int64_t ld_src, void *dst, int64_t ld_dst, int64_t N, int64_t F, int mode,
-                            const int32_t *counts, hipStream_t stream) {
+                            const int32_t *counts, hipStream_t stream, const int32_t *row_map = nullptr) {
     const int cpr = int(F / W);
     int64_t blocks = (N * cpr + 255) / 256;
     if (blocks > (int64_t(1) << 17)) blocks = int64_t(1) << 17;
     pad_scale_rows_kernel<W><<<static_cast<unsigned>(blocks), 256, 0, stream>>>(
-        static_cast<const float *>(src), ld_src, static_cast<float *>(dst), ld_dst, N, cpr, mode, counts);
+        static_cast<const float *>(src), ld_src, static_cast<float *>(dst), ld_dst, N, cpr, mode, counts, row_map);
     return hipGetLastError();
 }
 
 template <typename V>
 hipError_t launch_pad(const void *src, int64_t ld_src_bytes, void *dst, int64_t ld_dst_bytes, int64_t N,
-                      int64_t row_bytes, hipStream_t stream) {
+                      int64_t row_bytes, hipStream_t stream, const int32_t *row_map = nullptr) {
     const int cpr = int(row_bytes / sizeof(V));
     int64_t blocks = (N * cpr + 255) / 256;
     if (blocks > (int64_t(1) << 17)) blocks = int64_t(1) << 17;
     pad_rows_kernel<V><<<static_cast<unsigned>(blocks), 256, 0, stream>>>(
         static_cast<const V *>(src), ld_src_bytes / int64_t(sizeof(V)), static_cast<V *>(dst),
-        ld_dst_bytes / int64_t(sizeof(V)), N, cpr);
+        ld_dst_bytes / int64_t(sizeof(V)), N, cpr, row_map);
     return hipGetLastError();
 }
 
@@ -564,41 +593,60 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
     int64_t ldg = ldx;  // row stride of the matrix the kernel gathers from
     bool padded = false;
     const gnn_layout layout = gnn_choose_layout(plan, N, F, esz, ldx, reinterpret_cast<uintptr_t>(gathered) % 128 == 0,
-                                                o.flags, o.max_slices);
+                                                o.flags, o.max_slices, /*allow_tail=*/o.max_slices != 1);
     const bool slices_wanted = layout.slices_wanted;
-    {
-        const int64_t row_bytes = F * esz;
-        if (layout.padded_copy) {
-            const int64_t ld_pad = layout.ld_pad;
-            int rc = gnn_plan_padded(plan, N * ld_pad * esz);
+    // the caller's matrix stays the source of the own-row term of the hub rows (hub_finalize_kernel)
+    const void *orig = gathered;
+    const int orig_self_mode = self_mode;
+    const char *tail_table = nullptr;
+    gnn_rank_layout rl{};  // rank layout of the copy (see gnn_plan)
+    const int32_t *rank = nullptr, *rank_indices = nullptr;
+    if (layout.padded_copy) {
+        int rc = gnn_plan_padded(plan, layout.bytes);
+        if (rc != GNN_OK) return rc;
+        if (!(o.flags & GNN_FLAG_NO_RANK_ORDER) && plan->n_edges > 0) {
+            rc = gnn_plan_rank_indices(plan, indptr, indices, (o.flags & GNN_FLAG_FORCE_COLD_HINTS) != 0, stream, &rl);
             if (rc != GNN_OK) return rc;
-            // widest chunk the source rows allow
-            const int64_t src_ld_bytes = ldx * esz, dst_ld_bytes = ld_pad * esz;
-            const uintptr_t src_addr = reinterpret_cast<uintptr_t>(gathered);
-            hipError_t err;
-            if (esz == 4 && src_mode != kScaleNone) {
-                // fp32: the factor of the gathered rows goes into the copy
-                if (row_bytes % 16 == 0 && src_ld_bytes % 16 == 0 && src_addr % 16 == 0)
-                    err = launch_pad_scale<4>(gathered, ldx, plan->padded, ld_pad, N, F, src_mode, plan->col_counts, stream);
-                else if (row_bytes % 8 == 0 && src_ld_bytes % 8 == 0 && src_addr % 8 == 0)
-                    err = launch_pad_scale<2>(gathered, ldx, plan->padded, ld_pad, N, F, src_mode, plan->col_counts, stream);
-                else
-                    err = launch_pad_scale<1>(gathered, ldx, plan->padded, ld_pad, N, F, src_mode, plan->col_counts, stream);
-                src_mode = kScaleNone;
-                if (self_mode == kSelfInvPlus1) self_mode = kSelfPlain;  // the own row is already scaled
-            } else if (row_bytes % 16 == 0 && src_ld_bytes % 16 == 0 && src_addr % 16 == 0)
-                err = launch_pad<u32x4>(gathered, src_ld_bytes, plan->padded, dst_ld_bytes, N, row_bytes, stream);
-            else if (row_bytes % 8 == 0 && src_ld_bytes % 8 == 0 && src_addr % 8 == 0)
-                err = launch_pad<u32x2>(gathered, src_ld_bytes, plan->padded, dst_ld_bytes, N, row_bytes, stream);
-            else if (row_bytes % 4 == 0 && src_ld_bytes % 4 == 0 && src_addr % 4 == 0)
-                err = launch_pad<uint32_t>(gathered, src_ld_bytes, plan->padded, dst_ld_bytes, N, row_bytes, stream);
-            else
-                err = launch_pad<uint16_t>(gathered, src_ld_bytes, plan->padded, dst_ld_bytes, N, row_bytes, stream);
-            if (err != hipSuccess) return GNN_ERR_LAUNCH;
-            gathered = plan->padded;
-            ldg = ld_pad;
-            padded = true;
+            rank = rl.rank;
+            rank_indices = rl.indices;
         }
+        const bool scale_in_copy = esz == 4 && src_mode != kScaleNone;  // fp32: the factor of the gathered rows goes into the copy
+        const int copy_mode = src_mode;
+        // copies `ncols` columns starting at `src` into rows of stride dst_ld, with the widest chunks the source allows
+        auto copy_part = [&](const char *src, int64_t ncols, char *dst, int64_t dst_ld) -> hipError_t {
+            const int64_t row_bytes = ncols * esz, src_ld_bytes = ldx * esz, dst_ld_bytes = dst_ld * esz;
+            const uintptr_t addr = reinterpret_cast<uintptr_t>(src);
+            if (scale_in_copy) {
+                if (row_bytes % 16 == 0 && src_ld_bytes % 16 == 0 && addr % 16 == 0)
+                    return launch_pad_scale<4>(src, ldx, dst, dst_ld, N, ncols, copy_mode, plan->col_counts, stream, rank);
+                if (row_bytes % 8 == 0 && src_ld_bytes % 8 == 0 && addr % 8 == 0)
+                    return launch_pad_scale<2>(src, ldx, dst, dst_ld, N, ncols, copy_mode, plan->col_counts, stream, rank);
+                return launch_pad_scale<1>(src, ldx, dst, dst_ld, N, ncols, copy_mode, plan->col_counts, stream, rank);
+            }
+            if (row_bytes % 16 == 0 && src_ld_bytes % 16 == 0 && addr % 16 == 0)
+                return launch_pad<u32x4>(src, src_ld_bytes, dst, dst_ld_bytes, N, row_bytes, stream, rank);
+            if (row_bytes % 8 == 0 && src_ld_bytes % 8 == 0 && addr % 8 == 0)
+                return launch_pad<u32x2>(src, src_ld_bytes, dst, dst_ld_bytes, N, row_bytes, stream, rank);
+            if (row_bytes % 4 == 0 && src_ld_bytes % 4 == 0 && addr % 4 == 0)
+                return launch_pad<uint32_t>(src, src_ld_bytes, dst, dst_ld_bytes, N, row_bytes, stream, rank);
+            return launch_pad<uint16_t>(src, src_ld_bytes, dst, dst_ld_bytes, N, row_bytes, stream, rank);
+        };
+        const int64_t main_cols = F - layout.tail_elems;
+        char *dst = static_cast<char *>(plan->padded);
+        if (copy_part(static_cast<const char *>(gathered), main_cols, dst, layout.ld_pad) != hipSuccess) return GNN_ERR_LAUNCH;
+        if (layout.tail_elems > 0) {
+            char *tail_dst = dst + N * layout.ld_pad * esz;  // a multiple of 128 bytes into the buffer
+            if (copy_part(static_cast<const char *>(gathered) + main_cols * esz, layout.tail_elems, tail_dst, layout.tail_ld) != hipSuccess)
+                return GNN_ERR_LAUNCH;
+            tail_table = tail_dst;
+        }
+        if (scale_in_copy) {
+            src_mode = kScaleNone;
+            if (self_mode == kSelfInvPlus1) self_mode = kSelfPlain;  // the own row is already scaled
+        }
+        gathered = plan->padded;
+        ldg = layout.ld_pad;
+        padded = true;
     }
 
     if (src_mode != kScaleNone && plan->n_edges > 0) {
@@ -648,7 +696,7 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
     // than 8 slices is covered by several launches of 8, 4, 2 or 1 slices (column slabs in time),
     // so that every launch keeps all 8 XCDs equally busy.  The price is one read of the index
     // stream per slice.
-    struct Segment { int64_t f0, fw; int log2_s; int64_t slice_cols; };
+    struct Segment { int64_t f0, fw; int log2_s; int64_t slice_cols; int tail_slice; };
     Segment segs[64];
     int n_segs = 0;
     {
@@ -674,9 +722,12 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
                 g.log2_s = ls;
                 const int64_t end = g.f0 + (g.slice_cols << ls);
                 g.fw = (end < F ? end : F) - g.f0;
+                // the last unit is the dense tail, when there is one
+                g.tail_slice = (tail_table && units - 1 >= u0 && units - 1 < u0 + (int64_t(1) << ls)) ? int(units - 1 - u0) : -1;
                 u0 += int64_t(1) << ls;
             }
         } else {
+            if (tail_table) return GNN_ERR_UNSUPPORTED;  // a tail table is only laid out for sliced launches
             // no slices: slabs of up to 64 lanes * vec * kMaxPass columns
             const int64_t slab = int64_t(64) * vec * kMaxPass;
             for (int64_t f0 = 0; f0 < F && n_segs < 64; f0 += slab) {
@@ -685,6 +736,7 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
                 g.fw = F - f0 < slab ? F - f0 : slab;
                 g.log2_s = 0;
                 g.slice_cols = g.fw;
+                g.tail_slice = -1;
             }
             if ((F + slab - 1) / slab > 64) return GNN_ERR_UNSUPPORTED;
         }
@@ -693,8 +745,10 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
     // Sliced launches of a large power-law graph gather their rarely used sources with
     // non-temporal loads: the plan keeps a copy of the index array with those sources flagged.
     const int32_t *gather_indices = indices;
-    if (plan && ((n_segs > 0 && segs[0].log2_s > 0 && !(o.flags & GNN_FLAG_NO_COLD_HINTS)) ||
-                 (o.flags & GNN_FLAG_FORCE_COLD_HINTS))) {
+    if (rank_indices) {
+        gather_indices = rank_indices;  // the copy is in rank order; cold sources are flagged there too
+    } else if (plan && ((n_segs > 0 && segs[0].log2_s > 0 && !(o.flags & GNN_FLAG_NO_COLD_HINTS)) ||
+                        (o.flags & GNN_FLAG_FORCE_COLD_HINTS))) {
         const int32_t *flagged = nullptr;
         int rc = gnn_plan_cold_indices(plan, indices, (o.flags & GNN_FLAG_FORCE_COLD_HINTS) != 0, stream, &flagged);
         if (rc != GNN_OK) return rc;
@@ -727,6 +781,13 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         a.log2_slices = log2_s;
         a.slice_cols = int32_t(slice_cols);
         a.store_vec = store_vec;
+        a.row_map = rank_indices ? rank : nullptr;
+        a.p_indptr = rank_indices ? rl.p_indptr : nullptr;
+        a.p_chunks = rank_indices ? rl.p_chunks : nullptr;
+        a.cold_on = (o.flags & GNN_FLAG_NO_COLD_HINTS) ? 0 : 1;
+        a.X_tail = tail_table;
+        a.ld_tail = layout.tail_ld;
+        a.tail_slice = segs[gi].tail_slice;
         a.bias = bias ? bias + f0 : nullptr;
         a.relu = relu;
         if (plan) {
@@ -764,13 +825,13 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         if (o.dtype == GNN_F32)
             hub_finalize_kernel<float><<<grid, 256, 0, stream>>>(plan->row_perm + hub_begin, plan->n_hub_rows, plan->hub_chunk_offsets,
                                                                  partial, indptr, o.indptr_is_64 ? 1 : 0, dst_mode,
-                                                                 static_cast<float *>(out), ldy, int(F), gnn_partial_ld(F), self_mode,
-                                                                 static_cast<const float *>(gathered), ldg, plan->col_counts, bias, relu);
+                                                                 static_cast<float *>(out), ldy, int(F), gnn_partial_ld(F), orig_self_mode,
+                                                                 static_cast<const float *>(orig), ldx, plan->col_counts, bias, relu);
         else
             hub_finalize_kernel<bf16_t><<<grid, 256, 0, stream>>>(plan->row_perm + hub_begin, plan->n_hub_rows, plan->hub_chunk_offsets,
                                                                   partial, indptr, o.indptr_is_64 ? 1 : 0, dst_mode,
-                                                                  static_cast<bf16_t *>(out), ldy, int(F), gnn_partial_ld(F), self_mode,
-                                                                  static_cast<const bf16_t *>(gathered), ldg, plan->col_counts, bias, relu);
+                                                                  static_cast<bf16_t *>(out), ldy, int(F), gnn_partial_ld(F), orig_self_mode,
+                                                                  static_cast<const bf16_t *>(orig), ldx, plan->col_counts, bias, relu);
         if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
     }
     return GNN_OK;

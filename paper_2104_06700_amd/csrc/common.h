@@ -51,6 +51,17 @@ struct gnn_plan {
     int32_t *cold_indices = nullptr;
     int32_t cold_decided = 0;    // 0: not yet; 1: decided (cold_indices is null when it does not pay)
     int32_t cold_threshold = 0;  // sources gathered fewer times than this are cold
+    // Rank layout of the padded copy: rank[v] = position of v by descending column count; the copy
+    // stores row v at row rank[v] and the kernels gather through rank_indices[e] =
+    // rank[indices[e]] (bit 31: cold).  Built on first use.
+    int32_t *rank = nullptr;
+    int32_t *rank_indices = nullptr;
+    // ... and in PLAN ORDER: the edge list of the row at position i of row_perm occupies
+    // rank_indices[p_indptr[i] .. p_indptr[i+1]), so the rows a workgroup processes side by side read
+    // one contiguous stretch of the index stream.  p_chunks: the hub pieces in those coordinates,
+    // (row, begin, end, original position minus plan-order position) each.
+    int64_t *p_indptr = nullptr;
+    int64_t *p_chunks = nullptr;
 };
 
 // Row stride (floats) of the hub partial-sum scratch for width F: whole 32-byte groups, so that
@@ -67,10 +78,17 @@ struct gnn_layout {
     bool slices_wanted;   // spread column slices over the XCDs
     bool padded_copy;     // gather from a plan-owned copy with rows of an odd number of lines
     int64_t ld_pad;       // row stride of that copy in elements
+    // Dense tail: when the last line of a row would hold at most 64 bytes, those columns go into a
+    // table of their own with rows of 16-byte groups, packed back to back, so that an L2 line holds
+    // the tail of several rows (F = 100 fp32: 3 whole lines per row + a 16-byte tail, 8 rows per
+    // line) and the copy's rows are whole lines with nothing wasted.
+    int64_t tail_elems;   // columns of the tail table (0: none); the main part has F - tail_elems
+    int64_t tail_ld;      // its row stride in elements
+    int64_t bytes;        // size of the whole copy for N rows
 };
 
 static inline gnn_layout gnn_choose_layout(const gnn_plan *plan, int64_t N, int64_t F, int esz, int64_t ldx,
-                                           bool base_line_aligned, int flags, int max_slices) {
+                                           bool base_line_aligned, int flags, int max_slices, bool allow_tail = false) {
     gnn_layout L{};
     const int64_t line_elems = 128 / esz;
     const int64_t lines = (F + line_elems - 1) / line_elems;
@@ -99,6 +117,16 @@ static inline gnn_layout gnn_choose_layout(const gnn_plan *plan, int64_t N, int6
                           (!lines_ok || (even_stride && plan && plan->n_edges >= (row_bytes >= 768 ? 16 : 128) * N));
     L.padded_copy = plan && !(flags & GNN_FLAG_NO_PADDED_COPY) && (worth_it || (flags & GNN_FLAG_FORCE_PADDED_COPY));
     L.ld_pad = (lines | 1) * line_elems;
+    L.tail_elems = 0;
+    L.tail_ld = 0;
+    const int64_t rest = F % line_elems;
+    if (allow_tail && L.padded_copy && L.slices_wanted && lines >= 2 && lines <= 8 && rest > 0 && rest * esz <= 64) {
+        const int64_t group = 16 / esz;
+        L.tail_elems = rest;
+        L.tail_ld = (rest + group - 1) / group * group;
+        L.ld_pad = ((lines - 1) | 1) * line_elems;
+    }
+    L.bytes = N * (L.ld_pad + L.tail_ld) * esz;
     return L;
 }
 
@@ -109,6 +137,20 @@ int gnn_plan_padded(gnn_plan *plan, int64_t bytes);
 // for this graph (see plan.hip).  force: build it whatever the graph (tests).  Builds on first use
 // (allocation).
 int gnn_plan_cold_indices(gnn_plan *plan, const int32_t *indices, bool force, hipStream_t stream, const int32_t **out);
+
+// Rank layout (see gnn_plan): the vertex ranks and the rank-mapped, cold-flagged index copy.
+// force_cold: flag the sources outside the warmest quarter whatever the graph (tests).
+struct gnn_rank_layout {
+    const int32_t *rank;       // [N]
+    const int32_t *indices;    // [E] rank-mapped, cold-flagged, in plan order
+    const int64_t *p_indptr;   // [N+1]
+    const int64_t *p_chunks;   // [n_chunks * 4]
+};
+int gnn_plan_rank_indices(gnn_plan *plan, const void *indptr, const int32_t *indices, bool force_cold, hipStream_t stream,
+                          gnn_rank_layout *out);
+
+// rank[v] = position of vertex v by descending count, ties by ascending id (graph.hip).
+int gnn_rank_by_count(const int32_t *counts, int64_t N, int32_t *rank, hipStream_t stream);
 
 // mode: 1 = reciprocal, 2 = reciprocal square root, 3 = reciprocal of (count + 1).
 // Builds the array on first use (allocation).

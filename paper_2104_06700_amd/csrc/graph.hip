@@ -230,6 +230,21 @@ int radix_sort_pairs(const uint32_t *first_keys, uint32_t *buf_k[2], uint32_t *b
     return GNN_OK;
 }
 
+__global__ void __launch_bounds__(256) rank_keys_kernel(const int32_t *__restrict__ counts, int64_t N,
+                                                        uint32_t *__restrict__ keys, uint32_t *__restrict__ ids) {
+    const int64_t stride = int64_t(gridDim.x) * blockDim.x;
+    for (int64_t v = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; v < N; v += stride) {
+        keys[v] = ~uint32_t(counts[v]);  // ascending keys = descending counts
+        ids[v] = uint32_t(v);
+    }
+}
+
+__global__ void __launch_bounds__(256) rank_scatter_kernel(const uint32_t *__restrict__ ids_sorted, int64_t N,
+                                                           int32_t *__restrict__ rank) {
+    const int64_t stride = int64_t(gridDim.x) * blockDim.x;
+    for (int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < N; i += stride) rank[ids_sorted[i]] = int32_t(i);
+}
+
 int grid_for(int64_t n, int block, int64_t cap = (int64_t(1) << 16)) {
     int64_t g = (n + block - 1) / block;
     if (g < 1) g = 1;
@@ -351,4 +366,37 @@ extern "C" GNN_API int gnn_validate_csr(const void *indptr, const int32_t *indic
     (void)hipFree(bad);
     if (rc != GNN_OK) return rc;
     return host_bad ? GNN_ERR_INVALID_GRAPH : GNN_OK;
+}
+
+// rank[v] = position of vertex v when the vertices are ordered by descending count (equal counts
+// by ascending id: the sort is stable).  Temporary buffers are allocated and freed here; synchronous.
+int gnn_rank_by_count(const int32_t *counts, int64_t N, int32_t *rank, hipStream_t stream) {
+    if (N <= 0) return GNN_OK;
+    if (!counts || !rank || N > INT32_MAX) return GNN_ERR_INVALID_ARG;
+    (void)hipGetLastError();
+    uint32_t *buf_k[2] = {nullptr, nullptr}, *buf_v[2] = {nullptr, nullptr}, *table = nullptr, *sums = nullptr;
+    auto cleanup = [&]() {
+        (void)hipFree(buf_k[0]); (void)hipFree(buf_k[1]); (void)hipFree(buf_v[0]); (void)hipFree(buf_v[1]);
+        (void)hipFree(table); (void)hipFree(sums);
+    };
+    auto fail = [&](int s) { (void)hipStreamSynchronize(stream); cleanup(); return s; };
+    const int64_t n_tiles = (N + kSortTile - 1) / kSortTile;
+    const int64_t n_table = n_tiles * 256;
+    const int64_t n_sums = (n_table + kScanChunk - 1) / kScanChunk;
+    for (int i = 0; i < 2; ++i) {
+        if (hipMalloc(&buf_k[i], sizeof(uint32_t) * N) != hipSuccess) return fail(GNN_ERR_ALLOC);
+        if (hipMalloc(&buf_v[i], sizeof(uint32_t) * N) != hipSuccess) return fail(GNN_ERR_ALLOC);
+    }
+    if (hipMalloc(&table, sizeof(uint32_t) * n_table) != hipSuccess) return fail(GNN_ERR_ALLOC);
+    if (hipMalloc(&sums, sizeof(uint32_t) * (n_sums + 1)) != hipSuccess) return fail(GNN_ERR_ALLOC);
+    rank_keys_kernel<<<grid_for(N, 256), 256, 0, stream>>>(counts, N, buf_k[0], buf_v[0]);
+    if (hipGetLastError() != hipSuccess) return fail(GNN_ERR_LAUNCH);
+    int where = 0;
+    int rc = radix_sort_pairs(nullptr, buf_k, buf_v, N, 32, table, sums, stream, &where);
+    if (rc != GNN_OK) return fail(rc);
+    rank_scatter_kernel<<<grid_for(N, 256), 256, 0, stream>>>(buf_v[where], N, rank);
+    if (hipGetLastError() != hipSuccess) return fail(GNN_ERR_LAUNCH);
+    if (hipStreamSynchronize(stream) != hipSuccess) return fail(GNN_ERR_LAUNCH);
+    cleanup();
+    return GNN_OK;
 }

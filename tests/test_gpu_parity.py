@@ -542,3 +542,63 @@ def test_cold_hints_do_not_change_results(f, dtype):
             assert_close(dX, dXo, St, bf16, f"bwd hints={hint}")
             outs.append((Y, dX))
         assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+
+
+@pytest.mark.parametrize("dtype,f", [(torch.float32, 36), (torch.float32, 68), (torch.float32, 100), (torch.float32, 132),
+                                     (torch.float32, 237), (torch.bfloat16, 72), (torch.bfloat16, 136), (torch.bfloat16, 200)])
+@pytest.mark.parametrize("max_slices", [0, 2, 4])
+def test_dense_tail_table(dtype, f, max_slices):
+    """Widths whose last line holds at most 64 bytes: the padded copy keeps those columns in a
+    table of their own (several rows per L2 line).  Forced on a small graph with hub rows; every
+    op in both directions, including the own-row term of SAGE_GCN and the scale folded into the copy."""
+    el = synth.rmat_symmetric(5000, 140000, (0.57, 0.19, 0.19, 0.05), 12)
+    bf16 = dtype == torch.bfloat16
+    dg = device_graph(el, plan_params=gnn.make_plan_params([4, 32, 256], 64))
+    indptr, indices, indptr_t, indices_t, _ = host_csr(el)
+    din, dout = np.diff(indptr), np.diff(indptr_t)
+    X = synth.normal_features(el.n, f, 5, dtype=dtype)
+    Xd = X.to(DEV)
+    for op_name in ("sum", "mean", "gcn", "sage"):
+        op = OP_CODE[op_name]
+        Y = torch.full((el.n, f), float("nan"), dtype=dtype, device=DEV)
+        dX = torch.full((el.n, f), float("nan"), dtype=dtype, device=DEV)
+        gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, None, Xd, Y, el.n, f, op, plan=dg.plan_fwd,
+                              flags=gnn.GNN_FLAG_FORCE_PADDED_COPY, max_slices=max_slices)
+        gnn.gnn_aggregate_bwd(dg.indptr_t, dg.indices_t, None, Xd, dX, el.n, f, op, plan=dg.plan_bwd,
+                              flags=gnn.GNN_FLAG_FORCE_PADDED_COPY, max_slices=max_slices)
+        torch.cuda.synchronize()
+        Yo, S = oracle.aggregate_fwd(indptr, indices, X.float().numpy(), op=op, dout=dout, nthreads=8, want_scale=True)
+        dXo, St = oracle.aggregate_bwd(indptr_t, indices_t, X.float().numpy(), op=op, din=din, nthreads=8, want_scale=True)
+        assert_close(Y, Yo, S, bf16, f"fwd {op_name} F={f} S<={max_slices}")
+        assert_close(dX, dXo, St, bf16, f"bwd {op_name} F={f} S<={max_slices}")
+
+
+@pytest.mark.parametrize("dtype,f", [(torch.float32, 100), (torch.float32, 64), (torch.float32, 7), (torch.bfloat16, 136)])
+def test_rank_ordered_copy_does_not_change_results(dtype, f):
+    """The plan-owned padded copy stores rows by descending gather count and is gathered through a
+    rank-mapped index copy; with and without it (and with the cold flag forced on) the output is
+    bit-identical, and it matches the oracle: all ops, both directions, hub rows, own-row term."""
+    el = synth.rmat_symmetric(7000, 180000, (0.57, 0.19, 0.19, 0.05), 21)
+    bf16 = dtype == torch.bfloat16
+    indptr, indices, indptr_t, indices_t, _ = host_csr(el)
+    din, dout = np.diff(indptr), np.diff(indptr_t)
+    X = synth.normal_features(el.n, f, 6, dtype=dtype)
+    Xd = X.to(DEV)
+    base = gnn.GNN_FLAG_FORCE_PADDED_COPY
+    for op_name in ("mean", "gcn", "sage"):
+        op = OP_CODE[op_name]
+        Yo, S = oracle.aggregate_fwd(indptr, indices, X.float().numpy(), op=op, dout=dout, nthreads=8, want_scale=True)
+        dXo, St = oracle.aggregate_bwd(indptr_t, indices_t, X.float().numpy(), op=op, din=din, nthreads=8, want_scale=True)
+        outs = []
+        for extra in (gnn.GNN_FLAG_NO_RANK_ORDER | gnn.GNN_FLAG_NO_COLD_HINTS, 0, gnn.GNN_FLAG_FORCE_COLD_HINTS):
+            dg = device_graph(el, plan_params=gnn.make_plan_params([4, 32, 256], 64))
+            Y = torch.full((el.n, f), float("nan"), dtype=dtype, device=DEV)
+            dX = torch.full((el.n, f), float("nan"), dtype=dtype, device=DEV)
+            gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, None, Xd, Y, el.n, f, op, plan=dg.plan_fwd, flags=base | extra, max_slices=4)
+            gnn.gnn_aggregate_bwd(dg.indptr_t, dg.indices_t, None, Xd, dX, el.n, f, op, plan=dg.plan_bwd, flags=base | extra, max_slices=4)
+            torch.cuda.synchronize()
+            assert_close(Y, Yo, S, bf16, f"fwd {op_name} flags={extra}")
+            assert_close(dX, dXo, St, bf16, f"bwd {op_name} flags={extra}")
+            outs.append((Y, dX))
+        for Y, dX in outs[1:]:
+            assert torch.equal(Y, outs[0][0]) and torch.equal(dX, outs[0][1])
