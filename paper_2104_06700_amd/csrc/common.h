@@ -145,6 +145,7 @@ struct gnn_rank_layout {
     const int32_t *indices;    // [E] rank-mapped, cold-flagged, in plan order
     const int64_t *p_indptr;   // [N+1]
     const int64_t *p_chunks;   // [n_chunks * 4]
+    bool cold_pays;            // the graph is in the regime where non-temporal loads of cold rows pay
 };
 int gnn_plan_rank_indices(gnn_plan *plan, const void *indptr, const int32_t *indices, bool force_cold, hipStream_t stream,
                           gnn_rank_layout *out);

@@ -338,13 +338,9 @@ int gnn_plan_rank_indices(gnn_plan *plan, const void *indptr, const int32_t *ind
             int rc = gnn_rank_by_count(plan->col_counts, N, plan->rank, stream);
             if (rc != GNN_OK) { (void)hipFree(plan->rank); plan->rank = nullptr; return rc; }
         }
-        int64_t warm = N;  // no vertex is cold
-        if (force_cold) {
-            warm = (N + 3) / 4;
-        } else if (N >= 8 * int64_t(5) * 32768) {
-            const double cold_share = 1.0 - gnn_plan_top_share(plan, int64_t(5) * 32768);
-            if (cold_share >= 0.05 && cold_share <= 0.30) warm = int64_t(5) * 32768;
-        }
+        // The indices of this copy are ranks, so the kernel finds the cold sources by comparing with
+        // the warm-set size of the call; bit 31 is only set when the tests force it.
+        const int64_t warm = force_cold ? (N + 3) / 4 : N;
         int64_t *p_indptr = nullptr, *p_chunks = nullptr;
         int32_t *idx = nullptr;
         auto fail = [&](int s) { (void)hipFree(p_indptr); (void)hipFree(p_chunks); (void)hipFree(idx); return s; };
@@ -367,6 +363,11 @@ int gnn_plan_rank_indices(gnn_plan *plan, const void *indptr, const int32_t *ind
     }
     out->rank = plan->rank;
     out->indices = plan->rank_indices;
+    out->cold_pays = false;
+    if (plan->n_rows >= 8 * int64_t(5) * 32768) {  // the gate of gnn_plan_cold_indices
+        const double cold_share = 1.0 - gnn_plan_top_share(plan, int64_t(5) * 32768);
+        out->cold_pays = cold_share >= 0.05 && cold_share <= 0.30;
+    }
     out->p_indptr = plan->p_indptr;
     out->p_chunks = plan->p_chunks;
     return GNN_OK;
