@@ -331,12 +331,17 @@ GNN_API int64_t gnn_plan_workspace_bytes(const gnn_plan *plan, int64_t F);
 /* Grow the plan-owned scratch now, so later hot calls do not allocate. */
 GNN_API int gnn_plan_reserve(gnn_plan *plan, int64_t F);
 /* Everything a later hot call with (op, direction, F) would otherwise allocate on its first
- * use: the scratch of gnn_plan_reserve, and the plan-owned per-edge factor stream (4 bytes per
- * edge: 1/din or 1/sqrt(deg) of the gathered vertex) that MEAN backward and weight-less
- * GCN_SYM read instead of one random count lookup per edge, and -- for widths whose rows are
- * not whole 128-byte lines -- the plan-owned copy of the gathered matrix with padded rows
- * (N x roundup(F) elements of `dtype`) that the hot call fills and gathers from.  `indices` is the index array
- * of the plan's graph.  backward: 0 for gnn_aggregate_fwd, 1 for gnn_aggregate_bwd. */
+ * use: the scratch of gnn_plan_reserve; the plan-owned per-edge factor stream (4 bytes per edge:
+ * 1/din or 1/sqrt(deg) of the gathered vertex) that MEAN backward and weight-less GCN_SYM read
+ * instead of one random count lookup per edge; for large matrices whose rows are not whole
+ * 128-byte lines (or have an even line stride) the plan-owned copy of the gathered matrix that
+ * the hot call fills and gathers from (about N x F elements of `dtype`, rows stored by descending
+ * gather count, a short last line kept in a dense table of its own); and the index copy that goes
+ * with it (4 bytes per edge + 12 per vertex: source ids mapped to their rank, edge lists in the
+ * plan's row order), or -- where no copy of the matrix is made but column slices are used on a
+ * large power-law graph -- the index copy with the cold sources flagged.  `indices` is the index
+ * array of the plan's graph, and the row pointers the plan was created from must still be alive.
+ * backward: 0 for gnn_aggregate_fwd, 1 for gnn_aggregate_bwd. */
 GNN_API int gnn_plan_prepare(gnn_plan *plan, const int32_t *indices, int op, int backward, int64_t F,
                              int dtype, void *stream);
 
