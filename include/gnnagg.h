@@ -100,6 +100,9 @@ typedef struct gnn_opts {
  * count, gathered through a rank-mapped copy of the index array; 4 bytes per edge and per vertex
  * of plan memory).  For A/B measurements; results do not depend on it. */
 #define GNN_FLAG_NO_RANK_ORDER 64
+/* Keep the plan-owned padded copy row-major (default for sliced launches: one table per 128-byte
+ * column slice).  For A/B measurements; results do not depend on it. */
+#define GNN_FLAG_NO_SLICE_TABLES 128
 
 /* Degree-binning parameters.  thresholds t[0] < ... < t[k-1], all > 0, cut the
  * row-length axis into k+1 bins, bin(v) = #{i : t[i] <= deg(v)}.  If

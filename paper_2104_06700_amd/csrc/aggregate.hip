@@ -58,6 +58,7 @@ struct AggArgs {
     const int64_t *p_chunks;  // rank layout: hub pieces (row, begin, end, original - plan-order position)
     int32_t cold_on;      // honour the cold flag (bit 31) of the indices
     int32_t warm_rank;    // rank layout: sources of rank >= this are cold too (INT32_MAX: none)
+    int64_t slice_stride;  // > 0: slice-major copy, slice s of the launch reads the table at X + s * slice_stride elements
     const void *X_tail;   // dense tail table (see gnn_layout), read by slice `tail_slice` of the launch
     int64_t ld_tail;
     int32_t tail_slice;   // -1: none
@@ -303,8 +304,10 @@ __global__ void __launch_bounds__(kBlockThreads) aggregate_kernel(const AggArgs 
 
     // the slice that holds the last, short line of the rows gathers it from the dense tail table
     const bool is_tail = slice == a.tail_slice;
-    const T *__restrict__ X = static_cast<const T *>(is_tail ? a.X_tail : a.X);
-    const int64_t ldx = is_tail ? a.ld_tail : a.ldx;
+    const bool own_table = is_tail || a.slice_stride > 0;  // columns are addressed within the slice
+    const T *__restrict__ X = is_tail ? static_cast<const T *>(a.X_tail)
+                                      : static_cast<const T *>(a.X) + int64_t(slice) * a.slice_stride;
+    const int64_t ldx = is_tail ? a.ld_tail : (a.slice_stride > 0 ? int64_t(a.slice_cols) : a.ldx);
     int col[NPASS];    // column in the output (and in a caller's matrix)
     int lcol[NPASS];   // column in the table this slice gathers from
     int ncols[NPASS];  // valid columns of the strip (< VEC only for the last strip of a padded matrix)
@@ -313,7 +316,7 @@ __global__ void __launch_bounds__(kBlockThreads) aggregate_kernel(const AggArgs 
     for (int p = 0; p < NPASS; ++p) {
         const int lc = (p * C + c) * VEC;
         col[p] = col_base + lc;
-        lcol[p] = is_tail ? lc : col[p];
+        lcol[p] = own_table ? lc : col[p];
         col_ok[p] = lc < Fk;
         ncols[p] = Fk - lc < VEC ? Fk - lc : VEC;
     }
@@ -466,14 +469,17 @@ __global__ void __launch_bounds__(256) hub_finalize_kernel(const int32_t *__rest
 template <typename V>
 __global__ void __launch_bounds__(256) pad_rows_kernel(const V *__restrict__ src, int64_t ld_src, V *__restrict__ dst,
                                                        int64_t ld_dst, int64_t N, int chunks_per_row,
-                                                       const int32_t *__restrict__ row_map) {
+                                                       const int32_t *__restrict__ row_map, int chunks_per_line,
+                                                       int64_t table_stride) {
     const int64_t total = N * chunks_per_row;
     const int64_t stride = int64_t(gridDim.x) * blockDim.x;
     for (int64_t g = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; g < total; g += stride) {
         const int64_t row = g / chunks_per_row;
         const int c = int(g - row * chunks_per_row);
         const int64_t drow = row_map ? int64_t(row_map[row]) : row;
-        __builtin_nontemporal_store(src[row * ld_src + c], &dst[drow * ld_dst + c]);
+        // row-major: chunks_per_line is "infinite" (one table); slice-major: one table per line
+        const int line = c / chunks_per_line, within = c - line * chunks_per_line;
+        __builtin_nontemporal_store(src[row * ld_src + c], &dst[line * table_stride + drow * ld_dst + within]);
     }
 }
 
@@ -485,7 +491,8 @@ __global__ void __launch_bounds__(256) pad_scale_rows_kernel(const float *__rest
                                                              float *__restrict__ dst, int64_t ld_dst, int64_t N,
                                                              int chunks_per_row, int mode,
                                                              const int32_t *__restrict__ counts,
-                                                             const int32_t *__restrict__ row_map) {
+                                                             const int32_t *__restrict__ row_map, int chunks_per_line,
+                                                             int64_t table_stride) {
     const int64_t total = N * chunks_per_row;
     const int64_t stride = int64_t(gridDim.x) * blockDim.x;
     for (int64_t g = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; g < total; g += stride) {
@@ -497,30 +504,35 @@ __global__ void __launch_bounds__(256) pad_scale_rows_kernel(const float *__rest
 #pragma unroll
         for (int i = 0; i < W; ++i) v[i] *= f;
         const int64_t drow = row_map ? int64_t(row_map[row]) : row;
-        VecIO<float, W>::store(dst + drow * ld_dst + int64_t(c) * W, v);
+        const int line = c / chunks_per_line, within = c - line * chunks_per_line;
+        VecIO<float, W>::store(dst + line * table_stride + drow * ld_dst + int64_t(within) * W, v);
     }
 }
 
 template <int W>
 hipError_t launch_pad_scale(const void *src, int64_t ld_src, void *dst, int64_t ld_dst, int64_t N, int64_t F, int mode,
-                            const int32_t *counts, hipStream_t stream, const int32_t *row_map = nullptr) {
+                            const int32_t *counts, hipStream_t stream, const int32_t *row_map = nullptr,
+                            int64_t table_stride = 0) {
     const int cpr = int(F / W);
     int64_t blocks = (N * cpr + 255) / 256;
     if (blocks > (int64_t(1) << 17)) blocks = int64_t(1) << 17;
     pad_scale_rows_kernel<W><<<static_cast<unsigned>(blocks), 256, 0, stream>>>(
-        static_cast<const float *>(src), ld_src, static_cast<float *>(dst), ld_dst, N, cpr, mode, counts, row_map);
+        static_cast<const float *>(src), ld_src, static_cast<float *>(dst), ld_dst, N, cpr, mode, counts, row_map,
+        table_stride > 0 ? 32 / W : INT32_MAX, table_stride);
     return hipGetLastError();
 }
 
 template <typename V>
 hipError_t launch_pad(const void *src, int64_t ld_src_bytes, void *dst, int64_t ld_dst_bytes, int64_t N,
-                      int64_t row_bytes, hipStream_t stream, const int32_t *row_map = nullptr) {
+                      int64_t row_bytes, hipStream_t stream, const int32_t *row_map = nullptr,
+                      int64_t table_stride_bytes = 0) {
     const int cpr = int(row_bytes / sizeof(V));
     int64_t blocks = (N * cpr + 255) / 256;
     if (blocks > (int64_t(1) << 17)) blocks = int64_t(1) << 17;
     pad_rows_kernel<V><<<static_cast<unsigned>(blocks), 256, 0, stream>>>(
         static_cast<const V *>(src), ld_src_bytes / int64_t(sizeof(V)), static_cast<V *>(dst),
-        ld_dst_bytes / int64_t(sizeof(V)), N, cpr, row_map);
+        ld_dst_bytes / int64_t(sizeof(V)), N, cpr, row_map,
+        table_stride_bytes > 0 ? int(128 / sizeof(V)) : INT32_MAX, table_stride_bytes / int64_t(sizeof(V)));
     return hipGetLastError();
 }
 
@@ -601,6 +613,7 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
     const void *orig = gathered;
     const int orig_self_mode = self_mode;
     const char *tail_table = nullptr;
+    bool slice_major = false;  // the copy holds one table per 128-byte column slice
     gnn_rank_layout rl{};  // rank layout of the copy (see gnn_plan)
     const int32_t *rank = nullptr, *rank_indices = nullptr;
     if (layout.padded_copy) {
@@ -615,30 +628,32 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         const bool scale_in_copy = esz == 4 && src_mode != kScaleNone;  // fp32: the factor of the gathered rows goes into the copy
         const int copy_mode = src_mode;
         // copies `ncols` columns starting at `src` into rows of stride dst_ld, with the widest chunks the source allows
-        auto copy_part = [&](const char *src, int64_t ncols, char *dst, int64_t dst_ld) -> hipError_t {
+        auto copy_part = [&](const char *src, int64_t ncols, char *dst, int64_t dst_ld, int64_t tstride) -> hipError_t {
             const int64_t row_bytes = ncols * esz, src_ld_bytes = ldx * esz, dst_ld_bytes = dst_ld * esz;
             const uintptr_t addr = reinterpret_cast<uintptr_t>(src);
             if (scale_in_copy) {
                 if (row_bytes % 16 == 0 && src_ld_bytes % 16 == 0 && addr % 16 == 0)
-                    return launch_pad_scale<4>(src, ldx, dst, dst_ld, N, ncols, copy_mode, plan->col_counts, stream, rank);
+                    return launch_pad_scale<4>(src, ldx, dst, dst_ld, N, ncols, copy_mode, plan->col_counts, stream, rank, tstride);
                 if (row_bytes % 8 == 0 && src_ld_bytes % 8 == 0 && addr % 8 == 0)
-                    return launch_pad_scale<2>(src, ldx, dst, dst_ld, N, ncols, copy_mode, plan->col_counts, stream, rank);
-                return launch_pad_scale<1>(src, ldx, dst, dst_ld, N, ncols, copy_mode, plan->col_counts, stream, rank);
+                    return launch_pad_scale<2>(src, ldx, dst, dst_ld, N, ncols, copy_mode, plan->col_counts, stream, rank, tstride);
+                return launch_pad_scale<1>(src, ldx, dst, dst_ld, N, ncols, copy_mode, plan->col_counts, stream, rank, tstride);
             }
             if (row_bytes % 16 == 0 && src_ld_bytes % 16 == 0 && addr % 16 == 0)
-                return launch_pad<u32x4>(src, src_ld_bytes, dst, dst_ld_bytes, N, row_bytes, stream, rank);
+                return launch_pad<u32x4>(src, src_ld_bytes, dst, dst_ld_bytes, N, row_bytes, stream, rank, tstride * esz);
             if (row_bytes % 8 == 0 && src_ld_bytes % 8 == 0 && addr % 8 == 0)
-                return launch_pad<u32x2>(src, src_ld_bytes, dst, dst_ld_bytes, N, row_bytes, stream, rank);
+                return launch_pad<u32x2>(src, src_ld_bytes, dst, dst_ld_bytes, N, row_bytes, stream, rank, tstride * esz);
             if (row_bytes % 4 == 0 && src_ld_bytes % 4 == 0 && addr % 4 == 0)
-                return launch_pad<uint32_t>(src, src_ld_bytes, dst, dst_ld_bytes, N, row_bytes, stream, rank);
-            return launch_pad<uint16_t>(src, src_ld_bytes, dst, dst_ld_bytes, N, row_bytes, stream, rank);
+                return launch_pad<uint32_t>(src, src_ld_bytes, dst, dst_ld_bytes, N, row_bytes, stream, rank, tstride * esz);
+            return launch_pad<uint16_t>(src, src_ld_bytes, dst, dst_ld_bytes, N, row_bytes, stream, rank, tstride * esz);
         };
         const int64_t main_cols = F - layout.tail_elems;
         char *dst = static_cast<char *>(plan->padded);
-        if (copy_part(static_cast<const char *>(gathered), main_cols, dst, layout.ld_pad) != hipSuccess) return GNN_ERR_LAUNCH;
+        if (copy_part(static_cast<const char *>(gathered), main_cols, dst, layout.ld_pad, layout.table_stride) != hipSuccess)
+            return GNN_ERR_LAUNCH;
         if (layout.tail_elems > 0) {
-            char *tail_dst = dst + N * layout.ld_pad * esz;  // a multiple of 128 bytes into the buffer
-            if (copy_part(static_cast<const char *>(gathered) + main_cols * esz, layout.tail_elems, tail_dst, layout.tail_ld) != hipSuccess)
+            // behind the main part, a multiple of 128 bytes into the buffer
+            char *tail_dst = dst + (layout.slice_major ? layout.main_lines * layout.table_stride : N * layout.ld_pad) * esz;
+            if (copy_part(static_cast<const char *>(gathered) + main_cols * esz, layout.tail_elems, tail_dst, layout.tail_ld, 0) != hipSuccess)
                 return GNN_ERR_LAUNCH;
             tail_table = tail_dst;
         }
@@ -649,6 +664,7 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         gathered = plan->padded;
         ldg = layout.ld_pad;
         padded = true;
+        slice_major = layout.slice_major;
     }
 
     if (src_mode != kScaleNone && plan->n_edges > 0) {
@@ -729,7 +745,7 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
                 u0 += int64_t(1) << ls;
             }
         } else {
-            if (tail_table) return GNN_ERR_UNSUPPORTED;  // a tail table is only laid out for sliced launches
+            if (tail_table || slice_major) return GNN_ERR_UNSUPPORTED;  // those layouts are only made for sliced launches
             // no slices: slabs of up to 64 lanes * vec * kMaxPass columns
             const int64_t slab = int64_t(64) * vec * kMaxPass;
             for (int64_t f0 = 0; f0 < F && n_segs < 64; f0 += slab) {
@@ -770,7 +786,9 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         a.indptr = indptr;
         a.indices = gather_indices;
         a.w = w;
-        a.X = static_cast<const char *>(gathered) + f0 * esz;
+        // row-major: the segment starts f0 columns into every row; slice-major: at its first slice table
+        a.X = static_cast<const char *>(gathered) + (slice_major ? (f0 / line_elems) * layout.table_stride : f0) * esz;
+        a.slice_stride = slice_major ? layout.table_stride : 0;
         a.Y = static_cast<char *>(out) + f0 * esz;
         a.ldx = ldg;
         a.ldy = ldy;

@@ -84,6 +84,13 @@ struct gnn_layout {
     // line) and the copy's rows are whole lines with nothing wasted.
     int64_t tail_elems;   // columns of the tail table (0: none); the main part has F - tail_elems
     int64_t tail_ld;      // its row stride in elements
+    // Slice-major: the main part is stored as one table per 128-byte column slice (line k of every
+    // row, rows back to back), because a launch's slice k is only ever read by the XCDs that serve
+    // it: their page and DRAM-row footprint shrinks to that table, and no row padding is needed to
+    // spread the L2 channels.
+    bool slice_major;
+    int64_t table_stride; // elements between two slice tables (N * elements per line)
+    int64_t main_lines;   // number of slice tables
     int64_t bytes;        // size of the whole copy for N rows
 };
 
@@ -126,7 +133,17 @@ static inline gnn_layout gnn_choose_layout(const gnn_plan *plan, int64_t N, int6
         L.tail_ld = (rest + group - 1) / group * group;
         L.ld_pad = ((lines - 1) | 1) * line_elems;
     }
-    L.bytes = N * (L.ld_pad + L.tail_ld) * esz;
+    L.main_lines = L.tail_elems > 0 ? lines - 1 : lines;
+    L.slice_major = allow_tail && L.padded_copy && L.slices_wanted && lines >= 2 && lines <= 256 &&
+                    !(flags & GNN_FLAG_NO_SLICE_TABLES);
+    L.table_stride = 0;
+    if (L.slice_major) {
+        L.ld_pad = line_elems;
+        L.table_stride = N * line_elems;
+        L.bytes = N * (L.main_lines * line_elems + L.tail_ld) * esz;
+    } else {
+        L.bytes = N * (L.ld_pad + L.tail_ld) * esz;
+    }
     return L;
 }
 

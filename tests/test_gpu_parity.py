@@ -602,3 +602,38 @@ def test_rank_ordered_copy_does_not_change_results(dtype, f):
             outs.append((Y, dX))
         for Y, dX in outs[1:]:
             assert torch.equal(Y, outs[0][0]) and torch.equal(dX, outs[0][1])
+
+
+@pytest.mark.parametrize("dtype,f", [(torch.float32, 100), (torch.float32, 96), (torch.float32, 300), (torch.float32, 602),
+                                     (torch.bfloat16, 200), (torch.bfloat16, 513)])
+@pytest.mark.parametrize("max_slices", [0, 2, 8])
+def test_slice_tables_do_not_change_results(dtype, f, max_slices):
+    """The padded copy of a sliced launch is stored as one table per 128-byte column slice; with
+    the row-major copy instead the output is bit-identical, and both match the oracle: rows of
+    up to 19 lines (several launches), a dense tail, hub rows, the own-row term, the folded scale."""
+    el = synth.rmat_symmetric(4500, 120000, (0.57, 0.19, 0.19, 0.05), 33)
+    bf16 = dtype == torch.bfloat16
+    indptr, indices, indptr_t, indices_t, _ = host_csr(el)
+    din, dout = np.diff(indptr), np.diff(indptr_t)
+    X = synth.normal_features(el.n, f, 9, dtype=dtype)
+    Xd = X.to(DEV)
+    base = gnn.GNN_FLAG_FORCE_PADDED_COPY
+    for op_name in ("mean", "gcn", "sage"):
+        op = OP_CODE[op_name]
+        Yo, S = oracle.aggregate_fwd(indptr, indices, X.float().numpy(), op=op, dout=dout, nthreads=8, want_scale=True)
+        dXo, St = oracle.aggregate_bwd(indptr_t, indices_t, X.float().numpy(), op=op, din=din, nthreads=8, want_scale=True)
+        outs = []
+        for extra in (gnn.GNN_FLAG_NO_SLICE_TABLES, 0, gnn.GNN_FLAG_NO_RANK_ORDER):
+            dg = device_graph(el, plan_params=gnn.make_plan_params([4, 32, 256], 64))
+            Y = torch.full((el.n, f), float("nan"), dtype=dtype, device=DEV)
+            dX = torch.full((el.n, f), float("nan"), dtype=dtype, device=DEV)
+            gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, None, Xd, Y, el.n, f, op, plan=dg.plan_fwd, flags=base | extra,
+                                  max_slices=max_slices)
+            gnn.gnn_aggregate_bwd(dg.indptr_t, dg.indices_t, None, Xd, dX, el.n, f, op, plan=dg.plan_bwd, flags=base | extra,
+                                  max_slices=max_slices)
+            torch.cuda.synchronize()
+            assert_close(Y, Yo, S, bf16, f"fwd {op_name} flags={extra}")
+            assert_close(dX, dXo, St, bf16, f"bwd {op_name} flags={extra}")
+            outs.append((Y, dX))
+        for Y, dX in outs[1:]:
+            assert torch.equal(Y, outs[0][0]) and torch.equal(dX, outs[0][1])
