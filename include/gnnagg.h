@@ -187,6 +187,10 @@ typedef struct gnn_ap_opts {
  * empty row -- and must be NULL for sum.  NaN inputs give an unspecified winner.  max / min need
  * E <= INT32_MAX.  16-byte loads are used when d, the strides and the base addresses allow,
  * scalar ones otherwise.  Hub rows use plan-owned scratch (grown on first use: allocation).
+ * copylhs / sum and mul / sum with a scalar f_E are what gnn_aggregate_fwd computes with GNN_SUM
+ * (plain or weighted) and run on that path, with its layouts; a scalar f_E that is strided or
+ * addressed through edge_ids is first gathered into a plan-owned array of E floats (allocated on
+ * first use) when a plan is given.
  * Asynchronous on opts->stream. */
 GNN_API int gnn_ap_fwd(const void *indptr, const int32_t *indices, const float *fV, const float *fE,
                        float *fO, int32_t *arg_e, int64_t N, int64_t d, int binop, int reduce,

@@ -518,6 +518,38 @@ int run_ap_fwd(const void *indptr, const int32_t *indices, const float *fV, cons
     (void)hipGetLastError();
 
     const bool wide = use_e && c.ewide;
+
+    // The sum of the neighbours' vectors, plain or weighted by a scalar per edge in CSR order, is
+    // the operation of the sum-only path (Alg. 1): that path has the layouts tuned for it.
+    // A scalar operand that is strided or reached through an edge-id map (the backward pass over the
+    // transposed graph) is first brought into CSR order, one pass over E values into a plan-owned
+    // array: the sliced launches then stream it instead of repeating random 4-byte reads per slice.
+    if (reduce == GNN_RED_SUM && (binop == GNN_BIN_COPY_LHS || (binop == GNN_BIN_MUL && !wide))) {
+        const float *w = nullptr;
+        if (binop == GNN_BIN_MUL) {
+            w = fE;
+            if (c.o.edge_ids || c.lde != 1) {
+                w = nullptr;
+                if (plan && plan->n_edges > 0) {
+                    rc = gnn_plan_edge_operand(plan, fE, c.lde, c.o.edge_ids, c.stream, &w);
+                    if (rc != GNN_OK) return rc;
+                }
+            }
+        }
+        if (binop == GNN_BIN_COPY_LHS || w) rc = GNN_OK; else rc = GNN_ERR_UNSUPPORTED;
+        gnn_opts g{};
+        g.dtype = GNN_F32;
+        g.indptr_is_64 = c.o.indptr_is_64;
+        g.ldx = c.ldv;
+        g.ldy = c.ldo;
+        g.stream = c.o.stream;
+        g.plan = plan;
+        g.flags = c.o.flags;
+        g.max_slices = c.o.max_slices;
+        if (rc == GNN_OK) rc = gnn_aggregate_fwd(indptr, indices, w, fV, fO, N, d, GNN_SUM, &g);
+        if (rc != GNN_ERR_UNSUPPORTED) return rc;  // shapes that path does not take go through the kernel below
+    }
+
     int vec = 4;
     if (d % 4 || c.ldo % 4 || !aligned16(fO)) vec = 1;
     if (use_v && (c.ldv % 4 || !aligned16(fV))) vec = 1;

@@ -62,6 +62,8 @@ struct gnn_plan {
     // (row, begin, end, original position minus plan-order position) each.
     int64_t *p_indptr = nullptr;
     int64_t *p_chunks = nullptr;
+    // a caller's scalar edge operand brought into CSR order (gnn_plan_edge_operand); refilled per call
+    float *edge_operand = nullptr;
 };
 
 // Row stride (floats) of the hub partial-sum scratch for width F: whole 32-byte groups, so that
@@ -172,6 +174,10 @@ int gnn_rank_by_count(const int32_t *counts, int64_t N, int32_t *rank, hipStream
 
 // mode: 1 = reciprocal, 2 = reciprocal square root, 3 = reciprocal of (count + 1).
 // Builds the array on first use (allocation).
+// out[e] = fE[(edge_ids ? edge_ids[e] : e) * lde] for the plan's n_edges edges, into a plan-owned
+// array (allocated on first use, refilled by every call).
+int gnn_plan_edge_operand(gnn_plan *plan, const float *fE, int64_t lde, const int64_t *edge_ids, hipStream_t stream,
+                          const float **out);
 int gnn_plan_edge_scale(gnn_plan *plan, const int32_t *indices, int mode, hipStream_t stream, const float **out);
 
 // gnn_aggregate_fwd with a fused epilogue: Y = act(aggregate(X) + bias), act = rectifier if relu.

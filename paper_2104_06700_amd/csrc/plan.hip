@@ -204,6 +204,32 @@ int gnn_plan_edge_scale(gnn_plan *plan, const int32_t *indices, int mode, hipStr
     return GNN_OK;
 }
 
+__global__ void __launch_bounds__(256) edge_operand_kernel(const float *__restrict__ fE, int64_t lde,
+                                                           const int64_t *__restrict__ edge_ids, int64_t E,
+                                                           float *__restrict__ out) {
+    const int64_t stride = int64_t(gridDim.x) * blockDim.x;
+    for (int64_t e = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; e < E; e += stride) {
+        const int64_t id = edge_ids ? edge_ids[e] : e;
+        __builtin_nontemporal_store(fE[id * lde], out + e);
+    }
+}
+
+int gnn_plan_edge_operand(gnn_plan *plan, const float *fE, int64_t lde, const int64_t *edge_ids, hipStream_t stream,
+                          const float **out) {
+    if (!plan || !out || !fE || lde < 1) return GNN_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (plan->n_edges == 0) return GNN_OK;
+    (void)hipGetLastError();
+    if (!plan->edge_operand && hipMalloc(&plan->edge_operand, sizeof(float) * plan->n_edges) != hipSuccess) {
+        plan->edge_operand = nullptr;
+        return GNN_ERR_ALLOC;
+    }
+    edge_operand_kernel<<<grid_for(plan->n_edges, 256, 1 << 16), 256, 0, stream>>>(fE, lde, edge_ids, plan->n_edges, plan->edge_operand);
+    if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
+    *out = plan->edge_operand;
+    return GNN_OK;
+}
+
 __global__ void __launch_bounds__(256) flag_cold_kernel(const int32_t *__restrict__ indices, int64_t E,
                                                         const int32_t *__restrict__ counts, int threshold,
                                                         int32_t *__restrict__ out) {
@@ -446,6 +472,7 @@ extern "C" GNN_API void gnn_plan_destroy(gnn_plan *plan) {
     (void)hipFree(plan->rank_indices);
     (void)hipFree(plan->p_indptr);
     (void)hipFree(plan->p_chunks);
+    (void)hipFree(plan->edge_operand);
     (void)hipFree(plan->row_perm);
     (void)hipFree(plan->col_counts);
     (void)hipFree(plan->chunks);
