@@ -730,19 +730,31 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         const int64_t units = (lines + unit_lines - 1) / unit_lines;
         const int64_t s_max = o.max_slices > 0 ? o.max_slices : 8;
         if (lines_ok && units >= 2 && units <= 256 && s_max >= 2 && slices_wanted) {
+            // The last unit is the dense tail, when there is one.  It gets a launch of its own over all
+            // XCDs: gathering 16 bytes costs a cache request per edge like a whole line does, and as one
+            // slice among others it kept its share of the XCDs busy nearly as long as a full line
+            // (F = 100 as 3 + tail in one launch: 5.77 ms; F = 96: 4.52 ms).
+            const int64_t main_units = tail_table ? units - 1 : units;
             int64_t u0 = 0;
-            while (u0 < units) {
+            while (u0 < main_units) {
                 int ls = 3;
-                while (ls > 0 && ((int64_t(1) << ls) > units - u0 || (int64_t(1) << ls) > s_max)) --ls;
+                while (ls > 0 && ((int64_t(1) << ls) > main_units - u0 || (int64_t(1) << ls) > s_max)) --ls;
                 Segment &g = segs[n_segs++];
                 g.f0 = u0 * unit_lines * line_elems;
                 g.slice_cols = unit_lines * line_elems;
                 g.log2_s = ls;
                 const int64_t end = g.f0 + (g.slice_cols << ls);
                 g.fw = (end < F ? end : F) - g.f0;
-                // the last unit is the dense tail, when there is one
-                g.tail_slice = (tail_table && units - 1 >= u0 && units - 1 < u0 + (int64_t(1) << ls)) ? int(units - 1 - u0) : -1;
+                g.tail_slice = -1;
                 u0 += int64_t(1) << ls;
+            }
+            if (tail_table) {
+                Segment &g = segs[n_segs++];
+                g.f0 = main_units * unit_lines * line_elems;
+                g.slice_cols = layout.tail_ld;  // few column lanes per row group: the lanes go to more edges instead
+                g.log2_s = 0;
+                g.fw = F - g.f0;
+                g.tail_slice = 0;
             }
         } else {
             if (tail_table || slice_major) return GNN_ERR_UNSUPPORTED;  // those layouts are only made for sliced launches
@@ -808,6 +820,8 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         // Warm-set size, measured on the 2.45 M-vertex graph: with <= 4 slices per launch (two or more
         // XCDs share a slice) 8 x 32,768 rows is best (F=100: 5.81 ms against 6.03 at 5 x), with 8
         // slices 5-6 x (F=256: 12.18 ms against 12.28 at 8 x and 12.64 at 3 x).
+        // Launches of one slice get none: no measurable effect on a whole line, and the dense tail loses
+        // with it (8 rows share a line there: F=100 5.70 -> 5.88 ms).
         a.warm_rank = INT32_MAX;
         if (rank_indices && rl.cold_pays && log2_s > 0) a.warm_rank = int32_t(32768) * (log2_s <= 2 ? 8 : 6);
         a.X_tail = tail_table;
