@@ -236,9 +236,11 @@ def measure(workload, steps, warmup, scale, dev, dump_graph=None):
                           "frac_of_hbm_peak": round(b / s / 1e9 / HBM_PEAK_GBS, 4),
                           "gathered_TBs": round(e * f * esz / s / 1e12, 2)})
     # Dominant kernel = aggregate_kernel: one template instantiation serves every call of this
-    # workload (forward and backward, all widths).  A call is that kernel plus, where the gathered
-    # rows are copied into padded rows first, the pad kernel, plus the small hub finalisation;
-    # the events bracket the call.
+    # workload (forward and backward, all widths).  The unit timed is a CALL: the launches of that
+    # kernel that cover the call's columns (one per group of up to 8 column slices, one for a dense
+    # tail) plus, where the gathered rows are copied into padded rows first, the pad kernel, plus
+    # the small hub finalisation; the events bracket the call, and the algorithmic bytes are the
+    # call's.
     all_bytes = sum(r["algorithmic_GB"] for r in call_rows)
     all_s = sum(r["ms"] for r in call_rows) * 1e-3
     achieved = all_bytes / all_s
@@ -247,6 +249,7 @@ def measure(workload, steps, warmup, scale, dev, dump_graph=None):
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "traffic_GBs": None if traffic is None else round(traffic / (all_s / len(call_rows)) / 1e9, 1),
                 "kernel": "aggregate_kernel (all calls of one step: forward and backward at every width)",
+                "per": "call (= its aggregate_kernel launches + pad copy + hub finalisation)",
                 "launches_per_step": len(call_rows), "avg_launch_ms": round(all_s * 1e3 / len(call_rows), 4)}
 
     result = {
