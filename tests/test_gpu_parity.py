@@ -378,7 +378,7 @@ def test_stream_and_repeatability():
     assert torch.equal(outs[0], outs[1])
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(40))
 def test_randomised_shapes_and_options(seed):
     """Seeded random draws over graph shape, width, dtype, op, weights, bin thresholds, hub
     piece size, row strides, base offsets and the layout switches; every draw must match the
@@ -406,7 +406,10 @@ def test_randomised_shapes_and_options(seed):
     k = int(rng.integers(0, 6))
     thr = sorted(set(int(t) for t in rng.integers(1, 200, size=k)))
     params = gnn.make_plan_params(thr, int(rng.choice([0, 3, 16, 64, 1024])))
-    flags = int(rng.choice([0, gnn.GNN_FLAG_FORCE_PADDED_COPY, gnn.GNN_FLAG_NO_COLUMN_SLICES, gnn.GNN_FLAG_NO_PADDED_COPY]))
+    flags = int(rng.choice([0, gnn.GNN_FLAG_FORCE_PADDED_COPY, gnn.GNN_FLAG_FORCE_PADDED_COPY, gnn.GNN_FLAG_NO_COLUMN_SLICES,
+                            gnn.GNN_FLAG_NO_PADDED_COPY]))
+    flags |= int(rng.choice([0, 0, gnn.GNN_FLAG_NO_SLICE_TABLES, gnn.GNN_FLAG_NO_RANK_ORDER, gnn.GNN_FLAG_FORCE_COLD_HINTS,
+                             gnn.GNN_FLAG_NO_COLD_HINTS]))
     max_slices = int(rng.choice([0, 0, 2, 4, 8]))
     ld = f + int(rng.choice([0, 0, 1, 3, 32, 96]))
     off = int(rng.choice([0, 0, 1, 4, 32]))
