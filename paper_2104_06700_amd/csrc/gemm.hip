@@ -104,7 +104,7 @@ struct Stager {
 
 // Workgroup tile (WM * TI * 32) x (WN * TJ * 32): WM x WN wavefronts, each TI x TJ MFMA tiles.
 template <bool A_K_CONTIG, bool B_K_CONTIG, int WM, int WN, int TI, int TJ>
-__global__ void __launch_bounds__(kThreads) gemm_kernel(const GemmArgs g, int a_vec_ok, int b_vec_ok) {
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))) gemm_kernel(const GemmArgs g, int a_vec_ok, int b_vec_ok) {
     static_assert(WM * WN == kThreads / 64, "four wavefronts");
     constexpr int BM = WM * TI * 32, BN = WN * TJ * 32;
     __shared__ __attribute__((aligned(16))) float As[BK][BM + PAD];
