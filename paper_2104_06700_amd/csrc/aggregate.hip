@@ -19,7 +19,13 @@
 //   * accumulation stays in registers for the whole neighbour loop and the
 //     output row is written once (the loop order of Algorithm 3);
 //   * rows of the hub bin are cut into pieces reduced by different wavefronts
-//     into an fp32 scratch; a second kernel adds the pieces in fixed order.
+//     into an fp32 scratch; a second kernel adds the pieces in fixed order;
+//   * workgroup b of a launch gathers only the 128-byte column slice b % S of
+//     the rows, so that the private L2 of the XCD it runs on holds one line of
+//     many rows instead of whole rows of few; for a large graph the gathered
+//     matrix is first copied into a plan-owned layout made for that: one table
+//     per slice, rows by descending gather count, a dense table for a short last
+//     line (run_aggregate below).
 #include "common.h"
 
 namespace {
