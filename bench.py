@@ -141,8 +141,11 @@ def cpu_baseline(el, widths, op_name, target_seconds=20.0):
             "one_core_sample": f"forward {op_name} at F={f0} on {len(one_rows)} sampled rows, {one_secs:.1f} s"}
 
 
-def measure(workload, steps, warmup, scale, dev, dump_graph=None):
-    """Setup + warm-up + the timed region for one workload; returns (result dict, host edge list factory)."""
+def measure(workload, steps, warmup, scale, dev, dump_graph=None, flush=False):
+    """Setup + warm-up + the timed region for one workload; returns (result dict, host edge list factory).
+    flush: overwrite a 1 GiB scratch buffer before every call (outside the call's events), so that
+    workloads whose matrices fit the caches start every call cold; value and ms_per_step are then
+    the sums of the per-call event times instead of the wall clock over the steps."""
     w = synth.WORKLOADS[workload]
     widths = list(w["widths"])
     op_names = w["op"].split("+")
@@ -197,6 +200,8 @@ def measure(workload, steps, warmup, scale, dev, dump_graph=None):
         else:
             gnn.gnn_aggregate_bwd(dg.indptr_t, dg.indices_t, dg.edge_w_t, dY, dX, n, f, op, plan=dg.plan_bwd)
 
+    scratch = torch.zeros(1 << 28, dtype=torch.float32, device=dev) if flush else None  # 1 GiB > L2 + Infinity Cache
+
     for _ in range(warmup):
         for op_name, d, layer in calls:
             one_call(op_name, d, layer)
@@ -209,6 +214,8 @@ def measure(workload, steps, warmup, scale, dev, dump_graph=None):
     t_start = time.perf_counter()
     for k in range(steps):
         for i, (op_name, d, layer) in enumerate(calls):
+            if flush:
+                scratch.add_(1.0)
             ev[k][i][0].record()
             one_call(op_name, d, layer)
             ev[k][i][1].record()
@@ -217,6 +224,8 @@ def measure(workload, steps, warmup, scale, dev, dump_graph=None):
 
     samples = [[ev[k][i][0].elapsed_time(ev[k][i][1]) for k in range(steps)] for i in range(len(calls))]
     per_call_ms = [float(np.mean(x)) for x in samples]
+    if flush:  # the flushes are not part of a step
+        t_total = sum(per_call_ms) * 1e-3 * steps
     ef_step = sum(2 * e * f for f in widths) * len(op_names)
     ms_per_step = t_total / steps * 1e3
     value = ef_step / (t_total / steps) / 1e9
@@ -259,7 +268,8 @@ def measure(workload, steps, warmup, scale, dev, dump_graph=None):
         "dtype": "bf16" if dtype == torch.bfloat16 else "f32", "data": "synthetic",
         "config": {"workload": f"{workload}: R-MAT/ER graph N={n} E={e}, op={w['op']}, widths={widths}, "
                                f"fwd+bwd per width" + ("" if scale == 1.0 else f" (SCALED x{scale}: not a result)"),
-                   "N": n, "E": e, "widths": widths, "op": w["op"], "indptr_bits": ip_bytes * 8, "parallelism": "1 GPU"},
+                   "N": n, "E": e, "widths": widths, "op": w["op"], "indptr_bits": ip_bytes * 8, "parallelism": "1 GPU",
+                   "cache_flushed_before_every_call": bool(flush)},
         "roofline": roofline,
         "calls": call_rows,
         "setup_ms": {"graph_generation": round(t_gen * 1e3, 1), "csr_and_transpose": round(t_csr * 1e3, 1),
@@ -394,6 +404,9 @@ def main():
                     help="skip the operator-table calls (gnn_ap_*) reported under 'general_primitive'")
     ap.add_argument("--no-layers", action="store_true",
                     help="skip the GraphSAGE layer calls (gnn_sage_layer_*) reported under 'layers'")
+    ap.add_argument("--flush-cache", action="store_true",
+                    help="overwrite a 1 GiB buffer before every call (for workloads that fit the caches); "
+                         "value is then the sum of the calls' event times")
     ap.add_argument("--dump-graph", default=None, metavar="DIR",
                     help="write the CSR and transposed CSR as raw arrays for the stand-alone profiling driver, then exit")
     args = ap.parse_args()
@@ -405,7 +418,7 @@ def main():
     torch.cuda.set_device(dev)
     gnn.load_library()
 
-    result, ctx = measure(args.workload, args.steps, args.warmup, args.scale, dev, args.dump_graph)
+    result, ctx = measure(args.workload, args.steps, args.warmup, args.scale, dev, args.dump_graph, args.flush_cache)
     if result is None:
         return
     el, widths, op_names = ctx
