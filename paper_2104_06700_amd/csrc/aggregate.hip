@@ -613,7 +613,8 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
     int64_t ldg = ldx;  // row stride of the matrix the kernel gathers from
     bool padded = false;
     const gnn_layout layout = gnn_choose_layout(plan, N, F, esz, ldx, reinterpret_cast<uintptr_t>(gathered) % 128 == 0,
-                                                o.flags, o.max_slices, /*allow_tail=*/o.max_slices != 1);
+                                                o.flags, o.max_slices, /*allow_tail=*/o.max_slices != 1,
+                                                /*scaled_source=*/src_mode != kScaleNone);
     const bool slices_wanted = layout.slices_wanted;
     // the caller's matrix stays the source of the own-row term of the hub rows (hub_finalize_kernel)
     const void *orig = gathered;

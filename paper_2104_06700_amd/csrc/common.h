@@ -97,7 +97,8 @@ struct gnn_layout {
 };
 
 static inline gnn_layout gnn_choose_layout(const gnn_plan *plan, int64_t N, int64_t F, int esz, int64_t ldx,
-                                           bool base_line_aligned, int flags, int max_slices, bool allow_tail = false) {
+                                           bool base_line_aligned, int flags, int max_slices, bool allow_tail = false,
+                                           bool scaled_source = false) {
     gnn_layout L{};
     const int64_t line_elems = 128 / esz;
     const int64_t lines = (F + line_elems - 1) / line_elems;
@@ -117,13 +118,19 @@ static inline gnn_layout gnn_choose_layout(const gnn_plan *plan, int64_t N, int6
     // of the XCD's 16 L2 channels (measured at F=256, 8 slices: 15.4 ms with 8-line rows, 12.5 ms
     // with 9-line rows).  An odd stride spreads them over all channels, so the padded copy always
     // has one; rows that are not whole lines, and line-aligned rows with an even stride when the
-    // gather (E rows) dwarfs the copy (N rows: >= 16 edges per vertex for rows of >= 768 bytes,
-    // >= 128 for shorter ones), are copied when slices are wanted.
+    // gather (E rows) dwarfs the copy (N rows: >= 16 edges per vertex for rows of >= 512 bytes,
+    // >= 128 for shorter ones), are copied when slices are wanted.  So are fp32 rows that carry a
+    // factor as gathered rows (scaled_source: MEAN / SAGE_GCN backward, weight-less GCN): the copy
+    // multiplies it in, which saves the per-edge factor stream and multiply (2.45 M vertices, 50
+    // edges each, backward MEAN: F=96 4.98 -> 4.53 ms, F=224 11.6 -> 10.6; 233 K vertices, 490 edges
+    // each: F=96 3.00 -> 2.48, F=224 6.85 -> 5.60).
     const bool lines_ok = (ldx % line_elems == 0) && base_line_aligned;
     const bool even_stride = lines_ok && (ldx / line_elems) % 2 == 0;
     const bool big = N * row_bytes >= (int64_t(32) << 20);
+    const bool dense_enough = plan && plan->n_edges >= 16 * N;
     const bool worth_it = row_bytes >= 192 && big && L.slices_wanted &&
-                          (!lines_ok || (even_stride && plan && plan->n_edges >= (row_bytes >= 768 ? 16 : 128) * N));
+                          (!lines_ok || (even_stride && plan && plan->n_edges >= (row_bytes >= 512 ? 16 : 128) * N) ||
+                           (scaled_source && esz == 4 && dense_enough));
     L.padded_copy = plan && !(flags & GNN_FLAG_NO_PADDED_COPY) && (worth_it || (flags & GNN_FLAG_FORCE_PADDED_COPY));
     L.ld_pad = (lines | 1) * line_elems;
     L.tail_elems = 0;

@@ -441,7 +441,9 @@ extern "C" GNN_API int gnn_plan_prepare(gnn_plan *plan, const int32_t *indices, 
     if (rc != GNN_OK) return rc;
     const int esz = dtype == GNN_BF16 ? 2 : 4;
     {   // the padded copy a hot call on a dense, line-aligned matrix (ld = F) would use, if any
-        const gnn_layout layout = gnn_choose_layout(plan, plan->n_rows, F, esz, F, true, 0, 0, /*allow_tail=*/true);
+        // (a weight-less GCN call is assumed: with explicit weights the rows carry no factor)
+        const bool scaled_source = ((op == GNN_MEAN || op == GNN_SAGE_GCN) && backward) || op == GNN_GCN_SYM;
+        const gnn_layout layout = gnn_choose_layout(plan, plan->n_rows, F, esz, F, true, 0, 0, /*allow_tail=*/true, scaled_source);
         if (layout.padded_copy) {
             rc = gnn_plan_padded(plan, layout.bytes);
             if (rc != GNN_OK) return rc;
