@@ -128,7 +128,7 @@ static inline gnn_layout gnn_choose_layout(const gnn_plan *plan, int64_t N, int6
     const bool even_stride = lines_ok && (ldx / line_elems) % 2 == 0;
     const bool big = N * row_bytes >= (int64_t(32) << 20);
     const bool dense_enough = plan && plan->n_edges >= 16 * N;
-    const bool worth_it = row_bytes >= 192 && big && L.slices_wanted &&
+    const bool worth_it = row_bytes > 128 && big && L.slices_wanted &&  // more than one line: something to slice
                           (!lines_ok || (even_stride && plan && plan->n_edges >= (row_bytes >= 512 ? 16 : 128) * N) ||
                            (scaled_source && esz == 4 && dense_enough));
     L.padded_copy = plan && !(flags & GNN_FLAG_NO_PADDED_COPY) && (worth_it || (flags & GNN_FLAG_FORCE_PADDED_COPY));
