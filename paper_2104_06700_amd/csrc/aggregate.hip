@@ -186,6 +186,49 @@ template <> struct VecIO<bf16_t, 1> {
     static __device__ __forceinline__ void store(bf16_t *p, const float (&v)[1]) { __builtin_nontemporal_store(f32_to_bf16(v[0]), &p->bits); }
 };
 
+// A gathered strip stays in the registers the load filled (the packed bits: 16 bytes are four
+// registers whether they hold 4 floats or 8 bf16) until it is added; unpacking at the load would
+// keep U * VEC floats alive per lane and halve the occupancy of the bf16 kernels.
+template <int BYTES> struct RawBits;
+template <> struct RawBits<16> { typedef u32x4 type; };
+template <> struct RawBits<8> { typedef u32x2 type; };
+template <> struct RawBits<4> { typedef uint32_t type; };
+template <> struct RawBits<2> { typedef uint16_t type; };
+
+template <typename T, int VEC>
+struct Strip {
+    static constexpr int BYTES = int(sizeof(T)) * VEC;
+    static constexpr int WORDS = BYTES >= 4 ? BYTES / 4 : 1;
+    using raw_t = typename RawBits<BYTES>::type;
+    static __device__ __forceinline__ raw_t load(const T *p) { return *reinterpret_cast<const raw_t *>(p); }
+    static __device__ __forceinline__ raw_t load_nt(const T *p) {
+        return __builtin_nontemporal_load(reinterpret_cast<const raw_t *>(p));
+    }
+    static __device__ __forceinline__ raw_t zero() {
+        if constexpr (BYTES >= 8) { raw_t z; for (int i = 0; i < WORDS; ++i) z[i] = 0u; return z; }
+        else return raw_t(0);
+    }
+    static __device__ __forceinline__ uint32_t word(const raw_t &r, int i) {
+        if constexpr (BYTES >= 8) return r[i];
+        else return uint32_t(r);
+    }
+    static __device__ __forceinline__ void unpack(const raw_t &r, float (&v)[VEC]) {
+        if constexpr (sizeof(T) == 4) {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) v[i] = __uint_as_float(word(r, i));
+        } else if constexpr (VEC == 1) {
+            v[0] = __uint_as_float(word(r, 0) << 16);
+        } else {
+#pragma unroll
+            for (int i = 0; i < VEC / 2; ++i) {
+                const uint32_t w = word(r, i);
+                v[2 * i] = __uint_as_float(w << 16);
+                v[2 * i + 1] = __uint_as_float(w & 0xFFFF0000u);
+            }
+        }
+    }
+};
+
 // fp32 store of VEC consecutive values (hub partial sums are fp32 whatever T is)
 template <int VEC>
 __device__ __forceinline__ void store_f32(float *p, const float (&v)[VEC]) {
@@ -217,11 +260,13 @@ __device__ __forceinline__ void store_strip(T *y, const float (&o)[VEC], int nco
             return;
         }
     }
+    // single elements: plain stores, so that the L2 merges the pieces of a line before it is
+    // written back (non-temporal 4-byte stores reach memory as partial lines)
 #pragma unroll
     for (int i = 0; i < VEC; ++i) {
         if (i < ncols) {
-            float one[1] = {o[i]};
-            VecIO<T, 1>::store(y + i, one);
+            if constexpr (sizeof(T) == 4) *reinterpret_cast<float *>(y + i) = o[i];
+            else reinterpret_cast<uint16_t *>(y + i)[0] = f32_to_bf16(o[i]);
         }
     }
 }
@@ -363,7 +408,11 @@ __global__ void __launch_bounds__(kBlockThreads) aggregate_kernel(const AggArgs 
                 if (COEF) cf[k] = __shfl(my_cf, src_lane);
                 ok[k] = j < n_tile;
             }
-            float x[U][NPASS][VEC];
+            // bf16 strips stay packed until they are added (see Strip); fp32 strips are floats already,
+            // and the plain arrays schedule slightly better (F=256: 12.04 against 12.26 ms)
+            constexpr bool PACKED = sizeof(T) == 2;
+            typename Strip<T, VEC>::raw_t xr_[PACKED ? U : 1][NPASS];
+            float x[PACKED ? 1 : U][NPASS][VEC];
 #pragma unroll
             for (int k = 0; k < U; ++k) {
                 // Bit 31 of an index marks a rarely gathered ("cold") source (plan-owned index copy):
@@ -375,23 +424,40 @@ __global__ void __launch_bounds__(kBlockThreads) aggregate_kernel(const AggArgs 
 #pragma unroll
                 for (int p = 0; p < NPASS; ++p) {
                     if (ok[k] && col_ok[p]) {
-                        if (cold) VecIO<T, VEC>::load_nt(xr + lcol[p], x[k][p]);
-                        else VecIO<T, VEC>::load(xr + lcol[p], x[k][p]);
+                        if constexpr (PACKED) {
+                            if (cold) xr_[k][p] = Strip<T, VEC>::load_nt(xr + lcol[p]);
+                            else xr_[k][p] = Strip<T, VEC>::load(xr + lcol[p]);
+                        } else {
+                            if (cold) VecIO<T, VEC>::load_nt(xr + lcol[p], x[k][p]);
+                            else VecIO<T, VEC>::load(xr + lcol[p], x[k][p]);
+                        }
                     } else {
+                        if constexpr (PACKED) {
+                            xr_[k][p] = Strip<T, VEC>::zero();
+                        } else {
 #pragma unroll
-                        for (int i = 0; i < VEC; ++i) x[k][p][i] = 0.0f;
+                            for (int i = 0; i < VEC; ++i) x[k][p][i] = 0.0f;
+                        }
                     }
                 }
             }
 #pragma unroll
             for (int k = 0; k < U; ++k)
 #pragma unroll
-                for (int p = 0; p < NPASS; ++p)
+                for (int p = 0; p < NPASS; ++p) {
+                    float xv[VEC];
+                    if constexpr (PACKED) {
+                        Strip<T, VEC>::unpack(xr_[k][p], xv);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < VEC; ++i) xv[i] = x[k][p][i];
+                    }
 #pragma unroll
                     for (int i = 0; i < VEC; ++i) {
-                        if (COEF) acc[p][i] = fmaf(ok[k] ? cf[k] : 0.0f, x[k][p][i], acc[p][i]);
-                        else acc[p][i] += x[k][p][i];
+                        if (COEF) acc[p][i] = fmaf(ok[k] ? cf[k] : 0.0f, xv[i], acc[p][i]);
+                        else acc[p][i] += xv[i];
                     }
+                }
         }
     }
 
@@ -475,17 +541,24 @@ __global__ void __launch_bounds__(256) hub_finalize_kernel(const int32_t *__rest
 template <typename V>
 __global__ void __launch_bounds__(256) pad_rows_kernel(const V *__restrict__ src, int64_t ld_src, V *__restrict__ dst,
                                                        int64_t ld_dst, int64_t N, int chunks_per_row,
-                                                       const int32_t *__restrict__ row_map, int chunks_per_line,
-                                                       int64_t table_stride) {
-    const int64_t total = N * chunks_per_row;
-    const int64_t stride = int64_t(gridDim.x) * blockDim.x;
-    for (int64_t g = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; g < total; g += stride) {
-        const int64_t row = g / chunks_per_row;
-        const int c = int(g - row * chunks_per_row);
+                                                       const int32_t *__restrict__ row_map, int log2_chunks_per_line,
+                                                       int64_t table_stride, int log2_tpr) {
+    // 2^log2_tpr consecutive threads walk the chunks of one row (no division per chunk)
+    const int tpr = 1 << log2_tpr;
+    const int64_t rows_per_block = blockDim.x >> log2_tpr;
+    const int c0 = threadIdx.x & (tpr - 1);
+    for (int64_t row = int64_t(blockIdx.x) * rows_per_block + (threadIdx.x >> log2_tpr); row < N;
+         row += int64_t(gridDim.x) * rows_per_block) {
         const int64_t drow = row_map ? int64_t(row_map[row]) : row;
-        // row-major: chunks_per_line is "infinite" (one table); slice-major: one table per line
-        const int line = c / chunks_per_line, within = c - line * chunks_per_line;
-        __builtin_nontemporal_store(src[row * ld_src + c], &dst[line * table_stride + drow * ld_dst + within]);
+        const V *in = src + row * ld_src;
+        for (int c = c0; c < chunks_per_row; c += tpr) {
+            // row-major: log2_chunks_per_line is 31 (one table); slice-major: one table per line
+            const int line = c >> log2_chunks_per_line, within = c - (line << log2_chunks_per_line);
+            // 16-byte chunks go out non-temporal; smaller ones as plain stores, which the L2 merges into lines
+            V *q = &dst[line * table_stride + drow * ld_dst + within];
+            if constexpr (sizeof(V) >= 16) __builtin_nontemporal_store(in[c], q);
+            else *q = in[c];
+        }
     }
 }
 
@@ -497,22 +570,42 @@ __global__ void __launch_bounds__(256) pad_scale_rows_kernel(const float *__rest
                                                              float *__restrict__ dst, int64_t ld_dst, int64_t N,
                                                              int chunks_per_row, int mode,
                                                              const int32_t *__restrict__ counts,
-                                                             const int32_t *__restrict__ row_map, int chunks_per_line,
-                                                             int64_t table_stride) {
-    const int64_t total = N * chunks_per_row;
-    const int64_t stride = int64_t(gridDim.x) * blockDim.x;
-    for (int64_t g = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; g < total; g += stride) {
-        const int64_t row = g / chunks_per_row;
-        const int c = int(g - row * chunks_per_row);
+                                                             const int32_t *__restrict__ row_map, int log2_chunks_per_line,
+                                                             int64_t table_stride, int log2_tpr) {
+    const int tpr = 1 << log2_tpr;
+    const int64_t rows_per_block = blockDim.x >> log2_tpr;
+    const int c0 = threadIdx.x & (tpr - 1);
+    for (int64_t row = int64_t(blockIdx.x) * rows_per_block + (threadIdx.x >> log2_tpr); row < N;
+         row += int64_t(gridDim.x) * rows_per_block) {
         const float f = scale_of(mode, counts[row]);
-        float v[W];
-        VecIO<float, W>::load(src + row * ld_src + int64_t(c) * W, v);
-#pragma unroll
-        for (int i = 0; i < W; ++i) v[i] *= f;
         const int64_t drow = row_map ? int64_t(row_map[row]) : row;
-        const int line = c / chunks_per_line, within = c - line * chunks_per_line;
-        VecIO<float, W>::store(dst + line * table_stride + drow * ld_dst + int64_t(within) * W, v);
+        const float *in = src + row * ld_src;
+        for (int c = c0; c < chunks_per_row; c += tpr) {
+            float v[W];
+            VecIO<float, W>::load(in + int64_t(c) * W, v);
+#pragma unroll
+            for (int i = 0; i < W; ++i) v[i] *= f;
+            const int line = c >> log2_chunks_per_line, within = c - (line << log2_chunks_per_line);
+            float *q = dst + line * table_stride + drow * ld_dst + int64_t(within) * W;
+            if constexpr (W == 4) {
+                VecIO<float, 4>::store(q, v);
+            } else {
+#pragma unroll
+                for (int i = 0; i < W; ++i) q[i] = v[i];
+            }
+        }
     }
+}
+
+// Threads per row of the pad kernels (a power of two <= 256 covering the row's chunks) and the grid.
+static inline void pad_launch_shape(int64_t N, int cpr, int *log2_tpr, unsigned *blocks) {
+    int l = 0;
+    while (l < 8 && (1 << l) < cpr) ++l;
+    *log2_tpr = l;
+    const int64_t rows_per_block = 256 >> l;
+    int64_t b = (N + rows_per_block - 1) / rows_per_block;
+    if (b > (int64_t(1) << 17)) b = int64_t(1) << 17;
+    *blocks = static_cast<unsigned>(b > 0 ? b : 1);
 }
 
 template <int W>
@@ -520,11 +613,12 @@ hipError_t launch_pad_scale(const void *src, int64_t ld_src, void *dst, int64_t 
                             const int32_t *counts, hipStream_t stream, const int32_t *row_map = nullptr,
                             int64_t table_stride = 0) {
     const int cpr = int(F / W);
-    int64_t blocks = (N * cpr + 255) / 256;
-    if (blocks > (int64_t(1) << 17)) blocks = int64_t(1) << 17;
-    pad_scale_rows_kernel<W><<<static_cast<unsigned>(blocks), 256, 0, stream>>>(
+    int log2_tpr;
+    unsigned blocks;
+    pad_launch_shape(N, cpr, &log2_tpr, &blocks);
+    pad_scale_rows_kernel<W><<<blocks, 256, 0, stream>>>(
         static_cast<const float *>(src), ld_src, static_cast<float *>(dst), ld_dst, N, cpr, mode, counts, row_map,
-        table_stride > 0 ? 32 / W : INT32_MAX, table_stride);
+        table_stride > 0 ? gnn_ilog2_ceil(32 / W) : 31, table_stride, log2_tpr);
     return hipGetLastError();
 }
 
@@ -533,12 +627,13 @@ hipError_t launch_pad(const void *src, int64_t ld_src_bytes, void *dst, int64_t 
                       int64_t row_bytes, hipStream_t stream, const int32_t *row_map = nullptr,
                       int64_t table_stride_bytes = 0) {
     const int cpr = int(row_bytes / sizeof(V));
-    int64_t blocks = (N * cpr + 255) / 256;
-    if (blocks > (int64_t(1) << 17)) blocks = int64_t(1) << 17;
-    pad_rows_kernel<V><<<static_cast<unsigned>(blocks), 256, 0, stream>>>(
+    int log2_tpr;
+    unsigned blocks;
+    pad_launch_shape(N, cpr, &log2_tpr, &blocks);
+    pad_rows_kernel<V><<<blocks, 256, 0, stream>>>(
         static_cast<const V *>(src), ld_src_bytes / int64_t(sizeof(V)), static_cast<V *>(dst),
         ld_dst_bytes / int64_t(sizeof(V)), N, cpr, row_map,
-        table_stride_bytes > 0 ? int(128 / sizeof(V)) : INT32_MAX, table_stride_bytes / int64_t(sizeof(V)));
+        table_stride_bytes > 0 ? gnn_ilog2_ceil(int64_t(128 / sizeof(V))) : 31, table_stride_bytes / int64_t(sizeof(V)), log2_tpr);
     return hipGetLastError();
 }
 
