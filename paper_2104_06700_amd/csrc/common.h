@@ -107,7 +107,7 @@ static inline gnn_layout gnn_choose_layout(const gnn_plan *plan, int64_t N, int6
     // sliced, one line each of 32768 rows.  Slicing is used when that wins at least 8 points of
     // the gathers (a power-law graph of a few million vertices: +20..30 points; a 111 M-vertex
     // graph with 2-line rows: ~+2 points, where the extra index reads and the loss of burst
-    // locality cost more than the hits bring: 103.8 -> 94.4 ms without slices).
+    // locality cost more than the hits bring: 76.2 ms sliced, 74.1 ms without slices).
     L.slices_wanted = !(flags & GNN_FLAG_NO_COLUMN_SLICES);
     if (L.slices_wanted && plan && plan->n_edges > 0 && max_slices == 0) {
         const double gain = gnn_plan_top_share(plan, 32768) - gnn_plan_top_share(plan, 32768 / (lines > 0 ? lines : 1));
