@@ -589,7 +589,7 @@ int run_ap_fwd(const void *indptr, const int32_t *indices, const float *fV, cons
     if (use_v && !wide && vec == 4 && plan && plan->n_edges > 0 && slice_ok) {
         const gnn_layout L = gnn_choose_layout(plan, N, d, 4, c.ldv, reinterpret_cast<uintptr_t>(fV) % 128 == 0, c.o.flags,
                                                c.o.max_slices);
-        if (L.padded_copy) {
+        if (L.padded_copy && d * 4 > 128) {  // rows of one line gain nothing from a copy in their own order
             rc = gnn_plan_padded(plan, N * L.ld_pad * 4);
             if (rc != GNN_OK) return rc;
             rc = gnn_pad_rows_f32(fV, c.ldv, static_cast<float *>(plan->padded), L.ld_pad, N, d, c.stream);

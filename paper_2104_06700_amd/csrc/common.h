@@ -128,15 +128,27 @@ static inline gnn_layout gnn_choose_layout(const gnn_plan *plan, int64_t N, int6
     const bool even_stride = lines_ok && (ldx / line_elems) % 2 == 0;
     const bool big = N * row_bytes >= (int64_t(32) << 20);
     const bool dense_enough = plan && plan->n_edges >= 16 * N;
-    const bool worth_it = row_bytes > 128 && big && L.slices_wanted &&  // more than one line: something to slice
-                          (!lines_ok || (even_stride && plan && plan->n_edges >= (row_bytes >= 512 ? 16 : 128) * N) ||
-                           (scaled_source && esz == 4 && dense_enough));
+    bool worth_it = row_bytes > 128 && big && L.slices_wanted &&  // more than one line: something to slice
+                    (!lines_ok || (even_stride && plan && plan->n_edges >= (row_bytes >= 512 ? 16 : 128) * N) ||
+                     (scaled_source && esz == 4 && dense_enough));
+    // Rows of at most one line are copied into rows of the next power of two bytes (16 ... 128), in
+    // rank order: no row straddles two lines, the most-gathered rows share lines (up to 8 per
+    // line), and 16-byte loads apply.  Worth it when rows would straddle in place (F = 24: 96-byte
+    // rows), when they are at most 64 bytes (rank order packs the hot rows), or when they carry a
+    // factor that the copy folds in.
+    int64_t narrow_bytes = 16;
+    while (narrow_bytes < row_bytes) narrow_bytes *= 2;
+    if (lines == 1) {
+        const int64_t stride_bytes = ldx * esz;
+        const bool in_place_ok = base_line_aligned && stride_bytes <= 128 && (stride_bytes & (stride_bytes - 1)) == 0;
+        worth_it = big && dense_enough && (!in_place_ok || row_bytes <= 64 || (scaled_source && esz == 4));
+    }
     L.padded_copy = plan && !(flags & GNN_FLAG_NO_PADDED_COPY) && (worth_it || (flags & GNN_FLAG_FORCE_PADDED_COPY));
-    L.ld_pad = (lines | 1) * line_elems;
+    L.ld_pad = lines == 1 ? narrow_bytes / esz : (lines | 1) * line_elems;
     L.tail_elems = 0;
     L.tail_ld = 0;
     const int64_t rest = F % line_elems;
-    if (allow_tail && L.padded_copy && L.slices_wanted && lines >= 2 && lines <= 8 && rest > 0 && rest * esz <= 64) {
+    if (allow_tail && L.padded_copy && L.slices_wanted && lines >= 2 && lines <= 256 && rest > 0 && rest * esz <= 64) {
         const int64_t group = 16 / esz;
         L.tail_elems = rest;
         L.tail_ld = (rest + group - 1) / group * group;
