@@ -126,22 +126,29 @@ static inline gnn_layout gnn_choose_layout(const gnn_plan *plan, int64_t N, int6
     // each: F=96 3.00 -> 2.48, F=224 6.85 -> 5.60).
     const bool lines_ok = (ldx % line_elems == 0) && base_line_aligned;
     const bool even_stride = lines_ok && (ldx / line_elems) % 2 == 0;
-    const bool big = N * row_bytes >= (int64_t(32) << 20);
-    const bool dense_enough = plan && plan->n_edges >= 16 * N;
-    bool worth_it = row_bytes > 128 && big && L.slices_wanted &&  // more than one line: something to slice
-                    (!lines_ok || (even_stride && plan && plan->n_edges >= (row_bytes >= 512 ? 16 : 128) * N) ||
-                     (scaled_source && esz == 4 && dense_enough));
+    const bool big = N * row_bytes >= (int64_t(32) << 20);  // well beyond the L2s: the layout decides the hit rate
+    const bool dense_enough = plan && plan->n_edges >= 16 * N;  // the copy (N rows) is small next to the gather (E rows)
+    const bool pays_at_any_size = dense_enough && N * row_bytes >= (int64_t(1) << 20);
+    const bool folds_factor = scaled_source && esz == 4;
+    // More than one line.  Rows that are not whole lines are copied whatever the size of the matrix
+    // (in place they are gathered with narrow loads and straddle lines: 233 K vertices, 490 edges
+    // each, F=33 fp32 3.16 -> 1.53 ms, F=65 bf16 8.16 -> 1.65), and so are rows that carry a factor;
+    // line-aligned rows with an even stride only when the matrix is large and slices are wanted.
+    bool worth_it = row_bytes > 128 &&
+                    ((!lines_ok && pays_at_any_size) || (folds_factor && pays_at_any_size) ||
+                     (big && L.slices_wanted && even_stride && plan && plan->n_edges >= (row_bytes >= 512 ? 16 : 128) * N));
     // Rows of at most one line are copied into rows of the next power of two bytes (16 ... 128), in
     // rank order: no row straddles two lines, the most-gathered rows share lines (up to 8 per
     // line), and 16-byte loads apply.  Worth it when rows would straddle in place (F = 24: 96-byte
-    // rows), when they are at most 64 bytes (rank order packs the hot rows), or when they carry a
-    // factor that the copy folds in.
+    // rows) or carry a factor that the copy folds in, and for large matrices when they are at most
+    // 64 bytes (rank order packs the hot rows).
     int64_t narrow_bytes = 16;
     while (narrow_bytes < row_bytes) narrow_bytes *= 2;
     if (lines == 1) {
         const int64_t stride_bytes = ldx * esz;
         const bool in_place_ok = base_line_aligned && stride_bytes <= 128 && (stride_bytes & (stride_bytes - 1)) == 0;
-        worth_it = big && dense_enough && (!in_place_ok || row_bytes <= 64 || (scaled_source && esz == 4));
+        worth_it = (!in_place_ok && pays_at_any_size) || (folds_factor && pays_at_any_size) ||
+                   (row_bytes <= 64 && big && dense_enough);
     }
     L.padded_copy = plan && !(flags & GNN_FLAG_NO_PADDED_COPY) && (worth_it || (flags & GNN_FLAG_FORCE_PADDED_COPY));
     L.ld_pad = lines == 1 ? narrow_bytes / esz : (lines | 1) * line_elems;
