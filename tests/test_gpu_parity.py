@@ -640,3 +640,33 @@ def test_slice_tables_do_not_change_results(dtype, f, max_slices):
             outs.append((Y, dX))
         for Y, dX in outs[1:]:
             assert torch.equal(Y, outs[0][0]) and torch.equal(dX, outs[0][1])
+
+
+@pytest.mark.parametrize("dtype,f", [(torch.float32, 4), (torch.float32, 24), (torch.float32, 31), (torch.float32, 33),
+                                     (torch.float32, 50), (torch.float32, 257), (torch.bfloat16, 33), (torch.bfloat16, 65),
+                                     (torch.bfloat16, 100)])
+def test_default_layout_rules_on_a_mid_size_graph(dtype, f):
+    """80,000 vertices x 40 edges: large enough for the default rules to copy rows that are not whole
+    lines, that straddle lines or that carry a factor (power-of-two rows, dense tail, slice tables,
+    rank order) without any forcing flag; every op, both directions, against the oracle, next to
+    the call that gathers in place (narrower loads and another row-group shape there, so the two
+    agree within the tolerance, not bit for bit)."""
+    el = synth.rmat_symmetric(80000, 3200000, (0.57, 0.19, 0.19, 0.05), 77)
+    bf16 = dtype == torch.bfloat16
+    indptr, indices, indptr_t, indices_t, _ = host_csr(el)
+    din, dout = np.diff(indptr), np.diff(indptr_t)
+    X = synth.normal_features(el.n, f, 12, dtype=dtype)
+    Xd = X.to(DEV)
+    dg = device_graph(el)
+    for op_name in ("mean", "gcn", "sage"):
+        op = OP_CODE[op_name]
+        Yo, S = oracle.aggregate_fwd(indptr, indices, X.float().numpy(), op=op, dout=dout, nthreads=8, want_scale=True)
+        dXo, St = oracle.aggregate_bwd(indptr_t, indices_t, X.float().numpy(), op=op, din=din, nthreads=8, want_scale=True)
+        for flags in (0, gnn.GNN_FLAG_NO_PADDED_COPY):
+            Y = torch.full((el.n, f), float("nan"), dtype=dtype, device=DEV)
+            dX = torch.full((el.n, f), float("nan"), dtype=dtype, device=DEV)
+            gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, None, Xd, Y, el.n, f, op, plan=dg.plan_fwd, flags=flags)
+            gnn.gnn_aggregate_bwd(dg.indptr_t, dg.indices_t, None, Xd, dX, el.n, f, op, plan=dg.plan_bwd, flags=flags)
+            torch.cuda.synchronize()
+            assert_close(Y, Yo, S, bf16, f"fwd {op_name} flags={flags}")
+            assert_close(dX, dXo, St, bf16, f"bwd {op_name} flags={flags}")
