@@ -162,7 +162,7 @@ __global__ void __launch_bounds__(kBlockThreads) ap_fwd_kernel(const ApArgs a) {
     constexpr bool USE_V = BIN != GNN_BIN_COPY_RHS;
     constexpr bool USE_E = BIN != GNN_BIN_COPY_LHS;
     constexpr bool WIDE = USE_E && EWIDE;
-    constexpr int U = (VEC == 4 && WIDE) ? 4 : 8;  // edges in flight per slot
+    constexpr int U = (VEC == 4 && (WIDE || RED != GNN_RED_SUM)) ? 4 : 8;  // edges in flight per slot (fewer where values and winners fill the registers)
     const int slab = a.log2_slices > 0 ? int(blockIdx.x) & ((1 << a.log2_slices) - 1) : int(blockIdx.y);
     const Group g = locate_group(a, int64_t(blockIdx.x) >> a.log2_slices);
     const int G = g.G, SR = g.SR;
