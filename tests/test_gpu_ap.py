@@ -350,3 +350,13 @@ def test_int64_row_pointers():
     _close(dfE, dE, SE, "edge gradient, int64 row pointers")
     (dV, SV), _ = oracle.ap_bwd(indptr, indices, fV, fE, dO, d, 2, 0)
     _close(dfV, dV, SV, "vertex gradient, int64 row pointers")
+
+
+@pytest.mark.parametrize("d", [33, 50])
+@pytest.mark.parametrize("use_eid", [False, True])
+def test_scalar_edge_gradient_of_odd_widths_on_a_mid_size_graph(d, use_eid):
+    """Large enough (80,000 vertices x 40 edges) for the scalar edge gradient of a width that is not a
+    multiple of four to take the zero-padded copies; every message, the forward and the vertex
+    gradient ride along on the 4-byte path."""
+    el = synth.rmat_symmetric(80000, 3200000, (0.57, 0.19, 0.19, 0.05), 78)
+    _check_all(el, None, d, 1, use_eid=use_eid, ties=False, seed=d, reduces={"sum": REDUCES["sum"]})
