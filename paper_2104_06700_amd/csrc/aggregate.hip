@@ -599,8 +599,16 @@ __global__ void __launch_bounds__(256) pad_scale_rows_kernel(const float *__rest
 
 // Threads per row of the pad kernels (a power of two <= 256 covering the row's chunks) and the grid.
 static inline void pad_launch_shape(int64_t N, int cpr, int *log2_tpr, unsigned *blocks) {
+    // the power of two (>= 8 threads: one 128-byte line of 16-byte chunks) that leaves the fewest idle
+    // slots in the last round over the row's chunks; the widest among equals
     int l = 0;
-    while (l < 8 && (1 << l) < cpr) ++l;
+    int64_t best_waste = INT64_MAX;
+    for (int cand = 8; cand >= 3; --cand) {
+        const int64_t tpr = int64_t(1) << cand;
+        const int64_t waste = (cpr + tpr - 1) / tpr * tpr - cpr;
+        if (waste < best_waste) { best_waste = waste; l = cand; }
+    }
+    if (cpr < 8) { l = 0; while ((1 << l) < cpr) ++l; }
     *log2_tpr = l;
     const int64_t rows_per_block = 256 >> l;
     int64_t b = (N + rows_per_block - 1) / rows_per_block;
