@@ -670,3 +670,37 @@ def test_default_layout_rules_on_a_mid_size_graph(dtype, f):
             torch.cuda.synchronize()
             assert_close(Y, Yo, S, bf16, f"fwd {op_name} flags={flags}")
             assert_close(dX, dXo, St, bf16, f"bwd {op_name} flags={flags}")
+
+
+def test_one_plan_serves_a_sequence_of_widths_dtypes_and_ops():
+    """The plan-owned copy, index copies and factor streams are re-laid out or reused from call to
+    call: a seeded random sequence of widths, storage types, ops, directions and layout switches
+    on ONE pair of plans (80,000 vertices x 40 edges, where the default rules copy) must match the
+    oracle call by call."""
+    el = synth.rmat_symmetric(80000, 3200000, (0.57, 0.19, 0.19, 0.05), 79)
+    indptr, indices, indptr_t, indices_t, _ = host_csr(el)
+    din, dout = np.diff(indptr), np.diff(indptr_t)
+    dg = device_graph(el)
+    rng = np.random.default_rng(5)
+    for it in range(16):
+        f = int(rng.choice([1, 3, 4, 8, 12, 16, 24, 31, 32, 33, 47, 50, 64, 65, 96, 100, 128, 129, 200, 256, 257, 300]))
+        dtype = torch.bfloat16 if rng.random() < 0.4 else torch.float32
+        op_name = str(rng.choice(["sum", "mean", "gcn", "sage"]))
+        fwd = rng.random() < 0.5
+        flags = int(rng.choice([0, 0, 0, gnn.GNN_FLAG_NO_PADDED_COPY, gnn.GNN_FLAG_NO_SLICE_TABLES, gnn.GNN_FLAG_NO_RANK_ORDER,
+                                gnn.GNN_FLAG_NO_COLUMN_SLICES]))
+        max_slices = int(rng.choice([0, 0, 0, 2, 8]))
+        X = synth.normal_features(el.n, f, 100 + it, dtype=dtype)
+        Xd = X.to(DEV)
+        out = torch.full((el.n, f), float("nan"), dtype=dtype, device=DEV)
+        op = OP_CODE[op_name]
+        what = f"call {it}: f={f} {dtype} {op_name} {'fwd' if fwd else 'bwd'} flags={flags} S<={max_slices}"
+        print(what, flush=True)
+        if fwd:
+            gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, None, Xd, out, el.n, f, op, plan=dg.plan_fwd, flags=flags, max_slices=max_slices)
+            ref, S = oracle.aggregate_fwd(indptr, indices, X.float().numpy(), op=op, dout=dout, nthreads=8, want_scale=True)
+        else:
+            gnn.gnn_aggregate_bwd(dg.indptr_t, dg.indices_t, None, Xd, out, el.n, f, op, plan=dg.plan_bwd, flags=flags, max_slices=max_slices)
+            ref, S = oracle.aggregate_bwd(indptr_t, indices_t, X.float().numpy(), op=op, din=din, nthreads=8, want_scale=True)
+        torch.cuda.synchronize()
+        assert_close(out, ref, S, dtype == torch.bfloat16, what)
