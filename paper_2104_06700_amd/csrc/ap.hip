@@ -30,6 +30,7 @@ struct ApArgs {
     const float *dO;   // edge gradient only: gradient of the output rows
     float *out;        // forward: f_O; edge gradient: dfE
     int32_t *arg_out;  // forward, max / min: winning positions (or nullptr)
+    int64_t ld_arg;    // row stride of arg_out (d, or the padded width of a staged call)
     const int32_t *arg_in;  // edge gradient, max / min
     int64_t ldv, lde, ldo;
     int32_t d;
@@ -275,7 +276,7 @@ __global__ void __launch_bounds__(kBlockThreads) ap_fwd_kernel(const ApArgs a) {
 #pragma unroll
         for (int i = 0; i < VEC; ++i)
             if (win[i] < 0) acc[i] = 0.0f;  // row without edges
-        if (a.arg_out) store_i<VEC>(a.arg_out + g.row * int64_t(a.d) + col, win);
+        if (a.arg_out) store_i<VEC>(a.arg_out + g.row * a.ld_arg + col, win);
     }
     store_f<VEC>(a.out + g.row * a.ldo + col, acc);
 }
@@ -286,7 +287,7 @@ __global__ void __launch_bounds__(256) ap_hub_finalize_kernel(const int32_t *__r
                                                               const int64_t *__restrict__ piece_offsets,
                                                               const float *__restrict__ pval, const int32_t *__restrict__ parg,
                                                               int64_t ldp, float *__restrict__ out, int64_t ldo,
-                                                              int32_t *__restrict__ arg_out, int d) {
+                                                              int32_t *__restrict__ arg_out, int64_t ld_arg, int d) {
     const int64_t i = blockIdx.x;
     if (i >= n_hub) return;
     const int64_t row = hub_rows[i];
@@ -304,7 +305,7 @@ __global__ void __launch_bounds__(256) ap_hub_finalize_kernel(const int32_t *__r
             }
         }
         out[row * ldo + col] = best;
-        if (RED != GNN_RED_SUM && arg_out) arg_out[row * int64_t(d) + col] = won;
+        if (RED != GNN_RED_SUM && arg_out) arg_out[row * ld_arg + col] = won;
     }
 }
 
@@ -501,6 +502,9 @@ void launch_fwd(int bin, int red, int vec, bool ewide, dim3 grid, hipStream_t st
     }
 }
 
+__global__ void unpad_rows_kernel(const float *__restrict__ val, const int32_t *__restrict__ arg, int64_t ld_src,
+                                  float *__restrict__ out, int64_t ldo, int32_t *__restrict__ arg_out, int64_t N, int d);
+
 int run_ap_fwd(const void *indptr, const int32_t *indices, const float *fV, const float *fE, float *fO, int32_t *arg_e,
                int64_t N, int64_t d, int binop, int reduce, const gnn_ap_opts *opts_in) {
     Common c;
@@ -555,6 +559,18 @@ int run_ap_fwd(const void *indptr, const int32_t *indices, const float *fV, cons
     if (use_v && (c.ldv % 4 || !aligned16(fV))) vec = 1;
     if (wide && (c.lde % 4 || !aligned16(fE))) vec = 1;
     if (arg_e && !aligned16(arg_e)) vec = 1;
+    // Staged call: a width or strides that forbid 16-byte accesses on a gather-bound call of a large
+    // graph.  f_V is copied into padded rows anyway (below); the results are computed in plan-owned
+    // rows of roundup(d, 4) columns as well and copied to the caller's arrays at the end, so the
+    // kernel runs its 16-byte instantiation (copylhs / max d = 33: 4.3 -> 3.7 ms, d = 101: 10.1 -> 7.9).
+    const int64_t d4 = (d + 3) / 4 * 4;
+    bool staged = false;
+    if (vec == 1 && use_v && !wide && plan && plan->n_edges >= 16 * N && N * d * 4 >= (int64_t(1) << 20) && d * 4 > 128) {
+        const gnn_layout Ls = gnn_choose_layout(plan, N, d, 4, c.ldv, reinterpret_cast<uintptr_t>(fV) % 128 == 0, c.o.flags,
+                                                c.o.max_slices);
+        staged = Ls.padded_copy;
+    }
+    if (staged) vec = 4;
 
     ApArgs a{};
     a.indptr = indptr;
@@ -564,6 +580,7 @@ int run_ap_fwd(const void *indptr, const int32_t *indices, const float *fV, cons
     a.fE = fE;
     a.out = fO;
     a.arg_out = arg_e;
+    a.ld_arg = d;
     a.ldv = c.ldv;
     a.lde = c.lde;
     a.ldo = c.ldo;
@@ -586,16 +603,28 @@ int run_ap_fwd(const void *indptr, const int32_t *indices, const float *fV, cons
     // repeated weight stream and winner bookkeeping cost more than the hits bring: 8.4 -> 9.0 ms).
     bool sliced = false;
     const bool slice_ok = !use_e || (!wide && !c.o.edge_ids && reduce == GNN_RED_SUM) || c.o.max_slices > 1;
-    if (use_v && !wide && vec == 4 && plan && plan->n_edges > 0 && slice_ok) {
-        const gnn_layout L = gnn_choose_layout(plan, N, d, 4, c.ldv, reinterpret_cast<uintptr_t>(fV) % 128 == 0, c.o.flags,
-                                               c.o.max_slices);
+    if (use_v && !wide && vec == 4 && plan && plan->n_edges > 0 && (slice_ok || staged)) {
+        gnn_layout L = gnn_choose_layout(plan, N, d, 4, c.ldv, reinterpret_cast<uintptr_t>(fV) % 128 == 0, c.o.flags,
+                                         c.o.max_slices);
+        if (!slice_ok) L.slices_wanted = false;  // staged only: the copy, not the slices
         if (L.padded_copy && d * 4 > 128) {  // rows of one line gain nothing from a copy in their own order
-            rc = gnn_plan_padded(plan, N * L.ld_pad * 4);
+            const int64_t copy_bytes = (N * L.ld_pad * 4 + 255) / 256 * 256;
+            const int64_t tmp_bytes = (N * d4 * 4 + 255) / 256 * 256;
+            rc = gnn_plan_padded(plan, copy_bytes + (staged ? tmp_bytes * (arg_e ? 2 : 1) : 0));
             if (rc != GNN_OK) return rc;
             rc = gnn_pad_rows_f32(fV, c.ldv, static_cast<float *>(plan->padded), L.ld_pad, N, d, c.stream);
             if (rc != GNN_OK) return rc;
             a.fV = static_cast<const float *>(plan->padded);
             a.ldv = L.ld_pad;
+            if (staged) {
+                char *base = static_cast<char *>(plan->padded) + copy_bytes;
+                a.out = reinterpret_cast<float *>(base);
+                a.ldo = d4;
+                if (arg_e) {
+                    a.arg_out = reinterpret_cast<int32_t *>(base + tmp_bytes);
+                    a.ld_arg = d4;
+                }
+            }
         }
         const int64_t line = 32;  // floats per 128-byte line
         const bool lines_ok = a.ldv % line == 0 && reinterpret_cast<uintptr_t>(a.fV) % 128 == 0;
@@ -656,11 +685,17 @@ int run_ap_fwd(const void *indptr, const int32_t *indices, const float *fV, cons
         dim3 grid(static_cast<unsigned>(plan->n_hub_rows));
         const int32_t *hub_rows = plan->row_perm + hub_begin;
         if (reduce == GNN_RED_SUM)
-            ap_hub_finalize_kernel<GNN_RED_SUM><<<grid, 256, 0, c.stream>>>(hub_rows, plan->n_hub_rows, plan->hub_chunk_offsets, a.pval, a.parg, a.ldp, fO, c.ldo, arg_e, int(d));
+            ap_hub_finalize_kernel<GNN_RED_SUM><<<grid, 256, 0, c.stream>>>(hub_rows, plan->n_hub_rows, plan->hub_chunk_offsets, a.pval, a.parg, a.ldp, a.out, a.ldo, a.arg_out, a.ld_arg, int(d));
         else if (reduce == GNN_RED_MAX)
-            ap_hub_finalize_kernel<GNN_RED_MAX><<<grid, 256, 0, c.stream>>>(hub_rows, plan->n_hub_rows, plan->hub_chunk_offsets, a.pval, a.parg, a.ldp, fO, c.ldo, arg_e, int(d));
+            ap_hub_finalize_kernel<GNN_RED_MAX><<<grid, 256, 0, c.stream>>>(hub_rows, plan->n_hub_rows, plan->hub_chunk_offsets, a.pval, a.parg, a.ldp, a.out, a.ldo, a.arg_out, a.ld_arg, int(d));
         else
-            ap_hub_finalize_kernel<GNN_RED_MIN><<<grid, 256, 0, c.stream>>>(hub_rows, plan->n_hub_rows, plan->hub_chunk_offsets, a.pval, a.parg, a.ldp, fO, c.ldo, arg_e, int(d));
+            ap_hub_finalize_kernel<GNN_RED_MIN><<<grid, 256, 0, c.stream>>>(hub_rows, plan->n_hub_rows, plan->hub_chunk_offsets, a.pval, a.parg, a.ldp, a.out, a.ldo, a.arg_out, a.ld_arg, int(d));
+        if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
+    }
+    if (a.out != fO) {  // staged call: hand the results over
+        int64_t blocks = (N * d + 255) / 256;
+        if (blocks > (int64_t(1) << 17)) blocks = int64_t(1) << 17;
+        unpad_rows_kernel<<<static_cast<unsigned>(blocks), 256, 0, c.stream>>>(a.out, a.arg_out, a.ldo, fO, c.ldo, arg_e, N, int(d));
         if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
     }
     return GNN_OK;
@@ -679,6 +714,20 @@ void launch_edge_bin(int vec, bool ewide, bool masked, dim3 grid, hipStream_t st
     } else {
         if (ewide) launch_edge_masked<BIN, 1, true>(masked, grid, stream, a);
         else launch_edge_masked<BIN, 1, false>(masked, grid, stream, a);
+    }
+}
+
+// Results of a staged call go from the padded rows they were computed in to the caller's arrays.
+__global__ void __launch_bounds__(256) unpad_rows_kernel(const float *__restrict__ val, const int32_t *__restrict__ arg,
+                                                         int64_t ld_src, float *__restrict__ out, int64_t ldo,
+                                                         int32_t *__restrict__ arg_out, int64_t N, int d) {
+    const int64_t total = N * d;
+    const int64_t stride = int64_t(gridDim.x) * blockDim.x;
+    for (int64_t t = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; t < total; t += stride) {
+        const int64_t r = t / d;
+        const int c = int(t - r * d);
+        out[r * ldo + c] = val[r * ld_src + c];
+        if (arg_out) arg_out[r * int64_t(d) + c] = arg[r * ld_src + c];
     }
 }
 

@@ -355,8 +355,9 @@ def test_int64_row_pointers():
 @pytest.mark.parametrize("d", [33, 50])
 @pytest.mark.parametrize("use_eid", [False, True])
 def test_scalar_edge_gradient_of_odd_widths_on_a_mid_size_graph(d, use_eid):
-    """Large enough (80,000 vertices x 40 edges) for the scalar edge gradient of a width that is not a
-    multiple of four to take the zero-padded copies; every message, the forward and the vertex
-    gradient ride along on the 4-byte path."""
+    """Large enough (80,000 vertices x 40 edges) for a width that is not a multiple of four to take
+    the staged routes: the forward call computes in plan-owned padded rows and hands the results
+    (values and winners) over at the end, the scalar edge gradient reads zero-padded copies; every
+    message, sum and max, with and without an edge-id map."""
     el = synth.rmat_symmetric(80000, 3200000, (0.57, 0.19, 0.19, 0.05), 78)
-    _check_all(el, None, d, 1, use_eid=use_eid, ties=False, seed=d, reduces={"sum": REDUCES["sum"]})
+    _check_all(el, None, d, 1, use_eid=use_eid, ties=False, seed=d, reduces={"sum": REDUCES["sum"], "max": REDUCES["max"]})
