@@ -187,7 +187,8 @@ typedef struct gnn_ap_opts {
  * empty row -- and must be NULL for sum.  NaN inputs give an unspecified winner.  max / min need
  * E <= INT32_MAX.  16-byte loads are used when d, the strides and the base addresses allow,
  * scalar ones otherwise; a gather-bound call on a large graph with a plan is then staged through
- * plan-owned padded rows (1.1-1.2x the time of the next multiple of 4).  Hub rows use plan-owned scratch (grown on first use: allocation).
+ * plan-owned padded rows (1.1-1.2x the time of the next multiple of 4).  Hub rows use plan-owned
+ * scratch (grown on first use: allocation).
  * copylhs / sum and mul / sum with a scalar f_E are what gnn_aggregate_fwd computes with GNN_SUM
  * (plain or weighted) and run on that path, with its layouts; a scalar f_E that is strided or
  * addressed through edge_ids is first gathered into a plan-owned array of E floats (allocated on
