@@ -677,6 +677,8 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
     if (N < 0 || F < 0) return GNN_ERR_INVALID_ARG;
     if (op != GNN_SUM && op != GNN_MEAN && op != GNN_GCN_SYM && op != GNN_SAGE_GCN) return GNN_ERR_INVALID_ARG;
     if (o.dtype != GNN_F32 && o.dtype != GNN_BF16) return GNN_ERR_INVALID_ARG;
+    if (o.max_slices != 0 && o.max_slices != 1 && o.max_slices != 2 && o.max_slices != 4 && o.max_slices != 8)
+        return GNN_ERR_INVALID_ARG;
     if (N == 0 || F == 0) return GNN_OK;
     if (!indptr || !gathered || !out) return GNN_ERR_INVALID_ARG;
     if (N > INT32_MAX || F > INT32_MAX) return GNN_ERR_INVALID_ARG;
@@ -825,7 +827,9 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
     // so that every launch keeps all 8 XCDs equally busy.  The price is one read of the index
     // stream per slice.
     struct Segment { int64_t f0, fw; int log2_s; int64_t slice_cols; int tail_slice; };
-    Segment segs[64];
+    // Sliced: at most 256 one-unit slices, two or more per launch, plus the tail; unsliced: at most 64 slabs.
+    constexpr int kMaxSegs = 130;
+    Segment segs[kMaxSegs];
     int n_segs = 0;
     {
         const bool lines_ok = (ldg % line_elems == 0) && reinterpret_cast<uintptr_t>(gathered) % 128 == 0;
@@ -849,6 +853,7 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
             while (u0 < main_units) {
                 int ls = 3;
                 while (ls > 0 && ((int64_t(1) << ls) > main_units - u0 || (int64_t(1) << ls) > s_max)) --ls;
+                if (n_segs >= kMaxSegs - 1) return GNN_ERR_UNSUPPORTED;  // rows this wide take the unsliced route (max_slices = 1)
                 Segment &g = segs[n_segs++];
                 g.f0 = u0 * unit_lines * line_elems;
                 g.slice_cols = unit_lines * line_elems;

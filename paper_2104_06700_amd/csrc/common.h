@@ -51,6 +51,8 @@ struct gnn_plan {
     int32_t *cold_indices = nullptr;
     int32_t cold_decided = 0;    // 0: not yet; 1: decided (cold_indices is null when it does not pay)
     int32_t cold_threshold = 0;  // sources gathered fewer times than this are cold
+    int32_t cold_forced = 0;     // the copy was built under GNN_FLAG_FORCE_COLD_HINTS (a call without it rebuilds)
+    int32_t rank_forced = 0;     // likewise for rank_indices
     // Rank layout of the padded copy: rank[v] = position of v by descending column count; the copy
     // stores row v at row rank[v] and the kernels gather through rank_indices[e] =
     // rank[indices[e]] (bit 31: cold).  Built on first use.

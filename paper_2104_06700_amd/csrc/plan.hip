@@ -198,7 +198,11 @@ int gnn_plan_edge_scale(gnn_plan *plan, const int32_t *indices, int mode, hipStr
         (void)hipGetLastError();
         if (hipMalloc(&arr, sizeof(float) * plan->n_edges) != hipSuccess) { arr = nullptr; return GNN_ERR_ALLOC; }
         edge_scale_kernel<<<grid_for(plan->n_edges, 256, 1 << 16), 256, 0, stream>>>(indices, plan->n_edges, plan->col_counts, mode, arr);
-        if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
+        if (hipGetLastError() != hipSuccess) {  // an unfilled array must not serve a later call
+            (void)hipFree(arr);
+            arr = nullptr;
+            return GNN_ERR_LAUNCH;
+        }
     }
     *out = arr;
     return GNN_OK;
@@ -258,6 +262,11 @@ static int64_t bucket_lower_bound(int b) {
 int gnn_plan_cold_indices(gnn_plan *plan, const int32_t *indices, bool force, hipStream_t stream, const int32_t **out) {
     *out = nullptr;
     if (!plan || plan->n_edges <= 0) return GNN_OK;
+    if (plan->cold_decided && plan->cold_forced != (force ? 1 : 0)) {  // built under the other rule: build again
+        (void)hipFree(plan->cold_indices);
+        plan->cold_indices = nullptr;
+        plan->cold_decided = 0;
+    }
     if (!plan->cold_decided) {
         const int64_t warm = force ? (plan->n_rows + 3) / 4 : int64_t(5) * 32768;
         bool enable = force;
@@ -282,9 +291,14 @@ int gnn_plan_cold_indices(gnn_plan *plan, const int32_t *indices, bool force, hi
             plan->cold_threshold = int32_t(thr > INT32_MAX ? INT32_MAX : thr);
             flag_cold_kernel<<<grid_for(plan->n_edges, 256, 1 << 16), 256, 0, stream>>>(indices, plan->n_edges, plan->col_counts,
                                                                                        plan->cold_threshold, plan->cold_indices);
-            if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
+            if (hipGetLastError() != hipSuccess) {
+                (void)hipFree(plan->cold_indices);
+                plan->cold_indices = nullptr;
+                return GNN_ERR_LAUNCH;
+            }
         }
         plan->cold_decided = 1;
+        plan->cold_forced = force ? 1 : 0;
     }
     *out = plan->cold_indices;
     return GNN_OK;
@@ -355,6 +369,14 @@ int gnn_plan_rank_indices(gnn_plan *plan, const void *indptr, const int32_t *ind
                           gnn_rank_layout *out) {
     *out = gnn_rank_layout{};
     if (!plan || plan->n_edges <= 0 || plan->n_rows <= 0) return GNN_OK;
+    if (plan->rank_indices && plan->rank_forced != (force_cold ? 1 : 0)) {  // flagged under the other rule: build again
+        (void)hipFree(plan->rank_indices);
+        (void)hipFree(plan->p_indptr);
+        (void)hipFree(plan->p_chunks);
+        plan->rank_indices = nullptr;
+        plan->p_indptr = nullptr;
+        plan->p_chunks = nullptr;
+    }
     if (!plan->rank_indices) {
         if (!indices || !indptr) return GNN_ERR_INVALID_ARG;
         const int64_t N = plan->n_rows;
@@ -386,6 +408,7 @@ int gnn_plan_rank_indices(gnn_plan *plan, const void *indptr, const int32_t *ind
         plan->p_indptr = p_indptr;
         plan->p_chunks = p_chunks;
         plan->rank_indices = idx;
+        plan->rank_forced = force_cold ? 1 : 0;
     }
     out->rank = plan->rank;
     out->indices = plan->rank_indices;

@@ -59,6 +59,10 @@ def test_argument_checks_that_need_no_device():
     o.ldx = 2
     assert lib.gnn_aggregate_fwd(one, one, None, one, one, 4, 4, 0, ctypes.byref(o)) == gnn.GNN_ERR_INVALID_ARG
     o.ldx = 0
+    for bad_slices in (3, 5, 16, -1):  # the number of XCD column slices is 1, 2, 4 or 8 (0 = automatic)
+        o.max_slices = bad_slices
+        assert lib.gnn_aggregate_fwd(one, one, None, one, one, 4, 4, 0, ctypes.byref(o)) == gnn.GNN_ERR_INVALID_ARG
+    o.max_slices = 0
     assert lib.gnn_aggregate_bwd(one, one, None, one, one, 4, 4, 1, ctypes.byref(o)) == gnn.GNN_ERR_UNSUPPORTED
     assert lib.gnn_aggregate_bwd(one, one, None, one, one, 4, 4, 3, ctypes.byref(o)) == gnn.GNN_ERR_UNSUPPORTED
     assert lib.gnn_plan_create(None, None, 5, 0, None, None, ctypes.byref(ctypes.c_void_p())) == gnn.GNN_ERR_INVALID_ARG

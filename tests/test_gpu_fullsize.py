@@ -106,3 +106,23 @@ def test_fullsize_dense_wide_f602():
 def test_fullsize_weighted_narrow_f8():
     """132,534 vertices / 79,000,000 edges, F=8, explicit fp32 weights."""
     _fullsize("rmat_weighted_narrow", 8, "sum", weighted=True)
+
+
+def test_fullsize_dense_wide_f256():
+    """The hidden width of the dense-degree workload (232,965 vertices, F=256, MEAN)."""
+    _fullsize("rmat_dense_wide", 256, "mean")
+
+
+def test_fullsize_weighted_narrow_f64():
+    """132,534 vertices / 79,000,000 edges, F=64, explicit fp32 weights."""
+    _fullsize("rmat_weighted_narrow", 64, "sum", weighted=True)
+
+
+def test_fullsize_weighted_narrow_f64_gcn_without_weights():
+    """Symmetric normalisation derived from the degrees (no weight array), full size: the
+    coefficients come from the plan's column counts, folded into the copy of the gathered rows."""
+    _fullsize("rmat_weighted_narrow", 64, "gcn")
+
+
+def test_fullsize_sparse_stack_f100_gcn_without_weights():
+    _fullsize("rmat_sparse_stack", 100, "gcn")

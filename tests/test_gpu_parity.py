@@ -173,6 +173,24 @@ def test_column_slices_over_xcds_on_and_off(f, dtype, hubs):
         outs.append(Y)
 
 
+@pytest.mark.parametrize("f,max_slices", [(4160, 2), (8160, 4), (8192, 2), (4100, 2)])
+def test_very_wide_rows_take_many_sliced_launches(f, max_slices):
+    """Rows of more than 64 lines with few slices per launch: 65 ... 128 launches plus a dense tail
+    (the launch list once had room for 64)."""
+    el = synth.make_graph("rmat_sparse_stack", scale=0.0004, seed=72)
+    dg = device_graph(el, plan_params=gnn.make_plan_params([1, 4, 32], 48))
+    indptr, indices, *_ = host_csr(el)
+    X = synth.normal_features(el.n, f, 10)
+    Yo, S = oracle.aggregate_fwd(indptr, indices, X.numpy(), op=oracle.OP_MEAN, nthreads=8, want_scale=True)
+    Xd = X.to(DEV)
+    for flags in (0, gnn.GNN_FLAG_FORCE_PADDED_COPY):
+        Y = torch.full_like(Xd, float("nan"))
+        gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, None, Xd, Y, el.n, f, gnn.GNN_MEAN, plan=dg.plan_fwd, flags=flags,
+                              max_slices=max_slices)
+        torch.cuda.synchronize()
+        assert_close(Y, Yo, S, False, f"wide rows F={f} max_slices={max_slices} flags={flags}")
+
+
 @pytest.mark.parametrize("f,dtype", [(100, torch.float32), (602, torch.float32), (30, torch.float32), (7, torch.float32),
                                      (129, torch.float32), (2052, torch.float32), (100, torch.bfloat16),
                                      (602, torch.bfloat16), (9, torch.bfloat16), (1000, torch.bfloat16)])

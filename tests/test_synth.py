@@ -1,5 +1,6 @@
 """The seeded input generators: determinism, shape, canonical order."""
 import numpy as np
+import pytest
 import torch
 
 import synth
@@ -55,3 +56,24 @@ def test_gcn_edge_weights():
     deg = np.bincount(el.dst.numpy(), minlength=el.n).astype(np.float64)
     ref = 1.0 / np.sqrt(deg[el.src.numpy()] * deg[el.dst.numpy()])
     assert np.allclose(w.numpy(), ref.astype(np.float32))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name,scale", [("er_tiny", 1.0), ("rmat_dense_wide", 0.01), ("rmat_sparse_stack", 0.004),
+                                        ("rmat_weighted_narrow", 0.02), ("rmat_capacity", 0.0002)])
+def test_generators_give_the_same_graph_on_cpu_and_gpu(name, scale):
+    """Every random bit comes from integer counters, so the device must not matter: the oracle side
+    (CPU tensors) and the HIP side (GPU tensors) of a parity test see the same edges."""
+    a = synth.make_graph(name, scale=scale)
+    b = synth.make_graph(name, scale=scale, device=torch.device("cuda:0"))
+    assert (a.n, a.e) == (b.n, b.e)
+    assert torch.equal(a.src, b.src.cpu()) and torch.equal(a.dst, b.dst.cpu())
+    # Features pass through log / cos, whose last bit may differ between the two math libraries:
+    # the parity tests therefore generate a matrix once and hand the same bits to both sides.
+    x = synth.make_features(name, 257, 33, 9)
+    y = synth.make_features(name, 257, 33, 9, device=torch.device("cuda:0"))
+    assert torch.allclose(x.float(), y.cpu().float(), rtol=1e-2 if x.dtype == torch.bfloat16 else 1e-5, atol=1e-6)
+    if synth.WORKLOADS[name].get("weighted"):
+        wa = synth.gcn_sym_edge_weights(a.dst, a.src, a.n)
+        wb = synth.gcn_sym_edge_weights(b.dst, b.src, b.n)
+        assert torch.equal(wa, wb.cpu())
