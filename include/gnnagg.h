@@ -32,7 +32,9 @@ typedef enum gnn_status {
     GNN_ERR_UNSUPPORTED = 2, /* valid request this build cannot serve (e.g. an op that needs a plan, without one) */
     GNN_ERR_ALLOC = 3,       /* device or host allocation failed (plan creation / workspace growth only) */
     GNN_ERR_LAUNCH = 4,      /* the HIP runtime reported an error at launch or copy */
-    GNN_ERR_INVALID_GRAPH = 5 /* gnn_validate_csr found a violated precondition */
+    GNN_ERR_INVALID_GRAPH = 5, /* gnn_validate_csr found a violated precondition */
+    GNN_ERR_SCRATCH_CAPACITY = 6 /* gnn_aggregate_fwd_noalloc: the hub partial sums of this plan and width
+                                    do not fit the library's fixed scratch array */
 } gnn_status;
 
 /* Reduce variants.  All are sum-reductions over the in-neighbours (Table 1:
@@ -133,6 +135,24 @@ typedef struct gnn_plan_params {
  * GNN_OK and does nothing.  opts == NULL means all defaults.
  * MEAN needs no plan; GCN_SYM without edge_w needs a plan (it holds dout). */
 GNN_API int gnn_aggregate_fwd(const void *indptr, const int32_t *indices, const float *edge_w,
+                      const void *X, void *Y, int64_t N, int64_t F, int op, const gnn_opts *opts);
+
+/* gnn_aggregate_fwd for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same result as
+ * gnn_aggregate_fwd called with GNN_FLAG_NO_PADDED_COPY | GNN_FLAG_NO_COLD_HINTS, but the call
+ * never allocates, frees or grows anything, on the device or in a plan:
+ *   - the partial sums of the hub rows go into a fixed array of GNN_NOALLOC_SCRATCH_BYTES that is
+ *     part of the library's device code (every GPU the library runs on holds one until the process
+ *     ends); a plan and width that need more (gnn_plan_workspace_bytes(plan, F)) are rejected with
+ *     GNN_ERR_SCRATCH_CAPACITY before anything is enqueued; opts->workspace is ignored;
+ *   - rows are gathered from X where they lie (no plan-owned copy of X or of the index array);
+ *   - GNN_GCN_SYM without edge_w reads the plan's per-edge factor stream, which must exist already
+ *     (gnn_plan_prepare with GNN_GCN_SYM), else GNN_ERR_UNSUPPORTED.
+ * All calls on one GPU share that GPU's array, whatever their stream or plan: calls that overlap
+ * in time on one GPU race on it and must be ordered by the caller.  The array keeps the last
+ * call's contents; every element that is read has been written by the same call first. */
+#define GNN_NOALLOC_SCRATCH_BYTES (32 << 20)
+GNN_API int gnn_aggregate_fwd_noalloc(const void *indptr, const int32_t *indices, const float *edge_w,
                       const void *X, void *Y, int64_t N, int64_t F, int op, const gnn_opts *opts);
 
 /* Backward aggregation: the adjoint of the forward map over the transposed

@@ -16,6 +16,8 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libgnnagg.so")
 
 GNN_OK, GNN_ERR_INVALID_ARG, GNN_ERR_UNSUPPORTED, GNN_ERR_ALLOC, GNN_ERR_LAUNCH, GNN_ERR_INVALID_GRAPH = range(6)
+GNN_ERR_SCRATCH_CAPACITY = 6
+GNN_NOALLOC_SCRATCH_BYTES = 32 << 20
 GNN_SUM, GNN_MEAN, GNN_GCN_SYM, GNN_SAGE_GCN = 0, 1, 2, 3
 GNN_F32, GNN_BF16 = 0, 1
 GNN_MAX_THRESHOLDS = 15
@@ -31,7 +33,7 @@ GNN_BIN_ADD, GNN_BIN_SUB, GNN_BIN_MUL, GNN_BIN_DIV, GNN_BIN_COPY_LHS, GNN_BIN_CO
 GNN_RED_SUM, GNN_RED_MAX, GNN_RED_MIN = range(3)
 
 EXPORTED_SYMBOLS = (
-    "gnn_aggregate_fwd", "gnn_aggregate_bwd", "gnn_csr_from_sorted_coo", "gnn_transpose_csr",
+    "gnn_aggregate_fwd", "gnn_aggregate_bwd", "gnn_aggregate_fwd_noalloc", "gnn_csr_from_sorted_coo", "gnn_transpose_csr",
     "gnn_validate_csr", "gnn_plan_default_params", "gnn_plan_create", "gnn_plan_destroy",
     "gnn_plan_sizes", "gnn_plan_export", "gnn_plan_gather_share", "gnn_plan_workspace_bytes", "gnn_plan_reserve",
     "gnn_plan_prepare",
@@ -97,6 +99,7 @@ def load_library() -> ctypes.CDLL:
         vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
         lib.gnn_aggregate_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, ctypes.POINTER(GnnOpts)]
         lib.gnn_aggregate_bwd.argtypes = lib.gnn_aggregate_fwd.argtypes
+        lib.gnn_aggregate_fwd_noalloc.argtypes = lib.gnn_aggregate_fwd.argtypes
         lib.gnn_csr_from_sorted_coo.argtypes = [vp, i64, i64, vp, i32, vp]
         lib.gnn_transpose_csr.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, vp, vp]
         lib.gnn_validate_csr.argtypes = [vp, vp, i64, i64, i32, vp]
@@ -282,6 +285,26 @@ def gnn_aggregate_fwd(indptr, indices, edge_w, X, Y, N, F, op, plan: Optional[Pl
     """Y[v] = scale_v * sum_e c_e X[indices[e]] over the CSR by destination (see include/gnnagg.h)."""
     _aggregate("gnn_aggregate_fwd", indptr, indices, edge_w, X, Y, N, F, op, plan, stream, workspace, ldx, ldy, flags,
                max_slices)
+
+
+def gnn_aggregate_fwd_noalloc(indptr, indices, edge_w, X, Y, N, F, op, plan: Optional[Plan] = None, stream=None,
+                              ldx=None, ldy=None, flags=0, max_slices=0) -> None:
+    """gnn_aggregate_fwd that allocates nothing: hub partial sums in the library's fixed scratch array."""
+    lib = load_library()
+    if X.dtype != Y.dtype:
+        raise TypeError("input and output features must have the same dtype")
+    o = GnnOpts()
+    o.dtype = _dtype_code(X)
+    o.indptr_is_64 = _is64(indptr)
+    o.ldx = int(ldx if ldx is not None else (X.stride(0) if X.dim() == 2 and X.shape[0] > 1 else 0))
+    o.ldy = int(ldy if ldy is not None else (Y.stride(0) if Y.dim() == 2 and Y.shape[0] > 1 else 0))
+    o.stream = _stream(stream)
+    o.plan = plan.handle if plan is not None else None
+    o.flags = int(flags)
+    o.max_slices = int(max_slices)
+    # no retry through torch's allocator here: this call must not allocate, so ALLOC cannot come back
+    _check("gnn_aggregate_fwd_noalloc", lib.gnn_aggregate_fwd_noalloc(
+        _ptr(indptr), _ptr(indices), _ptr(edge_w), _ptr(X), _ptr(Y), int(N), int(F), int(op), ctypes.byref(o)))
 
 
 def gnn_aggregate_bwd(indptr_t, indices_t, edge_w_t, dY, dX, N, F, op, plan: Optional[Plan] = None, stream=None,

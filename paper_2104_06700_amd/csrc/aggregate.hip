@@ -26,9 +26,35 @@
 //     matrix is first copied into a plan-owned layout made for that: one table
 //     per slice, rows by descending gather count, a dense table for a short last
 //     line (run_aggregate below).
+#include <mutex>
+
 #include "common.h"
 
+// Hub partial sums of gnn_aggregate_fwd_noalloc, the entry point that allocates nothing: one array
+// per GPU, part of the loaded code object, held until the process ends.  In host code this name
+// only stands for the symbol; the device address is looked up once per device and kept
+// (static_scratch_of_current_device), and only that address is ever handed to a kernel.
+static __device__ __align__(256) float scratch[GNN_NOALLOC_SCRATCH_BYTES / sizeof(float)];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float *g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// Device address of `scratch` on the current device (looked up on the first call there).
+int static_scratch_of_current_device(float **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return GNN_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return GNN_ERR_LAUNCH;
+        g_scratch_ptr[dev] = static_cast<float *>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return GNN_OK;
+}
 
 constexpr int kBlockThreads = 256;
 constexpr int kWavesPerBlock = kBlockThreads / 64;
@@ -669,11 +695,20 @@ constexpr int kMaxPass = 8;
 
 // One direction of the aggregation.  `gathered` is X (forward) or dY (backward).  bias / relu:
 // the epilogue of a fused layer (out = act(aggregate + bias)), or nullptr / 0.
+// no_alloc: the hub partial sums go into the library's fixed device array and the call allocates
+// nothing (gnn_aggregate_fwd_noalloc); else into the plan's or the caller's workspace.
 int run_aggregate(const void *indptr, const int32_t *indices, const float *w, const void *gathered, void *out,
                   int64_t N, int64_t F, int op, const gnn_opts *opts_in, bool backward, const float *bias = nullptr,
-                  int relu = 0) {
+                  int relu = 0, bool no_alloc = false) {
     gnn_opts o{};
     if (opts_in) o = *opts_in;
+    if (no_alloc) {
+        // nothing that a plan would have to grow: rows are gathered where they lie, from the caller's index array
+        o.flags = (o.flags | GNN_FLAG_NO_PADDED_COPY | GNN_FLAG_NO_COLD_HINTS) &
+                  ~(GNN_FLAG_FORCE_PADDED_COPY | GNN_FLAG_FORCE_COLD_HINTS);
+        o.workspace = nullptr;
+        o.workspace_bytes = 0;
+    }
     if (N < 0 || F < 0) return GNN_ERR_INVALID_ARG;
     if (op != GNN_SUM && op != GNN_MEAN && op != GNN_GCN_SYM && op != GNN_SAGE_GCN) return GNN_ERR_INVALID_ARG;
     if (o.dtype != GNN_F32 && o.dtype != GNN_BF16) return GNN_ERR_INVALID_ARG;
@@ -782,6 +817,7 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
     if (src_mode != kScaleNone && plan->n_edges > 0) {
         // streamed per-edge factors (built once per plan and mode) instead of a random 4-byte
         // lookup per edge, which would cost a 128-byte line each
+        if (no_alloc && !plan->edge_scale[src_mode - 1]) return GNN_ERR_UNSUPPORTED;  // gnn_plan_prepare builds it
         int rc = gnn_plan_edge_scale(plan, indices, src_mode, stream, &edge_scale);
         if (rc != GNN_OK) return rc;
     }
@@ -805,7 +841,11 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
     const bool has_hub = plan && plan->n_chunks > 0;
     if (has_hub) {
         const int64_t need = gnn_plan_workspace_bytes(plan, F);
-        if (o.workspace && o.workspace_bytes >= need) {
+        if (no_alloc) {
+            if (need > int64_t(GNN_NOALLOC_SCRATCH_BYTES)) return GNN_ERR_SCRATCH_CAPACITY;
+            const int rc = static_scratch_of_current_device(&partial);
+            if (rc != GNN_OK) return rc;
+        } else if (o.workspace && o.workspace_bytes >= need) {
             partial = static_cast<float *>(o.workspace);
         } else if (o.workspace) {
             return GNN_ERR_INVALID_ARG;
@@ -1017,6 +1057,11 @@ int gnn_aggregate_fwd_epilogue(const void *indptr, const int32_t *indices, const
 extern "C" GNN_API int gnn_aggregate_fwd(const void *indptr, const int32_t *indices, const float *edge_w, const void *X,
                                  void *Y, int64_t N, int64_t F, int op, const gnn_opts *opts) {
     return run_aggregate(indptr, indices, edge_w, X, Y, N, F, op, opts, /*backward=*/false);
+}
+
+extern "C" GNN_API int gnn_aggregate_fwd_noalloc(const void *indptr, const int32_t *indices, const float *edge_w,
+                                                 const void *X, void *Y, int64_t N, int64_t F, int op, const gnn_opts *opts) {
+    return run_aggregate(indptr, indices, edge_w, X, Y, N, F, op, opts, /*backward=*/false, nullptr, 0, /*no_alloc=*/true);
 }
 
 extern "C" GNN_API int gnn_aggregate_bwd(const void *indptr_t, const int32_t *indices_t, const float *edge_w_t,

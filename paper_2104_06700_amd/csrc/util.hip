@@ -19,6 +19,7 @@ extern "C" GNN_API const char *gnn_status_string(int status) {
         case GNN_ERR_ALLOC: return "allocation failed";
         case GNN_ERR_LAUNCH: return "HIP runtime error";
         case GNN_ERR_INVALID_GRAPH: return "graph violates the CSR preconditions";
+        case GNN_ERR_SCRATCH_CAPACITY: return "hub partial sums exceed the fixed scratch array of the no-allocation entry point";
         default: return "unknown status";
     }
 }

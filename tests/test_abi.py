@@ -25,8 +25,8 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_status_strings_and_defaults():
-    names = {gnn.status_string(s) for s in range(6)}
-    assert len(names) == 6 and "ok" in names
+    names = {gnn.status_string(s) for s in range(7)}
+    assert len(names) == 7 and "ok" in names and "unknown status" not in names
     assert gnn.status_string(99) == "unknown status"
     p = gnn.gnn_plan_default_params()
     thr = list(p.thresholds)[:p.n_thresholds]
@@ -53,6 +53,7 @@ def test_argument_checks_that_need_no_device():
     assert lib.gnn_aggregate_fwd(one, one, None, one, one, 0, 4, 0, None) == gnn.GNN_OK
     assert lib.gnn_aggregate_bwd(one, one, None, one, one, 4, 0, 1, None) == gnn.GNN_OK
     assert lib.gnn_aggregate_fwd(None, one, None, one, one, 4, 4, 0, None) == gnn.GNN_ERR_INVALID_ARG
+    assert lib.gnn_aggregate_fwd_noalloc(one, one, None, one, one, 4, 4, 9, None) == gnn.GNN_ERR_INVALID_ARG
     o.dtype = 5
     assert lib.gnn_aggregate_fwd(one, one, None, one, one, 4, 4, 0, ctypes.byref(o)) == gnn.GNN_ERR_INVALID_ARG
     o.dtype = 0
