@@ -106,6 +106,10 @@ typedef struct gnn_opts {
  * column slice).  For A/B measurements; results do not depend on it. */
 #define GNN_FLAG_NO_SLICE_TABLES 128
 
+/* Do not process the long rows as source-blocked pieces (see gnn_blocking_params).  For A/B
+ * measurements; results agree within rounding (the order of the additions differs). */
+#define GNN_FLAG_NO_SOURCE_BLOCKS 256
+
 /* Degree-binning parameters.  thresholds t[0] < ... < t[k-1], all > 0, cut the
  * row-length axis into k+1 bins, bin(v) = #{i : t[i] <= deg(v)}.  If
  * hub_chunk > 0 the rows of the LAST bin are "hub" rows: each is cut into
@@ -118,6 +122,18 @@ typedef struct gnn_plan_params {
     int64_t thresholds[GNN_MAX_THRESHOLDS];
     int64_t hub_chunk;
 } gnn_plan_params;
+
+/* Source blocking of the long rows (Section 4.2 blocks the SOURCE vertices so that a block of f_V
+ * stays in cache while all destination rows sweep over it; here only the rows of at least
+ * `min_degree` edges take part, cut into pieces along blocks of source vertices ordered by
+ * descending gather count, and the pieces of one block run side by side).  All zero = automatic. */
+typedef struct gnn_blocking_params {
+    int64_t min_degree;      /* rows this long are cut into pieces; must be one of the plan's thresholds.  < 0: never block */
+    int64_t hot_lines;       /* sources in block 0 (the most-gathered ones) */
+    int64_t block_lines;     /* sources per further block */
+    int64_t max_piece;       /* edges per piece at most */
+    int64_t rest_min_count;  /* sources gathered fewer times than this share one last block (at most 16) */
+} gnn_blocking_params;
 
 /* ---------------------------------------------------------------- hot path */
 
@@ -373,6 +389,20 @@ GNN_API int gnn_plan_reserve(gnn_plan *plan, int64_t F);
  * backward: 0 for gnn_aggregate_fwd, 1 for gnn_aggregate_bwd. */
 GNN_API int gnn_plan_prepare(gnn_plan *plan, const int32_t *indices, int op, int backward, int64_t F,
                              int dtype, void *stream);
+
+/* Sets the source-blocking parameters of a plan (before its first hot call or gnn_plan_prepare;
+ * later calls return GNN_ERR_UNSUPPORTED once the layout is built).  NULL = automatic. */
+GNN_API int gnn_plan_set_blocking(gnn_plan *plan, const gnn_blocking_params *params /* host */);
+/* Sizes of the source-blocked layout (all 0 when the plan has none, or has not built it yet):
+ * rows served as pieces, their edges, pieces, blocks. */
+GNN_API int gnn_plan_blocked_sizes(const gnn_plan *plan, int64_t *n_rows, int64_t *n_edges, int64_t *n_pieces,
+                                   int32_t *n_blocks);
+/* Host copies for bit-exact checks: indices int32[n_edges] (source ranks in block-major piece
+ * order), epos uint32[n_edges] (CSR position of each), pieces int32[n_pieces*4] as (begin, length,
+ * partial slot, row index within the blocked rows), rowbase uint32[n_rows+1], rank int32[N] (rank of
+ * every vertex by descending gather count, ties by ascending id).  Any may be NULL. */
+GNN_API int gnn_plan_export_blocked(const gnn_plan *plan, int32_t *indices, uint32_t *epos, int32_t *pieces,
+                                    uint32_t *rowbase, int32_t *rank);
 
 /* ---------------------------------------------------------------- utilities */
 GNN_API const char *gnn_status_string(int status);

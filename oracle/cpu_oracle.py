@@ -175,6 +175,73 @@ def plan(indptr, thresholds, hub_chunk: int):
     return bin_offsets, row_perm, chunks
 
 
+def blocked_layout(indptr, indices, thresholds, min_degree: int, hot_lines: int, block_lines: int, max_piece: int,
+                   rest_min_count: int):
+    """Source-blocked layout of the long rows (the reading of Section 4.2's source blocks taken for
+    the GPU: only rows of at least `min_degree` edges are cut along blocks of sources), as a plain
+    definition written with numpy sorts.
+
+    rank[v]   position of v among the vertices ordered by descending occurrence count in `indices`,
+              equal counts by ascending id
+    block(r)  0 for r < hot_lines; the last block for r >= rest_begin = #{v: count[v] >= rest_min_count}
+              (or hot_lines if that is larger); else 1 + (r - hot_lines) // block_lines
+    rows      those of degree >= min_degree, numbered h = 0, 1, ... by ascending (bin, row id), the
+              order of the plan's row permutation (bin = number of thresholds <= degree)
+    edges     of those rows, ordered by (block of the source's rank, h, rank, CSR position)
+    pieces    maximal runs of equal (block, h) in that order, cut every max_piece edges:
+              (begin, length, slot, h); the pieces of row h get the slots rowbase[h], rowbase[h]+1, ...
+              in that order
+    Returns (ranks int32[E_b], epos uint32[E_b], pieces int32[P, 4], rowbase uint32[R + 1], rank int32[N])."""
+    indptr = _i64(indptr)
+    indices = _i64(indices)
+    n = indptr.shape[0] - 1
+    deg = np.diff(indptr)
+    count = np.bincount(indices, minlength=n)
+    order = np.lexsort((np.arange(n), -count))          # by descending count, then ascending id
+    rank = np.empty(n, dtype=np.int64)
+    rank[order] = np.arange(n)
+    thr = np.asarray(thresholds, dtype=np.int64)
+    bins = (deg[:, None] >= thr[None, :]).sum(axis=1)
+    rows = np.flatnonzero(deg >= min_degree)
+    rows = rows[np.lexsort((rows, bins[rows]))]
+    rest_begin = max(int((count >= rest_min_count).sum()), min(hot_lines, n))
+    hot = min(hot_lines, n)
+    n_mid = -(-(rest_begin - hot) // block_lines)
+    n_blocks = n_mid + 2
+    e_h, e_rank, e_pos = [], [], []
+    for h, v in enumerate(rows):
+        pos = np.arange(indptr[v], indptr[v + 1])
+        e_pos.append(pos)
+        e_rank.append(rank[indices[pos]])
+        e_h.append(np.full(pos.shape[0], h, dtype=np.int64))
+    if not e_h:
+        z = np.zeros(0, dtype=np.int32)
+        return z, z.astype(np.uint32), np.zeros((0, 4), dtype=np.int32), np.zeros(0, dtype=np.uint32), rank.astype(np.int32)
+    e_h, e_rank, e_pos = np.concatenate(e_h), np.concatenate(e_rank), np.concatenate(e_pos)
+    blk = np.where(e_rank < hot, 0, np.where(e_rank >= rest_begin, n_blocks - 1, 1 + (e_rank - hot) // block_lines))
+    o = np.lexsort((e_pos, e_rank, e_h, blk))
+    e_h, e_rank, e_pos, blk = e_h[o], e_rank[o], e_pos[o], blk[o]
+    pieces = []
+    next_slot_in_row = np.zeros(len(rows), dtype=np.int64)
+    pieces_of_row = np.zeros(len(rows), dtype=np.int64)
+    i, total = 0, e_h.shape[0]
+    runs = []
+    while i < total:
+        j = i
+        while j < total and blk[j] == blk[i] and e_h[j] == e_h[i]:
+            j += 1
+        for b in range(i, j, max_piece):
+            runs.append((b, min(max_piece, j - b), int(e_h[i])))
+            pieces_of_row[e_h[i]] += 1
+        i = j
+    rowbase = np.concatenate(([0], np.cumsum(pieces_of_row)))
+    for b, ln, h in runs:
+        pieces.append((b, ln, rowbase[h] + next_slot_in_row[h], h))
+        next_slot_in_row[h] += 1
+    return (e_rank.astype(np.int32), e_pos.astype(np.uint32), np.asarray(pieces, dtype=np.int32).reshape(-1, 4),
+            rowbase.astype(np.uint32), rank.astype(np.int32))
+
+
 # ---------------------------------------------------------------- general primitive (Table 1)
 BIN_ADD, BIN_SUB, BIN_MUL, BIN_DIV, BIN_COPY_LHS, BIN_COPY_RHS = range(6)
 RED_SUM, RED_MAX, RED_MIN = range(3)

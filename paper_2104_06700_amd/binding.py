@@ -29,6 +29,7 @@ GNN_FLAG_NO_COLD_HINTS = 16
 GNN_FLAG_FORCE_COLD_HINTS = 32
 GNN_FLAG_NO_RANK_ORDER = 64
 GNN_FLAG_NO_SLICE_TABLES = 128
+GNN_FLAG_NO_SOURCE_BLOCKS = 256
 GNN_BIN_ADD, GNN_BIN_SUB, GNN_BIN_MUL, GNN_BIN_DIV, GNN_BIN_COPY_LHS, GNN_BIN_COPY_RHS = range(6)
 GNN_RED_SUM, GNN_RED_MAX, GNN_RED_MIN = range(3)
 
@@ -36,7 +37,7 @@ EXPORTED_SYMBOLS = (
     "gnn_aggregate_fwd", "gnn_aggregate_bwd", "gnn_aggregate_fwd_noalloc", "gnn_csr_from_sorted_coo", "gnn_transpose_csr",
     "gnn_validate_csr", "gnn_plan_default_params", "gnn_plan_create", "gnn_plan_destroy",
     "gnn_plan_sizes", "gnn_plan_export", "gnn_plan_gather_share", "gnn_plan_workspace_bytes", "gnn_plan_reserve",
-    "gnn_plan_prepare",
+    "gnn_plan_prepare", "gnn_plan_set_blocking", "gnn_plan_blocked_sizes", "gnn_plan_export_blocked",
     "gnn_ap_fwd", "gnn_ap_bwd_vertex", "gnn_ap_bwd_vertex_arg", "gnn_ap_bwd_edge",
     "gnn_matmul", "gnn_matmul_workspace_bytes",
     "gnn_sage_layer_fwd", "gnn_sage_layer_bwd", "gnn_sage_layer_saved_elems", "gnn_sage_layer_workspace_bytes",
@@ -79,6 +80,11 @@ class GnnPlanParams(ctypes.Structure):
     ]
 
 
+class GnnBlockingParams(ctypes.Structure):
+    _fields_ = [("min_degree", ctypes.c_int64), ("hot_lines", ctypes.c_int64), ("block_lines", ctypes.c_int64),
+                ("max_piece", ctypes.c_int64), ("rest_min_count", ctypes.c_int64)]
+
+
 class GnnError(RuntimeError):
     def __init__(self, fn: str, status: int):
         self.status = status
@@ -116,6 +122,10 @@ def load_library() -> ctypes.CDLL:
         lib.gnn_plan_workspace_bytes.restype = i64
         lib.gnn_plan_reserve.argtypes = [vp, i64]
         lib.gnn_plan_prepare.argtypes = [vp, vp, i32, i32, i64, i32, vp]
+        lib.gnn_plan_set_blocking.argtypes = [vp, ctypes.POINTER(GnnBlockingParams)]
+        lib.gnn_plan_blocked_sizes.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64),
+                                               ctypes.POINTER(ctypes.c_int32)]
+        lib.gnn_plan_export_blocked.argtypes = [vp, vp, vp, vp, vp, vp]
         ap = ctypes.POINTER(GnnApOpts)
         lib.gnn_ap_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i32, i32, ap]
         lib.gnn_ap_bwd_vertex.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, ap]
@@ -219,6 +229,32 @@ class Plan:
             self.handle, bin_offsets.ctypes.data, row_perm.ctypes.data if n else None,
             chunks.ctypes.data if c else None, col_counts.ctypes.data if n else None))
         return bin_offsets, row_perm, chunks, col_counts
+
+    def set_blocking(self, min_degree=0, hot_lines=0, block_lines=0, max_piece=0, rest_min_count=0) -> None:
+        """Parameters of the source-blocked layout of the long rows (zeros: automatic; min_degree < 0: off)."""
+        p = GnnBlockingParams(int(min_degree), int(hot_lines), int(block_lines), int(max_piece), int(rest_min_count))
+        _check("gnn_plan_set_blocking", load_library().gnn_plan_set_blocking(self.handle, ctypes.byref(p)))
+
+    def blocked_sizes(self):
+        """(rows served as pieces, their edges, pieces, blocks); zeros when the plan has no such layout (yet)."""
+        r = ctypes.c_int64(); e = ctypes.c_int64(); p = ctypes.c_int64(); b = ctypes.c_int32()
+        _check("gnn_plan_blocked_sizes", load_library().gnn_plan_blocked_sizes(
+            self.handle, ctypes.byref(r), ctypes.byref(e), ctypes.byref(p), ctypes.byref(b)))
+        return r.value, e.value, p.value, b.value
+
+    def export_blocked(self):
+        """Host copies of the source-blocked layout: (indices int32[E_b], epos uint32[E_b], pieces int32[P,4],
+        rowbase uint32[R+1], rank int32[N])."""
+        import numpy as np
+        r, e, p, _ = self.blocked_sizes()
+        n = self.sizes()[0]
+        indices = np.zeros(e, dtype=np.int32); epos = np.zeros(e, dtype=np.uint32)
+        pieces = np.zeros((p, 4), dtype=np.int32); rowbase = np.zeros(r + 1 if p else 0, dtype=np.uint32)
+        rank = np.zeros(n, dtype=np.int32)
+        _check("gnn_plan_export_blocked", load_library().gnn_plan_export_blocked(
+            self.handle, indices.ctypes.data if e else None, epos.ctypes.data if e else None,
+            pieces.ctypes.data if p else None, rowbase.ctypes.data if p else None, rank.ctypes.data if n else None))
+        return indices, epos, pieces, rowbase, rank
 
     def gather_share(self, K: int) -> float:
         return float(load_library().gnn_plan_gather_share(self.handle, int(K)))

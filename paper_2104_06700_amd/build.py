@@ -13,7 +13,7 @@ INCLUDE = os.path.join(ROOT, "include")
 LIB = os.path.join(PKG, "libgnnagg.so")
 OBJ_DIR = os.path.join(PKG, "_build")
 
-SOURCES = ["aggregate.hip", "ap.hip", "gemm.hip", "layer.hip", "plan.hip", "graph.hip", "util.hip"]
+SOURCES = ["aggregate.hip", "blocked.hip", "ap.hip", "gemm.hip", "layer.hip", "plan.hip", "graph.hip", "util.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

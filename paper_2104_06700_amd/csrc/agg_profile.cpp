@@ -6,7 +6,9 @@
 //
 // usage: agg_profile DIR OP(0|1|2) REPS [noslice] F [F ...]      (fp32 features)
 // "noslice" switches the XCD column slicing off for the widths that follow it; "flags=N" sets
-// gnn_opts.flags (GNN_FLAG_* bits) for the widths that follow it.
+// gnn_opts.flags (GNN_FLAG_* bits) for the widths that follow it; "block=D,H,B,P,R" (anywhere) sets
+// the source-blocking parameters of both plans (min_degree, hot_lines, block_lines, max_piece,
+// rest_min_count; 0 = default, D = -1 switches blocking off).
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
@@ -71,12 +73,22 @@ int main(int argc, char **argv) {
     gnn_plan *pf = nullptr, *pb = nullptr;
     GCHECK(gnn_plan_create(indptr, (const int32_t *)indices, N, ip64, nullptr, nullptr, &pf));
     GCHECK(gnn_plan_create(indptr_t, (const int32_t *)indices_t, N, ip64, nullptr, nullptr, &pb));
+    for (int a = 4; a < argc; ++a) {
+        if (std::string(argv[a]).rfind("block=", 0) != 0) continue;
+        gnn_blocking_params bp{};
+        long long v[5] = {0, 0, 0, 0, 0};
+        sscanf(argv[a] + 6, "%lld,%lld,%lld,%lld,%lld", &v[0], &v[1], &v[2], &v[3], &v[4]);
+        bp.min_degree = v[0]; bp.hot_lines = v[1]; bp.block_lines = v[2]; bp.max_piece = v[3]; bp.rest_min_count = v[4];
+        GCHECK(gnn_plan_set_blocking(pf, &bp));
+        GCHECK(gnn_plan_set_blocking(pb, &bp));
+    }
 
     int flags = 0, max_slices = 0;
     for (int a = 4; a < argc; ++a) {
         if (std::string(argv[a]) == "noslice") { flags = GNN_FLAG_NO_COLUMN_SLICES; continue; }
         if (std::string(argv[a]).rfind("flags=", 0) == 0) { flags = atoi(argv[a] + 6); continue; }
         if (std::string(argv[a]).rfind("slices=", 0) == 0) { max_slices = atoi(argv[a] + 7); continue; }
+        if (std::string(argv[a]).rfind("block=", 0) == 0) continue;
         const long long F = atoll(argv[a]);
         const size_t bytes = (size_t)N * F * 4;
         void *X = nullptr, *Y = nullptr;
@@ -105,6 +117,11 @@ int main(int argc, char **argv) {
         printf("N=%lld E=%lld F=%lld op=%d flags=%d slices<=%d fwd %.4f ms  bwd %.4f ms  (%.1f / %.1f GEF/s)\n", N, E, F, op, flags, max_slices, ms_f / reps,
                ms_b / reps, E * F / (ms_f / reps) / 1e6, E * F / (ms_b / reps) / 1e6);
         CHECK(hipFree(X)); CHECK(hipFree(Y));
+    }
+    {
+        int64_t r = 0, e = 0, pc = 0; int32_t nb = 0;
+        gnn_plan_blocked_sizes(pf, &r, &e, &pc, &nb);
+        printf("source blocks (forward plan): %lld rows, %lld edges, %lld pieces, %d blocks\n", (long long)r, (long long)e, (long long)pc, nb);
     }
     gnn_plan_destroy(pf);
     gnn_plan_destroy(pb);

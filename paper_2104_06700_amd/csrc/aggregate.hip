@@ -540,15 +540,144 @@ __global__ void __launch_bounds__(256) hub_finalize_kernel(const int32_t *__rest
                                                            int F, int64_t ldp, int self_mode,
                                                            const T *__restrict__ G, int64_t ldg,
                                                            const int32_t *__restrict__ col_counts,
-                                                           const float *__restrict__ bias, int relu) {
+                                                           const float *__restrict__ bias, int relu, int col_begin) {
     const int64_t i = blockIdx.x;
     if (i >= n_hub) return;
     const int64_t row = hub_rows[i];
     const int64_t p0 = piece_offsets[i], p1 = piece_offsets[i + 1];
     const float ds = scale_of(dst_mode, load_ip(indptr, ip64, row + 1) - load_ip(indptr, ip64, row));
-    for (int colx = threadIdx.x; colx < F; colx += blockDim.x) {
+    for (int colx = col_begin + threadIdx.x; colx < F; colx += blockDim.x) {
         float sum = 0.0f;
         for (int64_t p = p0; p < p1; ++p) sum += partial[p * ldp + colx];
+        if (self_mode != kSelfNone) {
+            float xs[1];
+            VecIO<T, 1>::load(G + row * ldg + colx, xs);
+            sum = fmaf(self_mode == kSelfInvPlus1 ? scale_of(kScaleInvPlus1, col_counts[row]) : 1.0f, xs[0], sum);
+        }
+        float o[1] = {sum * ds};
+        if (bias) o[0] += bias[colx];
+        if (relu) o[0] = o[0] > 0.0f ? o[0] : 0.0f;
+        VecIO<T, 1>::store(Y + row * ldy + colx, o);
+    }
+}
+
+// ---- source-blocked pieces of the long rows (see blocked.hip) ----
+struct PieceArgs {
+    const int32_t *pieces;   // [n_pieces * 4] (begin, length, partial slot, row index)
+    int64_t n_pieces;
+    const int32_t *idx;      // source ranks, block-major piece order
+    const uint32_t *epos;    // CSR position of each edge (for the caller's per-edge streams)
+    const float *w;
+    const float *edge_scale;
+    const void *X;           // first slice table of the launch
+    int64_t slice_stride;    // elements between two slice tables
+    float *partial;          // [slices][n_pieces][floats per line]
+    int32_t log2_slices;
+};
+
+// Eight lanes own one piece and one 128-byte line of every gathered row (16 bytes each); a wavefront
+// works on eight consecutive pieces, i.e. on 64 lines in flight.  The pieces of a launch follow the
+// block order of the layout, so the workgroups that run side by side gather from the same block of
+// source rows.  Every piece writes one fp32 partial line; blk_finalize_kernel adds them.
+template <typename T, bool COEF>
+__global__ void __launch_bounds__(kBlockThreads) piece_kernel(const PieceArgs a) {
+    constexpr int VEC = 16 / int(sizeof(T));   // elements per lane
+    constexpr int LINE = 8 * VEC;              // elements per line = floats per partial line
+    constexpr int U = 8;
+    const int lane = threadIdx.x & 63;
+    const int slice = int(blockIdx.x) & ((1 << a.log2_slices) - 1);
+    const int64_t vblock = int64_t(blockIdx.x) >> a.log2_slices;
+    const int c = lane & 7, gbase = lane & ~7;
+    const int64_t piece = (vblock * kWavesPerBlock + (threadIdx.x >> 6)) * 8 + (lane >> 3);
+    uint32_t begin = 0;
+    int len = 0;
+    int64_t slot = 0;
+    if (piece < a.n_pieces) {
+        const int4 d = *reinterpret_cast<const int4 *>(a.pieces + 4 * piece);
+        begin = uint32_t(d.x); len = d.y; slot = d.z;
+    }
+    const T *__restrict__ X = static_cast<const T *>(a.X) + int64_t(slice) * a.slice_stride + c * VEC;
+    float acc[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
+
+    auto fetch = [&](int t, int &u_out, float &cf_out) {
+        u_out = 0;
+        cf_out = 0.0f;
+        const int j = t + c;
+        if (j < len) {
+            u_out = a.idx[begin + uint32_t(j)];
+            if (COEF) {
+                const uint32_t e = a.epos[begin + uint32_t(j)];
+                cf_out = a.w ? a.w[e] : 1.0f;
+                if (a.edge_scale) cf_out *= a.edge_scale[e];
+            }
+        }
+    };
+    int nxt_u;
+    float nxt_cf;
+    fetch(0, nxt_u, nxt_cf);
+    for (int t = 0; __any(t < len); t += U) {
+        const int my_u = nxt_u;
+        const float my_cf = nxt_cf;
+        fetch(t + U, nxt_u, nxt_cf);
+        typename Strip<T, VEC>::raw_t x[U];
+        float cf[U];
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            const int u = __shfl(my_u, gbase + k);
+            if (COEF) cf[k] = __shfl(my_cf, gbase + k);
+            if (t + k < len) x[k] = Strip<T, VEC>::load(X + int64_t(u) * LINE);
+            else x[k] = Strip<T, VEC>::zero();
+        }
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            float xv[VEC];
+            Strip<T, VEC>::unpack(x[k], xv);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) {
+                if (COEF) acc[i] = fmaf(t + k < len ? cf[k] : 0.0f, xv[i], acc[i]);
+                else acc[i] += xv[i];
+            }
+        }
+    }
+    if (piece < a.n_pieces) {
+        float *out = a.partial + (int64_t(slice) * a.n_pieces + slot) * LINE + c * VEC;
+#pragma unroll
+        for (int i = 0; i < VEC; i += 4) {
+            const f32x4 v = {acc[i], acc[i + 1], acc[i + 2], acc[i + 3]};
+            __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(out + i));
+        }
+    }
+}
+
+// Adds the partial lines of every long row in slot order (the block order of its pieces) and writes
+// the columns [0, fw) of the launch: one workgroup per row, a thread per column.
+template <typename T>
+__global__ void __launch_bounds__(256) blk_finalize_kernel(const int32_t *__restrict__ rows, int64_t n_rows,
+                                                           const uint32_t *__restrict__ rowbase,
+                                                           const float *__restrict__ partial, int64_t n_pieces,
+                                                           const void *indptr, int ip64, int dst_mode, T *__restrict__ Y,
+                                                           int64_t ldy, int fw, int self_mode, const T *__restrict__ G,
+                                                           int64_t ldg, const int32_t *__restrict__ col_counts,
+                                                           const float *__restrict__ bias, int relu) {
+    constexpr int LINE = 128 / int(sizeof(T));
+    const int64_t i = blockIdx.x;
+    if (i >= n_rows) return;
+    const int64_t row = rows[i];
+    const int64_t p0 = rowbase[i], p1 = rowbase[i + 1];
+    const float ds = scale_of(dst_mode, load_ip(indptr, ip64, row + 1) - load_ip(indptr, ip64, row));
+    for (int colx = threadIdx.x; colx < fw; colx += blockDim.x) {
+        const float *__restrict__ src = partial + int64_t(colx / LINE) * n_pieces * LINE + (colx % LINE);
+        float sum = 0.0f;
+        int64_t p = p0;
+        for (; p + 4 <= p1; p += 4) {  // four loads in flight, added in slot order
+            const float v0 = __builtin_nontemporal_load(src + (p + 0) * LINE), v1 = __builtin_nontemporal_load(src + (p + 1) * LINE);
+            const float v2 = __builtin_nontemporal_load(src + (p + 2) * LINE), v3 = __builtin_nontemporal_load(src + (p + 3) * LINE);
+            sum = ((sum + v0) + v1) + v2;
+            sum += v3;
+        }
+        for (; p < p1; ++p) sum += __builtin_nontemporal_load(src + p * LINE);
         if (self_mode != kSelfNone) {
             float xs[1];
             VecIO<T, 1>::load(G + row * ldg + colx, xs);
@@ -940,6 +1069,16 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         if (flagged) gather_indices = flagged;
     }
 
+    // The long rows of a large power-law graph are served as source-blocked pieces (blocked.hip) in
+    // every launch that gathers from slice tables; the dense tail keeps the plain path.
+    gnn_blocked_layout bl{};
+    if (slice_major && rank_indices && !(o.flags & GNN_FLAG_NO_SOURCE_BLOCKS)) {
+        const int rc = gnn_plan_blocked(plan, indptr, stream, &bl);
+        if (rc != GNN_OK) return rc;
+    }
+    bool plain_hub_columns = false;   // some launch left its hub rows to hub_finalize_kernel
+    int64_t plain_hub_col_begin = F;  // ... from this column on
+
     for (int gi = 0; gi < n_segs; ++gi) {
         const int64_t f0 = segs[gi].f0, fw = segs[gi].fw;
         const int log2_s = segs[gi].log2_s;
@@ -991,8 +1130,48 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
             a.partial = partial ? partial + f0 : nullptr;
             a.ldp = gnn_partial_ld(F);
         }
+        const bool blocked = bl.active && segs[gi].tail_slice < 0;
+        if (blocked) {
+            const int line_floats = int(line_elems);
+            int rc = gnn_plan_blocked_partial(plan, 1 << log2_s, line_floats);
+            if (rc != GNN_OK) return rc;
+            PieceArgs pa{};
+            pa.pieces = bl.pieces;
+            pa.n_pieces = bl.n_pieces;
+            pa.idx = bl.indices;
+            pa.epos = bl.epos;
+            pa.w = w;
+            pa.edge_scale = edge_scale;
+            pa.X = a.X;
+            pa.slice_stride = layout.table_stride;
+            pa.partial = static_cast<float *>(plan->blk_partial);
+            pa.log2_slices = log2_s;
+            const int64_t pblocks = ((bl.n_pieces + 8 * kWavesPerBlock - 1) / (8 * kWavesPerBlock)) << log2_s;
+            if (pblocks > INT32_MAX) return GNN_ERR_UNSUPPORTED;
+            const dim3 pgrid(static_cast<unsigned>(pblocks)), fgrid(static_cast<unsigned>(bl.n_hot));
+            const int32_t *hot_rows = plan->row_perm + bl.hot_begin;
+            if (o.dtype == GNN_F32) {
+                if (coef) piece_kernel<float, true><<<pgrid, kBlockThreads, 0, stream>>>(pa);
+                else piece_kernel<float, false><<<pgrid, kBlockThreads, 0, stream>>>(pa);
+                blk_finalize_kernel<float><<<fgrid, 256, 0, stream>>>(
+                    hot_rows, bl.n_hot, bl.rowbase, pa.partial, bl.n_pieces, indptr, o.indptr_is_64 ? 1 : 0, dst_mode,
+                    static_cast<float *>(out) + f0, ldy, int(fw), orig_self_mode, static_cast<const float *>(orig) + f0, ldx,
+                    plan->col_counts, bias ? bias + f0 : nullptr, relu);
+            } else {
+                if (coef) piece_kernel<bf16_t, true><<<pgrid, kBlockThreads, 0, stream>>>(pa);
+                else piece_kernel<bf16_t, false><<<pgrid, kBlockThreads, 0, stream>>>(pa);
+                blk_finalize_kernel<bf16_t><<<fgrid, 256, 0, stream>>>(
+                    hot_rows, bl.n_hot, bl.rowbase, pa.partial, bl.n_pieces, indptr, o.indptr_is_64 ? 1 : 0, dst_mode,
+                    static_cast<bf16_t *>(out) + f0, ldy, int(fw), orig_self_mode, static_cast<const bf16_t *>(orig) + f0, ldx,
+                    plan->col_counts, bias ? bias + f0 : nullptr, relu);
+            }
+            if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
+        } else if (has_hub) {
+            plain_hub_columns = true;
+            if (f0 < plain_hub_col_begin) plain_hub_col_begin = f0;
+        }
         int32_t nb = 0;
-        int64_t next_block = gnn_fill_bins(a.bins, &nb, plan, N, log2_c);
+        int64_t next_block = gnn_fill_bins(a.bins, &nb, plan, N, log2_c, blocked ? bl.first_bin : INT32_MAX);
         a.n_bins = nb;
         if (nb == 0 || next_block == 0) continue;
         next_block <<= log2_s;
@@ -1013,19 +1192,19 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         if (err != hipSuccess) return GNN_ERR_LAUNCH;
     }
 
-    if (has_hub) {
+    if (has_hub && plain_hub_columns) {
         const int64_t hub_begin = plan->bin_offsets[plan->n_bins - 1];
         dim3 grid(static_cast<unsigned>(plan->n_hub_rows));
         if (o.dtype == GNN_F32)
             hub_finalize_kernel<float><<<grid, 256, 0, stream>>>(plan->row_perm + hub_begin, plan->n_hub_rows, plan->hub_chunk_offsets,
                                                                  partial, indptr, o.indptr_is_64 ? 1 : 0, dst_mode,
                                                                  static_cast<float *>(out), ldy, int(F), gnn_partial_ld(F), orig_self_mode,
-                                                                 static_cast<const float *>(orig), ldx, plan->col_counts, bias, relu);
+                                                                 static_cast<const float *>(orig), ldx, plan->col_counts, bias, relu, int(plain_hub_col_begin));
         else
             hub_finalize_kernel<bf16_t><<<grid, 256, 0, stream>>>(plan->row_perm + hub_begin, plan->n_hub_rows, plan->hub_chunk_offsets,
                                                                   partial, indptr, o.indptr_is_64 ? 1 : 0, dst_mode,
                                                                   static_cast<bf16_t *>(out), ldy, int(F), gnn_partial_ld(F), orig_self_mode,
-                                                                  static_cast<const bf16_t *>(orig), ldx, plan->col_counts, bias, relu);
+                                                                  static_cast<const bf16_t *>(orig), ldx, plan->col_counts, bias, relu, int(plain_hub_col_begin));
         if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
     }
     return GNN_OK;

@@ -66,7 +66,56 @@ struct gnn_plan {
     int64_t *p_chunks = nullptr;
     // a caller's scalar edge operand brought into CSR order (gnn_plan_edge_operand); refilled per call
     float *edge_operand = nullptr;
+    // Source-blocked layout of the long rows (see gnn_plan_blocked); built on first use.
+    gnn_blocking_params blocking{};   // requested parameters (zeros: automatic)
+    int32_t blk_decided = 0;          // 0: not yet; 1: decided (blk_n_pieces == 0 when it does not apply)
+    int32_t blk_first_bin = 0;        // rows of bins >= this are processed as pieces
+    int64_t blk_hot_begin = 0;        // their range in row_perm is [blk_hot_begin, n_rows)
+    int64_t blk_n_hot = 0;
+    int64_t blk_n_edges = 0;          // edges of those rows
+    int64_t blk_n_pieces = 0;
+    int32_t blk_n_blocks = 0;
+    int32_t *blk_indices = nullptr;   // [blk_n_edges] source ranks, block-major piece order
+    uint32_t *blk_epos = nullptr;     // [blk_n_edges] CSR position of each (the caller's per-edge streams are read there)
+    int32_t *blk_pieces = nullptr;    // [blk_n_pieces * 4] (begin, length, partial slot, row index in the hot range)
+    uint32_t *blk_rowbase = nullptr;  // [blk_n_hot + 1] first partial slot of each hot row
+    void *blk_partial = nullptr;      // fp32 partial sums of one launch: [slices][blk_n_pieces][floats per line]
+    int64_t blk_partial_bytes = 0;
 };
+
+// Source blocking (the GPU reading of Section 4.2's blocks of source vertices, applied to the long
+// rows only).  Rows of at least `min_degree` edges are cut into pieces along blocks of source RANK
+// (block 0 = the `hot_lines` most-gathered sources, then blocks of `block_lines`, then one block for
+// the sources gathered fewer than `rest_min_count` times), and the pieces are processed block by
+// block: all rows that gather from a block do so within a short time, so a source row is fetched
+// into an L2 once per block instead of once per gather.  Pieces write fp32 partial rows that a
+// second kernel adds in a fixed order.
+struct gnn_blocked_layout {
+    bool active;
+    int32_t first_bin;       // bins >= this are served by pieces
+    int64_t hot_begin, n_hot, n_pieces;
+    const int32_t *indices;  // block-major
+    const uint32_t *epos;
+    const int32_t *pieces;
+    const uint32_t *rowbase;
+};
+// Builds the layout on first use (allocation; needs the rank layout) and reports it.  Inactive when
+// the graph or the plan's thresholds do not suit it.
+int gnn_plan_blocked(gnn_plan *plan, const void *indptr, hipStream_t stream, gnn_blocked_layout *out);
+// Makes plan->blk_partial large enough for `slices` column slices of `line_floats` floats per piece.
+int gnn_plan_blocked_partial(gnn_plan *plan, int slices, int line_floats);
+
+// Stable LSD radix sort of 32-bit (key, value) pairs on the low `bits` bits (graph.hip).  buf_k[0] /
+// buf_v[0] hold the input (first_keys, if given, replaces buf_k[0] as read-only input of the first
+// pass); the result is in buf_k[*out] / buf_v[*out].  table / sums: scratch of gnn_sort_table_elems(n)
+// and gnn_sort_sums_elems(n) words.
+int gnn_radix_sort_pairs(const uint32_t *first_keys, uint32_t *buf_k[2], uint32_t *buf_v[2], int64_t n, int bits,
+                         uint32_t *table, uint32_t *sums, hipStream_t stream, int *out);
+int64_t gnn_sort_table_elems(int64_t n);
+int64_t gnn_sort_sums_elems(int64_t n);
+// In-place exclusive prefix sum of n 32-bit words; sums: scratch of gnn_scan_sums_elems(n) words.
+int gnn_scan_exclusive_u32(uint32_t *data, int64_t n, uint32_t *sums, hipStream_t stream);
+int64_t gnn_scan_sums_elems(int64_t n);
 
 // Row stride (floats) of the hub partial-sum scratch for width F: whole 32-byte groups, so that
 // vector stores of a last, partial strip stay inside the row.
@@ -233,7 +282,9 @@ constexpr int GNN_WAVES_PER_BLOCK = 4;  // 256-thread workgroups
 
 // Fills `bins` for a launch whose row groups have 2^log2_c column lanes; returns the number of
 // workgroups.  plan == nullptr: all N rows in one bin, whole wavefronts per row.
-static inline int64_t gnn_fill_bins(gnn_bin_desc *bins, int32_t *n_bins, const gnn_plan *plan, int64_t N, int log2_c) {
+// first_excluded_bin: rows of bins >= it (and the hub pieces) are left out (they are served as source-blocked pieces).
+static inline int64_t gnn_fill_bins(gnn_bin_desc *bins, int32_t *n_bins, const gnn_plan *plan, int64_t N, int log2_c,
+                                    int first_excluded_bin = INT32_MAX) {
     const int max_log2_sr = 6 - log2_c;
     int64_t next_block = 0;
     int nb = 0;
@@ -254,8 +305,9 @@ static inline int64_t gnn_fill_bins(gnn_bin_desc *bins, int32_t *n_bins, const g
         const int last = plan->n_bins - 1;
         const bool has_hub = plan->n_chunks > 0;
         // heaviest work first: hub pieces, then bins from long rows to short rows
-        if (has_hub) add_bin(GNN_BIN_HUB_PIECES, 0, plan->n_chunks, max_log2_sr);
+        if (has_hub && first_excluded_bin > last) add_bin(GNN_BIN_HUB_PIECES, 0, plan->n_chunks, max_log2_sr);
         for (int bi = last; bi >= 0; --bi) {
+            if (bi >= first_excluded_bin) continue;
             if (bi == last && has_hub) continue;  // handled as pieces (+ finalize)
             const int64_t lo = bi == 0 ? 0 : plan->params.thresholds[bi - 1];
             // Edge slots per row: enough that the shortest row of the bin still takes ~16 steps

@@ -267,6 +267,23 @@ int read_edge_count(const void *indptr, int64_t N, int ip64, hipStream_t stream,
 
 }  // namespace
 
+int gnn_radix_sort_pairs(const uint32_t *first_keys, uint32_t *buf_k[2], uint32_t *buf_v[2], int64_t n, int bits,
+                         uint32_t *table, uint32_t *sums, hipStream_t stream, int *out) {
+    return radix_sort_pairs(first_keys, buf_k, buf_v, n, bits, table, sums, stream, out);
+}
+int64_t gnn_sort_table_elems(int64_t n) { return (n + kSortTile - 1) / kSortTile * 256; }
+int64_t gnn_sort_sums_elems(int64_t n) { return (gnn_sort_table_elems(n) + kScanChunk - 1) / kScanChunk + 1; }
+int64_t gnn_scan_sums_elems(int64_t n) { return (n + kScanChunk - 1) / kScanChunk + 1; }
+int gnn_scan_exclusive_u32(uint32_t *data, int64_t n, uint32_t *sums, hipStream_t stream) {
+    if (n <= 0) return GNN_OK;
+    const int64_t n_sums = (n + kScanChunk - 1) / kScanChunk;
+    if (n_sums > INT32_MAX) return GNN_ERR_UNSUPPORTED;
+    scan_block_sums_kernel<<<static_cast<unsigned>(n_sums), 256, 0, stream>>>(data, n, sums);
+    scan_sums_kernel<<<1, 1024, 0, stream>>>(sums, n_sums);
+    scan_local_kernel<<<static_cast<unsigned>(n_sums), 256, 0, stream>>>(data, n, sums);
+    return hipGetLastError() == hipSuccess ? GNN_OK : GNN_ERR_LAUNCH;
+}
+
 extern "C" GNN_API int gnn_csr_from_sorted_coo(const int32_t *dst_sorted, int64_t E, int64_t N, void *indptr_out,
                                        int indptr_is_64, void *stream_v) {
     if (N < 0 || E < 0 || !indptr_out || (E > 0 && !dst_sorted)) return GNN_ERR_INVALID_ARG;

@@ -473,6 +473,17 @@ extern "C" GNN_API int gnn_plan_prepare(gnn_plan *plan, const int32_t *indices, 
             gnn_rank_layout unused{};  // built from the row pointers the plan was created from
             rc = gnn_plan_rank_indices(plan, plan->indptr_seen, indices, false, static_cast<hipStream_t>(stream), &unused);
             if (rc != GNN_OK) return rc;
+            if (layout.slice_major) {  // the long rows as source-blocked pieces, and their partial sums
+                gnn_blocked_layout bl{};
+                rc = gnn_plan_blocked(plan, plan->indptr_seen, static_cast<hipStream_t>(stream), &bl);
+                if (rc != GNN_OK) return rc;
+                if (bl.active) {
+                    int slices = 1;
+                    while (slices < 8 && slices * 2 <= layout.main_lines) slices *= 2;
+                    rc = gnn_plan_blocked_partial(plan, slices, 128 / esz);
+                    if (rc != GNN_OK) return rc;
+                }
+            }
         } else if (layout.slices_wanted) {  // the flagged index copy of the cold hints, where they pay
             const int32_t *unused_idx = nullptr;
             rc = gnn_plan_cold_indices(plan, indices, false, static_cast<hipStream_t>(stream), &unused_idx);
@@ -498,6 +509,11 @@ extern "C" GNN_API void gnn_plan_destroy(gnn_plan *plan) {
     (void)hipFree(plan->p_indptr);
     (void)hipFree(plan->p_chunks);
     (void)hipFree(plan->edge_operand);
+    (void)hipFree(plan->blk_indices);
+    (void)hipFree(plan->blk_epos);
+    (void)hipFree(plan->blk_pieces);
+    (void)hipFree(plan->blk_rowbase);
+    (void)hipFree(plan->blk_partial);
     (void)hipFree(plan->row_perm);
     (void)hipFree(plan->col_counts);
     (void)hipFree(plan->chunks);

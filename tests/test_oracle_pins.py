@@ -340,3 +340,65 @@ def test_pins_under_undefined_behaviour_sanitizer():
         out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=600)
         assert out.returncode == 0, out.stderr[-2000:]
         assert "pins ok under ubsan" in out.stdout
+
+
+# ---------------------------------------------------------------- source-blocked layout of the long rows
+@pytest.mark.parametrize("params", [dict(min_degree=8, hot_lines=20, block_lines=50, max_piece=6, rest_min_count=2),
+                                    dict(min_degree=2, hot_lines=1, block_lines=7, max_piece=3, rest_min_count=1),
+                                    dict(min_degree=32, hot_lines=5000, block_lines=10, max_piece=100, rest_min_count=16)])
+def test_blocked_layout_invariants(params):
+    """The layout is pinned by what it must satisfy, recounted by brute force: the pieces tile the
+    edge array, every piece lies in one row and one block, blocks never go backwards, inside a
+    (block, row) run the ranks ascend, the edges of the long rows appear exactly once each with the
+    CSR position they came from, and the slots of a row are consecutive in block order."""
+    el = synth.rmat_symmetric(700, 9000, (0.57, 0.19, 0.19, 0.05), 5)
+    dst, src = synth.to_csr_numpy(el)
+    indptr = oracle.csr_indptr(dst, el.n)
+    thr = [2, 8, 32, 128]
+    ranks, epos, pieces, rowbase, rank = oracle.blocked_layout(indptr, src, thr, **params)
+    n = el.n
+    count = np.bincount(src, minlength=n)
+    # rank: a permutation that orders by descending count, ties by id
+    inv = np.empty(n, dtype=np.int64); inv[rank] = np.arange(n)
+    assert sorted(rank.tolist()) == list(range(n))
+    for a, b in zip(inv[:-1], inv[1:]):
+        assert count[a] > count[b] or (count[a] == count[b] and a < b)
+    deg = np.diff(indptr)
+    long_rows = [v for v in range(n) if deg[v] >= params["min_degree"]]
+    assert len(long_rows) == rowbase.shape[0] - 1 and len(long_rows) > 0
+    # every edge of a long row exactly once, at its CSR position, with the rank of its source
+    assert sorted(epos.tolist()) == sorted(e for v in long_rows for e in range(indptr[v], indptr[v + 1]))
+    assert np.array_equal(ranks, rank[src[epos]])
+    row_of_edge = np.searchsorted(indptr, epos, side="right") - 1
+    hot = min(params["hot_lines"], n)
+    rest = max(int((count >= params["rest_min_count"]).sum()), hot)
+
+    def block(r):
+        if r < hot:
+            return 0
+        if r >= rest:
+            return 10 ** 9
+        return 1 + (r - hot) // params["block_lines"]
+
+    # pieces tile [0, E_b) in order; one row, one block each; blocks non-decreasing; capped length
+    pos, last_key, slots_seen = 0, (-1, -1), {}
+    order_rows = sorted(long_rows, key=lambda v: (sum(t <= deg[v] for t in thr), v))
+    for begin, length, slot, h in pieces.tolist():
+        assert begin == pos and 0 < length <= params["max_piece"]
+        pos += length
+        v = order_rows[h]
+        assert set(row_of_edge[begin:begin + length].tolist()) == {v}
+        blks = {block(int(r)) for r in ranks[begin:begin + length]}
+        assert len(blks) == 1
+        key = (blks.pop(), h)
+        assert key >= last_key                       # block-major, rows ascending inside a block
+        seg = ranks[begin:begin + length]
+        assert np.all(seg[1:] >= seg[:-1])
+        if key == last_key:                          # a run cut by max_piece: only the last piece may be short
+            assert prev_length == params["max_piece"] and ranks[begin] >= ranks[begin - 1]
+        last_key, prev_length = key, length
+        slots_seen.setdefault(h, []).append(slot)
+    assert pos == epos.shape[0]
+    for h, slots in slots_seen.items():
+        assert slots == list(range(rowbase[h], rowbase[h + 1]))
+    assert sorted(slots_seen) == list(range(len(long_rows)))
