@@ -652,42 +652,72 @@ __global__ void __launch_bounds__(kBlockThreads) piece_kernel(const PieceArgs a)
 }
 
 // Adds the partial lines of every long row in slot order (the block order of its pieces) and writes
-// the columns [0, fw) of the launch: one workgroup per row, a thread per column.
+// the columns [0, fw) of the launch.  Eight lanes own one (row, slice) pair, 16 bytes of the output
+// row each, so a wavefront finishes eight rows of a slice whose partial lines lie back to back.
 template <typename T>
 __global__ void __launch_bounds__(256) blk_finalize_kernel(const int32_t *__restrict__ rows, int64_t n_rows,
                                                            const uint32_t *__restrict__ rowbase,
-                                                           const float *__restrict__ partial, int64_t n_pieces,
+                                                           const float *__restrict__ partial, int64_t n_pieces, int n_slices,
                                                            const void *indptr, int ip64, int dst_mode, T *__restrict__ Y,
-                                                           int64_t ldy, int fw, int self_mode, const T *__restrict__ G,
-                                                           int64_t ldg, const int32_t *__restrict__ col_counts,
+                                                           int64_t ldy, int fw, int store_vec, int self_mode,
+                                                           const T *__restrict__ G, int64_t ldg,
+                                                           const int32_t *__restrict__ col_counts,
                                                            const float *__restrict__ bias, int relu) {
-    constexpr int LINE = 128 / int(sizeof(T));
-    const int64_t i = blockIdx.x;
-    if (i >= n_rows) return;
+    constexpr int VEC = 16 / int(sizeof(T));  // output columns per lane
+    constexpr int LINE = 8 * VEC;             // columns per slice = floats per partial line
+    const int64_t item = (int64_t(blockIdx.x) * blockDim.x + threadIdx.x) >> 3;
+    if (item >= n_rows * n_slices) return;
+    const int64_t i = item % n_rows;
+    const int slice = int(item / n_rows);
+    const int col0 = slice * LINE + int(threadIdx.x & 7) * VEC;
+    if (col0 >= fw) return;
     const int64_t row = rows[i];
     const int64_t p0 = rowbase[i], p1 = rowbase[i + 1];
-    const float ds = scale_of(dst_mode, load_ip(indptr, ip64, row + 1) - load_ip(indptr, ip64, row));
-    for (int colx = threadIdx.x; colx < fw; colx += blockDim.x) {
-        const float *__restrict__ src = partial + int64_t(colx / LINE) * n_pieces * LINE + (colx % LINE);
-        float sum = 0.0f;
-        int64_t p = p0;
-        for (; p + 4 <= p1; p += 4) {  // four loads in flight, added in slot order
-            const float v0 = __builtin_nontemporal_load(src + (p + 0) * LINE), v1 = __builtin_nontemporal_load(src + (p + 1) * LINE);
-            const float v2 = __builtin_nontemporal_load(src + (p + 2) * LINE), v3 = __builtin_nontemporal_load(src + (p + 3) * LINE);
-            sum = ((sum + v0) + v1) + v2;
-            sum += v3;
+    const float *__restrict__ src = partial + int64_t(slice) * n_pieces * LINE + int(threadIdx.x & 7) * VEC;
+    float sum[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) sum[k] = 0.0f;
+    auto load_line = [&](int64_t p, f32x4 (&v)[VEC / 4]) {
+#pragma unroll
+        for (int q = 0; q < VEC / 4; ++q) v[q] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(src + p * LINE) + q);
+    };
+    auto add_line = [&](const f32x4 (&v)[VEC / 4]) {
+#pragma unroll
+        for (int q = 0; q < VEC / 4; ++q) {
+            sum[4 * q] += v[q].x; sum[4 * q + 1] += v[q].y; sum[4 * q + 2] += v[q].z; sum[4 * q + 3] += v[q].w;
         }
-        for (; p < p1; ++p) sum += __builtin_nontemporal_load(src + p * LINE);
-        if (self_mode != kSelfNone) {
-            float xs[1];
-            VecIO<T, 1>::load(G + row * ldg + colx, xs);
-            sum = fmaf(self_mode == kSelfInvPlus1 ? scale_of(kScaleInvPlus1, col_counts[row]) : 1.0f, xs[0], sum);
-        }
-        float o[1] = {sum * ds};
-        if (bias) o[0] += bias[colx];
-        if (relu) o[0] = o[0] > 0.0f ? o[0] : 0.0f;
-        VecIO<T, 1>::store(Y + row * ldy + colx, o);
+    };
+    int64_t p = p0;
+    for (; p + 4 <= p1; p += 4) {  // four lines in flight, added in slot order
+        f32x4 v0[VEC / 4], v1[VEC / 4], v2[VEC / 4], v3[VEC / 4];
+        load_line(p, v0); load_line(p + 1, v1); load_line(p + 2, v2); load_line(p + 3, v3);
+        add_line(v0); add_line(v1); add_line(v2); add_line(v3);
     }
+    for (; p < p1; ++p) {
+        f32x4 v0[VEC / 4];
+        load_line(p, v0);
+        add_line(v0);
+    }
+    const int ncols = fw - col0 < VEC ? fw - col0 : VEC;
+    const float ds = scale_of(dst_mode, load_ip(indptr, ip64, row + 1) - load_ip(indptr, ip64, row));
+    const float self_cf = self_mode == kSelfInvPlus1 ? scale_of(kScaleInvPlus1, col_counts[row]) : 1.0f;
+    float o[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+        float v = sum[k];
+        if (k < ncols) {
+            if (self_mode != kSelfNone) {
+                float xs[1];
+                VecIO<T, 1>::load(G + row * ldg + col0 + k, xs);
+                v = fmaf(self_cf, xs[0], v);
+            }
+            v *= ds;
+            if (bias) v += bias[col0 + k];
+            if (relu) v = v > 0.0f ? v : 0.0f;
+        }
+        o[k] = v;
+    }
+    store_strip<T, VEC>(Y + row * ldy + col0, o, ncols, store_vec);
 }
 
 // Copies the gathered matrix into rows of whole 128-byte lines (plan-owned buffer), so that
@@ -1148,21 +1178,22 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
             pa.log2_slices = log2_s;
             const int64_t pblocks = ((bl.n_pieces + 8 * kWavesPerBlock - 1) / (8 * kWavesPerBlock)) << log2_s;
             if (pblocks > INT32_MAX) return GNN_ERR_UNSUPPORTED;
-            const dim3 pgrid(static_cast<unsigned>(pblocks)), fgrid(static_cast<unsigned>(bl.n_hot));
+            const int n_sl = 1 << log2_s;
+            const dim3 pgrid(static_cast<unsigned>(pblocks)), fgrid(static_cast<unsigned>((bl.n_hot * n_sl * 8 + 255) / 256));
             const int32_t *hot_rows = plan->row_perm + bl.hot_begin;
             if (o.dtype == GNN_F32) {
                 if (coef) piece_kernel<float, true><<<pgrid, kBlockThreads, 0, stream>>>(pa);
                 else piece_kernel<float, false><<<pgrid, kBlockThreads, 0, stream>>>(pa);
                 blk_finalize_kernel<float><<<fgrid, 256, 0, stream>>>(
-                    hot_rows, bl.n_hot, bl.rowbase, pa.partial, bl.n_pieces, indptr, o.indptr_is_64 ? 1 : 0, dst_mode,
-                    static_cast<float *>(out) + f0, ldy, int(fw), orig_self_mode, static_cast<const float *>(orig) + f0, ldx,
+                    hot_rows, bl.n_hot, bl.rowbase, pa.partial, bl.n_pieces, n_sl, indptr, o.indptr_is_64 ? 1 : 0, dst_mode,
+                    static_cast<float *>(out) + f0, ldy, int(fw), store_vec, orig_self_mode, static_cast<const float *>(orig) + f0, ldx,
                     plan->col_counts, bias ? bias + f0 : nullptr, relu);
             } else {
                 if (coef) piece_kernel<bf16_t, true><<<pgrid, kBlockThreads, 0, stream>>>(pa);
                 else piece_kernel<bf16_t, false><<<pgrid, kBlockThreads, 0, stream>>>(pa);
                 blk_finalize_kernel<bf16_t><<<fgrid, 256, 0, stream>>>(
-                    hot_rows, bl.n_hot, bl.rowbase, pa.partial, bl.n_pieces, indptr, o.indptr_is_64 ? 1 : 0, dst_mode,
-                    static_cast<bf16_t *>(out) + f0, ldy, int(fw), orig_self_mode, static_cast<const bf16_t *>(orig) + f0, ldx,
+                    hot_rows, bl.n_hot, bl.rowbase, pa.partial, bl.n_pieces, n_sl, indptr, o.indptr_is_64 ? 1 : 0, dst_mode,
+                    static_cast<bf16_t *>(out) + f0, ldy, int(fw), store_vec, orig_self_mode, static_cast<const bf16_t *>(orig) + f0, ldx,
                     plan->col_counts, bias ? bias + f0 : nullptr, relu);
             }
             if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
