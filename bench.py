@@ -47,16 +47,12 @@ def algorithmic_bytes(n, e, f, esz, ip_bytes, weighted, src_scaled):
     return b
 
 
-def read_traffic_note(workload):
-    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), if a
-    summary for this workload has been committed under profiles/."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
-    if not os.path.exists(path):
-        return None
-    for line in open(path):
-        if line.startswith("traffic_bytes_per_call"):
-            return float(line.split()[1])
-    return None
+def read_traffic_note(workload, widths):
+    """HBM-side bytes per call and L2 hit rate measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE,
+    TCC_*), from the summary that paper_2104_06700_amd.profile_summary wrote under profiles/ -- only if
+    that summary was measured on the kernel sources of this tree (it records their hash)."""
+    from paper_2104_06700_amd.profile_summary import read_traffic
+    return read_traffic(workload, list(widths))
 
 
 def calibrate(dev):
@@ -141,11 +137,12 @@ def cpu_baseline(el, widths, op_name, target_seconds=20.0):
             "one_core_sample": f"forward {op_name} at F={f0} on {len(one_rows)} sampled rows, {one_secs:.1f} s"}
 
 
-def measure(workload, steps, warmup, scale, dev, dump_graph=None, flush=False):
+def measure(workload, steps, warmup, scale, dev, dump_graph=None, flush=False, capture=False):
     """Setup + warm-up + the timed region for one workload; returns (result dict, host edge list factory).
     flush: overwrite a 1 GiB scratch buffer before every call (outside the call's events), so that
     workloads whose matrices fit the caches start every call cold; value and ms_per_step are then
-    the sums of the per-call event times instead of the wall clock over the steps."""
+    the sums of the per-call event times instead of the wall clock over the steps.
+    capture: also record one step into a HIP graph and time its replays (launch-bound workloads)."""
     w = synth.WORKLOADS[workload]
     widths = list(w["widths"])
     op_names = w["op"].split("+")
@@ -253,13 +250,38 @@ def measure(workload, steps, warmup, scale, dev, dump_graph=None, flush=False):
     all_bytes = sum(r["algorithmic_GB"] for r in call_rows)
     all_s = sum(r["ms"] for r in call_rows) * 1e-3
     achieved = all_bytes / all_s
-    traffic = read_traffic_note(workload) if scale == 1.0 else None
+    tnote = read_traffic_note(workload, widths * len(op_names)) if scale == 1.0 else {"traffic": None, "reason": "scaled run"}
+    traffic = tnote["traffic"]
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "traffic_GBs": None if traffic is None else round(traffic / (all_s / len(call_rows)) / 1e9, 1),
+                "traffic_note": tnote.get("reason") or f"rocprofv3 FETCH_SIZE + WRITE_SIZE per call, profiles/hbm_traffic_{workload}.txt "
+                                                       f"(kernel sources {tnote.get('source_hash')})",
+                "tcc_hit_pct": tnote.get("tcc_hit_pct"),
+                "gathered_bytes_per_call": round(sum(e * r["F"] * esz for r in call_rows) / len(call_rows)),
                 "kernel": "aggregate_kernel (all calls of one step: forward and backward at every width)",
                 "per": "call (= its aggregate_kernel launches + pad copy + hub finalisation)",
                 "launches_per_step": len(call_rows), "avg_launch_ms": round(all_s * 1e3 / len(call_rows), 4)}
+
+    replay = None
+    if capture:  # the same step as one captured graph: what is left when the launches cost nothing on the host
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for op_name, d, layer in calls:
+                    one_call(op_name, d, layer)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / steps
+        replay = {"ms_per_step": round(dt * 1e3, 4), "value": round(ef_step / dt / 1e9, 2), "unit": "GEF/s",
+                  "note": "one step captured into a HIP graph and replayed; same kernels, no per-call host work"}
 
     result = {
         "metric": "aggregation GEdge-features/s (edges*F/s) fwd+bwd; % of HBM peak GB/s",
@@ -275,6 +297,8 @@ def measure(workload, steps, warmup, scale, dev, dump_graph=None, flush=False):
         "setup_ms": {"graph_generation": round(t_gen * 1e3, 1), "csr_and_transpose": round(t_csr * 1e3, 1),
                      "plans_fwd_and_bwd": round(t_plan * 1e3, 1)},
     }
+    if replay is not None:
+        result["graph_replay"] = replay
     return result, (el, widths, op_names)
 
 
@@ -389,6 +413,45 @@ def measure_layers(workload, dev, reps=5):
                     "widths 100-256-256-47), Sections 6.2 and 6.3 -- other hardware and real data, context only"}
 
 
+def cpu_baseline_sampled(el, f, dtype, dev, n_rows=1_000_000):
+    """The oracle on a bounded sample of a workload whose host copy would not fit: `n_rows` uniformly
+    sampled destination rows become a compact sub-problem (their edges, the gathered vertices renumbered;
+    pure index plumbing on the generator's edge list) on which the oracle runs the forward sum and mean."""
+    import oracle
+    rng = np.random.default_rng(777)
+    rows = np.sort(rng.choice(el.n, size=min(n_rows, el.n), replace=False)).astype(np.int64)
+    rows_t = torch.from_numpy(rows).to(dev).to(el.dst.dtype)
+    lo = torch.searchsorted(el.dst, rows_t, right=False)
+    hi = torch.searchsorted(el.dst, rows_t, right=True)
+    cnt = hi - lo
+    indptr = torch.zeros(len(rows) + 1, dtype=torch.int64, device=dev)
+    indptr[1:] = torch.cumsum(cnt, 0)
+    total = int(indptr[-1])
+    owner = torch.repeat_interleave(torch.arange(len(rows), device=dev), cnt)
+    pos = lo[owner] + (torch.arange(total, device=dev) - indptr[owner])
+    used, inv = torch.unique(el.src[pos].long(), return_inverse=True)
+    del owner, pos
+    X = synth.normal_features(el.n, f, 100, device=dev, dtype=dtype)[used].float().cpu().numpy()
+    ip, ix = indptr.cpu().numpy(), inv.to(torch.int32).cpu().numpy()
+    threads = oracle.max_threads()
+    secs = 0.0
+    for op in (oracle.OP_SUM, oracle.OP_MEAN):
+        t0 = time.perf_counter()
+        oracle.aggregate_fwd(ip, ix, X, op=op, nthreads=threads)
+        secs += time.perf_counter() - t0
+    return {"value": round(2 * total * f / secs / 1e9, 4), "unit": "GEF/s", "cores": threads, "kind": "oracle",
+            "sample": f"SAMPLED: forward sum and forward mean at F={f} on {len(rows)} uniformly sampled rows ({total} edges, "
+                      f"{int(used.numel())} gathered vertices) of the same graph, {secs:.1f} s of CPU time, fp64 scalar loops, "
+                      f"OpenMP dynamic over rows"}
+
+
+BRIEF_KEYS = ("value", "unit", "ms_per_step", "steps", "dtype", "config", "roofline", "calls", "setup_ms", "graph_replay")
+
+
+def brief(res):
+    return {k: res[k] for k in BRIEF_KEYS if k in res}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -398,8 +461,8 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the graph (debugging only; invalid as a result)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-calibration", action="store_true")
-    ap.add_argument("--secondary", default="rmat_dense_wide",
-                    help="a second workload measured briefly in the same run and reported under 'secondary' ('' = none)")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the brief runs of the other four workloads reported under 'workloads'")
     ap.add_argument("--no-general-primitive", action="store_true",
                     help="skip the operator-table calls (gnn_ap_*) reported under 'general_primitive'")
     ap.add_argument("--no-layers", action="store_true",
@@ -423,25 +486,59 @@ def main():
         return
     el, widths, op_names = ctx
     e = el.e
-    if args.secondary and args.secondary != args.workload:
-        # one more workload in the same run, for context (not the headline value): fewer steps
-        torch.cuda.empty_cache()
-        sec, _ = measure(args.secondary, max(3, args.steps // 4), 1, 1.0, dev)
-        result["secondary"] = {k: sec[k] for k in ("value", "unit", "ms_per_step", "steps", "config", "calls", "setup_ms")}
-    if not args.no_general_primitive and args.scale == 1.0 and e <= 500_000_000:
-        torch.cuda.empty_cache()
+    full = args.scale == 1.0
+    if not args.no_cpu_baseline and e <= 500_000_000:
+        host_el = synth.EdgeList(el.n, el.src.cpu(), el.dst.cpu(), el.meta)
+    del el, ctx
+    torch.cuda.empty_cache()
+    if not args.no_general_primitive and full and e <= 500_000_000:
         result["general_primitive"] = measure_general_primitive(args.workload, dev)
         torch.cuda.empty_cache()
-    if not args.no_layers and args.scale == 1.0:
-        torch.cuda.empty_cache()
-        result["layers"] = [measure_layers(wl, dev) for wl in (args.workload, args.secondary) if wl in MODELS]
+    if not args.no_layers and full:
+        result["layers"] = [measure_layers(wl, dev) for wl in (args.workload, "rmat_dense_wide") if wl in MODELS]
         torch.cuda.empty_cache()
     if not args.no_calibration:
         result["ceilings"] = calibrate(dev)
+        # the on-chip ceiling next to the roofline: every gathered byte crosses from an L2 to a compute unit at
+        # least once; at the rate this kernel reaches on an L2-resident table that alone takes this share of a call
+        l2 = result["ceilings"]["gather_L2_resident_GBs"] * 1e9
+        rf = result["roofline"]
+        rf["on_chip_ceiling_frac"] = round(rf["gathered_bytes_per_call"] / l2 / (rf["avg_launch_ms"] * 1e-3), 4)
+        torch.cuda.empty_cache()
+    if not args.no_other_workloads and full:
+        # the other four workloads, briefly, so that every configuration has a figure from this very run
+        others = {}
+        few = max(3, args.steps // 4)
+        for name in synth.WORKLOADS:
+            if name == args.workload:
+                continue
+            torch.cuda.empty_cache()
+            if name == "er_tiny":
+                res, _ = measure(name, 200, 20, 1.0, dev, capture=True)
+                others[name] = brief(res)
+            elif name == "rmat_weighted_narrow":
+                res, _ = measure(name, few, 1, 1.0, dev)
+                others[name] = brief(res)
+                res, _ = measure(name, few, 1, 1.0, dev, flush=True)
+                others[name + " (caches flushed before every call)"] = brief(res)
+            elif name == "rmat_capacity":
+                res, ctx2 = measure(name, 2, 1, 1.0, dev)
+                others[name] = brief(res)
+                if not args.no_cpu_baseline:
+                    torch.cuda.empty_cache()
+                    w5 = synth.WORKLOADS[name]
+                    others[name]["cpu_baseline"] = cpu_baseline_sampled(ctx2[0], w5["widths"][0], torch.bfloat16, dev)
+                del ctx2
+            else:
+                res, _ = measure(name, few, 1, 1.0, dev)
+                others[name] = brief(res)
+            del res
+        result["workloads"] = others
+        torch.cuda.empty_cache()
     if not args.no_cpu_baseline and e > 500_000_000:
-        result["cpu_baseline"] = None  # the host copy of this workload alone is > 60 GB; see tests/test_gpu_capacity.py
+        result["cpu_baseline"] = None  # see 'workloads' for the sampled figure of such a workload when it is not the main one
     elif not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(synth.EdgeList(el.n, el.src.cpu(), el.dst.cpu(), el.meta), widths, op_names[0])
+        result["cpu_baseline"] = cpu_baseline(host_el, widths, op_names[0])
     else:
         result["cpu_baseline"] = None
     print(json.dumps(result))

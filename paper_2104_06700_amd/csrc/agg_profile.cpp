@@ -4,7 +4,9 @@
 // aggregation through the C ABI a few times, preceded by a 1 GiB streaming copy whose
 // counter readings calibrate FETCH_SIZE / WRITE_SIZE.
 //
-// usage: agg_profile DIR OP(0|1|2) REPS [noslice] F [F ...]      (fp32 features)
+// usage: agg_profile DIR OP(0|1|2|3) REPS [option ...] F [F ...]
+// options: "bf16" (features in bf16 from there on; default fp32), "weights" (an explicit fp32 weight
+// per edge, all equal, from there on),
 // "noslice" switches the XCD column slicing off for the widths that follow it; "flags=N" sets
 // gnn_opts.flags (GNN_FLAG_* bits) for the widths that follow it; "block=D,H,B,P,R" (anywhere) sets
 // the source-blocking parameters of both plans (min_degree, hot_lines, block_lines, max_piece,
@@ -83,38 +85,45 @@ int main(int argc, char **argv) {
         GCHECK(gnn_plan_set_blocking(pb, &bp));
     }
 
-    int flags = 0, max_slices = 0;
+    int flags = 0, max_slices = 0, esz = 4;
+    float *w = nullptr;
     for (int a = 4; a < argc; ++a) {
+        if (std::string(argv[a]) == "bf16") { esz = 2; continue; }
+        if (std::string(argv[a]) == "weights") {
+            if (!w) { CHECK(hipMalloc(&w, 4 * (size_t)E)); CHECK(hipMemset(w, 0x3c, 4 * (size_t)E)); }
+            continue;
+        }
         if (std::string(argv[a]) == "noslice") { flags = GNN_FLAG_NO_COLUMN_SLICES; continue; }
         if (std::string(argv[a]).rfind("flags=", 0) == 0) { flags = atoi(argv[a] + 6); continue; }
         if (std::string(argv[a]).rfind("slices=", 0) == 0) { max_slices = atoi(argv[a] + 7); continue; }
         if (std::string(argv[a]).rfind("block=", 0) == 0) continue;
         const long long F = atoll(argv[a]);
-        const size_t bytes = (size_t)N * F * 4;
+        const size_t bytes = (size_t)N * F * esz;
         void *X = nullptr, *Y = nullptr;
         CHECK(hipMalloc(&X, bytes)); CHECK(hipMalloc(&Y, bytes));
         CHECK(hipMemset(X, 0x3c, bytes));
         gnn_opts o{};
         o.indptr_is_64 = ip64;
+        o.dtype = esz == 2 ? GNN_BF16 : GNN_F32;
         o.flags = flags;
         o.max_slices = max_slices;
         o.plan = pf;
         hipEvent_t e0, e1;
         CHECK(hipEventCreate(&e0)); CHECK(hipEventCreate(&e1));
-        GCHECK(gnn_aggregate_fwd(indptr, (const int32_t *)indices, nullptr, X, Y, N, F, op, &o));  // warm-up
+        GCHECK(gnn_aggregate_fwd(indptr, (const int32_t *)indices, w, X, Y, N, F, op, &o));  // warm-up
         CHECK(hipEventRecord(e0, nullptr));
-        for (int r = 0; r < reps; ++r) GCHECK(gnn_aggregate_fwd(indptr, (const int32_t *)indices, nullptr, X, Y, N, F, op, &o));
+        for (int r = 0; r < reps; ++r) GCHECK(gnn_aggregate_fwd(indptr, (const int32_t *)indices, w, X, Y, N, F, op, &o));
         CHECK(hipEventRecord(e1, nullptr));
         CHECK(hipEventSynchronize(e1));
         float ms_f = 0; CHECK(hipEventElapsedTime(&ms_f, e0, e1));
         o.plan = pb;
-        GCHECK(gnn_aggregate_bwd(indptr_t, (const int32_t *)indices_t, nullptr, X, Y, N, F, op, &o));
+        GCHECK(gnn_aggregate_bwd(indptr_t, (const int32_t *)indices_t, w, X, Y, N, F, op, &o));
         CHECK(hipEventRecord(e0, nullptr));
-        for (int r = 0; r < reps; ++r) GCHECK(gnn_aggregate_bwd(indptr_t, (const int32_t *)indices_t, nullptr, X, Y, N, F, op, &o));
+        for (int r = 0; r < reps; ++r) GCHECK(gnn_aggregate_bwd(indptr_t, (const int32_t *)indices_t, w, X, Y, N, F, op, &o));
         CHECK(hipEventRecord(e1, nullptr));
         CHECK(hipEventSynchronize(e1));
         float ms_b = 0; CHECK(hipEventElapsedTime(&ms_b, e0, e1));
-        printf("N=%lld E=%lld F=%lld op=%d flags=%d slices<=%d fwd %.4f ms  bwd %.4f ms  (%.1f / %.1f GEF/s)\n", N, E, F, op, flags, max_slices, ms_f / reps,
+        printf("N=%lld E=%lld F=%lld %s%s op=%d flags=%d slices<=%d calls=%d fwd %.4f ms  bwd %.4f ms  (%.1f / %.1f GEF/s)\n", N, E, F, esz == 2 ? "bf16" : "fp32", w ? " weighted" : "", op, flags, max_slices, 2 * (reps + 1), ms_f / reps,
                ms_b / reps, E * F / (ms_f / reps) / 1e6, E * F / (ms_b / reps) / 1e6);
         CHECK(hipFree(X)); CHECK(hipFree(Y));
     }

@@ -79,6 +79,7 @@ struct gnn_plan {
     uint32_t *blk_epos = nullptr;     // [blk_n_edges] CSR position of each (the caller's per-edge streams are read there)
     int32_t *blk_pieces = nullptr;    // [blk_n_pieces * 4] (begin, length, partial slot, row index in the hot range)
     uint32_t *blk_rowbase = nullptr;  // [blk_n_hot + 1] first partial slot of each hot row
+    float *blk_edge_scale[3] = {nullptr, nullptr, nullptr};  // edge_scale[m] at blk_epos, i.e. in the order of blk_indices
     void *blk_partial = nullptr;      // fp32 partial sums of one launch: [slices][blk_n_pieces][floats per line]
     int64_t blk_partial_bytes = 0;
 };
@@ -92,6 +93,7 @@ struct gnn_plan {
 // second kernel adds in a fixed order.
 struct gnn_blocked_layout {
     bool active;
+    bool automatic;          // the plan chose to block by itself (no gnn_plan_set_blocking with a degree)
     int32_t first_bin;       // bins >= this are served by pieces
     int64_t hot_begin, n_hot, n_pieces;
     const int32_t *indices;  // block-major
@@ -104,6 +106,9 @@ struct gnn_blocked_layout {
 int gnn_plan_blocked(gnn_plan *plan, const void *indptr, hipStream_t stream, gnn_blocked_layout *out);
 // Makes plan->blk_partial large enough for `slices` column slices of `line_floats` floats per piece.
 int gnn_plan_blocked_partial(gnn_plan *plan, int slices, int line_floats);
+// The plan's per-edge factor stream `mode` (gnn_plan_edge_scale, which must have been built) in the order
+// of the block-major index array; built on first use (allocation).
+int gnn_plan_blocked_edge_scale(gnn_plan *plan, int mode, hipStream_t stream, const float **out);
 
 // Stable LSD radix sort of 32-bit (key, value) pairs on the low `bits` bits (graph.hip).  buf_k[0] /
 // buf_v[0] hold the input (first_keys, if given, replaces buf_k[0] as read-only input of the first

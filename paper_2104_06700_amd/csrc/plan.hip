@@ -491,9 +491,13 @@ extern "C" GNN_API int gnn_plan_prepare(gnn_plan *plan, const int32_t *indices, 
         }
     }
     const float *unused = nullptr;
-    if (op == GNN_MEAN && backward) rc = gnn_plan_edge_scale(plan, indices, 1, static_cast<hipStream_t>(stream), &unused);
-    if (op == GNN_GCN_SYM) rc = gnn_plan_edge_scale(plan, indices, 2, static_cast<hipStream_t>(stream), &unused);
-    if (op == GNN_SAGE_GCN && backward) rc = gnn_plan_edge_scale(plan, indices, 3, static_cast<hipStream_t>(stream), &unused);
+    const int mode = (op == GNN_MEAN && backward) ? 1 : (op == GNN_GCN_SYM ? 2 : ((op == GNN_SAGE_GCN && backward) ? 3 : 0));
+    if (mode) {
+        rc = gnn_plan_edge_scale(plan, indices, mode, static_cast<hipStream_t>(stream), &unused);
+        // ... and in the order of the source-blocked pieces, for the calls that read it there
+        if (rc == GNN_OK && plan->blk_decided && plan->blk_n_pieces > 0 && plan->n_edges > 0)
+            rc = gnn_plan_blocked_edge_scale(plan, mode, static_cast<hipStream_t>(stream), &unused);
+    }
     return rc;
 }
 
@@ -514,6 +518,7 @@ extern "C" GNN_API void gnn_plan_destroy(gnn_plan *plan) {
     (void)hipFree(plan->blk_pieces);
     (void)hipFree(plan->blk_rowbase);
     (void)hipFree(plan->blk_partial);
+    for (int i = 0; i < 3; ++i) (void)hipFree(plan->blk_edge_scale[i]);
     (void)hipFree(plan->row_perm);
     (void)hipFree(plan->col_counts);
     (void)hipFree(plan->chunks);

@@ -1,0 +1,296 @@
+"""Turns raw rocprofv3 output of the stand-alone profiling driver (agg_profile) into the short
+summaries kept under profiles/.
+
+Nothing here touches a GPU.  Input: a directory with one sub-directory per feature width, each
+holding the output directories of up to four rocprofv3 passes over the same agg_profile command
+plus the command's own output:
+
+    DIR/meta.txt                 workload, op, dtype, options, source hash, date, the commands run
+    DIR/F<width>/run.log         what agg_profile printed (its event timings)
+    DIR/F<width>/stats/          rocprofv3 --kernel-trace --stats
+    DIR/F<width>/fetch/          rocprofv3 --pmc FETCH_SIZE
+    DIR/F<width>/write/          rocprofv3 --pmc WRITE_SIZE
+    DIR/F<width>/tcc/            rocprofv3 --pmc TCC_HIT_sum TCC_MISS_sum TCC_REQ_sum
+
+Output: profiles/aggregate_kernels_<workload>.md (tables) and profiles/hbm_traffic_<workload>.txt
+(the figures bench.py prints as roofline.traffic, tagged with the hash of the kernel sources they
+were measured on, so that a stale file is recognised).
+
+    python -m paper_2104_06700_amd.profile_summary DIR [--out profiles]
+    python -m paper_2104_06700_amd.profile_summary --source-hash
+"""
+from __future__ import annotations
+
+import argparse
+import collections
+import csv
+import glob
+import hashlib
+import os
+import re
+import sys
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(PKG)
+
+# kernels that make up one aggregation call (everything else in a trace is once-per-plan setup)
+CALL_KERNELS = ("aggregate_kernel", "piece_kernel", "blk_finalize_kernel", "hub_finalize_kernel", "pad_rows_kernel",
+                "pad_scale_rows_kernel")
+CALIB_KERNEL = "copy16_kernel"
+CALIB_BYTES = 1 << 30  # the calibration copy reads 1 GiB and writes 1 GiB
+
+
+def source_hash() -> str:
+    """Hash of the kernel sources and the header: identifies what a counter run measured."""
+    h = hashlib.sha256()
+    files = sorted(glob.glob(os.path.join(PKG, "csrc", "*.hip")) + glob.glob(os.path.join(PKG, "csrc", "*.h")) +
+                   [os.path.join(ROOT, "include", "gnnagg.h")])
+    for f in files:
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def short_name(kernel: str) -> str:
+    """'void (anonymous namespace)::aggregate_kernel<float, 4, 1, false>((anonymous namespace)::AggArgs)'
+    -> 'aggregate_kernel<float, 4, 1, false>'."""
+    k = kernel.replace("(anonymous namespace)::", "").replace("void ", "").strip()
+    depth = 0
+    for i, ch in enumerate(k):
+        if ch == "<":
+            depth += 1
+        elif ch == ">":
+            depth -= 1
+        elif ch == "(" and depth == 0:
+            return k[:i]
+    return k[:60]
+
+
+def _find(d: str, pattern: str):
+    r = glob.glob(os.path.join(d, "**", pattern), recursive=True)
+    return r[0] if r else None
+
+
+def _counter_rows(d: str):
+    p = _find(d, "*counter_collection.csv")
+    return list(csv.DictReader(open(p))) if p else []
+
+
+def _per_kernel(rows, counter):
+    """{(kernel short name, grid): [values per dispatch]} for one counter."""
+    out = collections.defaultdict(list)
+    for r in rows:
+        if r["Counter_Name"] == counter:
+            out[(short_name(r["Kernel_Name"]), int(r["Grid_Size"]))].append(float(r["Counter_Value"]))
+    return out
+
+
+def _is_call_kernel(name: str) -> bool:
+    return any(name.startswith(k) for k in CALL_KERNELS)
+
+
+def read_meta(d: str) -> dict:
+    meta = {"commands": []}
+    p = os.path.join(d, "meta.txt")
+    if os.path.exists(p):
+        for line in open(p):
+            line = line.rstrip("\n")
+            if line.startswith("cmd: "):
+                meta["commands"].append(line[5:])
+            elif ": " in line:
+                k, v = line.split(": ", 1)
+                meta[k] = v
+    return meta
+
+
+def summarise_width(d: str) -> dict:
+    """All figures of one width directory."""
+    res = {"dir": d}
+    # the driver's own timing
+    log = os.path.join(d, "run.log")
+    res["driver"] = [line.strip() for line in open(log) if line.startswith("N=") or line.startswith("source blocks")] \
+        if os.path.exists(log) else []
+    m = re.search(r"fwd ([\d.]+) ms\s+bwd ([\d.]+) ms", " ".join(res["driver"]))
+    res["fwd_ms"], res["bwd_ms"] = (float(m.group(1)), float(m.group(2))) if m else (None, None)
+    m = re.search(r"N=(\d+) E=(\d+) F=(\d+) (\w+)( weighted)?", " ".join(res["driver"]))
+    if m:
+        res.update(N=int(m.group(1)), E=int(m.group(2)), F=int(m.group(3)), esz=2 if m.group(4) == "bf16" else 4,
+                   weighted=bool(m.group(5)))
+    # kernel trace: mean duration and number of dispatches per (kernel, grid)
+    trace = _find(os.path.join(d, "stats"), "*kernel_trace.csv")
+    durations = collections.defaultdict(list)
+    if trace:
+        for r in csv.DictReader(open(trace)):
+            grid = int(r["Grid_Size_X"]) * int(r.get("Grid_Size_Y", 1) or 1) * int(r.get("Grid_Size_Z", 1) or 1)
+            durations[(short_name(r["Kernel_Name"]), grid)].append(
+                (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e6)
+    res["durations"] = durations
+    # calls in each pass: the driver prints how many it made (forward and backward, warm-up included)
+    def calls_of(pass_name):
+        p = os.path.join(d, pass_name + ".log")
+        m2 = re.search(r"calls=(\d+)", open(p).read()) if os.path.exists(p) else None
+        return int(m2.group(1)) if m2 else None
+    n_calls = calls_of("stats")
+    res["n_calls"] = n_calls
+    counters = {}
+    for sub, names in (("fetch", ["FETCH_SIZE"]), ("write", ["WRITE_SIZE"]), ("tcc", ["TCC_HIT_sum", "TCC_MISS_sum", "TCC_REQ_sum"])):
+        rows = _counter_rows(os.path.join(d, sub))
+        for n in names:
+            counters[n] = _per_kernel(rows, n)
+    res["counters"] = counters
+    # calibration: what the counters read for the copy of known size
+    scale = {}
+    for n, true_kib in (("FETCH_SIZE", CALIB_BYTES / 1024), ("WRITE_SIZE", CALIB_BYTES / 1024)):
+        vals = [v for (k, _), vs in counters.get(n, {}).items() if k.startswith(CALIB_KERNEL) for v in vs]
+        scale[n] = (true_kib / (sum(vals) / len(vals))) if vals and sum(vals) > 0 else None
+    res["scale"] = scale
+    # per call totals over the kernels of a call
+    def per_call(counter, factor):
+        tot, seen = 0.0, False
+        for (k, _), vs in counters.get(counter, {}).items():
+            if _is_call_kernel(k):
+                tot += sum(vs)
+                seen = True
+        n = calls_of({"FETCH_SIZE": "fetch", "WRITE_SIZE": "write"}.get(counter, "tcc"))
+        return (tot * factor / n) if seen and n else None
+    fs, ws = scale["FETCH_SIZE"], scale["WRITE_SIZE"]
+    res["read_bytes_per_call"] = per_call("FETCH_SIZE", 1024.0 * fs) if fs else None
+    res["write_bytes_per_call"] = per_call("WRITE_SIZE", 1024.0 * ws) if ws else None
+    hit, miss, req = (per_call(c, 1.0) for c in ("TCC_HIT_sum", "TCC_MISS_sum", "TCC_REQ_sum"))
+    res["tcc"] = (hit, miss, req)
+    trace_ms = 0.0
+    for (k, _), vs in durations.items():
+        if _is_call_kernel(k):
+            trace_ms += sum(vs)
+    res["trace_ms_per_call"] = trace_ms / n_calls if n_calls else None
+    return res
+
+
+def algorithmic_bytes(n, e, f, esz, ip_bytes, weighted, src_scaled):
+    b = 2 * n * f * esz + 4 * e + (n + 1) * ip_bytes
+    if weighted:
+        b += 4 * e
+    if src_scaled:
+        b += 4 * n
+    return b
+
+
+def write_summary(d: str, out_dir: str) -> None:
+    meta = read_meta(d)
+    workload = meta.get("workload", os.path.basename(d.rstrip("/")).replace("prof_", ""))
+    widths = sorted((int(os.path.basename(p)[1:]), p) for p in glob.glob(os.path.join(d, "F*")) if os.path.isdir(p))
+    if not widths:
+        sys.exit(f"no F<width> directories under {d}")
+    results = [(f, summarise_width(p)) for f, p in widths]
+    ip_bytes = int(meta.get("indptr_bytes", 4))
+    lines = []
+    r0 = results[0][1]
+    lines.append(f"# Aggregation kernels on {workload} (N={r0.get('N')}, E={r0.get('E')}, op={meta.get('op', '?')}, "
+                 f"{'bf16' if r0.get('esz') == 2 else 'fp32'}{', explicit edge weights' if r0.get('weighted') else ''})")
+    lines.append("")
+    lines.append(f"Written by `python -m paper_2104_06700_amd.profile_summary` from rocprofv3 output; kernel sources "
+                 f"`{meta.get('source_hash', '?')}` (hash of csrc/ and the header), {meta.get('date', '?')}.")
+    lines.append("One agg_profile process per width and pass; a CALL = all kernels of one gnn_aggregate_fwd / _bwd "
+                 "(copy into the plan's layout, piece / row / tail launches, finalisation).  Commands, from the repository root "
+                 "on the MI355X box:")
+    lines.append("")
+    for c in meta["commands"]:
+        lines.append(f"    {c}")
+    lines.append("")
+    traffic_lines = [f"# HBM-side traffic of one aggregation call on {workload}: (FETCH_SIZE x scale + WRITE_SIZE x scale) bytes summed",
+                     "# over the kernels of a call, scale = 1 GiB / what the same counter reads for a 1 GiB copy in the same run.",
+                     f"# Written by paper_2104_06700_amd.profile_summary from {os.path.basename(d.rstrip('/'))}; see aggregate_kernels_{workload}.md.",
+                     f"source_hash {meta.get('source_hash', 'unknown')}"]
+    for f, r in results:
+        lines.append(f"## F = {f}")
+        lines.append("")
+        for t in r["driver"]:
+            lines.append(f"    {t}")
+        lines.append("")
+        lines.append("    kernel                              grid  dispatches   mean ms   FETCH_SIZE KiB   WRITE_SIZE KiB      TCC_REQ      TCC_HIT   hit %")
+        keys = sorted((k for k in r["durations"] if _is_call_kernel(k[0]) or k[0].startswith(CALIB_KERNEL)),
+                      key=lambda k: (-sum(r["durations"][k]), k))
+        for k in keys:
+            dur = r["durations"][k]
+            def mean(c):
+                v = r["counters"].get(c, {}).get(k)
+                return sum(v) / len(v) if v else None
+            fe, wr, rq, hi = mean("FETCH_SIZE"), mean("WRITE_SIZE"), mean("TCC_REQ_sum"), mean("TCC_HIT_sum")
+            fmt = lambda x, w: f"{x:{w},.0f}" if x is not None else " " * (w - 1) + "-"
+            hitp = f"{100.0 * hi / rq:6.1f}" if rq and hi is not None else "     -"
+            lines.append(f"    {k[0]:34s} {k[1]:>9d} {len(dur):>7d} {sum(dur) / len(dur):>10.3f} {fmt(fe, 16)} {fmt(wr, 16)} "
+                         f"{fmt(rq, 12)} {fmt(hi, 12)}  {hitp}")
+        lines.append("")
+        sc = r["scale"]
+        lines.append(f"    counter scale from the 1 GiB copy: FETCH_SIZE x {sc['FETCH_SIZE']:.3f}, WRITE_SIZE x {sc['WRITE_SIZE']:.3f}"
+                     if sc["FETCH_SIZE"] and sc["WRITE_SIZE"] else "    counter scale: calibration copy not found in this run")
+        if r.get("N") and r["read_bytes_per_call"] is not None and r["write_bytes_per_call"] is not None:
+            n, e, esz = r["N"], r["E"], r["esz"]
+            alg = algorithmic_bytes(n, e, f, esz, ip_bytes, r["weighted"], False)
+            gathered = e * f * esz
+            rd, wr = r["read_bytes_per_call"], r["write_bytes_per_call"]
+            ms = (r["fwd_ms"] + r["bwd_ms"]) / 2 if r["fwd_ms"] else None
+            hit, miss, req = r["tcc"]
+            hitp = 100.0 * hit / req if req else None
+            lines.append(f"    per call: L2-miss reads {rd / 1e9:.2f} GB + writes {wr / 1e9:.2f} GB = {(rd + wr) / 1e9:.2f} GB behind the L2s; "
+                         f"compulsory {alg / 1e9:.2f} GB ({(rd + wr) / alg:.1f}x); gathered {gathered / 1e9:.1f} GB "
+                         f"(reuse = gathered / fetched = {gathered / rd:.2f})")
+            if ms:
+                lines.append(f"    per call: {ms:.3f} ms by the driver's events ({r['trace_ms_per_call']:.3f} ms summed over the kernel trace): "
+                             f"{(rd + wr) / ms / 1e9:.2f} TB/s behind the L2s, {gathered / ms / 1e9:.2f} TB/s gathered, "
+                             f"{alg / ms / 1e9 / 8.0 * 100:.2f} % of the 8 TB/s peak on compulsory bytes"
+                             + (f"; L2 hit rate {hitp:.1f} %" if hitp is not None else ""))
+            traffic_lines.append(f"traffic_bytes_F{f}_call {rd + wr:.4e}")
+            if hitp is not None:
+                traffic_lines.append(f"tcc_hit_pct_F{f} {hitp:.2f}")
+            if ms:
+                traffic_lines.append(f"ms_F{f}_call {ms:.4f}")
+        lines.append("")
+    os.makedirs(out_dir, exist_ok=True)
+    with open(os.path.join(out_dir, f"aggregate_kernels_{workload}.md"), "w") as fh:
+        fh.write("\n".join(lines) + "\n")
+    with open(os.path.join(out_dir, f"hbm_traffic_{workload}.txt"), "w") as fh:
+        fh.write("\n".join(traffic_lines) + "\n")
+    print(f"wrote {out_dir}/aggregate_kernels_{workload}.md and hbm_traffic_{workload}.txt")
+
+
+def read_traffic(workload: str, widths) -> dict:
+    """What bench.py reports next to its roofline: the mean HBM-side bytes per call over the calls of a
+    step (two per width) and the L2 hit rate, or the reason why there is none."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return {"traffic": None, "reason": "no counter summary for this workload under profiles/"}
+    vals = {}
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        k, v = line.split()[:2]
+        vals[k] = v
+    if vals.get("source_hash") != source_hash():
+        return {"traffic": None, "reason": f"profiles/hbm_traffic_{workload}.txt was measured on other kernel sources "
+                                           f"({vals.get('source_hash')}, now {source_hash()})"}
+    try:
+        per = [float(vals[f"traffic_bytes_F{f}_call"]) for f in widths]
+    except KeyError as err:
+        return {"traffic": None, "reason": f"no counter run for width {err}"}
+    hits = [float(vals[f"tcc_hit_pct_F{f}"]) for f in widths if f"tcc_hit_pct_F{f}" in vals]
+    return {"traffic": sum(per) / len(per), "per_width": dict(zip(map(str, widths), per)),
+            "tcc_hit_pct": round(sum(hits) / len(hits), 2) if hits else None, "source_hash": vals["source_hash"]}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("dir", nargs="?")
+    ap.add_argument("--out", default=os.path.join(ROOT, "profiles"))
+    ap.add_argument("--source-hash", action="store_true")
+    args = ap.parse_args()
+    if args.source_hash:
+        print(source_hash())
+        return
+    if not args.dir:
+        ap.error("DIR is required")
+    write_summary(args.dir, args.out)
+
+
+if __name__ == "__main__":
+    main()
