@@ -137,7 +137,7 @@ def cpu_baseline(el, widths, op_name, target_seconds=20.0):
             "one_core_sample": f"forward {op_name} at F={f0} on {len(one_rows)} sampled rows, {one_secs:.1f} s"}
 
 
-def measure(workload, steps, warmup, scale, dev, dump_graph=None, flush=False, capture=False):
+def measure(workload, steps, warmup, scale, dev, dump_graph=None, flush=False, capture=False, relabel=None):
     """Setup + warm-up + the timed region for one workload; returns (result dict, host edge list factory).
     flush: overwrite a 1 GiB scratch buffer before every call (outside the call's events), so that
     workloads whose matrices fit the caches start every call cold; value and ms_per_step are then
@@ -152,6 +152,8 @@ def measure(workload, steps, warmup, scale, dev, dump_graph=None, flush=False, c
     # ---- setup (not timed as part of a step) ----
     t0 = time.perf_counter()
     el = synth.make_graph(workload, device=dev, scale=scale)
+    if relabel:  # the same graph under another vertex order (reuse study)
+        el = synth.relabel(el, relabel, seed=w["seed"])
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t0
     weights = synth.gcn_sym_edge_weights(el.dst, el.src, el.n) if w.get("weighted") else None
@@ -470,6 +472,9 @@ def main():
     ap.add_argument("--flush-cache", action="store_true",
                     help="overwrite a 1 GiB buffer before every call (for workloads that fit the caches); "
                          "value is then the sum of the calls' event times")
+    ap.add_argument("--relabel", default=None, choices=["degree", "rmat_prefix", "random"],
+                    help="rename the vertices of the workload's graph first (descending degree, the order of the R-MAT "
+                         "recursion, or a random order): the vertex-reordering axis of the reuse study")
     ap.add_argument("--dump-graph", default=None, metavar="DIR",
                     help="write the CSR and transposed CSR as raw arrays for the stand-alone profiling driver, then exit")
     args = ap.parse_args()
@@ -481,7 +486,8 @@ def main():
     torch.cuda.set_device(dev)
     gnn.load_library()
 
-    result, ctx = measure(args.workload, args.steps, args.warmup, args.scale, dev, args.dump_graph, args.flush_cache)
+    result, ctx = measure(args.workload, args.steps, args.warmup, args.scale, dev, args.dump_graph, args.flush_cache,
+                          relabel=args.relabel)
     if result is None:
         return
     el, widths, op_names = ctx

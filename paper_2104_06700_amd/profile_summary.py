@@ -254,6 +254,81 @@ def write_summary(d: str, out_dir: str) -> None:
     print(f"wrote {out_dir}/aggregate_kernels_{workload}.md and hbm_traffic_{workload}.txt")
 
 
+def write_bench_stats(d: str, out_dir: str) -> None:
+    """rocprofv3 --kernel-trace --stats of the bench command itself (DIR holds its output and bench.json,
+    the JSON line of the same run): the kernels of the aggregation calls, and whether their summed mean
+    agrees with the call time the JSON line reports."""
+    import json
+    stats = _find(d, "*kernel_stats.csv")
+    line = [l for l in open(os.path.join(d, "bench.json")) if l.startswith("{")][-1]
+    res = json.loads(line)
+    cmd = open(os.path.join(d, "cmd.txt")).read().strip() if os.path.exists(os.path.join(d, "cmd.txt")) else "?"
+    workload = res["config"]["workload"].split(":")[0]
+    rows = list(csv.DictReader(open(stats)))
+    n_calls = (res["steps"] + res["warmup"]) * res["roofline"]["launches_per_step"]
+    out = [f"# rocprofv3 kernel statistics of the bench command ({workload}, {res['steps']} steps + {res['warmup']} warm-up)", "",
+           "Written by `python -m paper_2104_06700_amd.profile_summary --bench-stats`.  Command (repository root, MI355X box):", "",
+           f"    {cmd}", "",
+           "    kernel                                      calls    total ms     mean ms      %"]
+    call_total = 0.0
+    for r in rows:
+        name = short_name(r["Name"])
+        if not _is_call_kernel(name):
+            continue
+        call_total += float(r["TotalDurationNs"]) / 1e6
+        out.append(f"    {name:42s} {int(r['Calls']):>6d} {float(r['TotalDurationNs']) / 1e6:>11.3f} {float(r['AverageNs']) / 1e6:>11.4f} "
+                   f"{float(r['Percentage']):>6.2f}")
+    out += ["", f"{n_calls} aggregation calls = ({res['steps']} + {res['warmup']}) steps x {res['roofline']['launches_per_step']} calls; "
+                f"the kernels above sum to {call_total:.3f} ms = {call_total / n_calls:.3f} ms per call.",
+            f"The JSON line of the same run: value {res['value']} {res['unit']}, {res['ms_per_step']} ms per step, mean call "
+            f"{res['roofline']['avg_launch_ms']} ms by events on the launch stream (`roofline.avg_launch_ms`; the unit the roofline is "
+            f"taken over is the call = its copy into the plan's layout + piece / row / tail launches + finalisation), "
+            f"roofline.frac {res['roofline']['frac']}.", "",
+            "Per call (events, ms): " + ", ".join(f"{c['dir']} F={c['F']} {c['ms']}" for c in res["calls"]), ""]
+    os.makedirs(out_dir, exist_ok=True)
+    path = os.path.join(out_dir, f"bench_kernel_stats_{workload}.md")
+    open(path, "w").write("\n".join(out))
+    print(f"wrote {path}")
+
+
+def write_reuse_study(d: str, out_dir: str) -> None:
+    """Reuse of gathered rows (the quantity of the paper's Table 3) per variant: DIR holds one directory per
+    variant (NN_name/F<width>/{run.log, fetch/, tcc/}, plus variant.txt and order.txt) and meta.txt."""
+    meta = read_meta(d)
+    workload = meta.get("workload", "?")
+    rows = []
+    for v in sorted(p for p in glob.glob(os.path.join(d, "*")) if os.path.isdir(p)):
+        fdirs = glob.glob(os.path.join(v, "F*"))
+        if not fdirs:
+            continue
+        r = summarise_width(fdirs[0])
+        name = os.path.basename(v).split("_", 1)[1].replace("_", " ")
+        args = open(os.path.join(v, "variant.txt")).read().strip()
+        order = open(os.path.join(v, "order.txt")).read().strip()
+        rows.append((name, order, args, r))
+    if not rows:
+        sys.exit(f"no variants under {d}")
+    r0 = rows[0][3]
+    gathered = r0["E"] * r0["F"] * r0["esz"]
+    out = [f"# Reuse of gathered rows on {workload} (N={r0['N']}, E={r0['E']}, F={r0['F']}, fp32 MEAN, forward and backward)", "",
+           f"Written by `python -m paper_2104_06700_amd.profile_summary --reuse-study`; kernel sources `{meta.get('source_hash')}`, "
+           f"{meta.get('date')}.  reuse = gathered bytes E*F*4 ({gathered / 1e9:.1f} GB) / bytes fetched past the L2s per call "
+           f"(FETCH_SIZE x the scale a 1 GiB copy gives in the same run, all kernels of a call); the ideal is the average degree "
+           f"{r0['E'] / r0['N']:.1f} (every row fetched once).  Commands:", ""]
+    out += [f"    {c}" for c in meta["commands"]]
+    out += ["", "    variant                                   vertex order   VARIANT arguments              ms/call   fetched GB   reuse   L2 hit %"]
+    for name, order, args, r in rows:
+        rd = r["read_bytes_per_call"]
+        hit, miss, req = r["tcc"]
+        ms = (r["fwd_ms"] + r["bwd_ms"]) / 2
+        out.append(f"    {name:41s} {order:14s} {args:28s} {ms:>9.3f} {rd / 1e9:>12.2f} {gathered / rd:>7.2f} {100.0 * hit / req:>10.1f}")
+    out.append("")
+    os.makedirs(out_dir, exist_ok=True)
+    path = os.path.join(out_dir, f"reuse_study_{workload}.md")
+    open(path, "w").write("\n".join(out))
+    print(f"wrote {path}")
+
+
 def read_traffic(workload: str, widths) -> dict:
     """What bench.py reports next to its roofline: the mean HBM-side bytes per call over the calls of a
     step (two per width) and the L2 hit rate, or the reason why there is none."""
@@ -283,13 +358,20 @@ def main():
     ap.add_argument("dir", nargs="?")
     ap.add_argument("--out", default=os.path.join(ROOT, "profiles"))
     ap.add_argument("--source-hash", action="store_true")
+    ap.add_argument("--reuse-study", action="store_true", help="DIR holds one directory per variant of the reuse study")
+    ap.add_argument("--bench-stats", action="store_true", help="DIR holds rocprofv3 --stats output of bench.py and its bench.json")
     args = ap.parse_args()
     if args.source_hash:
         print(source_hash())
         return
     if not args.dir:
         ap.error("DIR is required")
-    write_summary(args.dir, args.out)
+    if args.bench_stats:
+        write_bench_stats(args.dir, args.out)
+    elif args.reuse_study:
+        write_reuse_study(args.dir, args.out)
+    else:
+        write_summary(args.dir, args.out)
 
 
 if __name__ == "__main__":

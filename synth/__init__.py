@@ -13,6 +13,7 @@ from .graphs import (
     rmat_symmetric,
     small_random_multigraph,
     regular_random_neighbours,
+    relabel,
     to_csr_numpy,
 )
 from .features import uniform_features, normal_features, gcn_sym_edge_weights
@@ -20,7 +21,7 @@ from .workloads import WORKLOADS, make_graph, make_features
 
 __all__ = [
     "mix64", "uniform01", "EdgeList", "erdos_renyi_directed", "rmat_directed",
-    "rmat_symmetric", "small_random_multigraph", "regular_random_neighbours", "to_csr_numpy",
+    "rmat_symmetric", "small_random_multigraph", "regular_random_neighbours", "relabel", "to_csr_numpy",
     "uniform_features", "normal_features", "gcn_sym_edge_weights",
     "WORKLOADS", "make_graph", "make_features",
 ]

@@ -165,6 +165,52 @@ def rmat_symmetric(n: int, e: int, probs, seed: int, device="cpu", batch: int | 
                                           "symmetric": True})
 
 
+def _unscramble(x: torch.Tensor, scale: int, seed: int) -> torch.Tensor:
+    """Inverse of _scramble on [0, 2**scale)."""
+    mask = (1 << scale) - 1
+    half = (scale + 1) // 2
+    a1 = (stream_key(seed, 21) | 1) & mask
+    b1 = stream_key(seed, 22) & mask
+    a2 = (stream_key(seed, 23) | 1) & mask
+    b2 = stream_key(seed, 24) & mask
+    inv1 = pow(a1, -1, 1 << scale)
+    inv2 = pow(a2, -1, 1 << scale)
+    x = x ^ (x >> half)          # 2 * half >= scale: the xor-shift is its own inverse
+    x = ((x - b2) * inv2) & mask
+    x = x ^ (x >> half)
+    x = ((x - b1) * inv1) & mask
+    return x
+
+
+def relabel(el: EdgeList, kind: str, seed: int = 0) -> EdgeList:
+    """The same graph with its vertices renamed (and the edge list brought back into (dst, src)
+    order): what a vertex reordering does to an aggregation is a property of the input, so the
+    orders live here with the generators.
+      "degree":      by descending in-degree, equal degrees by old id
+      "rmat_prefix": the order of the R-MAT quadrant recursion (vertices sharing the leading bits of
+                     their pre-scramble id become neighbours); `seed` is the graph's seed
+      "random":      a seeded random permutation"""
+    n = el.n
+    dev = el.src.device
+    ids = torch.arange(n, dtype=torch.int64, device=dev)
+    if kind == "degree":
+        deg = torch.bincount(el.dst.long(), minlength=n)
+        order = torch.sort(-deg, stable=True).indices
+    elif kind == "rmat_prefix":
+        scale = max(1, math.ceil(math.log2(n)))
+        order = torch.sort(_unscramble(ids, scale, seed), stable=True).indices
+    elif kind == "random":
+        order = torch.sort(mix64(ids ^ stream_key(seed, 81)), stable=True).indices
+    else:
+        raise KeyError(kind)
+    new_id = torch.empty(n, dtype=torch.int64, device=dev)
+    new_id[order] = ids
+    keys = torch.sort(new_id[el.dst.long()] * n + new_id[el.src.long()]).values
+    meta = dict(el.meta)
+    meta["relabel"] = kind
+    return _edge_list_from_keys(keys, n, meta)
+
+
 def small_random_multigraph(n: int, e: int, seed: int, allow_dups: bool = True) -> EdgeList:
     """Tiny test graphs that MAY contain duplicate edges and self-loops (the
     aggregation definition is multigraph-safe and the tests exercise that)."""

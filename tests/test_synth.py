@@ -77,3 +77,21 @@ def test_generators_give_the_same_graph_on_cpu_and_gpu(name, scale):
         wa = synth.gcn_sym_edge_weights(a.dst, a.src, a.n)
         wb = synth.gcn_sym_edge_weights(b.dst, b.src, b.n)
         assert torch.equal(wa, wb.cpu())
+
+
+@pytest.mark.parametrize("kind", ["degree", "rmat_prefix", "random"])
+def test_relabel_keeps_the_graph(kind):
+    """A vertex reordering renames vertices and nothing else: same edge count, same degree
+    multiset, canonical order, still symmetric; the degree order really is by descending degree."""
+    el = synth.make_graph("rmat_sparse_stack", scale=0.002)
+    r = synth.relabel(el, kind, seed=3)
+    assert (r.n, r.e) == (el.n, el.e) and _canonical(r)
+    d0 = torch.bincount(el.dst.long(), minlength=el.n)
+    d1 = torch.bincount(r.dst.long(), minlength=el.n)
+    assert torch.equal(torch.sort(d0).values, torch.sort(d1).values)
+    assert torch.equal(d1, torch.bincount(r.src.long(), minlength=el.n))  # symmetric graph stays symmetric
+    if kind == "degree":
+        assert bool((d1[1:] <= d1[:-1]).all())
+    from synth.graphs import _scramble, _unscramble
+    x = torch.arange(1 << 13, dtype=torch.int64)
+    assert torch.equal(_unscramble(_scramble(x, 13, 7), 13, 7), x)
