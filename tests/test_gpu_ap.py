@@ -361,3 +361,39 @@ def test_scalar_edge_gradient_of_odd_widths_on_a_mid_size_graph(d, use_eid):
     message, sum and max, with and without an edge-id map."""
     el = synth.rmat_symmetric(80000, 3200000, (0.57, 0.19, 0.19, 0.05), 78)
     _check_all(el, None, d, 1, use_eid=use_eid, ties=False, seed=d, reduces={"sum": REDUCES["sum"], "max": REDUCES["max"]})
+
+
+def test_winner_scatter_spread_between_runs_is_bounded():
+    """gnn_ap_bwd_vertex_arg adds with fp32 hardware atomics, so the order of the additions, and with it
+    the last bits, may differ from run to run.  What cannot differ by more than rounding: two fp32 sums
+    of the same k terms in different orders are at most 2 (k - 1) 2^-24 sum|terms| apart.  Bound the
+    spread of five runs by exactly that, element by element, on a graph whose hubs win thousands of rows."""
+    el = synth.rmat_symmetric(20000, 600000, (0.57, 0.19, 0.19, 0.05), 5)
+    n, d = el.n, 24
+    dg = device_graph(el)
+    fV = synth.normal_features(n, d, 1).to(DEV)
+    dO = synth.normal_features(n, d, 2).to(DEV)
+    fO = torch.empty((n, d), device=DEV)
+    arg = torch.empty((n, d), dtype=torch.int32, device=DEV)
+    gnn.gnn_ap_fwd(dg.indptr, dg.indices, fV, None, fO, arg, n, d, gnn.GNN_BIN_COPY_LHS, gnn.GNN_RED_MAX, plan=dg.plan_fwd)
+    runs = []
+    for _ in range(5):
+        dfV = torch.full((n, d), float("nan"), device=DEV)
+        gnn.gnn_ap_bwd_vertex_arg(dg.indices, arg, dO, None, dfV, n, n, d, gnn.GNN_BIN_COPY_LHS)
+        torch.cuda.synchronize()
+        runs.append(dfV.double().cpu())
+    # per element: number of terms and sum of their magnitudes, from the winners (index plumbing in fp64 on the host)
+    a = arg.cpu().long()
+    won = a >= 0
+    src = dg.indices.cpu().long()[a.clamp(min=0)]
+    cols = torch.arange(d).expand(n, d)
+    flat = (src * d + cols)[won]
+    k = torch.zeros(n * d, dtype=torch.float64).index_add_(0, flat, torch.ones(flat.numel(), dtype=torch.float64)).reshape(n, d)
+    S = torch.zeros(n * d, dtype=torch.float64).index_add_(0, flat, dO.double().cpu().abs()[won]).reshape(n, d)
+    assert int(k.max()) > 1000                      # hubs do win thousands of rows here
+    bound = 2.0 * (k - 1).clamp(min=0) * 2.0 ** -24 * S
+    spread = torch.stack(runs).max(0).values - torch.stack(runs).min(0).values
+    assert bool((spread <= bound).all()), float((spread - bound).max())
+    assert bool((spread[k <= 1] == 0).all())        # a single term is exact whatever the order
+    print(f"winner scatter: largest spread between five runs {float(spread.max()):.3e} "
+          f"({float((spread / S.clamp(min=1e-30)).max()):.2e} of the magnitude sum)")
