@@ -185,6 +185,33 @@ GNN_API int gnn_aggregate_fwd_noalloc(const void *indptr, const int32_t *indices
 GNN_API int gnn_aggregate_bwd(const void *indptr_t, const int32_t *indices_t, const float *edge_w_t,
                       const void *dY, void *dX, int64_t N, int64_t F, int op, const gnn_opts *opts);
 
+/* Packed copies that the caller keeps (Section 3: full-batch training aggregates the SAME input
+ * features in every epoch).  A call on a large graph first copies the gathered matrix into the
+ * plan's layout: one table per 128-byte column slice, rows ordered by descending gather count,
+ * plus one dense table for a last slice of at most 64 bytes.  A caller whose matrix does not
+ * change between calls makes that copy once, into a buffer of its own, and gathers from it.
+ *
+ * gnn_packed_bytes: size of the copy of an [N, F] matrix; 0 when F is at most one line of 128
+ *   bytes or more than 256 lines (such rows are not laid out as tables) or an argument is invalid.
+ * gnn_pack_rows: writes the copy of X (row stride opts->ldx, 0 = F) into `packed` (device memory,
+ *   aligned to 128 bytes, packed_bytes >= gnn_packed_bytes, else GNN_ERR_INVALID_ARG).  `op` and
+ *   `backward` must be those of the calls that will gather from it: where the gathered rows carry
+ *   a factor (backward GNN_MEAN and GNN_SAGE_GCN, weight-less GNN_GCN_SYM) an fp32 copy holds the
+ *   rows already multiplied by it.  Needs opts->plan of the graph the calls run on (the row order
+ *   is that plan's), else GNN_ERR_UNSUPPORTED; a graph without edges is GNN_ERR_UNSUPPORTED too.
+ * gnn_aggregate_packed: gnn_aggregate_fwd (backward == 0: the arrays describe the graph) or
+ *   gnn_aggregate_bwd (backward != 0: the transposed graph) reading `packed` in place of the
+ *   matrix; same result as those calls with GNN_FLAG_FORCE_PADDED_COPY and max_slices = 8, bit
+ *   for bit, without their copy.  opts->ldx is ignored; the layout flags of opts are overridden.
+ * The buffer stays the caller's; the library keeps no reference to it after the call's work has
+ * run. */
+GNN_API int64_t gnn_packed_bytes(int64_t N, int64_t F, int dtype);
+GNN_API int gnn_pack_rows(const void *indptr, const int32_t *indices, const void *X, void *packed,
+                      int64_t packed_bytes, int64_t N, int64_t F, int op, int backward, const gnn_opts *opts);
+GNN_API int gnn_aggregate_packed(const void *indptr, const int32_t *indices, const float *edge_w,
+                      const void *packed, int64_t packed_bytes, void *Y, int64_t N, int64_t F, int op,
+                      int backward, const gnn_opts *opts);
+
 /* ------------------------------------- general aggregation primitive (fp32) */
 
 /* The operator table of Section 4.1 (Table 1).  x = f_V[u, j] of the source vertex, y = f_E[e, j]
@@ -287,13 +314,21 @@ typedef struct gnn_layer_opts {
     int32_t relu;        /* 1: rectifier after the bias; 0: identity (a last layer) */
     int32_t order;       /* 0: aggregate first iff F_in <= F_out, else transform first (the two linear
                             steps commute; the narrower rows are gathered); 1 / 2 force either */
-    int32_t reserved;
+    int32_t flags;       /* bit set of GNN_LAYER_*; 0 = defaults */
     void *stream;
     gnn_plan *plan;      /* REQUIRED: plan of the graph passed in the same call (forward plan for _fwd,
                             plan of the transposed graph for _bwd) */
     void *workspace;     /* _bwd only: device scratch of gnn_sage_layer_workspace_bytes(), 16-byte aligned */
     int64_t workspace_bytes;
 } gnn_layer_opts;
+
+/* Producer-side layouts: inside a layer the matrix that the aggregation gathers is often produced by the
+ * step before it (X W when transforming first; dH masked, or its product with W^T, in the backward
+ * pass).  Where the aggregation would first copy that matrix into the plan's layout (large graphs),
+ * the producing kernel writes it there directly.  FORCE: whatever the size of the graph (tests);
+ * NO: never (A/B measurements).  Results do not depend on it beyond rounding. */
+#define GNN_LAYER_FORCE_PRODUCER_LAYOUT 1
+#define GNN_LAYER_NO_PRODUCER_LAYOUT 2
 
 /* One layer of the paper's model: the aggregation (Section 6.1: sum of the in-neighbours' vectors
  * plus the vertex's own, divided by in-degree + 1) followed by the dense update (Section 6.3,

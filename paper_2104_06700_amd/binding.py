@@ -34,7 +34,8 @@ GNN_BIN_ADD, GNN_BIN_SUB, GNN_BIN_MUL, GNN_BIN_DIV, GNN_BIN_COPY_LHS, GNN_BIN_CO
 GNN_RED_SUM, GNN_RED_MAX, GNN_RED_MIN = range(3)
 
 EXPORTED_SYMBOLS = (
-    "gnn_aggregate_fwd", "gnn_aggregate_bwd", "gnn_aggregate_fwd_noalloc", "gnn_csr_from_sorted_coo", "gnn_transpose_csr",
+    "gnn_aggregate_fwd", "gnn_aggregate_bwd", "gnn_aggregate_fwd_noalloc", "gnn_packed_bytes", "gnn_pack_rows",
+    "gnn_aggregate_packed", "gnn_csr_from_sorted_coo", "gnn_transpose_csr",
     "gnn_validate_csr", "gnn_plan_default_params", "gnn_plan_create", "gnn_plan_destroy",
     "gnn_plan_sizes", "gnn_plan_export", "gnn_plan_gather_share", "gnn_plan_workspace_bytes", "gnn_plan_reserve",
     "gnn_plan_prepare", "gnn_plan_set_blocking", "gnn_plan_blocked_sizes", "gnn_plan_export_blocked",
@@ -66,7 +67,7 @@ class GnnApOpts(ctypes.Structure):
 
 class GnnLayerOpts(ctypes.Structure):
     _fields_ = [
-        ("indptr_is_64", ctypes.c_int32), ("relu", ctypes.c_int32), ("order", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("indptr_is_64", ctypes.c_int32), ("relu", ctypes.c_int32), ("order", ctypes.c_int32), ("flags", ctypes.c_int32),
         ("stream", ctypes.c_void_p), ("plan", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
         ("workspace_bytes", ctypes.c_int64),
     ]
@@ -106,6 +107,10 @@ def load_library() -> ctypes.CDLL:
         lib.gnn_aggregate_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, ctypes.POINTER(GnnOpts)]
         lib.gnn_aggregate_bwd.argtypes = lib.gnn_aggregate_fwd.argtypes
         lib.gnn_aggregate_fwd_noalloc.argtypes = lib.gnn_aggregate_fwd.argtypes
+        lib.gnn_packed_bytes.argtypes = [i64, i64, i32]
+        lib.gnn_packed_bytes.restype = i64
+        lib.gnn_pack_rows.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i32, ctypes.POINTER(GnnOpts)]
+        lib.gnn_aggregate_packed.argtypes = [vp, vp, vp, vp, i64, vp, i64, i64, i32, i32, ctypes.POINTER(GnnOpts)]
         lib.gnn_csr_from_sorted_coo.argtypes = [vp, i64, i64, vp, i32, vp]
         lib.gnn_transpose_csr.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, vp, vp]
         lib.gnn_validate_csr.argtypes = [vp, vp, i64, i64, i32, vp]
@@ -343,6 +348,44 @@ def gnn_aggregate_fwd_noalloc(indptr, indices, edge_w, X, Y, N, F, op, plan: Opt
         _ptr(indptr), _ptr(indices), _ptr(edge_w), _ptr(X), _ptr(Y), int(N), int(F), int(op), ctypes.byref(o)))
 
 
+def gnn_packed_bytes(N, F, dtype) -> int:
+    """Bytes of a caller-kept packed copy of an [N, F] matrix (0: such rows are not laid out as tables)."""
+    return int(load_library().gnn_packed_bytes(int(N), int(F), int(dtype)))
+
+
+def gnn_pack_rows(indptr, indices, X, packed, N, F, op, backward, plan: Plan, stream=None, ldx=None) -> None:
+    """Writes the packed copy of X that gnn_aggregate_packed gathers from (see include/gnnagg.h)."""
+    lib = load_library()
+    o = GnnOpts()
+    o.dtype = _dtype_code(X)
+    o.indptr_is_64 = _is64(indptr)
+    o.ldx = int(ldx if ldx is not None else (X.stride(0) if X.dim() == 2 and X.shape[0] > 1 else 0))
+    o.stream = _stream(stream)
+    o.plan = plan.handle if plan is not None else None
+    _call_allocating("gnn_pack_rows", lambda: lib.gnn_pack_rows(
+        _ptr(indptr), _ptr(indices), _ptr(X), _ptr(packed), packed.numel() * packed.element_size(), int(N), int(F),
+        int(op), int(bool(backward)), ctypes.byref(o)))
+
+
+def gnn_aggregate_packed(indptr, indices, edge_w, packed, Y, N, F, op, backward, plan: Plan, stream=None, workspace=None,
+                         ldy=None, flags=0) -> None:
+    """gnn_aggregate_fwd / _bwd reading a packed copy in place of the gathered matrix (see include/gnnagg.h)."""
+    lib = load_library()
+    o = GnnOpts()
+    o.dtype = _dtype_code(Y)
+    o.indptr_is_64 = _is64(indptr)
+    o.ldy = int(ldy if ldy is not None else (Y.stride(0) if Y.dim() == 2 and Y.shape[0] > 1 else 0))
+    o.stream = _stream(stream)
+    o.plan = plan.handle if plan is not None else None
+    o.flags = int(flags)
+    if workspace is not None:
+        o.workspace = workspace.data_ptr()
+        o.workspace_bytes = workspace.numel() * workspace.element_size()
+    _call_allocating("gnn_aggregate_packed", lambda: lib.gnn_aggregate_packed(
+        _ptr(indptr), _ptr(indices), _ptr(edge_w), _ptr(packed), packed.numel() * packed.element_size(), _ptr(Y),
+        int(N), int(F), int(op), int(bool(backward)), ctypes.byref(o)))
+
+
 def gnn_aggregate_bwd(indptr_t, indices_t, edge_w_t, dY, dX, N, F, op, plan: Optional[Plan] = None, stream=None,
                       workspace=None, ldx=None, ldy=None, flags=0, max_slices=0) -> None:
     """dX = adjoint of the forward map, over the transposed graph (see include/gnnagg.h)."""
@@ -467,8 +510,13 @@ def gnn_sage_layer_workspace_bytes(N, F_in, F_out, relu=True, order=0) -> int:
     return int(load_library().gnn_sage_layer_workspace_bytes(int(N), int(F_in), int(F_out), 1 if relu else 0, int(order)))
 
 
-def _layer_opts(indptr, plan, relu, order, stream, workspace=None) -> GnnLayerOpts:
+GNN_LAYER_FORCE_PRODUCER_LAYOUT = 1
+GNN_LAYER_NO_PRODUCER_LAYOUT = 2
+
+
+def _layer_opts(indptr, plan, relu, order, stream, workspace=None, flags=0) -> GnnLayerOpts:
     o = GnnLayerOpts()
+    o.flags = int(flags)
     o.indptr_is_64 = _is64(indptr)
     o.relu = 1 if relu else 0
     o.order = int(order)
@@ -480,22 +528,22 @@ def _layer_opts(indptr, plan, relu, order, stream, workspace=None) -> GnnLayerOp
     return o
 
 
-def gnn_sage_layer_fwd(indptr, indices, X, W, bias, saved, H, plan: Plan, relu=True, order=0, stream=None) -> None:
+def gnn_sage_layer_fwd(indptr, indices, X, W, bias, saved, H, plan: Plan, relu=True, order=0, stream=None, flags=0) -> None:
     """H = act(aggregate(X) W + b), one GraphSAGE layer (see include/gnnagg.h)."""
     _f32(X, W, bias, saved, H)
     _dense(X, W, bias, saved, H)
-    o = _layer_opts(indptr, plan, relu, order, stream)
+    o = _layer_opts(indptr, plan, relu, order, stream, flags=flags)
     _call_allocating("gnn_sage_layer_fwd", lambda: load_library().gnn_sage_layer_fwd(
         _ptr(indptr), _ptr(indices), _ptr(X), _ptr(W), _ptr(bias), _ptr(saved), _ptr(H), int(X.shape[0]), int(W.shape[0]),
         int(W.shape[1]), ctypes.byref(o)))
 
 
 def gnn_sage_layer_bwd(indptr_t, indices_t, X, W, saved, H, dH, dX, dW, db, plan: Plan, workspace, relu=True, order=0,
-                       stream=None) -> None:
+                       stream=None, flags=0) -> None:
     """Gradients of one layer over the transposed graph (see include/gnnagg.h)."""
     _f32(X, W, saved, H, dH, dX, dW, db)
     _dense(X, W, saved, H, dH, dX, dW, db)
-    o = _layer_opts(indptr_t, plan, relu, order, stream, workspace)
+    o = _layer_opts(indptr_t, plan, relu, order, stream, workspace, flags=flags)
     _call_allocating("gnn_sage_layer_bwd", lambda: load_library().gnn_sage_layer_bwd(
         _ptr(indptr_t), _ptr(indices_t), _ptr(X), _ptr(W), _ptr(saved), _ptr(H), _ptr(dH), _ptr(dX), _ptr(dW), _ptr(db),
         int(X.shape[0]), int(W.shape[0]), int(W.shape[1]), ctypes.byref(o)))

@@ -302,12 +302,35 @@ __device__ __forceinline__ int64_t load_ip(const void *indptr, int ip64, int64_t
                 : static_cast<int64_t>(static_cast<const int32_t *>(indptr)[i]);
 }
 
-__device__ __forceinline__ float scale_of(int mode, int64_t deg) {
-    if (mode == kScaleInvPlus1) return 1.0f / static_cast<float>(deg + 1);
-    float d = static_cast<float>(deg > 1 ? deg : 1);
-    if (mode == kScaleInv) return 1.0f / d;
-    if (mode == kScaleRsqrt) return 1.0f / sqrtf(d);
-    return 1.0f;
+__device__ __forceinline__ float scale_of(int mode, int64_t deg) { return gnn_row_factor(mode, deg); }
+
+// The own-row term of a finalisation kernel reads the caller's matrix G, or -- when a producer wrote the
+// gathered matrix straight into the plan's layout and no row-major copy exists -- that layout.
+struct OwnRowSrc {
+    const void *G;        // row-major [N, ldg], already offset to the first column of the launch; nullptr: use the layout
+    int64_t ldg;
+    const void *tbl;      // slice tables
+    int64_t table_stride;
+    int32_t main_cols;
+    const void *tail;
+    int64_t tail_ld;
+    const int32_t *rank;
+    int32_t col_off;      // first column of the launch within the matrix
+};
+template <typename T>
+__device__ __forceinline__ float own_row_value(const OwnRowSrc &o, int64_t row, int colx) {
+    constexpr int LINE = 128 / int(sizeof(T));
+    float xs[1];
+    if (o.G) {
+        VecIO<T, 1>::load(static_cast<const T *>(o.G) + row * o.ldg + colx, xs);
+    } else {
+        const int col = o.col_off + colx;
+        const int64_t r = o.rank[row];
+        const T *q = col < o.main_cols ? static_cast<const T *>(o.tbl) + (col / LINE) * o.table_stride + r * LINE + col % LINE
+                                       : static_cast<const T *>(o.tail) + r * o.tail_ld + (col - o.main_cols);
+        VecIO<T, 1>::load(q, xs);
+    }
+    return xs[0];
 }
 
 // ---------------------------------------------------------------- main kernel
@@ -537,8 +560,7 @@ __global__ void __launch_bounds__(256) hub_finalize_kernel(const int32_t *__rest
                                                            const int64_t *__restrict__ piece_offsets,
                                                            const float *__restrict__ partial, const void *indptr,
                                                            int ip64, int dst_mode, T *__restrict__ Y, int64_t ldy,
-                                                           int F, int64_t ldp, int self_mode,
-                                                           const T *__restrict__ G, int64_t ldg,
+                                                           int F, int64_t ldp, int self_mode, const OwnRowSrc own,
                                                            const int32_t *__restrict__ col_counts,
                                                            const float *__restrict__ bias, int relu, int col_begin) {
     const int64_t i = blockIdx.x;
@@ -549,11 +571,9 @@ __global__ void __launch_bounds__(256) hub_finalize_kernel(const int32_t *__rest
     for (int colx = col_begin + threadIdx.x; colx < F; colx += blockDim.x) {
         float sum = 0.0f;
         for (int64_t p = p0; p < p1; ++p) sum += partial[p * ldp + colx];
-        if (self_mode != kSelfNone) {
-            float xs[1];
-            VecIO<T, 1>::load(G + row * ldg + colx, xs);
-            sum = fmaf(self_mode == kSelfInvPlus1 ? scale_of(kScaleInvPlus1, col_counts[row]) : 1.0f, xs[0], sum);
-        }
+        if (self_mode != kSelfNone)
+            sum = fmaf(self_mode == kSelfInvPlus1 ? scale_of(kScaleInvPlus1, col_counts[row]) : 1.0f,
+                       own_row_value<T>(own, row, colx), sum);
         float o[1] = {sum * ds};
         if (bias) o[0] += bias[colx];
         if (relu) o[0] = o[0] > 0.0f ? o[0] : 0.0f;
@@ -659,7 +679,7 @@ __global__ void __launch_bounds__(256) blk_finalize_kernel(const int32_t *__rest
                                                            const float *__restrict__ partial, int64_t n_pieces, int n_slices,
                                                            const void *indptr, int ip64, int dst_mode, T *__restrict__ Y,
                                                            int64_t ldy, int fw, int store_vec, int self_mode,
-                                                           const T *__restrict__ G, int64_t ldg,
+                                                           const OwnRowSrc own,
                                                            const int32_t *__restrict__ col_counts,
                                                            const float *__restrict__ bias, int relu) {
     constexpr int VEC = 16 / int(sizeof(T));  // output columns per lane
@@ -705,11 +725,7 @@ __global__ void __launch_bounds__(256) blk_finalize_kernel(const int32_t *__rest
     for (int k = 0; k < VEC; ++k) {
         float v = sum[k];
         if (k < ncols) {
-            if (self_mode != kSelfNone) {
-                float xs[1];
-                VecIO<T, 1>::load(G + row * ldg + col0 + k, xs);
-                v = fmaf(self_cf, xs[0], v);
-            }
+            if (self_mode != kSelfNone) v = fmaf(self_cf, own_row_value<T>(own, row, col0 + k), v);
             v *= ds;
             if (bias) v += bias[col0 + k];
             if (relu) v = v > 0.0f ? v : 0.0f;
@@ -857,7 +873,12 @@ constexpr int kMaxPass = 8;
 // nothing (gnn_aggregate_fwd_noalloc); else into the plan's or the caller's workspace.
 int run_aggregate(const void *indptr, const int32_t *indices, const float *w, const void *gathered, void *out,
                   int64_t N, int64_t F, int op, const gnn_opts *opts_in, bool backward, const float *bias = nullptr,
-                  int relu = 0, bool no_alloc = false) {
+                  int relu = 0, bool no_alloc = false, bool prepacked = false, void *ext_tables = nullptr,
+                  int64_t ext_bytes = 0, bool pack_only = false) {
+    // prepacked: the gathered matrix already lies in the plan's layout (written there by a producer, see
+    // gnn_packed_target_for, or by an earlier pack_only call); `gathered` is not read, no copy is made.
+    // ext_tables: that layout lives in the caller's buffer of ext_bytes instead of the plan's.
+    // pack_only: write the layout from `gathered` and return.
     gnn_opts o{};
     if (opts_in) o = *opts_in;
     if (no_alloc) {
@@ -873,8 +894,12 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
     if (o.max_slices != 0 && o.max_slices != 1 && o.max_slices != 2 && o.max_slices != 4 && o.max_slices != 8)
         return GNN_ERR_INVALID_ARG;
     if (N == 0 || F == 0) return GNN_OK;
-    if (!indptr || !gathered || !out) return GNN_ERR_INVALID_ARG;
+    if (!indptr || (!gathered && !prepacked) || !out) return GNN_ERR_INVALID_ARG;
     if (N > INT32_MAX || F > INT32_MAX) return GNN_ERR_INVALID_ARG;
+    if ((prepacked || pack_only) && !o.plan) return GNN_ERR_UNSUPPORTED;
+    if (prepacked && !ext_tables && (o.dtype != GNN_F32 || w)) return GNN_ERR_INVALID_ARG;
+    if (prepacked && pack_only) return GNN_ERR_INVALID_ARG;
+    if (prepacked) { gathered = nullptr; o.ldx = 0; }
     const int64_t ldx = o.ldx ? o.ldx : F, ldy = o.ldy ? o.ldy : F;
     if (ldx < F || ldy < F) return GNN_ERR_INVALID_ARG;
     gnn_plan *plan = o.plan;
@@ -913,6 +938,10 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
     const gnn_layout layout = gnn_choose_layout(plan, N, F, esz, ldx, reinterpret_cast<uintptr_t>(gathered) % 128 == 0,
                                                 o.flags, o.max_slices, /*allow_tail=*/o.max_slices != 1,
                                                 /*scaled_source=*/src_mode != kScaleNone);
+    // what a producer can write into: the slice tables in rank order (the layout gnn_packed_target_for describes)
+    if ((prepacked || pack_only) &&
+        !(layout.padded_copy && layout.slice_major && !(o.flags & GNN_FLAG_NO_RANK_ORDER) && plan->n_edges > 0))
+        return ext_tables ? GNN_ERR_UNSUPPORTED : GNN_ERR_INVALID_ARG;
     const bool slices_wanted = layout.slices_wanted;
     // the caller's matrix stays the source of the own-row term of the hub rows (hub_finalize_kernel)
     const void *orig = gathered;
@@ -921,9 +950,18 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
     bool slice_major = false;  // the copy holds one table per 128-byte column slice
     gnn_rank_layout rl{};  // rank layout of the copy (see gnn_plan)
     const int32_t *rank = nullptr, *rank_indices = nullptr;
+    void *tables = nullptr;  // the copy: the plan's buffer or the caller's
+    bool factor_in_tables = false;
     if (layout.padded_copy) {
-        int rc = gnn_plan_padded(plan, layout.bytes);
-        if (rc != GNN_OK) return rc;
+        int rc = GNN_OK;
+        if (ext_tables) {
+            if (ext_bytes < layout.bytes || reinterpret_cast<uintptr_t>(ext_tables) % 128) return GNN_ERR_INVALID_ARG;
+            tables = ext_tables;
+        } else {
+            rc = gnn_plan_padded(plan, layout.bytes);
+            if (rc != GNN_OK) return rc;
+            tables = plan->padded;
+        }
         if (!(o.flags & GNN_FLAG_NO_RANK_ORDER) && plan->n_edges > 0) {
             rc = gnn_plan_rank_indices(plan, indptr, indices, (o.flags & GNN_FLAG_FORCE_COLD_HINTS) != 0, stream, &rl);
             if (rc != GNN_OK) return rc;
@@ -931,6 +969,8 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
             rank_indices = rl.indices;
         }
         const bool scale_in_copy = esz == 4 && src_mode != kScaleNone;  // fp32: the factor of the gathered rows goes into the copy
+        factor_in_tables = scale_in_copy;
+        if ((prepacked || pack_only) && !rank) return GNN_ERR_UNSUPPORTED;
         const int copy_mode = src_mode;
         // copies `ncols` columns starting at `src` into rows of stride dst_ld, with the widest chunks the source allows
         auto copy_part = [&](const char *src, int64_t ncols, char *dst, int64_t dst_ld, int64_t tstride) -> hipError_t {
@@ -952,13 +992,15 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
             return launch_pad<uint16_t>(src, src_ld_bytes, dst, dst_ld_bytes, N, row_bytes, stream, rank, tstride * esz);
         };
         const int64_t main_cols = F - layout.tail_elems;
-        char *dst = static_cast<char *>(plan->padded);
-        if (copy_part(static_cast<const char *>(gathered), main_cols, dst, layout.ld_pad, layout.table_stride) != hipSuccess)
+        char *dst = static_cast<char *>(tables);
+        if (!prepacked &&
+            copy_part(static_cast<const char *>(gathered), main_cols, dst, layout.ld_pad, layout.table_stride) != hipSuccess)
             return GNN_ERR_LAUNCH;
         if (layout.tail_elems > 0) {
             // behind the main part, a multiple of 128 bytes into the buffer
             char *tail_dst = dst + (layout.slice_major ? layout.main_lines * layout.table_stride : N * layout.ld_pad) * esz;
-            if (copy_part(static_cast<const char *>(gathered) + main_cols * esz, layout.tail_elems, tail_dst, layout.tail_ld, 0) != hipSuccess)
+            if (!prepacked &&
+                copy_part(static_cast<const char *>(gathered) + main_cols * esz, layout.tail_elems, tail_dst, layout.tail_ld, 0) != hipSuccess)
                 return GNN_ERR_LAUNCH;
             tail_table = tail_dst;
         }
@@ -966,7 +1008,8 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
             src_mode = kScaleNone;
             if (self_mode == kSelfInvPlus1) self_mode = kSelfPlain;  // the own row is already scaled
         }
-        gathered = plan->padded;
+        if (pack_only) return GNN_OK;
+        gathered = tables;
         ldg = layout.ld_pad;
         padded = true;
         slice_major = layout.slice_major;
@@ -1119,6 +1162,25 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
             if (rc != GNN_OK) return rc;
         }
     }
+    // Own-row term of the finalisation kernels: from the caller's matrix, or from the plan's layout when a
+    // producer wrote the matrix there (then already multiplied by the factor the rows carry).
+    const int fin_self_mode = (prepacked && factor_in_tables && orig_self_mode == kSelfInvPlus1) ? int(kSelfPlain) : orig_self_mode;
+    auto own_row_src = [&](int64_t f0) {
+        OwnRowSrc s{};
+        if (orig) {
+            s.G = static_cast<const char *>(orig) + f0 * esz;
+            s.ldg = ldx;
+        } else {
+            s.tbl = tables;
+            s.table_stride = layout.table_stride;
+            s.main_cols = int32_t(F - layout.tail_elems);
+            s.tail = tail_table;
+            s.tail_ld = layout.tail_ld;
+            s.rank = rank;
+            s.col_off = int32_t(f0);
+        }
+        return s;
+    };
     bool plain_hub_columns = false;   // some launch left its hub rows to hub_finalize_kernel
     int64_t plain_hub_col_begin = F;  // ... from this column on
 
@@ -1194,19 +1256,20 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
             const int n_sl = 1 << log2_s;
             const dim3 pgrid(static_cast<unsigned>(pblocks)), fgrid(static_cast<unsigned>((bl.n_hot * n_sl * 8 + 255) / 256));
             const int32_t *hot_rows = plan->row_perm + bl.hot_begin;
+            const OwnRowSrc own = own_row_src(f0);
             if (o.dtype == GNN_F32) {
                 if (coef) piece_kernel<float, true><<<pgrid, kBlockThreads, 0, stream>>>(pa);
                 else piece_kernel<float, false><<<pgrid, kBlockThreads, 0, stream>>>(pa);
                 blk_finalize_kernel<float><<<fgrid, 256, 0, stream>>>(
                     hot_rows, bl.n_hot, bl.rowbase, pa.partial, bl.n_pieces, n_sl, indptr, o.indptr_is_64 ? 1 : 0, dst_mode,
-                    static_cast<float *>(out) + f0, ldy, int(fw), store_vec, orig_self_mode, static_cast<const float *>(orig) + f0, ldx,
+                    static_cast<float *>(out) + f0, ldy, int(fw), store_vec, fin_self_mode, own,
                     plan->col_counts, bias ? bias + f0 : nullptr, relu);
             } else {
                 if (coef) piece_kernel<bf16_t, true><<<pgrid, kBlockThreads, 0, stream>>>(pa);
                 else piece_kernel<bf16_t, false><<<pgrid, kBlockThreads, 0, stream>>>(pa);
                 blk_finalize_kernel<bf16_t><<<fgrid, 256, 0, stream>>>(
                     hot_rows, bl.n_hot, bl.rowbase, pa.partial, bl.n_pieces, n_sl, indptr, o.indptr_is_64 ? 1 : 0, dst_mode,
-                    static_cast<bf16_t *>(out) + f0, ldy, int(fw), store_vec, orig_self_mode, static_cast<const bf16_t *>(orig) + f0, ldx,
+                    static_cast<bf16_t *>(out) + f0, ldy, int(fw), store_vec, fin_self_mode, own,
                     plan->col_counts, bias ? bias + f0 : nullptr, relu);
             }
             if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
@@ -1242,13 +1305,13 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         if (o.dtype == GNN_F32)
             hub_finalize_kernel<float><<<grid, 256, 0, stream>>>(plan->row_perm + hub_begin, plan->n_hub_rows, plan->hub_chunk_offsets,
                                                                  partial, indptr, o.indptr_is_64 ? 1 : 0, dst_mode,
-                                                                 static_cast<float *>(out), ldy, int(F), gnn_partial_ld(F), orig_self_mode,
-                                                                 static_cast<const float *>(orig), ldx, plan->col_counts, bias, relu, int(plain_hub_col_begin));
+                                                                 static_cast<float *>(out), ldy, int(F), gnn_partial_ld(F), fin_self_mode,
+                                                                 own_row_src(0), plan->col_counts, bias, relu, int(plain_hub_col_begin));
         else
             hub_finalize_kernel<bf16_t><<<grid, 256, 0, stream>>>(plan->row_perm + hub_begin, plan->n_hub_rows, plan->hub_chunk_offsets,
                                                                   partial, indptr, o.indptr_is_64 ? 1 : 0, dst_mode,
-                                                                  static_cast<bf16_t *>(out), ldy, int(F), gnn_partial_ld(F), orig_self_mode,
-                                                                  static_cast<const bf16_t *>(orig), ldx, plan->col_counts, bias, relu, int(plain_hub_col_begin));
+                                                                  static_cast<bf16_t *>(out), ldy, int(F), gnn_partial_ld(F), fin_self_mode,
+                                                                  own_row_src(0), plan->col_counts, bias, relu, int(plain_hub_col_begin));
         if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
     }
     return GNN_OK;
@@ -1269,6 +1332,90 @@ int gnn_pad_rows_f32(const float *src, int64_t ld_src, float *dst, int64_t ld_ds
     else
         err = launch_pad<uint32_t>(src, src_ld_bytes, dst, dst_ld_bytes, N, row_bytes, stream);
     return err == hipSuccess ? GNN_OK : GNN_ERR_LAUNCH;
+}
+
+int gnn_packed_target_for(gnn_plan *plan, const void *indptr, const int32_t *indices, int64_t N, int64_t F, int op, bool backward,
+                          bool force, hipStream_t stream, gnn_packed_target *out) {
+    *out = gnn_packed_target{};
+    if (!plan || !indptr || N <= 0 || F <= 0 || plan->n_rows != N || plan->n_edges <= 0) return GNN_OK;
+    int src_mode = kScaleNone;
+    if (op == GNN_MEAN && backward) src_mode = kScaleInv;
+    else if (op == GNN_GCN_SYM) src_mode = kScaleRsqrt;
+    else if (op == GNN_SAGE_GCN && backward) src_mode = kScaleInvPlus1;
+    const gnn_layout layout = gnn_choose_layout(plan, N, F, 4, F, true, force ? GNN_FLAG_FORCE_PADDED_COPY : 0, force ? 8 : 0,
+                                                /*allow_tail=*/true, /*scaled_source=*/src_mode != kScaleNone);
+    if (!(layout.padded_copy && layout.slice_major)) return GNN_OK;  // that call gathers rows where they lie
+    const int64_t lines = (F + 31) / 32;
+    if (lines < 2 || lines > 256) return GNN_OK;
+    int rc = gnn_plan_padded(plan, layout.bytes);
+    if (rc != GNN_OK) return rc;
+    gnn_rank_layout rl{};
+    rc = gnn_plan_rank_indices(plan, indptr, indices, false, stream, &rl);
+    if (rc != GNN_OK) return rc;
+    if (!rl.rank) return GNN_OK;
+    out->active = true;
+    out->base = static_cast<float *>(plan->padded);
+    out->table_stride = layout.table_stride;
+    out->main_cols = int32_t(F - layout.tail_elems);
+    out->tail = layout.tail_elems > 0 ? out->base + layout.main_lines * layout.table_stride : nullptr;
+    out->tail_ld = layout.tail_ld;
+    out->rank = rl.rank;
+    out->counts = plan->col_counts;
+    out->scale_mode = src_mode;
+    return GNN_OK;
+}
+
+int gnn_aggregate_prepacked(const void *indptr, const int32_t *indices, void *out, int64_t N, int64_t F, int op,
+                            const gnn_opts *opts, bool backward, bool force, const float *bias, int relu) {
+    gnn_opts o{};
+    if (opts) o = *opts;
+    if (force) {
+        o.flags |= GNN_FLAG_FORCE_PADDED_COPY;
+        o.max_slices = 8;
+    }
+    return run_aggregate(indptr, indices, nullptr, nullptr, out, N, F, op, &o, backward, bias, relu, /*no_alloc=*/false,
+                         /*prepacked=*/true);
+}
+
+// Caller-owned packed copies: the layout every packed call uses is the forced one (slice tables in rank
+// order whatever the size of the graph), so that the size depends on N, F and the element size only.
+static void packed_opts(const gnn_opts *opts, gnn_opts &o) {
+    o = gnn_opts{};
+    if (opts) o = *opts;
+    o.flags = (o.flags | GNN_FLAG_FORCE_PADDED_COPY) &
+              ~(GNN_FLAG_NO_PADDED_COPY | GNN_FLAG_NO_RANK_ORDER | GNN_FLAG_NO_COLUMN_SLICES | GNN_FLAG_NO_SLICE_TABLES);
+    o.max_slices = 8;
+}
+
+extern "C" GNN_API int64_t gnn_packed_bytes(int64_t N, int64_t F, int dtype) {
+    if (N <= 0 || F <= 0 || (dtype != GNN_F32 && dtype != GNN_BF16)) return 0;
+    const int64_t esz = dtype == GNN_BF16 ? 2 : 4, line_elems = 128 / esz;
+    const int64_t lines = (F + line_elems - 1) / line_elems;
+    if (lines < 2 || lines > 256) return 0;  // rows of one line are not laid out as slice tables
+    const int64_t rest = F % line_elems;
+    const bool tail = rest > 0 && rest * esz <= 64;
+    const int64_t group = 16 / esz;
+    return N * ((tail ? lines - 1 : lines) * line_elems + (tail ? (rest + group - 1) / group * group : 0)) * esz;
+}
+
+extern "C" GNN_API int gnn_pack_rows(const void *indptr, const int32_t *indices, const void *X, void *packed,
+                                     int64_t packed_bytes, int64_t N, int64_t F, int op, int backward, const gnn_opts *opts) {
+    gnn_opts o;
+    packed_opts(opts, o);
+    if (!packed || !X) return (N == 0 || F == 0) ? GNN_OK : GNN_ERR_INVALID_ARG;
+    // `packed` stands in for the output argument, which a pack-only call never writes
+    return run_aggregate(indptr, indices, nullptr, X, packed, N, F, op, &o, backward != 0, nullptr, 0, /*no_alloc=*/false,
+                         /*prepacked=*/false, packed, packed_bytes, /*pack_only=*/true);
+}
+
+extern "C" GNN_API int gnn_aggregate_packed(const void *indptr, const int32_t *indices, const float *edge_w, const void *packed,
+                                            int64_t packed_bytes, void *Y, int64_t N, int64_t F, int op, int backward,
+                                            const gnn_opts *opts) {
+    gnn_opts o;
+    packed_opts(opts, o);
+    if (!packed) return (N == 0 || F == 0) ? GNN_OK : GNN_ERR_INVALID_ARG;
+    return run_aggregate(indptr, indices, edge_w, nullptr, Y, N, F, op, &o, backward != 0, nullptr, 0, /*no_alloc=*/false,
+                         /*prepacked=*/true, const_cast<void *>(packed), packed_bytes, /*pack_only=*/false);
 }
 
 // Forward aggregation with the epilogue of a fused layer (used by layer.hip).

@@ -262,6 +262,42 @@ int gnn_plan_edge_operand(gnn_plan *plan, const float *fE, int64_t lde, const in
                           const float **out);
 int gnn_plan_edge_scale(gnn_plan *plan, const int32_t *indices, int mode, hipStream_t stream, const float **out);
 
+// ---- producer-side layout ----
+// Where a kernel that PRODUCES a matrix (the dense product of a layer, the masked output gradient)
+// writes it when the next step is an aggregation that would otherwise copy it into the plan's layout
+// first: directly into that layout -- one table per 128-byte column slice, rows by descending gather
+// count, a dense table for a short last line, the factor the rows carry as gathered rows multiplied
+// in.  fp32 only.  Element (v, j) of the matrix goes to
+//     j <  main_cols:  base[(j / 32) * table_stride + rank[v] * 32 + j % 32]
+//     j >= main_cols:  tail[rank[v] * tail_ld + (j - main_cols)]
+// times gnn_row_factor(scale_mode, counts[v]).
+struct gnn_packed_target {
+    bool active;            // false: the aggregation of this plan / width gathers rows where they lie (write them plainly)
+    float *base;
+    int64_t table_stride;
+    int32_t main_cols;
+    float *tail;
+    int64_t tail_ld;
+    const int32_t *rank;
+    const int32_t *counts;
+    int32_t scale_mode;     // 0 none, 1 reciprocal, 2 reciprocal square root, 3 reciprocal of (count + 1)
+};
+__host__ __device__ static inline float gnn_row_factor(int mode, int64_t count) {
+    if (mode == 3) return 1.0f / static_cast<float>(count + 1);
+    const float d = static_cast<float>(count > 1 ? count : 1);
+    if (mode == 1) return 1.0f / d;
+    if (mode == 2) return 1.0f / sqrtf(d);
+    return 1.0f;
+}
+// The target for the matrix that gnn_aggregate_fwd / _bwd (`backward`) with this plan, op and width F would
+// gather next (a dense fp32 [N, F] matrix).  Grows the plan's buffers on first use (allocation).
+// force: take the layout whatever the size of the graph (tests).
+int gnn_packed_target_for(gnn_plan *plan, const void *indptr, const int32_t *indices, int64_t N, int64_t F, int op, bool backward,
+                          bool force, hipStream_t stream, gnn_packed_target *out);
+// The aggregation over a matrix that a producer has written into that target (no copy; `force` as above).
+int gnn_aggregate_prepacked(const void *indptr, const int32_t *indices, void *out, int64_t N, int64_t F, int op,
+                            const gnn_opts *opts, bool backward, bool force, const float *bias, int relu);
+
 // gnn_aggregate_fwd with a fused epilogue: Y = act(aggregate(X) + bias), act = rectifier if relu.
 int gnn_aggregate_fwd_epilogue(const void *indptr, const int32_t *indices, const void *X, void *Y, int64_t N, int64_t F,
                                int op, const gnn_opts *opts, const float *bias, int relu);
@@ -336,9 +372,10 @@ static inline int64_t gnn_fill_bins(gnn_bin_desc *bins, int32_t *n_bins, const g
 int gnn_pad_rows_f32(const float *src, int64_t ld_src, float *dst, int64_t ld_dst, int64_t N, int64_t F, hipStream_t stream);
 
 // gnn_matmul on a typed stream (shared by the C entry point and the layer calls).
+// packed: write the result into a producer-side layout instead of C (C may then be nullptr; M = the plan's rows).
 int gnn_matmul_impl(const float *A, int64_t lda, int trans_a, const float *B, int64_t ldb, int trans_b, float *C, int64_t ldc,
                     int64_t M, int64_t N, int64_t K, const float *bias, int relu, void *workspace, int64_t workspace_bytes,
-                    hipStream_t stream);
+                    hipStream_t stream, const gnn_packed_target *packed = nullptr);
 
 static inline int gnn_ilog2_ceil(int64_t x) {
     int l = 0;

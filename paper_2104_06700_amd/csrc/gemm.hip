@@ -33,6 +33,7 @@ struct GemmArgs {
     int64_t k_per_split;
     int32_t relu;
     int32_t n_split;
+    gnn_packed_target packed;  // active: the result goes into a producer-side layout instead of C
 };
 
 // One [ROWS x BK] tile of an operand on its way from global memory to LDS (stored k-major as
@@ -165,13 +166,22 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4
             const int64_t n = n0 + wn + j * 32 + l32;
             if (n >= g.N) continue;
             const float bv = (g.bias && g.n_split == 1) ? g.bias[n] : 0.0f;
+            // producer-side layout: the 32 lanes of a row write one 128-byte line of a slice table (or a piece of the tail)
+            const gnn_packed_target &pk = g.packed;
+            float *pk_col = nullptr;
+            int64_t pk_ld = 0;
+            if (pk.active) {
+                if (n < pk.main_cols) { pk_col = pk.base + (n >> 5) * pk.table_stride + (n & 31); pk_ld = 32; }
+                else { pk_col = pk.tail + (n - pk.main_cols); pk_ld = pk.tail_ld; }
+            }
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int64_t m = m0 + wm + i * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
                 if (m >= g.M) continue;
                 float r = acc[i][j][v] + bv;
                 if (g.relu && g.n_split == 1) r = r > 0.0f ? r : 0.0f;
-                out[m * g.ldc + n] = r;
+                if (pk.active) pk_col[int64_t(pk.rank[m]) * pk_ld] = r * gnn_row_factor(pk.scale_mode, pk.counts[m]);
+                else out[m * g.ldc + n] = r;
             }
         }
 }
@@ -237,14 +247,18 @@ extern "C" GNN_API int gnn_matmul(const float *A, int64_t lda, int trans_a, cons
 
 int gnn_matmul_impl(const float *A, int64_t lda, int trans_a, const float *B, int64_t ldb, int trans_b, float *C, int64_t ldc,
                     int64_t M, int64_t N, int64_t K, const float *bias, int relu, void *workspace, int64_t workspace_bytes,
-                    hipStream_t stream) {
+                    hipStream_t stream, const gnn_packed_target *packed) {
     if (M < 0 || N < 0 || K < 0) return GNN_ERR_INVALID_ARG;
     if (M == 0 || N == 0) return GNN_OK;
-    if (!C || ldc < N) return GNN_ERR_INVALID_ARG;
+    const bool to_packed = packed && packed->active;
+    if (!to_packed && (!C || ldc < N)) return GNN_ERR_INVALID_ARG;
     if (K > 0 && (!A || !B)) return GNN_ERR_INVALID_ARG;
     // stored shapes: A is [M, K] (or [K, M] when trans_a), B is [K, N] (or [N, K] when trans_b)
     if (K > 0 && (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N))) return GNN_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(C) % 4 || reinterpret_cast<uintptr_t>(A) % 4 || reinterpret_cast<uintptr_t>(B) % 4)
+        return GNN_ERR_INVALID_ARG;
+    if (to_packed && (!packed->base || !packed->rank || (packed->scale_mode && !packed->counts) ||
+                      (packed->main_cols < N && !packed->tail)))
         return GNN_ERR_INVALID_ARG;
     (void)hipGetLastError();
 
@@ -256,6 +270,10 @@ int gnn_matmul_impl(const float *A, int64_t lda, int trans_a, const float *B, in
     g.relu = relu ? 1 : 0;
     int64_t split = choose_split(M, N, K);
     if (split > 1 && (!workspace || workspace_bytes < split * M * N * int64_t(sizeof(float)))) split = 1;
+    if (to_packed) {  // tall results only: no split reduction on this route
+        split = 1;
+        g.packed = *packed;
+    }
     g.n_split = int32_t(split);
     g.k_per_split = split > 1 ? ((K + split - 1) / split + BK - 1) / BK * BK : (K > 0 ? K : 1);
     if (split > 1) {

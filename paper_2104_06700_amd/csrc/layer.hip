@@ -38,9 +38,10 @@ hipStream_t side_stream() {
 // stride ldg when G != nullptr, plus the block's column sums.  A thread owns one column and every
 // (256 / cols)-th row of the block; the row lanes are added through LDS in a fixed order, so the
 // sums are reproducible.  cols = power of two >= F, at most 256 (wider F: several column passes).
+// pk.active: G goes into a producer-side layout (the tables the backward aggregation gathers from) instead.
 __global__ void __launch_bounds__(256) mask_colsum_kernel(const float *__restrict__ H, const float *__restrict__ dH,
                                                           float *__restrict__ G, int64_t ldg, float *__restrict__ partial,
-                                                          int64_t N, int F, int relu, int log2_cols) {
+                                                          int64_t N, int F, int relu, int log2_cols, const gnn_packed_target pk) {
     __shared__ float red[256];
     const int cols = 1 << log2_cols;
     const int row_lanes = 256 >> log2_cols;
@@ -54,7 +55,13 @@ __global__ void __launch_bounds__(256) mask_colsum_kernel(const float *__restric
             for (int64_t r = r0 + rl; r < r1; r += row_lanes) {
                 float g = dH[r * F + j];
                 if (relu) g = H[r * F + j] > 0.0f ? g : 0.0f;
-                if (G) G[r * ldg + j] = g;
+                if (pk.active) {
+                    float *q = j < pk.main_cols ? pk.base + (j >> 5) * pk.table_stride + int64_t(pk.rank[r]) * 32 + (j & 31)
+                                                : pk.tail + int64_t(pk.rank[r]) * pk.tail_ld + (j - pk.main_cols);
+                    *q = g * gnn_row_factor(pk.scale_mode, pk.counts[r]);
+                } else if (G) {
+                    G[r * ldg + j] = g;
+                }
                 s += g;
             }
         }
@@ -158,7 +165,19 @@ extern "C" GNN_API int gnn_sage_layer_fwd(const void *indptr, const int32_t *ind
         if (rc != GNN_OK) return rc;
         return gnn_matmul_impl(saved, F_in, 0, W, F_out, 0, H, F_out, N, F_out, F_in, bias, o.relu, nullptr, 0, stream);
     }
-    // X W is written with padded rows (the padding is never written and never used: the gather
+    const bool force = (o.flags & GNN_LAYER_FORCE_PRODUCER_LAYOUT) != 0;
+    // X W goes straight into the tables the aggregation gathers from, when that call would copy it there anyway
+    gnn_packed_target pk{};
+    if (!(o.flags & GNN_LAYER_NO_PRODUCER_LAYOUT)) {
+        rc = gnn_packed_target_for(o.plan, indptr, indices, N, F_out, GNN_SAGE_GCN, /*backward=*/false, force, stream, &pk);
+        if (rc != GNN_OK) return rc;
+    }
+    if (pk.active) {
+        rc = gnn_matmul_impl(X, F_in, 0, W, F_out, 0, nullptr, 0, N, F_out, F_in, nullptr, 0, nullptr, 0, stream, &pk);
+        if (rc != GNN_OK) return rc;
+        return gnn_aggregate_prepacked(indptr, indices, H, N, F_out, GNN_SAGE_GCN, &a, /*backward=*/false, force, bias, o.relu);
+    }
+    // else X W is written with padded rows (the padding is never written and never used: the gather
     // reads it with 16-byte loads and drops it)
     const int64_t ldp = gather_ld(F_out);
     rc = gnn_matmul_impl(X, F_in, 0, W, F_out, 0, saved, ldp, N, F_out, F_in, nullptr, 0, nullptr, 0, stream);
@@ -198,13 +217,26 @@ extern "C" GNN_API int gnn_sage_layer_bwd(const void *indptr_t, const int32_t *i
     void *mm_ws = ws + L.mm_off;
     const int64_t mm_bytes = L.total - L.mm_off;
 
+    // The matrix the backward aggregation gathers (G when transforming first, dZ = G W^T when aggregating
+    // first) is written straight into that call's tables when it would copy it there anyway.
+    const bool force = (o.flags & GNN_LAYER_FORCE_PRODUCER_LAYOUT) != 0;
+    gnn_packed_target pk{};
+    if (dX || !agg_first) {
+        if (!(o.flags & GNN_LAYER_NO_PRODUCER_LAYOUT)) {
+            rc = gnn_packed_target_for(o.plan, indptr_t, indices_t, N, agg_first ? F_in : F_out, GNN_SAGE_GCN, /*backward=*/true,
+                                       force, stream, &pk);
+            if (rc != GNN_OK) return rc;
+        }
+    }
+    const gnn_packed_target pk_mask = agg_first ? gnn_packed_target{} : pk;
+
     // rectifier mask and bias gradient
     const int64_t n_blocks = (N + kRowsPerBlock - 1) / kRowsPerBlock;
     if (need_g || db) {
         int log2_cols = 0;
         while ((1 << log2_cols) < F_out && log2_cols < 8) ++log2_cols;
         mask_colsum_kernel<<<static_cast<unsigned>(n_blocks), 256, 0, stream>>>(H, dH, G, ldg, part, N, int(F_out),
-                                                                                o.relu ? 1 : 0, log2_cols);
+                                                                                o.relu ? 1 : 0, log2_cols, pk_mask);
         if (db) {
             const int64_t n2 = (n_blocks + 255) / 256;
             colsum_reduce_kernel<<<static_cast<unsigned>(n2), 256, 0, stream>>>(part, n_blocks, int(F_out), part2, 256);
@@ -223,7 +255,7 @@ extern "C" GNN_API int gnn_sage_layer_bwd(const void *indptr_t, const int32_t *i
         if (!dX) return gnn_matmul_impl(saved, F_in, 1, Gm, F_out, 0, dW, F_out, F_in, F_out, N, nullptr, 0, mm_ws, mm_bytes, stream);
         // dZ = G W^T first; then fork: dW = Z^T G (matrix cores) on the side stream while the caller's
         // stream runs the gather-bound backward aggregation
-        rc = gnn_matmul_impl(Gm, F_out, 0, W, F_out, 1, T, F_in, N, F_in, F_out, nullptr, 0, nullptr, 0, stream);
+        rc = gnn_matmul_impl(Gm, F_out, 0, W, F_out, 1, T, F_in, N, F_in, F_out, nullptr, 0, nullptr, 0, stream, &pk);
         if (rc != GNN_OK) return rc;
         hipStream_t side = side_stream();
         hipEvent_t fork = nullptr, join = nullptr;
@@ -240,7 +272,8 @@ extern "C" GNN_API int gnn_sage_layer_bwd(const void *indptr_t, const int32_t *i
             return GNN_ERR_LAUNCH;
         }
         rc = gnn_matmul_impl(saved, F_in, 1, Gm, F_out, 0, dW, F_out, F_in, F_out, N, nullptr, 0, mm_ws, mm_bytes, side ? side : stream);
-        int rc2 = gnn_aggregate_bwd(indptr_t, indices_t, nullptr, T, dX, N, F_in, GNN_SAGE_GCN, &a);
+        int rc2 = pk.active ? gnn_aggregate_prepacked(indptr_t, indices_t, dX, N, F_in, GNN_SAGE_GCN, &a, /*backward=*/true, force, nullptr, 0)
+                            : gnn_aggregate_bwd(indptr_t, indices_t, nullptr, T, dX, N, F_in, GNN_SAGE_GCN, &a);
         if (side) {  // join, whatever happened above: the caller's stream must not run ahead of the side stream
             if (hipEventRecord(join, side) != hipSuccess || hipStreamWaitEvent(stream, join, 0) != hipSuccess) rc = GNN_ERR_LAUNCH;
             (void)hipEventDestroy(fork);  // released by the runtime once the recorded work has completed
@@ -248,10 +281,14 @@ extern "C" GNN_API int gnn_sage_layer_bwd(const void *indptr_t, const int32_t *i
         }
         return rc != GNN_OK ? rc : rc2;
     }
-    a.ldx = ldg;
     a.ldy = ldg;
-    a.flags = GNN_FLAG_PADDED_ROWS;
-    rc = gnn_aggregate_bwd(indptr_t, indices_t, nullptr, Gm, T, N, F_out, GNN_SAGE_GCN, &a);
+    if (pk.active) {
+        rc = gnn_aggregate_prepacked(indptr_t, indices_t, T, N, F_out, GNN_SAGE_GCN, &a, /*backward=*/true, force, nullptr, 0);
+    } else {
+        a.ldx = ldg;
+        a.flags = GNN_FLAG_PADDED_ROWS;
+        rc = gnn_aggregate_bwd(indptr_t, indices_t, nullptr, Gm, T, N, F_out, GNN_SAGE_GCN, &a);
+    }
     if (rc != GNN_OK) return rc;
     rc = gnn_matmul_impl(X, F_in, 1, T, ldg, 0, dW, F_out, F_in, F_out, N, nullptr, 0, mm_ws, mm_bytes, stream);
     if (rc != GNN_OK || !dX) return rc;

@@ -104,7 +104,7 @@ def _graph(kind):
     raise KeyError(kind)
 
 
-def _layer_case(el, params, fi, fo, relu, order, seed, use_bias=True, want_dx=True):
+def _layer_case(el, params, fi, fo, relu, order, seed, use_bias=True, want_dx=True, flags=0):
     rng = np.random.default_rng(seed)
     n = el.n
     dg = device_graph(el, plan_params=params)
@@ -119,7 +119,7 @@ def _layer_case(el, params, fi, fo, relu, order, seed, use_bias=True, want_dx=Tr
     bd = None if b is None else torch.from_numpy(b).to(DEV)
     saved = torch.full((gnn.gnn_sage_layer_saved_elems(n, fi, fo, order),), float("nan"), device=DEV)
     H = torch.full((n, fo), float("nan"), device=DEV)
-    gnn.gnn_sage_layer_fwd(dg.indptr, dg.indices, Xd, Wd, bd, saved, H, dg.plan_fwd, relu=relu, order=order)
+    gnn.gnn_sage_layer_fwd(dg.indptr, dg.indices, Xd, Wd, bd, saved, H, dg.plan_fwd, relu=relu, order=order, flags=flags)
     torch.cuda.synchronize()
     Z, Ho, SH = oracle.sage_layer_fwd(indptr, indices, X, W, b, relu)
     _close(H, Ho, SH, "forward " + what)
@@ -130,7 +130,7 @@ def _layer_case(el, params, fi, fo, relu, order, seed, use_bias=True, want_dx=Tr
     dW = torch.full((fi, fo), float("nan"), device=DEV)
     db = torch.full((fo,), float("nan"), device=DEV)
     gnn.gnn_sage_layer_bwd(dg.indptr_t, dg.indices_t, Xd, Wd, saved, torch.from_numpy(Hs).to(DEV), dHd, dX, dW, db,
-                           dg.plan_bwd, ws, relu=relu, order=order)
+                           dg.plan_bwd, ws, relu=relu, order=order, flags=flags)
     torch.cuda.synchronize()
     g = oracle.sage_layer_bwd(indptr, indices, X, W, Hs, dH, relu)
     _close(dW, g["dW"][0], g["dW"][1], "dW " + what)
@@ -152,6 +152,18 @@ def test_layer_forward_and_gradients(kind, fi, fo, relu):
 def test_layer_either_order_gives_the_same_layer(order, fi, fo):
     el, params = _graph("rmat_hubs")
     _layer_case(el, params, fi, fo, True, order=order, seed=9)
+
+
+@pytest.mark.parametrize("order", [0, 1, 2])
+@pytest.mark.parametrize("fi,fo", [(100, 256), (256, 47), (64, 64), (40, 132), (130, 33)])
+@pytest.mark.parametrize("flags", [gnn.GNN_LAYER_FORCE_PRODUCER_LAYOUT, gnn.GNN_LAYER_NO_PRODUCER_LAYOUT])
+def test_layer_producer_side_layouts(order, fi, fo, flags):
+    """The matrix a layer's aggregation gathers (X W, the masked output gradient, its product with W^T)
+    written by its producer straight into the tables of the plan -- forced here on a small graph, with
+    hub rows, a dense tail (47, 100, 130) and both orders -- and, for comparison, never."""
+    el, params = _graph("rmat_hubs")
+    _layer_case(el, params, fi, fo, True, order=order, seed=21, flags=flags)
+    _layer_case(el, params, fi, fo, False, order=order, seed=22, flags=flags, use_bias=False)
 
 
 def test_layer_without_bias_and_without_input_gradient():
