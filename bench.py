@@ -397,7 +397,7 @@ MODELS = {  # layer widths of the paper's GraphSAGE models (Section 6.1; Table 2
 }
 
 
-def measure_layers(workload, dev, reps=5):
+def measure_layers(workload, dev, reps=5, flags=0):
     """Forward and backward of every layer of the paper's model for this graph shape (aggregation +
     dense update, gnn_sage_layer_*), each timed with events on the launch stream.  Not part of `value`."""
     dims = MODELS[workload]
@@ -429,15 +429,19 @@ def measure_layers(workload, dev, reps=5):
         dX = torch.empty((n, fi), device=dev) if li else None
         dW, db = torch.empty((fi, fo), device=dev), torch.empty(fo, device=dev)
         saved = torch.empty(gnn.gnn_sage_layer_saved_elems(n, fi, fo), device=dev)
-        ws = torch.empty(gnn.gnn_sage_layer_workspace_bytes(n, fi, fo, relu) // 4, device=dev)
-        tf = timed(lambda: gnn.gnn_sage_layer_fwd(dg.indptr, dg.indices, X, W, b, saved, H, dg.plan_fwd, relu=relu))
+        ws_bytes = gnn.gnn_sage_layer_workspace_bytes(n, fi, fo, relu)
+        if flags & gnn.GNN_LAYER_NO_GATE_FOLD:  # that route writes the masked gradient first and needs room for it
+            ws_bytes += n * fo * 4 + 256
+        ws = torch.empty(ws_bytes // 4, device=dev)
+        tf = timed(lambda: gnn.gnn_sage_layer_fwd(dg.indptr, dg.indices, X, W, b, saved, H, dg.plan_fwd, relu=relu, flags=flags))
         tb = timed(lambda: gnn.gnn_sage_layer_bwd(dg.indptr_t, dg.indices_t, X, W, saved, H, dH, dX, dW, db, dg.plan_bwd, ws,
-                                                  relu=relu))
+                                                  relu=relu, flags=flags))
         rows.append({"layer": f"{fi}->{fo}", "order": "aggregate first" if fi <= fo else "transform first",
                      "gathered_width": min(fi, fo), "fwd_ms": round(tf, 4), "bwd_ms": round(tb, 4),
-                     "dense_GFLOP_fwd": round(2.0 * n * fi * fo / 1e9, 2), "input_gradient": li > 0})
+                     "dense_GFLOP_fwd": round(2.0 * n * fi * fo / 1e9, 2), "input_gradient": li > 0,
+                     "bwd_workspace_GB": round(ws_bytes / 1e9, 3)})
         del X, W, H, dH, dX, saved, ws
-    return {"workload": workload, "widths": list(dims), "layers": rows,
+    return {"workload": workload, "widths": list(dims), "layers": rows, "calls_per_layer_and_direction": reps + 1, "layer_flags": flags,
             "fwd_ms": round(sum(r["fwd_ms"] for r in rows), 4), "bwd_ms": round(sum(r["bwd_ms"] for r in rows), 4),
             "note": "model compute of one full-batch epoch without loss and optimizer; the paper's epochs on one Xeon 8280 "
                     "socket: 0.88 s (232,965-vertex dataset, widths 602-16-41) and 11 s (2,449,029-vertex dataset, "
@@ -498,6 +502,9 @@ def main():
                     help="skip the operator-table calls (gnn_ap_*) reported under 'general_primitive'")
     ap.add_argument("--no-layers", action="store_true",
                     help="skip the GraphSAGE layer calls (gnn_sage_layer_*) reported under 'layers'")
+    ap.add_argument("--layers-only", action="store_true",
+                    help="run nothing but the layer calls of --workload (for profiling them); prints their section alone")
+    ap.add_argument("--layer-flags", type=int, default=0, help="GNN_LAYER_* bits for the layer calls (A/B measurements)")
     ap.add_argument("--flush-cache", action="store_true",
                     help="overwrite a 1 GiB buffer before every call (for workloads that fit the caches); "
                          "value is then the sum of the calls' event times")
@@ -515,6 +522,9 @@ def main():
     torch.cuda.set_device(dev)
     gnn.load_library()
 
+    if args.layers_only:
+        print(json.dumps({"layers": [measure_layers(args.workload, dev, flags=args.layer_flags)]}))
+        return
     result, ctx = measure(args.workload, args.steps, args.warmup, args.scale, dev, args.dump_graph, args.flush_cache,
                           relabel=args.relabel, packed_input=args.scale == 1.0 and args.workload != "rmat_capacity")
     if result is None:
@@ -530,7 +540,7 @@ def main():
         result["general_primitive"] = measure_general_primitive(args.workload, dev)
         torch.cuda.empty_cache()
     if not args.no_layers and full:
-        result["layers"] = [measure_layers(wl, dev) for wl in (args.workload, "rmat_dense_wide") if wl in MODELS]
+        result["layers"] = [measure_layers(wl, dev, flags=args.layer_flags) for wl in (args.workload, "rmat_dense_wide") if wl in MODELS]
         torch.cuda.empty_cache()
     if not args.no_calibration:
         result["ceilings"] = calibrate(dev)

@@ -329,6 +329,14 @@ typedef struct gnn_layer_opts {
  * NO: never (A/B measurements).  Results do not depend on it beyond rounding. */
 #define GNN_LAYER_FORCE_PRODUCER_LAYOUT 1
 #define GNN_LAYER_NO_PRODUCER_LAYOUT 2
+/* Backward pass, aggregating first: the masked gradient G = dH where H > 0 is an operand of two
+ * products only, so they read dH and H themselves and apply the rectifier while staging the
+ * operand, and the weight-gradient product also adds up the bias gradient; G is never written.
+ * NO_GATE_FOLD: write G first with a kernel of its own instead (A/B measurements; with a rectifier the
+ * workspace must then be N * F_out * 4 + 256 bytes larger than gnn_sage_layer_workspace_bytes says).
+ * dW and db are reproducible run to run either way; between the two settings they differ by
+ * rounding only. */
+#define GNN_LAYER_NO_GATE_FOLD 4
 
 /* One layer of the paper's model: the aggregation (Section 6.1: sum of the in-neighbours' vectors
  * plus the vertex's own, divided by in-degree + 1) followed by the dense update (Section 6.3,

@@ -512,6 +512,7 @@ def gnn_sage_layer_workspace_bytes(N, F_in, F_out, relu=True, order=0) -> int:
 
 GNN_LAYER_FORCE_PRODUCER_LAYOUT = 1
 GNN_LAYER_NO_PRODUCER_LAYOUT = 2
+GNN_LAYER_NO_GATE_FOLD = 4
 
 
 def _layer_opts(indptr, plan, relu, order, stream, workspace=None, flags=0) -> GnnLayerOpts:

@@ -373,9 +373,22 @@ int gnn_pad_rows_f32(const float *src, int64_t ld_src, float *dst, int64_t ld_ds
 
 // gnn_matmul on a typed stream (shared by the C entry point and the layer calls).
 // packed: write the result into a producer-side layout instead of C (C may then be nullptr; M = the plan's rows).
+// Rectifier gate of a layer's backward pass folded into the product's operand loads: an element of the
+// operand counts as 0 where the gate matrix (same shape and strides) is not positive.  a_gate needs
+// trans_a == 0 and trans_b != 0 (dZ = G W^T), b_gate and colsum need trans_a != 0 and trans_b == 0
+// (dW = Z^T G).  colsum: room for colsum_planes planes of N floats; the call writes n_planes of them
+// (the column sums of the gated B over each part of the split reduction, to be added in plane order).
+struct gnn_gemm_fold {
+    const float *a_gate;
+    const float *b_gate;
+    float *colsum;
+    int64_t colsum_planes;
+    int64_t n_planes;  // out
+};
+
 int gnn_matmul_impl(const float *A, int64_t lda, int trans_a, const float *B, int64_t ldb, int trans_b, float *C, int64_t ldc,
                     int64_t M, int64_t N, int64_t K, const float *bias, int relu, void *workspace, int64_t workspace_bytes,
-                    hipStream_t stream, const gnn_packed_target *packed = nullptr);
+                    hipStream_t stream, const gnn_packed_target *packed = nullptr, gnn_gemm_fold *fold = nullptr);
 
 static inline int gnn_ilog2_ceil(int64_t x) {
     int l = 0;

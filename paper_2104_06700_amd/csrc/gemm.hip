@@ -34,20 +34,36 @@ struct GemmArgs {
     int32_t relu;
     int32_t n_split;
     gnn_packed_target packed;  // active: the result goes into a producer-side layout instead of C
+    // Rectifier gate folded into the operand loads (the backward pass of a layer multiplies by
+    // G = dH where H > 0): an element of A (of B) counts as 0 where the gate matrix, which has the
+    // operand's shape and strides, is not positive.  colsum: [n_split][N] column sums of opB(B) after
+    // its gate (the bias gradient), written by the workgroups of the first tile row.
+    const float *a_gate, *b_gate;
+    float *colsum;
 };
 
 // One [ROWS x BK] tile of an operand on its way from global memory to LDS (stored k-major as
 // tile[k][r]).  X(r, k) = base[r * sr + k * sk].  K_CONTIG: sk == 1 (threads run along k), else
 // sr == 1 (threads run along the rows); 16-byte loads when aligned.  load() and store() are
 // separate so that the loads of the next tile are in flight while the matrix cores work.
-template <bool K_CONTIG, int ROWS>
+template <bool K_CONTIG, int ROWS, bool GATED = false>
 struct Stager {
     static constexpr int QUADS = ROWS * BK / 4;
     static constexpr int PER_THREAD = (QUADS + kThreads - 1) / kThreads;
     float v[PER_THREAD][4];
+    float gate[GATED ? PER_THREAD : 1][4];  // the gate's elements travel beside the operand's and are applied in store()
 
-    __device__ __forceinline__ void load(const float *__restrict__ base, int64_t sr, int64_t sk, int64_t r0, int64_t r_end,
-                                         int64_t k0, int64_t k_end, bool vec_ok) {
+    __device__ __forceinline__ void load(const float *__restrict__ base, const float *__restrict__ gate_base, int64_t sr, int64_t sk,
+                                         int64_t r0, int64_t r_end, int64_t k0, int64_t k_end, bool vec_ok) {
+        fetch(base, v, sr, sk, r0, r_end, k0, k_end, vec_ok);
+        if constexpr (GATED) {
+            if (gate_base) fetch(gate_base, gate, sr, sk, r0, r_end, k0, k_end, vec_ok);
+        }
+    }
+
+    template <int ROWS_OF_V>
+    __device__ __forceinline__ void fetch(const float *__restrict__ base, float (&v)[ROWS_OF_V][4], int64_t sr, int64_t sk, int64_t r0,
+                                          int64_t r_end, int64_t k0, int64_t k_end, bool vec_ok) {
 #pragma unroll
         for (int h = 0; h < PER_THREAD; ++h) {
             const int q = int(threadIdx.x) + h * kThreads;
@@ -86,7 +102,15 @@ struct Stager {
         }
     }
 
-    __device__ __forceinline__ void store(float (*tile)[ROWS + PAD]) const {
+    __device__ __forceinline__ void store(float (*tile)[ROWS + PAD], bool gated) {
+        if constexpr (GATED) {
+            if (gated) {
+#pragma unroll
+                for (int h = 0; h < PER_THREAD; ++h)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v[h][i] = gate[h][i] > 0.0f ? v[h][i] : 0.0f;
+            }
+        }
 #pragma unroll
         for (int h = 0; h < PER_THREAD; ++h) {
             const int q = int(threadIdx.x) + h * kThreads;
@@ -104,8 +128,10 @@ struct Stager {
 };
 
 // Workgroup tile (WM * TI * 32) x (WN * TJ * 32): WM x WN wavefronts, each TI x TJ MFMA tiles.
-template <bool A_K_CONTIG, bool B_K_CONTIG, int WM, int WN, int TI, int TJ>
-__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))) gemm_kernel(const GemmArgs g, int a_vec_ok, int b_vec_ok) {
+// FOLD: 0 = plain operands; 1 = A may carry a gate; 2 = B may carry a gate and its column sums may be asked for.
+// (The 256 x 64 tile with a gated operand stages 32 more registers: three waves per SIMD instead of spilling.)
+template <bool A_K_CONTIG, bool B_K_CONTIG, int WM, int WN, int TI, int TJ, int FOLD = 0>
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu((FOLD != 0 && WM == 4 && TJ == 2) ? 3 : 4, 8))) gemm_kernel(const GemmArgs g, int a_vec_ok, int b_vec_ok) {
     static_assert(WM * WN == kThreads / 64, "four wavefronts");
     constexpr int BM = WM * TI * 32, BN = WN * TJ * 32;
     __shared__ __attribute__((aligned(16))) float As[BK][BM + PAD];
@@ -125,20 +151,27 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    Stager<A_K_CONTIG, BM> sa;
-    Stager<B_K_CONTIG, BN> sb;
+    Stager<A_K_CONTIG, BM, FOLD == 1> sa;
+    Stager<B_K_CONTIG, BN, FOLD == 2> sb;
+    const bool a_gated = FOLD == 1 && g.a_gate, b_gated = FOLD == 2 && g.b_gate;
+    const bool sums = FOLD == 2 && g.colsum && blockIdx.x == 0 && int(threadIdx.x) < BN;  // one thread per column of the tile
+    float col_sum = 0.0f;
     if (k_begin < k_end) {
-        sa.load(g.A, g.sam, g.sak, m0, g.M, k_begin, k_end, a_vec_ok != 0);
-        sb.load(g.B, g.sbn, g.sbk, n0, g.N, k_begin, k_end, b_vec_ok != 0);
+        sa.load(g.A, g.a_gate, g.sam, g.sak, m0, g.M, k_begin, k_end, a_vec_ok != 0);
+        sb.load(g.B, g.b_gate, g.sbn, g.sbk, n0, g.N, k_begin, k_end, b_vec_ok != 0);
     }
     const int l32 = lane & 31, lk = lane >> 5;
     for (int64_t k0 = k_begin; k0 < k_end; k0 += BK) {
-        sa.store(As);
-        sb.store(Bs);
+        sa.store(As, a_gated);
+        sb.store(Bs, b_gated);
         __syncthreads();
         if (k0 + BK < k_end) {  // next tile's loads fly while this tile is multiplied
-            sa.load(g.A, g.sam, g.sak, m0, g.M, k0 + BK, k_end, a_vec_ok != 0);
-            sb.load(g.B, g.sbn, g.sbk, n0, g.N, k0 + BK, k_end, b_vec_ok != 0);
+            sa.load(g.A, g.a_gate, g.sam, g.sak, m0, g.M, k0 + BK, k_end, a_vec_ok != 0);
+            sb.load(g.B, g.b_gate, g.sbn, g.sbk, n0, g.N, k0 + BK, k_end, b_vec_ok != 0);
+        }
+        if (sums) {  // rows past k_end were staged as zeros
+#pragma unroll
+            for (int kk = 0; kk < BK; ++kk) col_sum += Bs[kk][threadIdx.x];
         }
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
@@ -155,6 +188,8 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4
         }
         __syncthreads();
     }
+
+    if (sums && n0 + int(threadIdx.x) < g.N) g.colsum[int64_t(blockIdx.z) * g.N + n0 + threadIdx.x] = col_sum;
 
     // result layout: register v of lane l is C[8 * (v / 4) + 4 * (l / 32) + v % 4][l % 32]
     float *out = g.C;
@@ -188,7 +223,10 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4
 
 template <int WM, int WN, int TI, int TJ>
 void launch_gemm(bool a_k, bool b_k, dim3 grid, hipStream_t stream, const GemmArgs &g, int a_vec, int b_vec) {
-    if (a_k && !b_k) gemm_kernel<true, false, WM, WN, TI, TJ><<<grid, kThreads, 0, stream>>>(g, a_vec, b_vec);
+    // the two products of a layer's backward pass that take G = (dH where H > 0) as an operand
+    if (g.a_gate) gemm_kernel<true, true, WM, WN, TI, TJ, 1><<<grid, kThreads, 0, stream>>>(g, a_vec, b_vec);
+    else if (g.b_gate || g.colsum) gemm_kernel<false, false, WM, WN, TI, TJ, 2><<<grid, kThreads, 0, stream>>>(g, a_vec, b_vec);
+    else if (a_k && !b_k) gemm_kernel<true, false, WM, WN, TI, TJ><<<grid, kThreads, 0, stream>>>(g, a_vec, b_vec);
     else if (a_k && b_k) gemm_kernel<true, true, WM, WN, TI, TJ><<<grid, kThreads, 0, stream>>>(g, a_vec, b_vec);
     else if (!a_k && !b_k) gemm_kernel<false, false, WM, WN, TI, TJ><<<grid, kThreads, 0, stream>>>(g, a_vec, b_vec);
     else gemm_kernel<false, true, WM, WN, TI, TJ><<<grid, kThreads, 0, stream>>>(g, a_vec, b_vec);
@@ -247,8 +285,9 @@ extern "C" GNN_API int gnn_matmul(const float *A, int64_t lda, int trans_a, cons
 
 int gnn_matmul_impl(const float *A, int64_t lda, int trans_a, const float *B, int64_t ldb, int trans_b, float *C, int64_t ldc,
                     int64_t M, int64_t N, int64_t K, const float *bias, int relu, void *workspace, int64_t workspace_bytes,
-                    hipStream_t stream, const gnn_packed_target *packed) {
+                    hipStream_t stream, const gnn_packed_target *packed, gnn_gemm_fold *fold) {
     if (M < 0 || N < 0 || K < 0) return GNN_ERR_INVALID_ARG;
+    if (fold) fold->n_planes = 0;
     if (M == 0 || N == 0) return GNN_OK;
     const bool to_packed = packed && packed->active;
     if (!to_packed && (!C || ldc < N)) return GNN_ERR_INVALID_ARG;
@@ -260,10 +299,14 @@ int gnn_matmul_impl(const float *A, int64_t lda, int trans_a, const float *B, in
     if (to_packed && (!packed->base || !packed->rank || (packed->scale_mode && !packed->counts) ||
                       (packed->main_cols < N && !packed->tail)))
         return GNN_ERR_INVALID_ARG;
+    // gates and column sums exist for the operand layouts of the layer's backward products only
+    if (fold && fold->a_gate && (trans_a || !trans_b || fold->b_gate || fold->colsum)) return GNN_ERR_UNSUPPORTED;
+    if (fold && (fold->b_gate || fold->colsum) && (!trans_a || trans_b)) return GNN_ERR_UNSUPPORTED;
     (void)hipGetLastError();
 
     GemmArgs g{};
     g.A = A; g.B = B; g.C = C; g.bias = bias;
+    if (fold) { g.a_gate = fold->a_gate; g.b_gate = fold->b_gate; g.colsum = fold->colsum; }
     g.sam = trans_a ? 1 : lda;  g.sak = trans_a ? lda : 1;
     g.sbk = trans_b ? 1 : ldb;  g.sbn = trans_b ? ldb : 1;
     g.ldc = ldc; g.M = M; g.N = N; g.K = K;
@@ -273,6 +316,10 @@ int gnn_matmul_impl(const float *A, int64_t lda, int trans_a, const float *B, in
     if (to_packed) {  // tall results only: no split reduction on this route
         split = 1;
         g.packed = *packed;
+    }
+    if (fold && fold->colsum) {
+        if (fold->colsum_planes < split) return GNN_ERR_INVALID_ARG;
+        fold->n_planes = split;
     }
     g.n_split = int32_t(split);
     g.k_per_split = split > 1 ? ((K + split - 1) / split + BK - 1) / BK * BK : (K > 0 ? K : 1);

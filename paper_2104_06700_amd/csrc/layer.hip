@@ -103,13 +103,14 @@ int64_t gather_ld(int64_t Fo) { return round_up(Fo, 4); }
 
 struct BwdLayout {
     int64_t g_off, t_off, part_off, part2_off, mm_off, total;
+    int64_t total_unfolded;  // with room for G behind everything else (aggregate first, rectifier, GNN_LAYER_NO_GATE_FOLD)
 };
 
 BwdLayout bwd_layout(int64_t N, int64_t Fi, int64_t Fo, bool agg_first, bool relu) {
     BwdLayout L{};
     int64_t off = 0;
     L.g_off = off;
-    if (relu || !agg_first) off += round_up(N * (agg_first ? Fo : gather_ld(Fo)) * 4, 256);
+    if (!agg_first) off += round_up(N * gather_ld(Fo) * 4, 256);  // aggregating first, the products read dH and H: no G
     L.t_off = off;
     off += round_up(N * (agg_first ? Fi : gather_ld(Fo)) * 4, 256);
     const int64_t n_blocks = (N + kRowsPerBlock - 1) / kRowsPerBlock;
@@ -120,6 +121,11 @@ BwdLayout bwd_layout(int64_t N, int64_t Fi, int64_t Fo, bool agg_first, bool rel
     L.mm_off = off;
     off += round_up(gnn_matmul_workspace_bytes(Fi, Fo, N), 256);
     L.total = off;
+    L.total_unfolded = off;
+    if (agg_first && relu) {
+        L.g_off = off;
+        L.total_unfolded = off + round_up(N * Fo * 4, 256);
+    }
     return L;
 }
 
@@ -198,7 +204,9 @@ extern "C" GNN_API int gnn_sage_layer_bwd(const void *indptr_t, const int32_t *i
     const bool agg_first = aggregate_first(o.order, F_in, F_out);
     if (N > 0 && (!indptr_t || !X || (agg_first && !saved))) return GNN_ERR_INVALID_ARG;
     const BwdLayout L = bwd_layout(N > 0 ? N : 1, F_in, F_out, agg_first, o.relu != 0);
-    if (N > 0 && (!o.workspace || o.workspace_bytes < L.total || reinterpret_cast<uintptr_t>(o.workspace) % 16))
+    const bool fold_gate = agg_first && !(o.flags & GNN_LAYER_NO_GATE_FOLD);
+    if (N > 0 && (!o.workspace || o.workspace_bytes < (fold_gate ? L.total : L.total_unfolded) ||
+                  reinterpret_cast<uintptr_t>(o.workspace) % 16))
         return GNN_ERR_INVALID_ARG;
     hipStream_t stream = static_cast<hipStream_t>(o.stream);
     (void)hipGetLastError();
@@ -210,12 +218,12 @@ extern "C" GNN_API int gnn_sage_layer_bwd(const void *indptr_t, const int32_t *i
     }
     const bool need_g = o.relu || !agg_first;  // transform first gathers G: always the padded copy
     const int64_t ldg = agg_first ? F_out : gather_ld(F_out);
-    float *G = need_g ? reinterpret_cast<float *>(ws + L.g_off) : nullptr;
+    float *G = (need_g && !fold_gate) ? reinterpret_cast<float *>(ws + L.g_off) : nullptr;
     float *T = reinterpret_cast<float *>(ws + L.t_off);
     float *part = reinterpret_cast<float *>(ws + L.part_off);
     float *part2 = reinterpret_cast<float *>(ws + L.part2_off);
     void *mm_ws = ws + L.mm_off;
-    const int64_t mm_bytes = L.total - L.mm_off;
+    const int64_t mm_bytes = L.total - L.mm_off;  // (the optional G lies behind L.total)
 
     // The matrix the backward aggregation gathers (G when transforming first, dZ = G W^T when aggregating
     // first) is written straight into that call's tables when it would copy it there anyway.
@@ -230,9 +238,13 @@ extern "C" GNN_API int gnn_sage_layer_bwd(const void *indptr_t, const int32_t *i
     }
     const gnn_packed_target pk_mask = agg_first ? gnn_packed_target{} : pk;
 
+    // Aggregating first, G is an operand of the two products only: they read dH and H themselves and
+    // apply the rectifier while staging the operand, and the weight-gradient product adds up the bias
+    // gradient from the tiles it stages anyway; G is never written.
+
     // rectifier mask and bias gradient
     const int64_t n_blocks = (N + kRowsPerBlock - 1) / kRowsPerBlock;
-    if (need_g || db) {
+    if (!fold_gate && (need_g || db)) {
         int log2_cols = 0;
         while ((1 << log2_cols) < F_out && log2_cols < 8) ++log2_cols;
         mask_colsum_kernel<<<static_cast<unsigned>(n_blocks), 256, 0, stream>>>(H, dH, G, ldg, part, N, int(F_out),
@@ -244,7 +256,22 @@ extern "C" GNN_API int gnn_sage_layer_bwd(const void *indptr_t, const int32_t *i
         }
         if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
     }
-    const float *Gm = need_g ? G : dH;
+    const float *Gm = (need_g && !fold_gate) ? G : dH;
+    const float *gate = (fold_gate && o.relu) ? H : nullptr;
+    // dW = Z^T G on `st`, and with the gate folded also db = the column sums of G, added in plane order
+    auto weight_gradient = [&](hipStream_t st) -> int {
+        if (!fold_gate) return gnn_matmul_impl(saved, F_in, 1, Gm, F_out, 0, dW, F_out, F_in, F_out, N, nullptr, 0, mm_ws, mm_bytes, st);
+        gnn_gemm_fold fold{};
+        fold.b_gate = gate;
+        fold.colsum = db ? part : nullptr;
+        fold.colsum_planes = n_blocks;
+        int rcw = gnn_matmul_impl(saved, F_in, 1, dH, F_out, 0, dW, F_out, F_in, F_out, N, nullptr, 0, mm_ws, mm_bytes, st, nullptr, &fold);
+        if (rcw != GNN_OK || !db) return rcw;
+        const int64_t n2 = (fold.n_planes + 255) / 256;
+        colsum_reduce_kernel<<<static_cast<unsigned>(n2), 256, 0, st>>>(part, fold.n_planes, int(F_out), part2, 256);
+        colsum_reduce_kernel<<<1, 256, 0, st>>>(part2, n2, int(F_out), db, int(n2));
+        return hipGetLastError() == hipSuccess ? GNN_OK : GNN_ERR_LAUNCH;
+    };
 
     gnn_opts a{};
     a.dtype = GNN_F32;
@@ -252,10 +279,12 @@ extern "C" GNN_API int gnn_sage_layer_bwd(const void *indptr_t, const int32_t *i
     a.stream = o.stream;
     a.plan = o.plan;
     if (agg_first) {
-        if (!dX) return gnn_matmul_impl(saved, F_in, 1, Gm, F_out, 0, dW, F_out, F_in, F_out, N, nullptr, 0, mm_ws, mm_bytes, stream);
+        if (!dX) return weight_gradient(stream);
         // dZ = G W^T first; then fork: dW = Z^T G (matrix cores) on the side stream while the caller's
         // stream runs the gather-bound backward aggregation
-        rc = gnn_matmul_impl(Gm, F_out, 0, W, F_out, 1, T, F_in, N, F_in, F_out, nullptr, 0, nullptr, 0, stream, &pk);
+        gnn_gemm_fold fold_a{};
+        fold_a.a_gate = gate;
+        rc = gnn_matmul_impl(Gm, F_out, 0, W, F_out, 1, T, F_in, N, F_in, F_out, nullptr, 0, nullptr, 0, stream, &pk, &fold_a);
         if (rc != GNN_OK) return rc;
         hipStream_t side = side_stream();
         hipEvent_t fork = nullptr, join = nullptr;
@@ -271,7 +300,7 @@ extern "C" GNN_API int gnn_sage_layer_bwd(const void *indptr_t, const int32_t *i
             (void)hipEventDestroy(join);
             return GNN_ERR_LAUNCH;
         }
-        rc = gnn_matmul_impl(saved, F_in, 1, Gm, F_out, 0, dW, F_out, F_in, F_out, N, nullptr, 0, mm_ws, mm_bytes, side ? side : stream);
+        rc = weight_gradient(side ? side : stream);
         int rc2 = pk.active ? gnn_aggregate_prepacked(indptr_t, indices_t, dX, N, F_in, GNN_SAGE_GCN, &a, /*backward=*/true, force, nullptr, 0)
                             : gnn_aggregate_bwd(indptr_t, indices_t, nullptr, T, dX, N, F_in, GNN_SAGE_GCN, &a);
         if (side) {  // join, whatever happened above: the caller's stream must not run ahead of the side stream

@@ -125,7 +125,8 @@ def _layer_case(el, params, fi, fo, relu, order, seed, use_bias=True, want_dx=Tr
     _close(H, Ho, SH, "forward " + what)
     # backward; the stored forward output that decides the rectifier's mask is the oracle's, for both sides
     Hs = Ho.astype(np.float32)
-    ws = torch.empty(max(1, gnn.gnn_sage_layer_workspace_bytes(n, fi, fo, relu, order) // 4), device=DEV)
+    extra = n * fo + 64 if flags & gnn.GNN_LAYER_NO_GATE_FOLD else 0  # room for the masked gradient
+    ws = torch.empty(max(1, gnn.gnn_sage_layer_workspace_bytes(n, fi, fo, relu, order) // 4) + extra, device=DEV)
     dX = torch.full((n, fi), float("nan"), device=DEV) if want_dx else None
     dW = torch.full((fi, fo), float("nan"), device=DEV)
     db = torch.full((fo,), float("nan"), device=DEV)
@@ -166,6 +167,45 @@ def test_layer_producer_side_layouts(order, fi, fo, flags):
     _layer_case(el, params, fi, fo, False, order=order, seed=22, flags=flags, use_bias=False)
 
 
+@pytest.mark.parametrize("fi,fo", [(100, 256), (40, 47), (64, 64), (20, 24), (130, 133)])
+@pytest.mark.parametrize("flags", [0, gnn.GNN_LAYER_NO_GATE_FOLD, gnn.GNN_LAYER_FORCE_PRODUCER_LAYOUT])
+def test_layer_backward_with_the_rectifier_folded_into_the_products(fi, fo, flags):
+    """Aggregating first, the two backward products read dH and H themselves (the gate is applied while
+    the operand is staged, the bias gradient is added up from the staged tiles) -- all three tile shapes of
+    the product (outputs of up to 32, up to 64 and more columns), with and without a rectifier, with and
+    without an input gradient -- and, for comparison, with the masked gradient written first."""
+    el, params = _graph("rmat_hubs")
+    _layer_case(el, params, fi, fo, True, order=1, seed=31, flags=flags)
+    _layer_case(el, params, fi, fo, False, order=1, seed=32, flags=flags)
+    _layer_case(el, params, fi, fo, True, order=1, seed=33, flags=flags, want_dx=False)
+    _layer_case(el, params, fi, fo, True, order=1, seed=34, flags=flags, use_bias=False)
+
+
+@pytest.mark.parametrize("flags", [0, gnn.GNN_LAYER_NO_GATE_FOLD])
+def test_layer_backward_folded_rectifier_with_a_split_reduction(flags):
+    """Enough vertices that the weight-gradient product splits its reduction: the bias gradient then comes
+    in one plane per part and is added in plane order; twice the same bits."""
+    el = synth.small_random_multigraph(9500, 60000, 8)
+    assert gnn.gnn_matmul_workspace_bytes(72, 40, el.n) > 0
+    _layer_case(el, None, 72, 40, True, order=1, seed=41, flags=flags)
+    _layer_case(el, None, 24, 140, True, order=0, seed=42, flags=flags)
+    n, fi, fo = el.n, 24, 140
+    dg = device_graph(el)
+    g = torch.Generator(device="cpu").manual_seed(3)
+    X, W, H, dH = (torch.randn(s_, generator=g).to(DEV) for s_ in ((n, fi), (fi, fo), (n, fo), (n, fo)))
+    saved = torch.randn(n, fi, generator=g).to(DEV)
+    ws = torch.empty(gnn.gnn_sage_layer_workspace_bytes(n, fi, fo, True, 0) // 4 + n * fo + 64, device=DEV)
+    outs = []
+    for _ in range(2):
+        dX, dW, db = torch.empty(n, fi, device=DEV), torch.empty(fi, fo, device=DEV), torch.empty(fo, device=DEV)
+        gnn.gnn_sage_layer_bwd(dg.indptr_t, dg.indices_t, X, W, saved, H, dH, dX, dW, db, dg.plan_bwd, ws, relu=True, order=0,
+                               flags=flags)
+        torch.cuda.synchronize()
+        outs.append((dX, dW, db))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
 def test_layer_without_bias_and_without_input_gradient():
     el, params = _graph("multi")
     _layer_case(el, params, 40, 24, True, order=0, seed=10, use_bias=False, want_dx=False)
@@ -180,7 +220,7 @@ def test_layer_gradients_are_reproducible():
     W = torch.randn(fi, fo, device=DEV)
     H = torch.randn(n, fo, device=DEV)
     dH = torch.randn(n, fo, device=DEV)
-    ws = torch.empty(gnn.gnn_sage_layer_workspace_bytes(n, fi, fo, True, 0) // 4, device=DEV)
+    ws = torch.empty(gnn.gnn_sage_layer_workspace_bytes(n, fi, fo, True, 0) // 4 + n * fo + 64, device=DEV)
     outs = []
     for _ in range(2):
         dX, dW, db = torch.empty(n, fi, device=DEV), torch.empty(fi, fo, device=DEV), torch.empty(fo, device=DEV)
