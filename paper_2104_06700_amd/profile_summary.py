@@ -291,6 +291,60 @@ def write_bench_stats(d: str, out_dir: str) -> None:
     print(f"wrote {path}")
 
 
+LAYER_KERNELS = CALL_KERNELS + ("gemm_kernel", "gemm_reduce_kernel", "mask_colsum_kernel", "colsum_reduce_kernel", "zero_kernel")
+
+
+def write_layer_summary(d: str, out_dir: str) -> None:
+    """Kernels and bytes of the GraphSAGE layer calls.  DIR holds one directory per variant (named for the
+    GNN_LAYER_* flags it ran with), each with bench.json (the line of `bench.py --layers-only`), cmd.txt and
+    the rocprofv3 output directories stats/ (--kernel-trace --stats), fetch/ and write/ (--pmc FETCH_SIZE /
+    WRITE_SIZE) of that same command."""
+    import json
+    variants = sorted(x for x in os.listdir(d) if os.path.isdir(os.path.join(d, x)))
+    out, workload = [], "?"
+    fscale, wscale = 2.0, 1.0  # counter units per KiB, from the 1 GiB copy of the aggregation profiles of the same machine type
+    for v in variants:
+        vd = os.path.join(d, v)
+        res = json.loads([l for l in open(os.path.join(vd, "bench.json")) if l.startswith("{")][-1])["layers"][0]
+        workload = res["workload"]
+        calls = res["calls_per_layer_and_direction"]
+        cmd = open(os.path.join(vd, "cmd.txt")).read().strip()
+        stats = {short_name(r["Name"]): r for r in csv.DictReader(open(_find(os.path.join(vd, "stats"), "*kernel_stats.csv")))}
+        fetch, write = collections.defaultdict(float), collections.defaultdict(float)
+        for sub, counter, acc in (("fetch", "FETCH_SIZE", fetch), ("write", "WRITE_SIZE", write)):
+            for r in _counter_rows(os.path.join(vd, sub)):
+                if r["Counter_Name"] == counter:
+                    acc[short_name(r["Kernel_Name"])] += float(r["Counter_Value"])
+        out += [f"## layer flags = {res['layer_flags']} ({v})", "", f"    {cmd}", "",
+                f"    {'kernel':46s} {'calls':>6s} {'mean ms':>9s} {'ms/epoch':>9s} {'read GB/epoch':>14s} {'written GB/epoch':>17s}"]
+        tot_ms = tot_r = tot_w = 0.0
+        for name in sorted(stats, key=lambda k: -float(stats[k]["TotalDurationNs"])):
+            if not any(name.startswith(k) for k in LAYER_KERNELS):
+                continue
+            r = stats[name]
+            ms = float(r["TotalDurationNs"]) / 1e6 / calls
+            rd, wr = fetch.get(name, 0.0) * fscale * 1024 / 1e9 / calls, write.get(name, 0.0) * wscale * 1024 / 1e9 / calls
+            tot_ms += ms
+            tot_r += rd
+            tot_w += wr
+            out.append(f"    {name:46s} {int(r['Calls']):>6d} {float(r['AverageNs']) / 1e6:>9.4f} {ms:>9.3f} {rd:>14.2f} {wr:>17.2f}")
+        out += [f"    {'all kernels of the layer calls':46s} {'':>6s} {'':>9s} {tot_ms:>9.3f} {tot_r:>14.2f} {tot_w:>17.2f}", "",
+                f"    per layer (events on the launch stream, ms; {calls} calls each): " +
+                "; ".join(f"{l['layer']} fwd {l['fwd_ms']} bwd {l['bwd_ms']} (workspace {l['bwd_workspace_GB']} GB)" for l in res["layers"]),
+                f"    model: forward {res['fwd_ms']} ms, backward {res['bwd_ms']} ms", ""]
+    head = [f"# Kernels and bytes behind the L2s of the GraphSAGE layer calls ({workload})", "",
+            f"Written by `python -m paper_2104_06700_amd.profile_summary --layers`; kernel sources `{source_hash()}`.",
+            "An epoch here = one forward and one backward call of every layer of the model (no loss, no optimizer).  Three runs of",
+            "the same command per variant: `rocprofv3 --kernel-trace --stats`, `--pmc FETCH_SIZE`, `--pmc WRITE_SIZE` (KiB per",
+            f"dispatch, scaled x {fscale:.0f} / x {wscale:.0f} as calibrated with the 1 GiB copy of the aggregation profiles).  ms/epoch of a kernel =",
+            "its total time / calls per layer and direction; kernels that run side by side on two streams (the weight-gradient",
+            "product beside the backward aggregation) both count in full, so the sum exceeds the epoch's wall time.", ""]
+    os.makedirs(out_dir, exist_ok=True)
+    path = os.path.join(out_dir, f"layer_kernels_{workload}.md")
+    open(path, "w").write("\n".join(head + out))
+    print(f"wrote {path}")
+
+
 def write_reuse_study(d: str, out_dir: str) -> None:
     """Reuse of gathered rows (the quantity of the paper's Table 3) per variant: DIR holds one directory per
     variant (NN_name/F<width>/{run.log, fetch/, tcc/}, plus variant.txt and order.txt) and meta.txt."""
@@ -360,13 +414,16 @@ def main():
     ap.add_argument("--source-hash", action="store_true")
     ap.add_argument("--reuse-study", action="store_true", help="DIR holds one directory per variant of the reuse study")
     ap.add_argument("--bench-stats", action="store_true", help="DIR holds rocprofv3 --stats output of bench.py and its bench.json")
+    ap.add_argument("--layers", action="store_true", help="DIR holds one directory per variant of `bench.py --layers-only`")
     args = ap.parse_args()
     if args.source_hash:
         print(source_hash())
         return
     if not args.dir:
         ap.error("DIR is required")
-    if args.bench_stats:
+    if args.layers:
+        write_layer_summary(args.dir, args.out)
+    elif args.bench_stats:
         write_bench_stats(args.dir, args.out)
     elif args.reuse_study:
         write_reuse_study(args.dir, args.out)

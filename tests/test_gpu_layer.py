@@ -95,6 +95,41 @@ def test_matmul_long_reduction_is_split_and_deterministic():
     _close(C, ref, S, "unsplit long reduction", rtol=2e-4)
 
 
+@pytest.mark.parametrize("m,n,k,ta,tb", [(128 * 21 + 5, 256, 40, False, False), (128 * 17, 300, 64, False, True),
+                                         (256 * 19 + 1, 47, 100, False, False), (128 * 40, 130, 33, True, True)])
+def test_matmul_tall_results_with_the_tile_order_for_the_xcds(m, n, k, ta, tb):
+    """Many row tiles and a few column tiles: the column tiles of one row tile get workgroup ids 8 apart
+    (same XCD), the last group of 8 row tiles is incomplete."""
+    rng = np.random.default_rng(m + n)
+    A = rng.normal(size=(k, m) if ta else (m, k)).astype(np.float32)
+    B = rng.normal(size=(n, k) if tb else (k, n)).astype(np.float32)
+    bias = rng.normal(size=n).astype(np.float32)
+    C = torch.full((m, n), float("nan"), device=DEV)
+    gnn.gnn_matmul(torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV), C, ta, tb, torch.from_numpy(bias).to(DEV), True)
+    torch.cuda.synchronize()
+    A64, B64 = A.astype(np.float64), B.astype(np.float64)   # the oracle's loop is pinned to this routine; see above
+    opA, opB = (A64.T if ta else A64), (B64.T if tb else B64)
+    ref = np.maximum(opA @ opB + bias, 0.0)
+    S = np.abs(opA) @ np.abs(opB) + np.abs(bias)
+    _close(C, ref, S, "tall product")
+
+
+def test_matmul_split_reduction_of_several_tiles():
+    """Four output tiles and a long reduction: all tiles of one part run on one XCD, parts on all eight."""
+    rng = np.random.default_rng(61)
+    rows, fi, fo = 70_000, 200, 140
+    Z = rng.normal(size=(rows, fi)).astype(np.float32)
+    G = rng.normal(size=(rows, fo)).astype(np.float32)
+    ws = torch.empty(gnn.gnn_matmul_workspace_bytes(fi, fo, rows) // 4, device=DEV)
+    assert ws.numel() >= 16 * fi * fo
+    C = torch.full((fi, fo), float("nan"), device=DEV)
+    gnn.gnn_matmul(torch.from_numpy(Z).to(DEV), torch.from_numpy(G).to(DEV), C, trans_a=True, workspace=ws)
+    torch.cuda.synchronize()
+    ref = Z.astype(np.float64).T @ G.astype(np.float64)
+    S = np.abs(Z.astype(np.float64)).T @ np.abs(G.astype(np.float64))
+    _close(C, ref, S, "split reduction over several tiles")
+
+
 # ------------------------------------------------------------------ one layer
 def _graph(kind):
     if kind == "multi":
@@ -189,6 +224,8 @@ def test_layer_backward_folded_rectifier_with_a_split_reduction(flags):
     assert gnn.gnn_matmul_workspace_bytes(72, 40, el.n) > 0
     _layer_case(el, None, 72, 40, True, order=1, seed=41, flags=flags)
     _layer_case(el, None, 24, 140, True, order=0, seed=42, flags=flags)
+    big = synth.small_random_multigraph(40000, 150000, 9)   # 39 parts of 4 tiles: the tile order for the XCDs
+    _layer_case(big, None, 130, 140, True, order=1, seed=43, flags=flags)
     n, fi, fo = el.n, 24, 140
     dg = device_graph(el)
     g = torch.Generator(device="cpu").manual_seed(3)
