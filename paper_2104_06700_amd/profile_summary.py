@@ -40,11 +40,14 @@ CALIB_KERNEL = "copy16_kernel"
 CALIB_BYTES = 1 << 30  # the calibration copy reads 1 GiB and writes 1 GiB
 
 
+# sources of the aggregation calls (the layer, product and operator-table files do not change what they do)
+AGGREGATION_SOURCES = ("aggregate.hip", "blocked.hip", "plan.hip", "graph.hip", "common.h")
+
+
 def source_hash() -> str:
-    """Hash of the kernel sources and the header: identifies what a counter run measured."""
+    """Hash of the sources of the aggregation kernels and the header: identifies what a counter run measured."""
     h = hashlib.sha256()
-    files = sorted(glob.glob(os.path.join(PKG, "csrc", "*.hip")) + glob.glob(os.path.join(PKG, "csrc", "*.h")) +
-                   [os.path.join(ROOT, "include", "gnnagg.h")])
+    files = [os.path.join(PKG, "csrc", f) for f in AGGREGATION_SOURCES] + [os.path.join(ROOT, "include", "gnnagg.h")]
     for f in files:
         h.update(os.path.basename(f).encode())
         h.update(open(f, "rb").read())
