@@ -40,6 +40,11 @@ struct GemmArgs {
     // its gate (the bias gradient), written by the workgroups of the first tile row.
     const float *a_gate, *b_gate;
     float *colsum;
+    // Tile order.  The launch is one-dimensional and workgroup b runs on XCD b % 8, each with an L2 of its own.
+    // The tiles that read the same rows of an operand (the column tiles of one row tile of a tall product; all
+    // tiles of one part of a split reduction) get ids 8 apart: the same XCD, one after the other, so the second
+    // read of those rows hits that XCD's L2.  inner = number of such tiles (0: plain order, x fastest).
+    int32_t gx, gy, gz, inner;
 };
 
 // One [ROWS x BK] tile of an operand on its way from global memory to LDS (stored k-major as
@@ -52,6 +57,62 @@ struct Stager {
     static constexpr int PER_THREAD = (QUADS + kThreads - 1) / kThreads;
     float v[PER_THREAD][4];
     float gate[GATED ? PER_THREAD : 1][4];  // the gate's elements travel beside the operand's and are applied in store()
+
+    // Whole tiles of an aligned operand: the thread keeps the address of its quad 0 in the tile at k_begin; quad h
+    // lies a uniform step further, a later tile a uniform offset further; rows are checked against a 32-bit
+    // count.  The kernel's main loop uses only this path, so that it stays a few hundred instructions long: with
+    // the general path below inlined (64-bit address arithmetic and a check per element, for every quad of up to
+    // three matrices) the loop of the gated products outgrew what the instruction cache serves at full speed.
+    const float *p0;
+    int64_t step_h, k_step, gate_off;
+    int32_t rows_left;
+
+    __device__ __forceinline__ void init(const float *__restrict__ base, const float *__restrict__ gate_base, int64_t sr, int64_t sk,
+                                         int64_t r0, int64_t r_end, int64_t k_begin) {
+        const int q = int(threadIdx.x);
+        if (K_CONTIG) {
+            p0 = base + (r0 + (q >> 2)) * sr + k_begin + (q & 3) * 4;
+            step_h = (kThreads / 4) * sr;
+            k_step = 1;
+        } else {
+            p0 = base + (k_begin + q / (ROWS / 4)) * sk + r0 + (q % (ROWS / 4)) * 4;
+            step_h = (kThreads / (ROWS / 4)) * sk;
+            k_step = sk;
+        }
+        gate_off = (GATED && gate_base) ? gate_base - base : 0;
+        const int64_t left = r_end - r0;
+        rows_left = left > 0x7fffffff ? 0x7fffffff : int32_t(left);
+    }
+
+    // k_off = first k of the tile - k_begin (uniform); the tile lies inside the k range whole
+    __device__ __forceinline__ void load_whole_tile(int64_t k_off, bool gated) {
+        const float *pt = p0 + k_off * k_step;
+#pragma unroll
+        for (int h = 0; h < PER_THREAD; ++h) {
+            const int q = int(threadIdx.x) + h * kThreads;
+            if (QUADS % kThreads != 0 && q >= QUADS) continue;
+            const int first_row = K_CONTIG ? (q >> 2) : (q % (ROWS / 4)) * 4;
+            const int rows = K_CONTIG ? 1 : 4;  // rows this quad touches
+            const float *p = pt + h * step_h;
+            if (first_row + rows <= rows_left) {
+                const float4 x = *reinterpret_cast<const float4 *>(p);
+                v[h][0] = x.x; v[h][1] = x.y; v[h][2] = x.z; v[h][3] = x.w;
+                if constexpr (GATED) {
+                    if (gated) {
+                        const float4 y = *reinterpret_cast<const float4 *>(p + gate_off);
+                        gate[h][0] = y.x; gate[h][1] = y.y; gate[h][2] = y.z; gate[h][3] = y.w;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const bool ok = !K_CONTIG && first_row + i < rows_left;  // a quad of rows that straddles the end
+                    v[h][i] = ok ? p[i] : 0.0f;
+                    if constexpr (GATED) gate[h][i] = (ok && gated) ? p[gate_off + i] : 0.0f;
+                }
+            }
+        }
+    }
 
     __device__ __forceinline__ void load(const float *__restrict__ base, const float *__restrict__ gate_base, int64_t sr, int64_t sk,
                                          int64_t r0, int64_t r_end, int64_t k0, int64_t k_end, bool vec_ok) {
@@ -102,6 +163,18 @@ struct Stager {
         }
     }
 
+    // Adds what this thread staged (after store() applied the gate) to its sums over k: for an operand whose
+    // rows are contiguous a thread holds the same four rows in every tile.
+    __device__ __forceinline__ void add_to_row_sums(float (&acc)[4]) const {
+        static_assert(!K_CONTIG, "row sums are kept for row-contiguous operands only");
+#pragma unroll
+        for (int h = 0; h < PER_THREAD; ++h) {
+            if (QUADS % kThreads != 0 && int(threadIdx.x) + h * kThreads >= QUADS) continue;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[i] += v[h][i];
+        }
+    }
+
     __device__ __forceinline__ void store(float (*tile)[ROWS + PAD], bool gated) {
         if constexpr (GATED) {
             if (gated) {
@@ -139,8 +212,23 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu((
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int wm = (wave / WN) * TI * 32, wn = (wave % WN) * TJ * 32;  // this wavefront's part of the tile
-    const int64_t m0 = int64_t(blockIdx.x) * BM, n0 = int64_t(blockIdx.y) * BN;
-    const int64_t k_begin = int64_t(blockIdx.z) * g.k_per_split;
+    int64_t bx, by, bz;
+    {
+        const int64_t b = blockIdx.x;
+        if (g.inner > 0) {
+            const int64_t per = int64_t(8) * g.inner, r = b % per;
+            const int64_t outer = b / per * 8 + (r & 7), in = r >> 3;
+            if (g.gz > 1) { bz = outer; bx = in % g.gx; by = in / g.gx; }
+            else { bx = outer; by = in; bz = 0; }
+            if (bx >= g.gx || bz >= g.gz) return;  // the last group of 8 may be incomplete (whole workgroup leaves)
+        } else {
+            bx = b % g.gx;
+            by = b / g.gx % g.gy;
+            bz = b / (int64_t(g.gx) * g.gy);
+        }
+    }
+    const int64_t m0 = bx * BM, n0 = by * BN;
+    const int64_t k_begin = bz * g.k_per_split;
     const int64_t k_end = k_begin + g.k_per_split < g.K ? k_begin + g.k_per_split : g.K;
 
     float16v acc[TI][TJ];
@@ -154,25 +242,17 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu((
     Stager<A_K_CONTIG, BM, FOLD == 1> sa;
     Stager<B_K_CONTIG, BN, FOLD == 2> sb;
     const bool a_gated = FOLD == 1 && g.a_gate, b_gated = FOLD == 2 && g.b_gate;
-    const bool sums = FOLD == 2 && g.colsum && blockIdx.x == 0 && int(threadIdx.x) < BN;  // one thread per column of the tile
-    float col_sum = 0.0f;
-    if (k_begin < k_end) {
-        sa.load(g.A, g.a_gate, g.sam, g.sak, m0, g.M, k_begin, k_end, a_vec_ok != 0);
-        sb.load(g.B, g.b_gate, g.sbn, g.sbk, n0, g.N, k_begin, k_end, b_vec_ok != 0);
-    }
+    const bool sums = FOLD == 2 && g.colsum && bx == 0;  // the first tile row also adds up the columns of B (uniform)
+    float col_sum[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     const int l32 = lane & 31, lk = lane >> 5;
-    for (int64_t k0 = k_begin; k0 < k_end; k0 += BK) {
+    auto stage = [&]() {  // registers -> LDS
         sa.store(As, a_gated);
         sb.store(Bs, b_gated);
-        __syncthreads();
-        if (k0 + BK < k_end) {  // next tile's loads fly while this tile is multiplied
-            sa.load(g.A, g.a_gate, g.sam, g.sak, m0, g.M, k0 + BK, k_end, a_vec_ok != 0);
-            sb.load(g.B, g.b_gate, g.sbn, g.sbk, n0, g.N, k0 + BK, k_end, b_vec_ok != 0);
+        if constexpr (FOLD == 2) {
+            if (sums) sb.add_to_row_sums(col_sum);  // rows past k_end were staged as zeros
         }
-        if (sums) {  // rows past k_end were staged as zeros
-#pragma unroll
-            for (int kk = 0; kk < BK; ++kk) col_sum += Bs[kk][threadIdx.x];
-        }
+    };
+    auto multiply = [&]() {
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
             // operand layout of the 32x32x2 instruction: lane l holds A[l % 32][l / 32] and B[l / 32][l % 32]
@@ -186,14 +266,62 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu((
 #pragma unroll
                 for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
         }
+    };
+    auto load_any = [&](int64_t k0) {
+        sa.load(g.A, g.a_gate, g.sam, g.sak, m0, g.M, k0, k_end, a_vec_ok != 0);
+        sb.load(g.B, g.b_gate, g.sbn, g.sbk, n0, g.N, k0, k_end, b_vec_ok != 0);
+    };
+    // Tiles t = 0 .. n_tiles - 1; the first n_fast of them are whole tiles of aligned operands.  The loads of tile
+    // t + 1 are issued before tile t is multiplied, so they fly while the matrix cores work.
+    const int64_t n_tiles = k_begin < k_end ? (k_end - k_begin + BK - 1) / BK : 0;
+    const int64_t n_fast = (a_vec_ok && b_vec_ok && k_begin < k_end) ? (k_end - k_begin) / BK : 0;
+    sa.init(g.A, g.a_gate, g.sam, g.sak, m0, g.M, k_begin);
+    sb.init(g.B, g.b_gate, g.sbn, g.sbk, n0, g.N, k_begin);
+    if (n_fast > 0) {
+        sa.load_whole_tile(0, a_gated);
+        sb.load_whole_tile(0, b_gated);
+    } else if (n_tiles > 0) {
+        load_any(k_begin);
+    }
+    int64_t t = 0;
+    for (; t + 1 < n_fast; ++t) {  // the main loop: tile t + 1 is a whole one
+        stage();
+        __syncthreads();
+        sa.load_whole_tile((t + 1) * BK, a_gated);
+        sb.load_whole_tile((t + 1) * BK, b_gated);
+        multiply();
+        __syncthreads();
+    }
+    for (; t < n_tiles; ++t) {  // what is left: a last partial tile, or every tile of an operand that is not aligned
+        stage();
+        __syncthreads();
+        if (t + 1 < n_tiles) load_any(k_begin + (t + 1) * BK);
+        multiply();
         __syncthreads();
     }
 
-    if (sums && n0 + int(threadIdx.x) < g.N) g.colsum[int64_t(blockIdx.z) * g.N + n0 + threadIdx.x] = col_sum;
+    if constexpr (FOLD == 2) {
+        if (sums) {
+            // a thread holds 4 columns of one k-row of every tile; the threads that hold the same columns are
+            // added in thread order through LDS (the operand tiles are no longer needed)
+            constexpr int GROUPS = BN / 4, SLOTS = kThreads / GROUPS;
+            float *scr = &As[0][0];
+            static_assert(SLOTS * BN <= BK * (BM + PAD), "scratch fits the A tile");
+            const int grp = int(threadIdx.x) % GROUPS, slot = int(threadIdx.x) / GROUPS;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) scr[slot * BN + grp * 4 + i] = col_sum[i];
+            __syncthreads();
+            if (int(threadIdx.x) < BN && n0 + int(threadIdx.x) < g.N) {
+                float tsum = 0.0f;
+                for (int sl = 0; sl < SLOTS; ++sl) tsum += scr[sl * BN + threadIdx.x];
+                g.colsum[bz * g.N + n0 + threadIdx.x] = tsum;
+            }
+        }
+    }
 
     // result layout: register v of lane l is C[8 * (v / 4) + 4 * (l / 32) + v % 4][l % 32]
     float *out = g.C;
-    if (g.n_split > 1) out += int64_t(blockIdx.z) * g.M * g.ldc;  // partial planes of M x ldc
+    if (g.n_split > 1) out += bz * g.M * g.ldc;  // partial planes of M x ldc
 #pragma unroll
     for (int i = 0; i < TI; ++i)
 #pragma unroll
@@ -331,9 +459,17 @@ int gnn_matmul_impl(const float *A, int64_t lda, int trans_a, const float *B, in
     choose_tile(N, &BM, &BN);
     const int64_t gx = (M + BM - 1) / BM, gy = (N + BN - 1) / BN;
     if (gx > INT32_MAX || gy > 65535 || split > 65535) return GNN_ERR_UNSUPPORTED;
-    dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy), static_cast<unsigned>(split));
-    const int a_vec = (lda % 4 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0) ? 1 : 0;
-    const int b_vec = (ldb % 4 == 0 && reinterpret_cast<uintptr_t>(B) % 16 == 0) ? 1 : 0;
+    g.gx = int32_t(gx); g.gy = int32_t(gy); g.gz = int32_t(split);
+    int64_t n_groups = gx * gy * split;
+    const int64_t inner = split > 1 ? gx * gy : gy, outer = split > 1 ? split : gx;
+    if (inner >= 2 && inner <= 16 && outer >= 16) {
+        g.inner = int32_t(inner);
+        n_groups = (outer + 7) / 8 * 8 * inner;
+    }
+    if (n_groups > INT32_MAX) return GNN_ERR_UNSUPPORTED;
+    dim3 grid(static_cast<unsigned>(n_groups));
+    const int a_vec = (lda % 4 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0 && reinterpret_cast<uintptr_t>(g.a_gate) % 16 == 0) ? 1 : 0;
+    const int b_vec = (ldb % 4 == 0 && reinterpret_cast<uintptr_t>(B) % 16 == 0 && reinterpret_cast<uintptr_t>(g.b_gate) % 16 == 0) ? 1 : 0;
     const bool a_k = !trans_a, b_k = trans_b != 0;  // is k the contiguous direction of the operand?
     if (BN == 128) launch_gemm<2, 2, 2, 2>(a_k, b_k, grid, stream, g, a_vec, b_vec);
     else if (BN == 64) launch_gemm<4, 1, 2, 2>(a_k, b_k, grid, stream, g, a_vec, b_vec);
