@@ -257,6 +257,7 @@ def measure(workload, steps, warmup, scale, dev, dump_graph=None, flush=False, c
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "traffic_GBs": None if traffic is None else round(traffic / (all_s / len(call_rows)) / 1e9, 1),
+                "traffic_frac_of_peak": None if traffic is None else round(traffic / (all_s / len(call_rows)) / 1e9 / HBM_PEAK_GBS, 4),
                 "traffic_note": tnote.get("reason") or f"rocprofv3 FETCH_SIZE + WRITE_SIZE per call, profiles/hbm_traffic_{workload}.txt "
                                                        f"(kernel sources {tnote.get('source_hash')})",
                 "tcc_hit_pct": tnote.get("tcc_hit_pct"),
