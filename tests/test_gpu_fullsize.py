@@ -41,6 +41,18 @@ def _fullsize(name, f, op_name, weighted=False, dtype=torch.float32):
     gnn.gnn_aggregate_bwd(dg.indptr_t, dg.indices_t, dg.edge_w_t, dY, dX, n, f, op, plan=dg.plan_bwd)
     torch.cuda.synchronize()
     assert bool(torch.isfinite(Y).all()) and bool(torch.isfinite(dX).all())
+    # the same two calls from packed copies kept by the caller (widths of more than one line)
+    Yp = dXp = None
+    code = gnn.GNN_BF16 if dtype == torch.bfloat16 else gnn.GNN_F32
+    if gnn.gnn_packed_bytes(n, f, code) > 0:
+        buf = torch.empty(gnn.gnn_packed_bytes(n, f, code) // 4, dtype=torch.float32, device=DEV)
+        Yp, dXp = torch.full_like(X, float("nan")), torch.full_like(dY, float("nan"))
+        gnn.gnn_pack_rows(dg.indptr, dg.indices, X, buf, n, f, op, False, plan=dg.plan_fwd)
+        gnn.gnn_aggregate_packed(dg.indptr, dg.indices, dg.edge_w, buf, Yp, n, f, op, False, plan=dg.plan_fwd)
+        gnn.gnn_pack_rows(dg.indptr_t, dg.indices_t, dY, buf, n, f, op, True, plan=dg.plan_bwd)
+        gnn.gnn_aggregate_packed(dg.indptr_t, dg.indices_t, dg.edge_w_t, buf, dXp, n, f, op, True, plan=dg.plan_bwd)
+        torch.cuda.synchronize()
+        del buf
 
     # adjoint identity on the whole output, fp64 dot products (holds at any size)
     lhs = (Y.double() * dY.double()).sum().item()
@@ -67,6 +79,8 @@ def _fullsize(name, f, op_name, weighted=False, dtype=torch.float32):
     dout = np.bincount(src_h, minlength=n)
     Yo, S = oracle.aggregate_fwd(indptr, src_h, Xh, op=op, w=w_h, dout=dout, rows=rows, nthreads=8, want_scale=True)
     assert_close(Y[torch.from_numpy(rows).to(DEV)], Yo, S, dtype == torch.bfloat16, f"{name} fwd rows")
+    if Yp is not None:
+        assert_close(Yp[torch.from_numpy(rows).to(DEV)], Yo, S, dtype == torch.bfloat16, f"{name} fwd rows from the packed copy")
     del Xh
     indptr_t, indices_t, perm = oracle.transpose(indptr, src_h)
     rows_t = _sample_rows(np.diff(indptr_t), 8)
@@ -74,6 +88,8 @@ def _fullsize(name, f, op_name, weighted=False, dtype=torch.float32):
     dXo, St = oracle.aggregate_bwd(indptr_t, indices_t, dY.float().cpu().numpy(), op=op, wt=wt_h, din=din, rows=rows_t,
                                    nthreads=8, want_scale=True)
     assert_close(dX[torch.from_numpy(rows_t).to(DEV)], dXo, St, dtype == torch.bfloat16, f"{name} bwd rows")
+    if dXp is not None:
+        assert_close(dXp[torch.from_numpy(rows_t).to(DEV)], dXo, St, dtype == torch.bfloat16, f"{name} bwd rows from the packed copy")
     # the integer structure at full size, bit for bit
     assert np.array_equal(dg.indptr.cpu().numpy().astype(np.int64), indptr)
     assert np.array_equal(dg.indptr_t.cpu().numpy().astype(np.int64), indptr_t)
