@@ -103,3 +103,28 @@ def test_argument_checks_that_need_no_device():
     assert lib.gnn_sage_layer_saved_elems(10, 3, 5, 0) == 30 and lib.gnn_sage_layer_saved_elems(10, 5, 3, 0) == 40  # rows padded to 4 floats
     assert lib.gnn_sage_layer_saved_elems(10, 5, 3, 1) == 50
     assert lib.gnn_sage_layer_workspace_bytes(1000, 8, 4, 1, 0) >= 1000 * 4 * 4 * 2
+
+
+def test_packed_copy_sizes_and_argument_checks_that_need_no_device():
+    """gnn_packed_bytes is host arithmetic: one table per whole 128-byte line of a row, a dense table of
+    16-byte groups for a last line of at most 64 bytes; nothing for rows of one line or of more than 256."""
+    assert gnn.gnn_packed_bytes(1000, 100, gnn.GNN_F32) == 1000 * (3 * 32 + 4) * 4
+    assert gnn.gnn_packed_bytes(1000, 256, gnn.GNN_F32) == 1000 * 256 * 4
+    assert gnn.gnn_packed_bytes(1000, 50, gnn.GNN_F32) == 1000 * 64 * 4
+    assert gnn.gnn_packed_bytes(1000, 47, gnn.GNN_F32) == 1000 * (32 + 16) * 4
+    assert gnn.gnn_packed_bytes(7, 65, gnn.GNN_BF16) == 7 * (64 + 8) * 2
+    assert gnn.gnn_packed_bytes(1000, 32, gnn.GNN_F32) == 0 and gnn.gnn_packed_bytes(1000, 64, gnn.GNN_BF16) == 0
+    assert gnn.gnn_packed_bytes(1000, 256 * 32, gnn.GNN_F32) == 1000 * 256 * 32 * 4
+    assert gnn.gnn_packed_bytes(1000, 256 * 32 + 1, gnn.GNN_F32) == 0
+    assert gnn.gnn_packed_bytes(0, 100, gnn.GNN_F32) == 0 and gnn.gnn_packed_bytes(-3, 100, gnn.GNN_F32) == 0
+    assert gnn.gnn_packed_bytes(10, 100, 7) == 0
+    lib = gnn.load_library()
+    one = ctypes.c_void_p(128)  # never dereferenced
+    o = gnn.GnnOpts()
+    # the row order of a packed copy is a plan's: without one the calls refuse before any device work
+    assert lib.gnn_pack_rows(one, one, one, one, 1 << 20, 100, 100, 0, 0, ctypes.byref(o)) == gnn.GNN_ERR_UNSUPPORTED
+    assert lib.gnn_aggregate_packed(one, one, None, one, 1 << 20, one, 100, 100, 0, 0, ctypes.byref(o)) == gnn.GNN_ERR_UNSUPPORTED
+    assert lib.gnn_pack_rows(one, one, one, one, 1 << 20, -1, 100, 0, 0, None) == gnn.GNN_ERR_INVALID_ARG
+    assert lib.gnn_pack_rows(one, one, one, one, 1 << 20, 100, 100, 9, 0, None) == gnn.GNN_ERR_INVALID_ARG
+    assert lib.gnn_aggregate_packed(one, one, None, None, 0, one, 0, 100, 0, 0, None) == gnn.GNN_OK
+    assert lib.gnn_aggregate_packed(one, one, None, None, 0, one, 5, 100, 0, 0, None) == gnn.GNN_ERR_INVALID_ARG

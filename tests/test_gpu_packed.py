@@ -110,3 +110,46 @@ def test_packed_sizes_and_argument_checks():
     with pytest.raises(gnn.GnnError):   # rows of one line are gathered where they lie
         gnn.gnn_pack_rows(dg.indptr, dg.indices, X[:, :32].contiguous(), one_line, el.n, 32, gnn.GNN_SUM, False, plan=dg.plan_fwd)
     torch.cuda.synchronize()
+
+
+def test_packed_calls_can_be_captured_into_a_graph():
+    """After one eager call (plan-owned index copies are built then) neither gnn_pack_rows nor
+    gnn_aggregate_packed allocates, records a memset or synchronises: a step that repacks a changing matrix
+    and aggregates from the copy replays bit for bit, with eager work between the replays."""
+    el = synth.rmat_symmetric(20000, 600000, (0.57, 0.19, 0.19, 0.05), 3)
+    dg = device_graph(el, plan_params=gnn.make_plan_params([4, 32, 256], 128))
+    f, op = 100, gnn.GNN_SAGE_GCN
+    X = synth.normal_features(el.n, f, 1).to(DEV)
+    Y, dX = torch.empty_like(X), torch.empty_like(X)
+    pf = torch.empty(gnn.gnn_packed_bytes(el.n, f, gnn.GNN_F32) // 4, device=DEV)
+    pb = torch.empty_like(pf)
+
+    def step():
+        gnn.gnn_pack_rows(dg.indptr, dg.indices, X, pf, el.n, f, op, False, plan=dg.plan_fwd)
+        gnn.gnn_aggregate_packed(dg.indptr, dg.indices, None, pf, Y, el.n, f, op, False, plan=dg.plan_fwd)
+        gnn.gnn_pack_rows(dg.indptr_t, dg.indices_t, Y, pb, el.n, f, op, True, plan=dg.plan_bwd)
+        gnn.gnn_aggregate_packed(dg.indptr_t, dg.indices_t, None, pb, dX, el.n, f, op, True, plan=dg.plan_bwd)
+
+    step()
+    torch.cuda.synchronize()
+    want = (Y.clone(), dX.clone())
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        Y.fill_(float("nan"))
+        dX.fill_(float("nan"))
+        pf.fill_(float("nan"))
+        pb.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y, want[0]) and torch.equal(dX, want[1]), f"replay {rep}"
+        X.mul_(1.25)
+        step()
+        torch.cuda.synchronize()
+        want = (Y.clone(), dX.clone())
