@@ -77,7 +77,16 @@ def calibrate(dev):
     src.normal_()
     s = timed(lambda: gnn.gnn_calib_copy(src, dst))
     out["stream_copy_read_plus_write_GBs"] = round(2 * src.numel() * 4 / s / 1e9, 1)
-    del dst
+    # bare gather of 128-byte lines (nothing accumulated into rows, nothing written but one float per thread):
+    # what the memory system delivers per line request, from a table that fits every L2 and from one that does not
+    ids = torch.empty(1 << 28, dtype=torch.int32, device=dev)
+    probe_out = dst[: 1 << 23]
+    for label, lines in (("line_gather_probe_L2_resident_GBs", 16_384), ("line_gather_probe_L2_miss_infinity_cache_GBs", 1 << 20)):
+        ids.random_(0, lines)
+        n = gnn.gnn_calib_gather(src, lines, ids, probe_out)
+        s = timed(lambda: gnn.gnn_calib_gather(src, lines, ids, probe_out), reps=3)
+        out[label] = round(n * 128 / s / 1e9, 1)
+    del dst, ids, probe_out
     n_rows, degree, f = 2_449_029, 50, 100
     x = src[: n_rows * f].view(n_rows, f)
     y = torch.empty((n_rows, f), dtype=torch.float32, device=dev)
@@ -262,6 +271,7 @@ def measure(workload, steps, warmup, scale, dev, dump_graph=None, flush=False, c
                                                        f"(kernel sources {tnote.get('source_hash')})",
                 "tcc_hit_pct": tnote.get("tcc_hit_pct"),
                 "gathered_bytes_per_call": round(sum(e * r["F"] * esz for r in call_rows) / len(call_rows)),
+                "line_requests_per_call": round(sum(e * ((r["F"] * esz + 127) // 128) for r in call_rows) / len(call_rows)),
                 "kernel": "aggregate_kernel (all calls of one step: forward and backward at every width)",
                 "per": "call (= its aggregate_kernel launches + pad copy + hub finalisation)",
                 "launches_per_step": len(call_rows), "avg_launch_ms": round(all_s * 1e3 / len(call_rows), 4)}
@@ -550,6 +560,10 @@ def main():
         l2 = result["ceilings"]["gather_L2_resident_GBs"] * 1e9
         rf = result["roofline"]
         rf["on_chip_ceiling_frac"] = round(rf["gathered_bytes_per_call"] / l2 / (rf["avg_launch_ms"] * 1e-3), 4)
+        # the same against the bare probe: every gather is at least one request for a 128-byte line (a dense tail of
+        # 16 bytes costs one too), and the probe shows how many of those the chip serves per second from its L2s
+        probe = result["ceilings"]["line_gather_probe_L2_resident_GBs"] * 1e9 / 128
+        rf["line_request_ceiling_frac"] = round(rf["line_requests_per_call"] / probe / (rf["avg_launch_ms"] * 1e-3), 4)
         torch.cuda.empty_cache()
     if not args.no_other_workloads and full:
         # the other four workloads, briefly, so that every configuration has a figure from this very run

@@ -455,6 +455,14 @@ GNN_API const char *gnn_status_string(int status);
  * calibrate the FETCH_SIZE / WRITE_SIZE counters. */
 GNN_API int gnn_calib_copy(const void *src, void *dst, int64_t n_bytes, void *stream);
 
+/* Bare gather of 128-byte lines, a second measured ceiling: `table` holds n_lines lines (128-byte
+ * aligned), line_ids [n_ids] uint32 names the lines to fetch (ids beyond the table are clamped to its
+ * last line), 8 lanes fetch a line, 16 lines are in flight per lane group; 8,388,608 threads each write
+ * one float of `out` (out_elems >= 8,388,608, else GNN_ERR_INVALID_ARG).  Gathers
+ * floor(n_ids / 1,048,576 / 16) * 16 lines per lane group (at least 16, else GNN_ERR_INVALID_ARG). */
+GNN_API int gnn_calib_gather(const void *table, int64_t n_lines, const uint32_t *line_ids, int64_t n_ids, float *out,
+                             int64_t out_elems, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -14,7 +14,7 @@ from .binding import (  # noqa: F401
     GnnError, GnnOpts, GnnApOpts, GnnLayerOpts, GnnPlanParams, Plan,
     load_library, status_string, make_plan_params,
     gnn_aggregate_fwd, gnn_aggregate_bwd, gnn_csr_from_sorted_coo, gnn_transpose_csr, gnn_validate_csr,
-    gnn_plan_default_params, gnn_plan_create, gnn_calib_copy,
+    gnn_plan_default_params, gnn_plan_create, gnn_calib_copy, gnn_calib_gather,
     gnn_ap_fwd, gnn_ap_bwd_vertex, gnn_ap_bwd_vertex_arg, gnn_ap_bwd_edge, gnn_matmul, gnn_matmul_workspace_bytes,
     gnn_sage_layer_fwd, gnn_sage_layer_bwd, gnn_sage_layer_saved_elems, gnn_sage_layer_workspace_bytes,
 )

@@ -42,7 +42,7 @@ EXPORTED_SYMBOLS = (
     "gnn_ap_fwd", "gnn_ap_bwd_vertex", "gnn_ap_bwd_vertex_arg", "gnn_ap_bwd_edge",
     "gnn_matmul", "gnn_matmul_workspace_bytes",
     "gnn_sage_layer_fwd", "gnn_sage_layer_bwd", "gnn_sage_layer_saved_elems", "gnn_sage_layer_workspace_bytes",
-    "gnn_status_string", "gnn_calib_copy",
+    "gnn_status_string", "gnn_calib_copy", "gnn_calib_gather",
 )
 
 
@@ -149,6 +149,7 @@ def load_library() -> ctypes.CDLL:
         lib.gnn_status_string.argtypes = [i32]
         lib.gnn_status_string.restype = ctypes.c_char_p
         lib.gnn_calib_copy.argtypes = [vp, vp, i64, vp]
+        lib.gnn_calib_gather.argtypes = [vp, i64, vp, i64, vp, i64, vp]
         _lib = lib
     return _lib
 
@@ -577,3 +578,11 @@ def gnn_validate_csr(indptr, indices, N, E, stream=None) -> int:
 def gnn_calib_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
     st = load_library().gnn_calib_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), _stream(stream))
     _check("gnn_calib_copy", st)
+
+
+def gnn_calib_gather(table: torch.Tensor, n_lines: int, line_ids: torch.Tensor, out: torch.Tensor, stream=None) -> int:
+    """Bare gather of 128-byte lines (see include/gnnagg.h); returns the number of lines one call fetches."""
+    st = load_library().gnn_calib_gather(_ptr(table), int(n_lines), _ptr(line_ids), line_ids.numel(), _ptr(out), out.numel(),
+                                         _stream(stream))
+    _check("gnn_calib_gather", st)
+    return line_ids.numel() // (1 << 20) // 16 * 16 * (1 << 20)

@@ -45,9 +45,9 @@ AGGREGATION_SOURCES = ("aggregate.hip", "blocked.hip", "plan.hip", "graph.hip", 
 
 
 def source_hash() -> str:
-    """Hash of the sources of the aggregation kernels and the header: identifies what a counter run measured."""
+    """Hash of the sources of the aggregation kernels: identifies what a counter run measured."""
     h = hashlib.sha256()
-    files = [os.path.join(PKG, "csrc", f) for f in AGGREGATION_SOURCES] + [os.path.join(ROOT, "include", "gnnagg.h")]
+    files = [os.path.join(PKG, "csrc", f) for f in AGGREGATION_SOURCES]
     for f in files:
         h.update(os.path.basename(f).encode())
         h.update(open(f, "rb").read())
@@ -192,7 +192,7 @@ def write_summary(d: str, out_dir: str) -> None:
                  f"{'bf16' if r0.get('esz') == 2 else 'fp32'}{', explicit edge weights' if r0.get('weighted') else ''})")
     lines.append("")
     lines.append(f"Written by `python -m paper_2104_06700_amd.profile_summary` from rocprofv3 output; kernel sources "
-                 f"`{meta.get('source_hash', '?')}` (hash of csrc/ and the header), {meta.get('date', '?')}.")
+                 f"`{meta.get('source_hash', '?')}` (hash of the aggregation sources), {meta.get('date', '?')}.")
     lines.append("One agg_profile process per width and pass; a CALL = all kernels of one gnn_aggregate_fwd / _bwd "
                  "(copy into the plan's layout, piece / row / tail launches, finalisation).  Commands, from the repository root "
                  "on the MI355X box:")
