@@ -109,6 +109,11 @@ typedef struct gnn_opts {
 /* Do not process the long rows as source-blocked pieces (see gnn_blocking_params).  For A/B
  * measurements; results agree within rounding (the order of the additions differs). */
 #define GNN_FLAG_NO_SOURCE_BLOCKS 256
+/* Where the long rows are processed as source-blocked pieces, the launches over the short rows run
+ * beside them on a second, library-owned stream (default priority; joined before the call's last
+ * kernels, so the caller sees one stream).  NO: everything on the caller's stream, one launch after
+ * the other (A/B measurements).  Results do not depend on it. */
+#define GNN_FLAG_NO_SHORT_ROW_OVERLAP 512
 
 /* Degree-binning parameters.  thresholds t[0] < ... < t[k-1], all > 0, cut the
  * row-length axis into k+1 bins, bin(v) = #{i : t[i] <= deg(v)}.  If

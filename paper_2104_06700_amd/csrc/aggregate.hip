@@ -867,6 +867,19 @@ hipError_t launch_coef(bool coef, int npass, dim3 grid, hipStream_t stream, cons
 
 constexpr int kMaxPass = 8;
 
+// A library-owned second stream per device (default priority, created on first use, kept until the process
+// ends): the launches over the short rows run there while the caller's stream sweeps the source blocks of the
+// long rows.
+hipStream_t overlap_stream() {
+    static std::mutex mu;
+    static hipStream_t streams[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!streams[dev] && hipStreamCreateWithFlags(&streams[dev], hipStreamNonBlocking) != hipSuccess) streams[dev] = nullptr;
+    return streams[dev];
+}
+
 // One direction of the aggregation.  `gathered` is X (forward) or dY (backward).  bias / relu:
 // the epilogue of a fused layer (out = act(aggregate + bias)), or nullptr / 0.
 // no_alloc: the hub partial sums go into the library's fixed device array and the call allocates
@@ -1184,6 +1197,35 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
     bool plain_hub_columns = false;   // some launch left its hub rows to hub_finalize_kernel
     int64_t plain_hub_col_begin = F;  // ... from this column on
 
+    // The short rows of the blocked launches run on a second stream beside the pieces: they write other rows and
+    // read the same tables, the pieces are bound by line requests that hit in the L2s and the short rows by the
+    // misses behind them (2.45 M vertices: F=100 5.57 -> 5.32 ms, F=256 10.11 -> 9.98)
+    hipStream_t side = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+    if (bl.active && !(o.flags & GNN_FLAG_NO_SHORT_ROW_OVERLAP)) {
+        side = overlap_stream();
+        if (side && (hipEventCreateWithFlags(&fork, hipEventDisableTiming) != hipSuccess ||
+                     hipEventCreateWithFlags(&join, hipEventDisableTiming) != hipSuccess)) {
+            if (fork) (void)hipEventDestroy(fork);
+            fork = join = nullptr;
+            side = nullptr;
+            (void)hipGetLastError();
+        }
+        if (side && (hipEventRecord(fork, stream) != hipSuccess || hipStreamWaitEvent(side, fork, 0) != hipSuccess)) {
+            (void)hipEventDestroy(fork);
+            (void)hipEventDestroy(join);
+            return GNN_ERR_LAUNCH;
+        }
+    }
+    auto finish_overlap = [&]() -> bool {  // the caller's stream waits for the second one; true = fine
+        if (!side) return true;
+        const bool ok = hipEventRecord(join, side) == hipSuccess && hipStreamWaitEvent(stream, join, 0) == hipSuccess;
+        (void)hipEventDestroy(fork);  // released by the runtime once the recorded work has completed
+        (void)hipEventDestroy(join);
+        side = nullptr;
+        return ok;
+    };
+
     for (int gi = 0; gi < n_segs; ++gi) {
         const int64_t f0 = segs[gi].f0, fw = segs[gi].fw;
         const int log2_s = segs[gi].log2_s;
@@ -1239,7 +1281,7 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         if (blocked) {
             const int line_floats = int(line_elems);
             int rc = gnn_plan_blocked_partial(plan, 1 << log2_s, line_floats);
-            if (rc != GNN_OK) return rc;
+            if (rc != GNN_OK) { finish_overlap(); return rc; }
             PieceArgs pa{};
             pa.pieces = bl.pieces;
             pa.n_pieces = bl.n_pieces;
@@ -1252,7 +1294,7 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
             pa.partial = static_cast<float *>(plan->blk_partial);
             pa.log2_slices = log2_s;
             const int64_t pblocks = ((bl.n_pieces + 8 * kWavesPerBlock - 1) / (8 * kWavesPerBlock)) << log2_s;
-            if (pblocks > INT32_MAX) return GNN_ERR_UNSUPPORTED;
+            if (pblocks > INT32_MAX) { finish_overlap(); return GNN_ERR_UNSUPPORTED; }
             const int n_sl = 1 << log2_s;
             const dim3 pgrid(static_cast<unsigned>(pblocks)), fgrid(static_cast<unsigned>((bl.n_hot * n_sl * 8 + 255) / 256));
             const int32_t *hot_rows = plan->row_perm + bl.hot_begin;
@@ -1272,7 +1314,7 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
                     static_cast<bf16_t *>(out) + f0, ldy, int(fw), store_vec, fin_self_mode, own,
                     plan->col_counts, bias ? bias + f0 : nullptr, relu);
             }
-            if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
+            if (hipGetLastError() != hipSuccess) { finish_overlap(); return GNN_ERR_LAUNCH; }
         } else if (has_hub) {
             plain_hub_columns = true;
             if (f0 < plain_hub_col_begin) plain_hub_col_begin = f0;
@@ -1282,23 +1324,25 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         a.n_bins = nb;
         if (nb == 0 || next_block == 0) continue;
         next_block <<= log2_s;
-        if (next_block > INT32_MAX) return GNN_ERR_UNSUPPORTED;
+        if (next_block > INT32_MAX) { finish_overlap(); return GNN_ERR_UNSUPPORTED; }
 
         dim3 grid(static_cast<unsigned>(next_block));
         hipError_t err = hipSuccess;
+        hipStream_t rows_stream = (blocked && side) ? side : stream;  // the short rows of a blocked launch may overlap the pieces
         if (o.dtype == GNN_F32) {
-            if (vec == 4) err = launch_coef<float, 4>(coef, npass, grid, stream, a);
-            else if (vec == 2) err = launch_coef<float, 2>(coef, npass, grid, stream, a);
-            else err = launch_coef<float, 1>(coef, npass, grid, stream, a);
+            if (vec == 4) err = launch_coef<float, 4>(coef, npass, grid, rows_stream, a);
+            else if (vec == 2) err = launch_coef<float, 2>(coef, npass, grid, rows_stream, a);
+            else err = launch_coef<float, 1>(coef, npass, grid, rows_stream, a);
         } else {
-            if (vec == 8) err = launch_coef<bf16_t, 8>(coef, npass, grid, stream, a);
-            else if (vec == 4) err = launch_coef<bf16_t, 4>(coef, npass, grid, stream, a);
-            else if (vec == 2) err = launch_coef<bf16_t, 2>(coef, npass, grid, stream, a);
-            else err = launch_coef<bf16_t, 1>(coef, npass, grid, stream, a);
+            if (vec == 8) err = launch_coef<bf16_t, 8>(coef, npass, grid, rows_stream, a);
+            else if (vec == 4) err = launch_coef<bf16_t, 4>(coef, npass, grid, rows_stream, a);
+            else if (vec == 2) err = launch_coef<bf16_t, 2>(coef, npass, grid, rows_stream, a);
+            else err = launch_coef<bf16_t, 1>(coef, npass, grid, rows_stream, a);
         }
-        if (err != hipSuccess) return GNN_ERR_LAUNCH;
+        if (err != hipSuccess) { finish_overlap(); return GNN_ERR_LAUNCH; }
     }
 
+    if (!finish_overlap()) return GNN_ERR_LAUNCH;
     if (has_hub && plain_hub_columns) {
         const int64_t hub_begin = plan->bin_offsets[plan->n_bins - 1];
         dim3 grid(static_cast<unsigned>(plan->n_hub_rows));

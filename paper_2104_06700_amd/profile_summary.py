@@ -106,6 +106,25 @@ def read_meta(d: str) -> dict:
     return meta
 
 
+def busy_ms(trace_csv: str, wanted) -> float:
+    """Time during which at least one kernel accepted by `wanted(short name)` ran: the union of their
+    [start, end] intervals.  Kernels of one call may run side by side on two streams (the short rows beside the
+    source-blocked pieces), so their durations do not add up to the call's time; the union does."""
+    spans = sorted((int(r["Start_Timestamp"]), int(r["End_Timestamp"])) for r in csv.DictReader(open(trace_csv))
+                   if wanted(short_name(r["Kernel_Name"])))
+    total, cur_a, cur_b = 0, None, None
+    for a, b in spans:
+        if cur_b is None or a > cur_b:
+            if cur_b is not None:
+                total += cur_b - cur_a
+            cur_a, cur_b = a, b
+        elif b > cur_b:
+            cur_b = b
+    if cur_b is not None:
+        total += cur_b - cur_a
+    return total / 1e6
+
+
 def summarise_width(d: str) -> dict:
     """All figures of one width directory."""
     res = {"dir": d}
@@ -166,6 +185,7 @@ def summarise_width(d: str) -> dict:
         if _is_call_kernel(k):
             trace_ms += sum(vs)
     res["trace_ms_per_call"] = trace_ms / n_calls if n_calls else None
+    res["busy_ms_per_call"] = busy_ms(trace, _is_call_kernel) / n_calls if trace and n_calls else None
     return res
 
 
@@ -239,7 +259,10 @@ def write_summary(d: str, out_dir: str) -> None:
                          f"compulsory {alg / 1e9:.2f} GB ({(rd + wr) / alg:.1f}x); gathered {gathered / 1e9:.1f} GB "
                          f"(reuse = gathered / fetched = {gathered / rd:.2f})")
             if ms:
-                lines.append(f"    per call: {ms:.3f} ms by the driver's events ({r['trace_ms_per_call']:.3f} ms summed over the kernel trace): "
+                busy = r.get("busy_ms_per_call")
+                lines.append(f"    per call: {ms:.3f} ms by the driver's events ({busy:.3f} ms of the kernel trace covered by at least one of "
+                             f"the call's kernels; their durations add up to {r['trace_ms_per_call']:.3f} ms because the short rows run beside "
+                             f"the pieces on a second stream): "
                              f"{(rd + wr) / ms / 1e9:.2f} TB/s behind the L2s, {gathered / ms / 1e9:.2f} TB/s gathered, "
                              f"{alg / ms / 1e9 / 8.0 * 100:.2f} % of the 8 TB/s peak on compulsory bytes"
                              + (f"; L2 hit rate {hitp:.1f} %" if hitp is not None else ""))
@@ -281,8 +304,13 @@ def write_bench_stats(d: str, out_dir: str) -> None:
         call_total += float(r["TotalDurationNs"]) / 1e6
         out.append(f"    {name:42s} {int(r['Calls']):>6d} {float(r['TotalDurationNs']) / 1e6:>11.3f} {float(r['AverageNs']) / 1e6:>11.4f} "
                    f"{float(r['Percentage']):>6.2f}")
+    trace = _find(d, "*kernel_trace.csv")
+    busy = busy_ms(trace, _is_call_kernel) if trace else None
+    busy_txt = (f"  At least one of them was running during {busy:.3f} ms = {busy / n_calls:.3f} ms per call (union of their intervals in "
+                f"the kernel trace: the launches over the short rows run beside the source-blocked pieces on a second stream, so the "
+                f"durations above overlap and do not add up to the call).") if busy is not None else ""
     out += ["", f"{n_calls} aggregation calls = ({res['steps']} + {res['warmup']}) steps x {res['roofline']['launches_per_step']} calls; "
-                f"the kernels above sum to {call_total:.3f} ms = {call_total / n_calls:.3f} ms per call.",
+                f"the kernels above sum to {call_total:.3f} ms = {call_total / n_calls:.3f} ms per call.{busy_txt}",
             f"The JSON line of the same run: value {res['value']} {res['unit']}, {res['ms_per_step']} ms per step, mean call "
             f"{res['roofline']['avg_launch_ms']} ms by events on the launch stream (`roofline.avg_launch_ms`; the unit the roofline is "
             f"taken over is the call = its copy into the plan's layout + piece / row / tail launches + finalisation), "

@@ -123,3 +123,44 @@ def test_blocked_results_are_reproducible_and_parameters_are_checked():
     gnn.gnn_aggregate_fwd(fresh.indptr, fresh.indices, None, X, Y, el.n, 100, gnn.GNN_MEAN, plan=fresh.plan_fwd, flags=SLICED, max_slices=8)
     torch.cuda.synchronize()
     assert fresh.plan_fwd.blocked_sizes() == (0, 0, 0, 0)
+
+
+def test_blocked_call_with_its_second_stream_can_be_captured_into_a_graph():
+    """The short rows run on a library-owned second stream beside the pieces (forked from and joined to the
+    caller's stream inside the call): the whole call is still one unit of work on the caller's stream, can be
+    captured, and replays bit for bit; switching the overlap off gives the same bits."""
+    el = _graph()
+    dg = _dg(el)
+    f = 100
+    X = synth.normal_features(el.n, f, 4).to(DEV)
+    Y, dX = torch.empty_like(X), torch.empty_like(X)
+
+    def step(flags=SLICED):
+        gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, None, X, Y, el.n, f, gnn.GNN_SAGE_GCN, plan=dg.plan_fwd, flags=flags, max_slices=4)
+        gnn.gnn_aggregate_bwd(dg.indptr_t, dg.indices_t, None, Y, dX, el.n, f, gnn.GNN_SAGE_GCN, plan=dg.plan_bwd, flags=flags, max_slices=4)
+
+    step()
+    torch.cuda.synchronize()
+    assert dg.plan_fwd.blocked_sizes()[2] > 0
+    want = (Y.clone(), dX.clone())
+    step(SLICED | gnn.GNN_FLAG_NO_SHORT_ROW_OVERLAP)
+    torch.cuda.synchronize()
+    assert torch.equal(Y, want[0]) and torch.equal(dX, want[1])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        Y.fill_(float("nan"))
+        dX.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y, want[0]) and torch.equal(dX, want[1]), f"replay {rep}"
+        X.mul_(0.75)
+        step()
+        torch.cuda.synchronize()
+        want = (Y.clone(), dX.clone())
