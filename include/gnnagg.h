@@ -111,8 +111,11 @@ typedef struct gnn_opts {
 #define GNN_FLAG_NO_SOURCE_BLOCKS 256
 /* Where the long rows are processed as source-blocked pieces, the launches over the short rows run
  * beside them on a second, library-owned stream (default priority; joined before the call's last
- * kernels, so the caller sees one stream).  NO: everything on the caller's stream, one launch after
- * the other (A/B measurements).  Results do not depend on it. */
+ * kernels, so the caller sees one stream; under stream capture that stream joins the capture for the
+ * length of the call).  The library has one such stream per device: calls of different host threads
+ * queue up on it, and two threads that capture graphs at the same time must set NO.  NO: everything
+ * on the caller's stream, one launch after the other (also for A/B measurements).  Results do not
+ * depend on it. */
 #define GNN_FLAG_NO_SHORT_ROW_OVERLAP 512
 
 /* Degree-binning parameters.  thresholds t[0] < ... < t[k-1], all > 0, cut the
