@@ -81,7 +81,8 @@ def calibrate(dev):
     # what the memory system delivers per line request, from a table that fits every L2 and from one that does not
     ids = torch.empty(1 << 28, dtype=torch.int32, device=dev)
     probe_out = dst[: 1 << 23]
-    for label, lines in (("line_gather_probe_L2_resident_GBs", 16_384), ("line_gather_probe_L2_miss_infinity_cache_GBs", 1 << 20)):
+    for label, lines in (("line_gather_probe_L2_resident_GBs", 16_384), ("line_gather_probe_two_thirds_L2_hits_GBs", 49_152),
+                         ("line_gather_probe_half_L2_hits_GBs", 65_536), ("line_gather_probe_L2_miss_infinity_cache_GBs", 1 << 20)):
         ids.random_(0, lines)
         n = gnn.gnn_calib_gather(src, lines, ids, probe_out)
         s = timed(lambda: gnn.gnn_calib_gather(src, lines, ids, probe_out), reps=3)
