@@ -260,9 +260,10 @@ def write_summary(d: str, out_dir: str) -> None:
                          f"(reuse = gathered / fetched = {gathered / rd:.2f})")
             if ms:
                 busy = r.get("busy_ms_per_call")
+                overlap = (f"; their durations add up to {r['trace_ms_per_call']:.3f} ms because the short rows run beside the pieces on a "
+                           f"second stream") if r["trace_ms_per_call"] > 1.02 * busy else ""
                 lines.append(f"    per call: {ms:.3f} ms by the driver's events ({busy:.3f} ms of the kernel trace covered by at least one of "
-                             f"the call's kernels; their durations add up to {r['trace_ms_per_call']:.3f} ms because the short rows run beside "
-                             f"the pieces on a second stream): "
+                             f"the call's kernels{overlap}): "
                              f"{(rd + wr) / ms / 1e9:.2f} TB/s behind the L2s, {gathered / ms / 1e9:.2f} TB/s gathered, "
                              f"{alg / ms / 1e9 / 8.0 * 100:.2f} % of the 8 TB/s peak on compulsory bytes"
                              + (f"; L2 hit rate {hitp:.1f} %" if hitp is not None else ""))
