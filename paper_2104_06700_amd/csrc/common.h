@@ -375,7 +375,7 @@ int gnn_pad_rows_f32(const float *src, int64_t ld_src, float *dst, int64_t ld_ds
 // packed: write the result into a producer-side layout instead of C (C may then be nullptr; M = the plan's rows).
 // Rectifier gate of a layer's backward pass folded into the product's operand loads: an element of the
 // operand counts as 0 where the gate matrix (same shape and strides) is not positive.  a_gate needs
-// trans_a == 0 and trans_b != 0 (dZ = G W^T), b_gate and colsum need trans_a != 0 and trans_b == 0
+// trans_a == 0 (dZ = G W^T, with W^T given either way), b_gate and colsum need trans_a != 0 and trans_b == 0
 // (dW = Z^T G).  colsum: room for colsum_planes planes of N floats; the call writes n_planes of them
 // (the column sums of the gated B over each part of the split reduction, to be added in plane order).
 struct gnn_gemm_fold {

@@ -322,6 +322,36 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu((
     // result layout: register v of lane l is C[8 * (v / 4) + 4 * (l / 32) + v % 4][l % 32]
     float *out = g.C;
     if (g.n_split > 1) out += bz * g.M * g.ldc;  // partial planes of M x ldc
+    const gnn_packed_target &pk = g.packed;
+    if (pk.active) {
+        // producer-side layout: the 32 lanes of a row write one 128-byte line of a slice table (or a piece of the
+        // tail) at the row's rank; rank and factor of a row are looked up once for all its column tiles
+        float *pk_col[TJ];
+        int64_t pk_ld[TJ];
+#pragma unroll
+        for (int j = 0; j < TJ; ++j) {
+            const int64_t n = n0 + wn + j * 32 + l32;
+            pk_col[j] = nullptr;
+            pk_ld[j] = 0;
+            if (n < g.N) {
+                if (n < pk.main_cols) { pk_col[j] = pk.base + (n >> 5) * pk.table_stride + (n & 31); pk_ld[j] = 32; }
+                else { pk_col[j] = pk.tail + (n - pk.main_cols); pk_ld[j] = pk.tail_ld; }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < TI; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int64_t m = m0 + wm + i * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
+                if (m >= g.M) continue;
+                const int64_t row = pk.rank[m];
+                const float fac = gnn_row_factor(pk.scale_mode, pk.scale_mode ? pk.counts[m] : 0);
+#pragma unroll
+                for (int j = 0; j < TJ; ++j)
+                    if (pk_col[j]) pk_col[j][row * pk_ld[j]] = acc[i][j][v] * fac;
+            }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < TI; ++i)
 #pragma unroll
@@ -329,22 +359,13 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu((
             const int64_t n = n0 + wn + j * 32 + l32;
             if (n >= g.N) continue;
             const float bv = (g.bias && g.n_split == 1) ? g.bias[n] : 0.0f;
-            // producer-side layout: the 32 lanes of a row write one 128-byte line of a slice table (or a piece of the tail)
-            const gnn_packed_target &pk = g.packed;
-            float *pk_col = nullptr;
-            int64_t pk_ld = 0;
-            if (pk.active) {
-                if (n < pk.main_cols) { pk_col = pk.base + (n >> 5) * pk.table_stride + (n & 31); pk_ld = 32; }
-                else { pk_col = pk.tail + (n - pk.main_cols); pk_ld = pk.tail_ld; }
-            }
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int64_t m = m0 + wm + i * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
                 if (m >= g.M) continue;
                 float r = acc[i][j][v] + bv;
                 if (g.relu && g.n_split == 1) r = r > 0.0f ? r : 0.0f;
-                if (pk.active) pk_col[int64_t(pk.rank[m]) * pk_ld] = r * gnn_row_factor(pk.scale_mode, pk.counts[m]);
-                else out[m * g.ldc + n] = r;
+                out[m * g.ldc + n] = r;
             }
         }
 }
@@ -352,7 +373,8 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu((
 template <int WM, int WN, int TI, int TJ>
 void launch_gemm(bool a_k, bool b_k, dim3 grid, hipStream_t stream, const GemmArgs &g, int a_vec, int b_vec) {
     // the two products of a layer's backward pass that take G = (dH where H > 0) as an operand
-    if (g.a_gate) gemm_kernel<true, true, WM, WN, TI, TJ, 1><<<grid, kThreads, 0, stream>>>(g, a_vec, b_vec);
+    if (g.a_gate && b_k) gemm_kernel<true, true, WM, WN, TI, TJ, 1><<<grid, kThreads, 0, stream>>>(g, a_vec, b_vec);
+    else if (g.a_gate) gemm_kernel<true, false, WM, WN, TI, TJ, 1><<<grid, kThreads, 0, stream>>>(g, a_vec, b_vec);
     else if (g.b_gate || g.colsum) gemm_kernel<false, false, WM, WN, TI, TJ, 2><<<grid, kThreads, 0, stream>>>(g, a_vec, b_vec);
     else if (a_k && !b_k) gemm_kernel<true, false, WM, WN, TI, TJ><<<grid, kThreads, 0, stream>>>(g, a_vec, b_vec);
     else if (a_k && b_k) gemm_kernel<true, true, WM, WN, TI, TJ><<<grid, kThreads, 0, stream>>>(g, a_vec, b_vec);
@@ -424,11 +446,12 @@ int gnn_matmul_impl(const float *A, int64_t lda, int trans_a, const float *B, in
     if (K > 0 && (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N))) return GNN_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(C) % 4 || reinterpret_cast<uintptr_t>(A) % 4 || reinterpret_cast<uintptr_t>(B) % 4)
         return GNN_ERR_INVALID_ARG;
+    if (to_packed && (bias || relu)) return GNN_ERR_UNSUPPORTED;  // the aggregation that follows applies them
     if (to_packed && (!packed->base || !packed->rank || (packed->scale_mode && !packed->counts) ||
                       (packed->main_cols < N && !packed->tail)))
         return GNN_ERR_INVALID_ARG;
     // gates and column sums exist for the operand layouts of the layer's backward products only
-    if (fold && fold->a_gate && (trans_a || !trans_b || fold->b_gate || fold->colsum)) return GNN_ERR_UNSUPPORTED;
+    if (fold && fold->a_gate && (trans_a || fold->b_gate || fold->colsum)) return GNN_ERR_UNSUPPORTED;
     if (fold && (fold->b_gate || fold->colsum) && (!trans_a || trans_b)) return GNN_ERR_UNSUPPORTED;
     (void)hipGetLastError();
 
