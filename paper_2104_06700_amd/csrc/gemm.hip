@@ -8,9 +8,9 @@
 // tiles (256 x 64 or 256 x 32 tiles for narrow outputs).  A and B tiles of 16 k-steps are staged
 // through LDS k-major ([k][m] and [k][n]), so that the 32 lanes of an MFMA operand read
 // consecutive words; the global loads follow whichever direction of the operand is contiguous
-// and are issued one tile ahead, so they fly while the matrix cores work on the current tile.  The reduction over a very long k (the weight gradient:
-// k = number of vertices) is split over blockIdx.z into partial tiles that a second kernel adds in
-// order (deterministic, no atomics).
+// and are issued one tile ahead, so they fly while the matrix cores work on the current tile.  The
+// reduction over a very long k (the weight gradient: k = number of vertices) is split into parts
+// whose partial tiles a second kernel adds in order (deterministic, no atomics).
 #include "common.h"
 
 namespace {
