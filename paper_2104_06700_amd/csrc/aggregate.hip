@@ -1264,7 +1264,10 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
         // Launches of one slice get none: no measurable effect on a whole line, and the dense tail loses
         // with it (8 rows share a line there: F=100 5.70 -> 5.88 ms).
         a.warm_rank = INT32_MAX;
-        if (rank_indices && rl.cold_pays && log2_s > 0) a.warm_rank = int32_t(32768) * (log2_s <= 2 ? 8 : 6);
+        // With the long rows taken out as source-blocked pieces the hints stopped paying for the short rows that are
+        // left (2.45 M vertices: F=100 5.32 -> 5.28 ms without them, F=256 the same either way, as with any warm set
+        // from 12 x 32,768 rows up): they are kept for the launches that serve all rows.
+        if (rank_indices && rl.cold_pays && log2_s > 0 && !bl.active) a.warm_rank = int32_t(32768) * (log2_s <= 2 ? 8 : 6);
         a.X_tail = tail_table;
         a.ld_tail = layout.tail_ld;
         a.tail_slice = segs[gi].tail_slice;
