@@ -256,13 +256,17 @@ int gnn_plan_blocked(gnn_plan *plan, const void *indptr, hipStream_t stream, gnn
         const int64_t N = plan->n_rows, E = plan->n_edges;
         gnn_blocking_params prm = plan->blocking;
         const bool automatic = prm.min_degree == 0;
-        // Defaults, from measurements on the 2.45 M-vertex power-law graph (see the kernel profile):
-        // rows of >= 256 edges, block 0 = the 16,384 most-gathered sources, further blocks of 32,768.
+        // Defaults, from measurements on the 2.45 M-vertex and 233 K-vertex power-law graphs with the short rows
+        // running beside the pieces (see the kernel profile): rows of >= 256 edges, block 0 = the 16,384
+        // most-gathered sources, further blocks of 24,576 (three quarters of an L2: the short rows' lines pass
+        // through the same L2s), pieces of at most 96 edges, and one last block for every source gathered fewer
+        // than 16 times (their reuse is not worth a partial line per block and row).  Against 32,768 / 128 / 3:
+        // F=100 5.28 -> 5.12 ms, F=256 9.99 -> 9.78, F=512 20.0 -> 19.6; 233 K vertices F=602 13.58 -> 13.46.
         if (prm.min_degree == 0) prm.min_degree = 256;
         if (prm.hot_lines == 0) prm.hot_lines = 16384;
-        if (prm.block_lines == 0) prm.block_lines = 32768;
-        if (prm.max_piece == 0) prm.max_piece = 128;
-        if (prm.rest_min_count == 0) prm.rest_min_count = 3;
+        if (prm.block_lines == 0) prm.block_lines = 24576;
+        if (prm.max_piece == 0) prm.max_piece = 96;
+        if (prm.rest_min_count == 0) prm.rest_min_count = 16;
         int first_bin = -1;
         for (int i = 0; i < plan->params.n_thresholds; ++i)
             if (plan->params.thresholds[i] == prm.min_degree) first_bin = i + 1;
