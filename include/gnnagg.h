@@ -140,7 +140,8 @@ typedef struct gnn_blocking_params {
     int64_t hot_lines;       /* sources in block 0 (the most-gathered ones) */
     int64_t block_lines;     /* sources per further block */
     int64_t max_piece;       /* edges per piece at most */
-    int64_t rest_min_count;  /* sources gathered fewer times than this share one last block (at most 16) */
+    int64_t rest_min_count;  /* sources gathered fewer times than this share one last block; 0 .. 16 or a boundary of
+                                the plan's count histogram above that: 18, 20, .. 32, 36, 40, .. 64, 72, .. (8 per octave) */
 } gnn_blocking_params;
 
 /* ---------------------------------------------------------------- hot path */

@@ -182,7 +182,11 @@ extern "C" GNN_API int gnn_plan_set_blocking(gnn_plan *plan, const gnn_blocking_
     gnn_blocking_params p{};
     if (params) p = *params;
     if (p.hot_lines < 0 || p.block_lines < 0 || p.max_piece < 0 || p.rest_min_count < 0) return GNN_ERR_INVALID_ARG;
-    if (p.hot_lines > INT32_MAX || p.block_lines > INT32_MAX || p.max_piece > 32767 || p.rest_min_count > 16) return GNN_ERR_INVALID_ARG;
+    if (p.hot_lines > INT32_MAX || p.block_lines > INT32_MAX || p.max_piece > 32767) return GNN_ERR_INVALID_ARG;
+    // the threshold must be a boundary of the plan's count histogram: 0 .. 16, 18, 20, .. 32, 36, 40, .. 64, 72, ...
+    if (p.rest_min_count > (1 << 20) ||
+        gnn_count_bucket_lower_bound(gnn_count_bucket_of(p.rest_min_count)) != p.rest_min_count)
+        return GNN_ERR_INVALID_ARG;
     if (p.min_degree > 0) {  // must be a boundary between two bins
         bool found = false;
         for (int i = 0; i < plan->params.n_thresholds; ++i) found |= plan->params.thresholds[i] == p.min_degree;
@@ -289,12 +293,9 @@ int gnn_plan_blocked(gnn_plan *plan, const void *indptr, hipStream_t stream, gnn
         if (enable && automatic) enable = N >= 4 * int64_t(32768) && n_edges * 4 >= E;
         BlockMap m{};
         if (enable) {
-            // sources gathered fewer than rest_min_count times share the last block (counts below 16 have a bucket each)
-            int64_t rest_begin = N;
-            if (prm.rest_min_count <= 16) {
-                rest_begin = 0;
-                for (int b = 255; b >= prm.rest_min_count && b >= 0; --b) rest_begin += plan->bucket_vertices[b];
-            }
+            // sources gathered fewer than rest_min_count times share the last block (the threshold is a bucket boundary)
+            int64_t rest_begin = 0;
+            for (int b = 255; b >= gnn_count_bucket_of(prm.rest_min_count) && b >= 0; --b) rest_begin += plan->bucket_vertices[b];
             m.hot = int32_t(prm.hot_lines < N ? prm.hot_lines : N);
             m.block = int32_t(prm.block_lines);
             m.rest_begin = int32_t(rest_begin > m.hot ? rest_begin : m.hot);

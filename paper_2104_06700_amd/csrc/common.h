@@ -122,6 +122,21 @@ int64_t gnn_sort_sums_elems(int64_t n);
 int gnn_scan_exclusive_u32(uint32_t *data, int64_t n, uint32_t *sums, hipStream_t stream);
 int64_t gnn_scan_sums_elems(int64_t n);
 
+// The 256 buckets over the count axis that a plan's histogram uses (plan.hip: count_bucket): counts below 16 one
+// bucket each, then 8 buckets per octave.  Host-side twins for code that turns a count threshold into a rank.
+static inline int gnn_count_bucket_of(int64_t c) {
+    if (c < 16) return c < 0 ? 0 : int(c);
+    int o = 0;
+    while ((c >> (o + 1)) > 0) ++o;
+    const int b = 16 + (o - 4) * 8 + int((c >> (o - 3)) & 7);
+    return b > 255 ? 255 : b;
+}
+static inline int64_t gnn_count_bucket_lower_bound(int b) {
+    if (b < 16) return b;
+    const int o = 4 + (b - 16) / 8, m = (b - 16) % 8;
+    return int64_t(8 + m) << (o - 3);
+}
+
 // Row stride (floats) of the hub partial-sum scratch for width F: whole 32-byte groups, so that
 // vector stores of a last, partial strip stay inside the row.
 static inline int64_t gnn_partial_ld(int64_t F) { return (F + 7) / 8 * 8; }

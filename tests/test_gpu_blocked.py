@@ -29,7 +29,8 @@ def _dg(el, weights=None, blocking=BLOCKING):
 
 
 @pytest.mark.parametrize("blocking", [BLOCKING, dict(min_degree=4, hot_lines=7, block_lines=33, max_piece=5, rest_min_count=1),
-                                      dict(min_degree=256, hot_lines=100000, block_lines=64, max_piece=1000, rest_min_count=16)])
+                                      dict(min_degree=256, hot_lines=100000, block_lines=64, max_piece=1000, rest_min_count=16),
+                                      dict(min_degree=32, hot_lines=50, block_lines=300, max_piece=40, rest_min_count=40)])
 def test_blocked_layout_bit_exact(blocking):
     el = _graph()
     dg = _dg(el, blocking=blocking)
@@ -117,7 +118,7 @@ def test_blocked_results_are_reproducible_and_parameters_are_checked():
     with pytest.raises(gnn.GnnError):   # not a boundary between two bins
         fresh.plan_fwd.set_blocking(min_degree=100)
     with pytest.raises(gnn.GnnError):
-        fresh.plan_fwd.set_blocking(min_degree=32, rest_min_count=40)
+        fresh.plan_fwd.set_blocking(min_degree=32, rest_min_count=41)  # not a boundary of the count histogram
     fresh.plan_fwd.set_blocking(min_degree=-1)  # switched off
     Y = torch.full_like(X, float("nan"))
     gnn.gnn_aggregate_fwd(fresh.indptr, fresh.indices, None, X, Y, el.n, 100, gnn.GNN_MEAN, plan=fresh.plan_fwd, flags=SLICED, max_slices=8)
