@@ -128,3 +128,14 @@ def test_packed_copy_sizes_and_argument_checks_that_need_no_device():
     assert lib.gnn_pack_rows(one, one, one, one, 1 << 20, 100, 100, 9, 0, None) == gnn.GNN_ERR_INVALID_ARG
     assert lib.gnn_aggregate_packed(one, one, None, None, 0, one, 0, 100, 0, 0, None) == gnn.GNN_OK
     assert lib.gnn_aggregate_packed(one, one, None, None, 0, one, 5, 100, 0, 0, None) == gnn.GNN_ERR_INVALID_ARG
+
+
+def test_calibration_calls_check_their_arguments_without_a_device():
+    lib = gnn.load_library()
+    one = ctypes.c_void_p(128)  # never dereferenced
+    bad = gnn.GNN_ERR_INVALID_ARG
+    assert lib.gnn_calib_gather(None, 10, one, 1 << 28, one, 1 << 23, None) == bad
+    assert lib.gnn_calib_gather(one, 0, one, 1 << 28, one, 1 << 23, None) == bad           # empty table
+    assert lib.gnn_calib_gather(one, 10, one, 1 << 20, one, 1 << 23, None) == bad           # fewer than 16 lines per lane group
+    assert lib.gnn_calib_gather(one, 10, one, 1 << 28, one, (1 << 23) - 1, None) == bad     # output too small
+    assert lib.gnn_calib_gather(ctypes.c_void_p(64), 10, one, 1 << 28, one, 1 << 23, None) == bad  # table not line-aligned

@@ -722,3 +722,23 @@ def test_one_plan_serves_a_sequence_of_widths_dtypes_and_ops():
             ref, S = oracle.aggregate_bwd(indptr_t, indices_t, X.float().numpy(), op=op, din=din, nthreads=8, want_scale=True)
         torch.cuda.synchronize()
         assert_close(out, ref, S, dtype == torch.bfloat16, what)
+
+
+def test_line_gather_probe_reads_what_it_is_told_to():
+    """The bare gather probe behind the measured ceilings: every thread's output is the sum of the 4 floats it
+    owns in each line its lane group was given; ids beyond the table are clamped to its last line."""
+    lines = 1000
+    table = torch.arange(lines * 32, dtype=torch.float32, device=DEV) % 1024
+    per = 16
+    ids = torch.randint(0, lines + 50, ((1 << 20) * per,), dtype=torch.int32, device=DEV)   # some beyond the table
+    out = torch.full((1 << 23,), float("nan"), device=DEV)
+    n = gnn.gnn_calib_gather(table, lines, ids, out)
+    torch.cuda.synchronize()
+    assert n == (1 << 20) * per
+    groups = [0, 1, 7, 12345, (1 << 20) - 1]
+    t = table.view(lines, 32).cpu()
+    for g in groups:
+        mine = ids[g * per:(g + 1) * per].clamp(max=lines - 1).long().cpu()
+        for sub in (0, 3, 7):
+            want = t[mine][:, sub * 4:sub * 4 + 4].double().sum().item()
+            assert abs(out[g * 8 + sub].item() - want) <= 1e-3 * max(1.0, abs(want)), (g, sub)
