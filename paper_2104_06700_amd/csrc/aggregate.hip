@@ -586,6 +586,9 @@ struct PieceArgs {
     const int32_t *pieces;   // [n_pieces * 4] (begin, length, partial slot, row index)
     int64_t n_pieces;
     const int32_t *idx;      // source ranks, block-major piece order
+    const uint16_t *idx16;   // the same as offsets from the block's first rank (null: none); not for the last block
+    const uint32_t *block_first;  // [n_blocks + 1] first piece of each block
+    int32_t n_blocks, hot_lines, block_lines;
     const uint32_t *epos;    // CSR position of each edge (for the caller's per-edge streams)
     const float *w;          // the caller's weights, read at epos (a random 4-byte read per edge)
     const float *scale_blk;  // plan-owned factor of the gathered vertex per edge, in the order of idx
@@ -616,6 +619,18 @@ __global__ void __launch_bounds__(kBlockThreads) piece_kernel(const PieceArgs a)
         const int4 d = *reinterpret_cast<const int4 *>(a.pieces + 4 * piece);
         begin = uint32_t(d.x); len = d.y; slot = d.z;
     }
+    // the piece's block, for the 16-bit indices: the last k whose first piece is not after this one
+    bool narrow = false;
+    int base = 0;
+    if (a.idx16 && len > 0) {
+        int lo = 0, hi = a.n_blocks;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (int64_t(a.block_first[mid]) <= piece) lo = mid; else hi = mid;
+        }
+        narrow = lo < a.n_blocks - 1;
+        base = lo == 0 ? 0 : a.hot_lines + (lo - 1) * a.block_lines;
+    }
     const T *__restrict__ X = static_cast<const T *>(a.X) + int64_t(slice) * a.slice_stride + c * VEC;
     float acc[VEC];
 #pragma unroll
@@ -626,7 +641,7 @@ __global__ void __launch_bounds__(kBlockThreads) piece_kernel(const PieceArgs a)
         cf_out = 0.0f;
         const int j = t + c;
         if (j < len) {
-            u_out = a.idx[begin + uint32_t(j)];
+            u_out = narrow ? base + int(a.idx16[begin + uint32_t(j)]) : a.idx[begin + uint32_t(j)];
             if (COEF) {
                 cf_out = a.w ? a.w[a.epos[begin + uint32_t(j)]] : 1.0f;
                 if (a.scale_blk) cf_out *= a.scale_blk[begin + uint32_t(j)];
@@ -1290,6 +1305,11 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
             pa.n_pieces = bl.n_pieces;
             pa.idx = bl.indices;
             pa.epos = bl.epos;
+            pa.idx16 = bl.idx16;
+            pa.block_first = bl.block_first;
+            pa.n_blocks = bl.n_blocks;
+            pa.hot_lines = bl.hot_lines;
+            pa.block_lines = bl.block_lines;
             pa.w = w;
             pa.scale_blk = scale_blk;
             pa.X = a.X;

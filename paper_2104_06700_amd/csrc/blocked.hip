@@ -154,7 +154,8 @@ __global__ void __launch_bounds__(256) blk_scatter_edges_kernel(int64_t n, const
                                                                 const void *__restrict__ indptr, int ip64, BlockMap m,
                                                                 const uint32_t *__restrict__ cell_start,
                                                                 const uint32_t *__restrict__ edge_off,
-                                                                int32_t *__restrict__ blk_indices, uint32_t *__restrict__ blk_epos) {
+                                                                int32_t *__restrict__ blk_indices, uint32_t *__restrict__ blk_epos,
+                                                                uint16_t *__restrict__ blk_idx16) {
     const int64_t stride = int64_t(gridDim.x) * blockDim.x;
     for (int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < n; i += stride) {
         const int64_t h = h_of[i];
@@ -164,11 +165,20 @@ __global__ void __launch_bounds__(256) blk_scatter_edges_kernel(int64_t n, const
         const int64_t row_begin = p_indptr[hot_begin + h] - p0;
         const int64_t dest = int64_t(edge_off[c]) + (i - row_begin - int64_t(cell_start[c]));
         blk_indices[dest] = r;
+        if (blk_idx16) blk_idx16[dest] = k < m.n_blocks - 1 ? uint16_t(r - block_lo(m, k)) : uint16_t(0);
         // CSR position of the edge: its offset within the row is the same in plan order and in the CSR
         const int64_t v = row_perm[hot_begin + h];
         const int64_t csr_begin = ip64 ? static_cast<const int64_t *>(indptr)[v] : int64_t(static_cast<const int32_t *>(indptr)[v]);
         blk_epos[dest] = uint32_t(csr_begin + (int64_t(sorted_pos[i]) - row_begin));
     }
+}
+
+// first piece of every block = the piece offset of the block's first cell; one more entry closes the list
+__global__ void __launch_bounds__(256) blk_block_first_kernel(int n_blocks, int64_t n_hot, const uint32_t *__restrict__ piece_off,
+                                                              uint32_t n_pieces, uint32_t *__restrict__ block_first) {
+    const int k = int(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (k < n_blocks) block_first[k] = piece_off[int64_t(k) * n_hot];
+    else if (k == n_blocks) block_first[k] = n_pieces;
 }
 
 template <typename T>
@@ -310,6 +320,9 @@ int gnn_plan_blocked(gnn_plan *plan, const void *indptr, hipStream_t stream, gnn
             uint32_t *cell_start = nullptr, *cell_count = nullptr, *cell_pieces = nullptr, *edge_off = nullptr, *row_prefix = nullptr;
             uint32_t *rowbase = nullptr, *blk_epos = nullptr;
             int32_t *blk_indices = nullptr, *pieces = nullptr;
+            uint16_t *blk_idx16 = nullptr;
+            uint32_t *block_first = nullptr;
+            const bool narrow = m.hot <= 65536 && m.block <= 65536;
             auto cleanup_tmp = [&]() {
                 (void)hipFree(h_of); (void)hipFree(buf_k[0]); (void)hipFree(buf_k[1]); (void)hipFree(buf_v[0]); (void)hipFree(buf_v[1]);
                 (void)hipFree(table); (void)hipFree(sums); (void)hipFree(cell_start); (void)hipFree(cell_count);
@@ -319,6 +332,7 @@ int gnn_plan_blocked(gnn_plan *plan, const void *indptr, hipStream_t stream, gnn
                 (void)hipStreamSynchronize(stream);
                 cleanup_tmp();
                 (void)hipFree(rowbase); (void)hipFree(blk_epos); (void)hipFree(blk_indices); (void)hipFree(pieces);
+                (void)hipFree(blk_idx16); (void)hipFree(block_first);
                 return s;
             };
             const int64_t scan_n = n_cells > n_hot + 1 ? n_cells : n_hot + 1;
@@ -329,6 +343,7 @@ int gnn_plan_blocked(gnn_plan *plan, const void *indptr, hipStream_t stream, gnn
                       dev_alloc(&cell_start, n_cells) && dev_alloc(&cell_count, n_cells) && dev_alloc(&cell_pieces, n_cells + 1) &&
                       dev_alloc(&edge_off, n_cells + 1) && dev_alloc(&row_prefix, n_cells) && dev_alloc(&rowbase, n_hot + 1) &&
                       dev_alloc(&blk_indices, n_edges) && dev_alloc(&blk_epos, n_edges);
+            if (ok && narrow) ok = dev_alloc(&blk_idx16, n_edges) && dev_alloc(&block_first, int64_t(m.n_blocks) + 1);
             if (!ok) return fail(GNN_ERR_ALLOC);
 
             blk_expand_rows_kernel<<<grid_for(n_hot * 64, 256), 256, 0, stream>>>(plan->p_indptr, hot_begin, n_hot, p0, h_of);
@@ -371,7 +386,10 @@ int gnn_plan_blocked(gnn_plan *plan, const void *indptr, hipStream_t stream, gnn
             blk_scatter_edges_kernel<<<grid_for(n_edges, 256), 256, 0, stream>>>(n_edges, h_of, sorted_r, sorted_pos, plan->p_indptr,
                                                                                 hot_begin, n_hot, p0, plan->row_perm, indptr,
                                                                                 plan->indptr_is_64, m, cell_start, edge_off,
-                                                                                blk_indices, blk_epos);
+                                                                                blk_indices, blk_epos, blk_idx16);
+            if (narrow)
+                blk_block_first_kernel<<<grid_for(m.n_blocks + 1, 256), 256, 0, stream>>>(m.n_blocks, n_hot, cell_pieces,
+                                                                                         uint32_t(n_pieces), block_first);
             if (hipGetLastError() != hipSuccess) return fail(GNN_ERR_LAUNCH);
             if (hipStreamSynchronize(stream) != hipSuccess) return fail(GNN_ERR_LAUNCH);
             cleanup_tmp();
@@ -383,6 +401,10 @@ int gnn_plan_blocked(gnn_plan *plan, const void *indptr, hipStream_t stream, gnn
             plan->blk_n_blocks = m.n_blocks;
             plan->blk_indices = blk_indices;
             plan->blk_epos = blk_epos;
+            plan->blk_idx16 = blk_idx16;
+            plan->blk_block_first = block_first;
+            plan->blk_hot_lines = m.hot;
+            plan->blk_block_lines = m.block;
             plan->blk_pieces = pieces;
             plan->blk_rowbase = rowbase;
         }
@@ -397,6 +419,11 @@ int gnn_plan_blocked(gnn_plan *plan, const void *indptr, hipStream_t stream, gnn
         out->n_pieces = plan->blk_n_pieces;
         out->indices = plan->blk_indices;
         out->epos = plan->blk_epos;
+        out->idx16 = plan->blk_idx16;
+        out->block_first = plan->blk_block_first;
+        out->n_blocks = plan->blk_n_blocks;
+        out->hot_lines = plan->blk_hot_lines;
+        out->block_lines = plan->blk_block_lines;
         out->pieces = plan->blk_pieces;
         out->rowbase = plan->blk_rowbase;
     }

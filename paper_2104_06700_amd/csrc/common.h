@@ -77,6 +77,13 @@ struct gnn_plan {
     int32_t blk_n_blocks = 0;
     int32_t *blk_indices = nullptr;   // [blk_n_edges] source ranks, block-major piece order
     uint32_t *blk_epos = nullptr;     // [blk_n_edges] CSR position of each (the caller's per-edge streams are read there)
+    // blk_indices again as 16-bit offsets from the first rank of each edge's block, for the kernel to
+    // read in place of the 32-bit ranks in all blocks but the last (whose range is not bounded); null
+    // when a block spans more than 65,536 ranks.  blk_block_first[k] = first piece of block k,
+    // [blk_n_blocks] = blk_n_pieces.
+    uint16_t *blk_idx16 = nullptr;
+    uint32_t *blk_block_first = nullptr;
+    int32_t blk_hot_lines = 0, blk_block_lines = 0;
     int32_t *blk_pieces = nullptr;    // [blk_n_pieces * 4] (begin, length, partial slot, row index in the hot range)
     uint32_t *blk_rowbase = nullptr;  // [blk_n_hot + 1] first partial slot of each hot row
     float *blk_edge_scale[3] = {nullptr, nullptr, nullptr};  // edge_scale[m] at blk_epos, i.e. in the order of blk_indices
@@ -98,6 +105,11 @@ struct gnn_blocked_layout {
     int64_t hot_begin, n_hot, n_pieces;
     const int32_t *indices;  // block-major
     const uint32_t *epos;
+    // 16-bit form of `indices` (null: none): block k < n_blocks - 1 begins at piece block_first[k] and at
+    // rank 0 (k = 0) or hot_lines + (k - 1) * block_lines; the last block keeps the 32-bit ranks
+    const uint16_t *idx16;
+    const uint32_t *block_first;
+    int32_t n_blocks, hot_lines, block_lines;
     const int32_t *pieces;
     const uint32_t *rowbase;
 };

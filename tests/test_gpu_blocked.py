@@ -101,6 +101,28 @@ def test_blocked_aggregation_with_edge_weights(dtype):
     assert_close(dX, dXo, St, bf16, "weighted bwd")
 
 
+@pytest.mark.parametrize("hot_lines,block_lines", [(65536, 65536), (65537, 300), (300, 65537), (20000, 30000)])
+def test_blocked_aggregation_with_blocks_at_and_beyond_the_16_bit_range(hot_lines, block_lines):
+    """The piece kernel reads 16-bit offsets from a block's first rank where every block but the last spans at
+    most 65,536 ranks, and the 32-bit ranks otherwise; both must give the oracle's result at the limit."""
+    el = synth.rmat_symmetric(150000, 1500000, (0.5, 0.2, 0.2, 0.1), 5)
+    indptr, indices, indptr_t, indices_t, _ = host_csr(el)
+    f = 72
+    X = synth.normal_features(el.n, f, 21)
+    Xd = X.to(DEV)
+    dg = _dg(el, blocking=dict(min_degree=32, hot_lines=hot_lines, block_lines=block_lines, max_piece=48, rest_min_count=1))
+    Yo, S = oracle.aggregate_fwd(indptr, indices, X.numpy(), op=oracle.OP_SUM, nthreads=8, want_scale=True)
+    dXo, St = oracle.aggregate_bwd(indptr_t, indices_t, X.numpy(), op=oracle.OP_SUM, nthreads=8, want_scale=True)
+    Y = torch.full((el.n, f), float("nan"), device=DEV)
+    dX = torch.full((el.n, f), float("nan"), device=DEV)
+    gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, None, Xd, Y, el.n, f, gnn.GNN_SUM, plan=dg.plan_fwd, flags=SLICED, max_slices=4)
+    gnn.gnn_aggregate_bwd(dg.indptr_t, dg.indices_t, None, Xd, dX, el.n, f, gnn.GNN_SUM, plan=dg.plan_bwd, flags=SLICED, max_slices=4)
+    torch.cuda.synchronize()
+    assert dg.plan_fwd.blocked_sizes()[3] >= 3
+    assert_close(Y, Yo, S, False, "fwd")
+    assert_close(dX, dXo, St, False, "bwd")
+
+
 def test_blocked_results_are_reproducible_and_parameters_are_checked():
     el = _graph()
     dg = _dg(el)
