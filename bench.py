@@ -186,6 +186,9 @@ def measure(workload, steps, warmup, scale, dev, dump_graph=None, flush=False, c
     t_plan = time.perf_counter() - t0
     n, e = el.n, el.e
     fmax = max(widths)
+    if weights is not None:  # the normalisation weights belong to the static graph: the plans keep them in piece order
+        dg.plan_fwd.bind_edge_weights(dg.edge_w)
+        dg.plan_bwd.bind_edge_weights(dg.edge_w_t)
     for op_name in op_names:
         for f in sorted(set(widths)):
             dg.plan_fwd.prepare(dg.indices, OPS[op_name], False, f, dtype)

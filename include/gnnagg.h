@@ -445,6 +445,18 @@ GNN_API int gnn_plan_prepare(gnn_plan *plan, const int32_t *indices, int op, int
 /* Sets the source-blocking parameters of a plan (before its first hot call or gnn_plan_prepare;
  * later calls return GNN_ERR_UNSUPPORTED once the layout is built).  NULL = automatic. */
 GNN_API int gnn_plan_set_blocking(gnn_plan *plan, const gnn_blocking_params *params /* host */);
+/* Declares an edge-weight array static (Section 3: full-batch training runs every layer and epoch over
+ * the same graph, and the edge features f_E of Algorithm 1 that normalise it belong to that graph): the plan
+ * keeps a copy of `edge_w` (device, fp32, in the CSR order of the plan's graph, as the hot calls take it)
+ * in the order its source-blocked pieces read, and hot calls with this plan that pass THE SAME POINTER
+ * serve their long rows as pieces, streaming the copy; other weight arrays keep the path without
+ * pieces (a piece would read the caller's array at random, 4 bytes per edge).  The copy is made on `stream`
+ * now if the plan's layout exists already, else by the first hot call or gnn_plan_prepare that builds it
+ * (one allocation of 4 bytes per edge of the long rows).  Call again whenever the array's contents
+ * change -- the short rows read the caller's array, the long rows the copy, so a stale copy gives
+ * results that mix the two; later hot calls on other streams must be ordered after `stream` by the
+ * caller.  NULL unbinds.  The array stays the caller's and must outlive the binding. */
+GNN_API int gnn_plan_bind_edge_weights(gnn_plan *plan, const float *edge_w /* device or NULL */, void *stream);
 /* Sizes of the source-blocked layout (all 0 when the plan has none, or has not built it yet):
  * rows served as pieces, their edges, pieces, blocks. */
 GNN_API int gnn_plan_blocked_sizes(const gnn_plan *plan, int64_t *n_rows, int64_t *n_edges, int64_t *n_pieces,

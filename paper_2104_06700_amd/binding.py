@@ -39,7 +39,7 @@ EXPORTED_SYMBOLS = (
     "gnn_aggregate_packed", "gnn_csr_from_sorted_coo", "gnn_transpose_csr",
     "gnn_validate_csr", "gnn_plan_default_params", "gnn_plan_create", "gnn_plan_destroy",
     "gnn_plan_sizes", "gnn_plan_export", "gnn_plan_gather_share", "gnn_plan_workspace_bytes", "gnn_plan_reserve",
-    "gnn_plan_prepare", "gnn_plan_set_blocking", "gnn_plan_blocked_sizes", "gnn_plan_export_blocked",
+    "gnn_plan_prepare", "gnn_plan_set_blocking", "gnn_plan_bind_edge_weights", "gnn_plan_blocked_sizes", "gnn_plan_export_blocked",
     "gnn_ap_fwd", "gnn_ap_bwd_vertex", "gnn_ap_bwd_vertex_arg", "gnn_ap_bwd_edge",
     "gnn_matmul", "gnn_matmul_workspace_bytes",
     "gnn_sage_layer_fwd", "gnn_sage_layer_bwd", "gnn_sage_layer_saved_elems", "gnn_sage_layer_workspace_bytes",
@@ -129,6 +129,7 @@ def load_library() -> ctypes.CDLL:
         lib.gnn_plan_reserve.argtypes = [vp, i64]
         lib.gnn_plan_prepare.argtypes = [vp, vp, i32, i32, i64, i32, vp]
         lib.gnn_plan_set_blocking.argtypes = [vp, ctypes.POINTER(GnnBlockingParams)]
+        lib.gnn_plan_bind_edge_weights.argtypes = [vp, vp, vp]
         lib.gnn_plan_blocked_sizes.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64),
                                                ctypes.POINTER(ctypes.c_int32)]
         lib.gnn_plan_export_blocked.argtypes = [vp, vp, vp, vp, vp, vp]
@@ -241,6 +242,17 @@ class Plan:
         """Parameters of the source-blocked layout of the long rows (zeros: automatic; min_degree < 0: off)."""
         p = GnnBlockingParams(int(min_degree), int(hot_lines), int(block_lines), int(max_piece), int(rest_min_count))
         _check("gnn_plan_set_blocking", load_library().gnn_plan_set_blocking(self.handle, ctypes.byref(p)))
+
+    def bind_edge_weights(self, edge_w, stream=None) -> None:
+        """Declares `edge_w` (fp32 device tensor in the plan's CSR order, or None) static: calls that pass this
+        tensor serve their long rows as source-blocked pieces from a plan-owned copy.  Bind again after the
+        contents change."""
+        ptr = None
+        if edge_w is not None:
+            if edge_w.dtype != torch.float32 or not edge_w.is_contiguous() or not edge_w.is_cuda:
+                raise ValueError("edge_w: contiguous fp32 device tensor expected")
+            ptr = edge_w.data_ptr()
+        _check("gnn_plan_bind_edge_weights", load_library().gnn_plan_bind_edge_weights(self.handle, ptr, _stream(stream)))
 
     def blocked_sizes(self):
         """(rows served as pieces, their edges, pieces, blocks); zeros when the plan has no such layout (yet)."""

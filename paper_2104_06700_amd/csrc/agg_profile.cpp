@@ -6,7 +6,7 @@
 //
 // usage: agg_profile DIR OP(0|1|2|3) REPS [option ...] F [F ...]
 // options: "bf16" (features in bf16 from there on; default fp32), "weights" (an explicit fp32 weight
-// per edge, all equal, from there on),
+// per edge, all equal, from there on; the array is bound to both plans as a static one, as the bench does),
 // "noslice" switches the XCD column slicing off for the widths that follow it; "flags=N" sets
 // gnn_opts.flags (GNN_FLAG_* bits) for the widths that follow it; "block=D,H,B,P,R" (anywhere) sets
 // the source-blocking parameters of both plans (min_degree, hot_lines, block_lines, max_piece,
@@ -90,7 +90,12 @@ int main(int argc, char **argv) {
     for (int a = 4; a < argc; ++a) {
         if (std::string(argv[a]) == "bf16") { esz = 2; continue; }
         if (std::string(argv[a]) == "weights") {
-            if (!w) { CHECK(hipMalloc(&w, 4 * (size_t)E)); CHECK(hipMemset(w, 0x3c, 4 * (size_t)E)); }
+            if (!w) {
+                CHECK(hipMalloc(&w, 4 * (size_t)E));
+                CHECK(hipMemset(w, 0x3c, 4 * (size_t)E));
+                GCHECK(gnn_plan_bind_edge_weights(pf, w, nullptr));
+                GCHECK(gnn_plan_bind_edge_weights(pb, w, nullptr));
+            }
             continue;
         }
         if (std::string(argv[a]) == "noslice") { flags = GNN_FLAG_NO_COLUMN_SLICES; continue; }

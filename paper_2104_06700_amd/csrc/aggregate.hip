@@ -590,7 +590,8 @@ struct PieceArgs {
     const uint32_t *block_first;  // [n_blocks + 1] first piece of each block
     int32_t n_blocks, hot_lines, block_lines;
     const uint32_t *epos;    // CSR position of each edge (for the caller's per-edge streams)
-    const float *w;          // the caller's weights, read at epos (a random 4-byte read per edge)
+    const float *w;          // the caller's weights, read at epos (a random 4-byte read per edge) ...
+    const float *w_blk;      // ... or their plan-owned copy in the order of idx (weights bound to the plan)
     const float *scale_blk;  // plan-owned factor of the gathered vertex per edge, in the order of idx
     const void *X;           // first slice table of the launch
     int64_t slice_stride;    // elements between two slice tables
@@ -643,7 +644,7 @@ __global__ void __launch_bounds__(kBlockThreads) piece_kernel(const PieceArgs a)
         if (j < len) {
             u_out = narrow ? base + int(a.idx16[begin + uint32_t(j)]) : a.idx[begin + uint32_t(j)];
             if (COEF) {
-                cf_out = a.w ? a.w[a.epos[begin + uint32_t(j)]] : 1.0f;
+                cf_out = a.w_blk ? a.w_blk[begin + uint32_t(j)] : (a.w ? a.w[a.epos[begin + uint32_t(j)]] : 1.0f);
                 if (a.scale_blk) cf_out *= a.scale_blk[begin + uint32_t(j)];
             }
         }
@@ -1172,21 +1173,27 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
     // The long rows of a large power-law graph are served as source-blocked pieces (blocked.hip) in
     // every launch that gathers from slice tables; the dense tail keeps the plain path.
     gnn_blocked_layout bl{};
-    const float *scale_blk = nullptr;
+    const float *scale_blk = nullptr, *w_blk = nullptr;
     if (slice_major && rank_indices && !(o.flags & GNN_FLAG_NO_SOURCE_BLOCKS)) {
         int rc = gnn_plan_blocked(plan, indptr, stream, &bl);
         if (rc != GNN_OK) return rc;
         // Explicit weights sit in CSR order, the pieces in rank order: every edge would cost a random 4-byte
         // read (measured: 1.44 -> 3.67 ms on the weighted workload at F=64), so such calls keep the plain
-        // path unless the plan's blocking was asked for explicitly.  The plan's own per-edge factors get a
-        // copy in piece order instead.
-        if (bl.active && w && bl.automatic) bl.active = false;
+        // path unless the plan's blocking was asked for explicitly, or the weights were bound to the plan
+        // (gnn_plan_bind_edge_weights), which then holds a copy of them in piece order.  The plan's own
+        // per-edge factors get such a copy too.
+        const bool bound = w && w == plan->bound_w;
+        if (bl.active && w && bl.automatic && !bound) bl.active = false;
         // bf16 pieces write partial lines twice as large as the lines they gather: on graphs of a few
         // L2s' worth of vertices that eats the gain (233 K vertices, F=256 backward 3.95 -> 4.07 ms;
         // 133 K vertices, F=128 1.16 -> 1.25), on the 2.45 M-vertex graph it does not (F=512 12.9 -> 11.6).
         if (bl.active && esz == 2 && bl.automatic && N < 8 * int64_t(32768)) bl.active = false;
         if (bl.active && edge_scale) {
             rc = gnn_plan_blocked_edge_scale(plan, src_mode, stream, &scale_blk);
+            if (rc != GNN_OK) return rc;
+        }
+        if (bl.active && bound) {
+            rc = gnn_plan_blocked_bound_weights(plan, stream, &w_blk);
             if (rc != GNN_OK) return rc;
         }
     }
@@ -1311,6 +1318,7 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
             pa.hot_lines = bl.hot_lines;
             pa.block_lines = bl.block_lines;
             pa.w = w;
+            pa.w_blk = w_blk;
             pa.scale_blk = scale_blk;
             pa.X = a.X;
             pa.slice_stride = layout.table_stride;

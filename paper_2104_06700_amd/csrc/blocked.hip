@@ -262,6 +262,38 @@ int gnn_plan_blocked_edge_scale(gnn_plan *plan, int mode, hipStream_t stream, co
     return GNN_OK;
 }
 
+int gnn_plan_blocked_bound_weights(gnn_plan *plan, hipStream_t stream, const float **out) {
+    if (!plan || !out || plan->blk_n_edges <= 0 || !plan->bound_w) return GNN_ERR_INVALID_ARG;
+    if (!plan->blk_bound_w) {
+        (void)hipGetLastError();
+        if (hipMalloc(&plan->blk_bound_w, sizeof(float) * size_t(plan->blk_n_edges)) != hipSuccess) {
+            plan->blk_bound_w = nullptr;
+            return GNN_ERR_ALLOC;
+        }
+        plan->bound_w_stale = true;
+    }
+    if (plan->bound_w_stale) {
+        blk_gather_u32_kernel<<<grid_for(plan->blk_n_edges, 256), 256, 0, stream>>>(
+            reinterpret_cast<const uint32_t *>(plan->bound_w), plan->blk_epos, plan->blk_n_edges, 0xFFFFFFFFu,
+            reinterpret_cast<uint32_t *>(plan->blk_bound_w));
+        if (hipGetLastError() != hipSuccess) return GNN_ERR_LAUNCH;
+        plan->bound_w_stale = false;
+    }
+    *out = plan->blk_bound_w;
+    return GNN_OK;
+}
+
+extern "C" GNN_API int gnn_plan_bind_edge_weights(gnn_plan *plan, const float *edge_w, void *stream) {
+    if (!plan) return GNN_ERR_INVALID_ARG;
+    plan->bound_w = edge_w;
+    plan->bound_w_stale = true;
+    if (edge_w && plan->blk_decided && plan->blk_n_pieces > 0) {
+        const float *unused = nullptr;
+        return gnn_plan_blocked_bound_weights(plan, static_cast<hipStream_t>(stream), &unused);
+    }
+    return GNN_OK;
+}
+
 int gnn_plan_blocked(gnn_plan *plan, const void *indptr, hipStream_t stream, gnn_blocked_layout *out) {
     *out = gnn_blocked_layout{};
     if (!plan) return GNN_ERR_INVALID_ARG;

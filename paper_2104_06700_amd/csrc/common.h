@@ -87,6 +87,12 @@ struct gnn_plan {
     int32_t *blk_pieces = nullptr;    // [blk_n_pieces * 4] (begin, length, partial slot, row index in the hot range)
     uint32_t *blk_rowbase = nullptr;  // [blk_n_hot + 1] first partial slot of each hot row
     float *blk_edge_scale[3] = {nullptr, nullptr, nullptr};  // edge_scale[m] at blk_epos, i.e. in the order of blk_indices
+    // Edge weights the caller declared static (gnn_plan_bind_edge_weights): the pointer they were bound
+    // under and their copy in the order of blk_indices, which the pieces of calls that pass that pointer
+    // stream instead of reading the caller's array at blk_epos.
+    const float *bound_w = nullptr;
+    float *blk_bound_w = nullptr;
+    bool bound_w_stale = false;       // the copy is older than the last binding
     void *blk_partial = nullptr;      // fp32 partial sums of one launch: [slices][blk_n_pieces][floats per line]
     int64_t blk_partial_bytes = 0;
 };
@@ -121,6 +127,9 @@ int gnn_plan_blocked_partial(gnn_plan *plan, int slices, int line_floats);
 // The plan's per-edge factor stream `mode` (gnn_plan_edge_scale, which must have been built) in the order
 // of the block-major index array; built on first use (allocation).
 int gnn_plan_blocked_edge_scale(gnn_plan *plan, int mode, hipStream_t stream, const float **out);
+// The bound edge weights in piece order: refreshed on `stream` when a binding is newer than the copy
+// (allocates on first use).  Needs the layout and a binding.
+int gnn_plan_blocked_bound_weights(gnn_plan *plan, hipStream_t stream, const float **out);
 
 // Stable LSD radix sort of 32-bit (key, value) pairs on the low `bits` bits (graph.hip).  buf_k[0] /
 // buf_v[0] hold the input (first_keys, if given, replaces buf_k[0] as read-only input of the first

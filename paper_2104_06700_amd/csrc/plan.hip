@@ -482,6 +482,11 @@ extern "C" GNN_API int gnn_plan_prepare(gnn_plan *plan, const int32_t *indices, 
                     while (slices < 8 && slices * 2 <= layout.main_lines) slices *= 2;
                     rc = gnn_plan_blocked_partial(plan, slices, 128 / esz);
                     if (rc != GNN_OK) return rc;
+                    if (plan->bound_w) {
+                        const float *unused_w = nullptr;
+                        rc = gnn_plan_blocked_bound_weights(plan, static_cast<hipStream_t>(stream), &unused_w);
+                        if (rc != GNN_OK) return rc;
+                    }
                 }
             }
         } else if (layout.slices_wanted) {  // the flagged index copy of the cold hints, where they pay
@@ -521,6 +526,7 @@ extern "C" GNN_API void gnn_plan_destroy(gnn_plan *plan) {
     (void)hipFree(plan->blk_rowbase);
     (void)hipFree(plan->blk_partial);
     for (int i = 0; i < 3; ++i) (void)hipFree(plan->blk_edge_scale[i]);
+    (void)hipFree(plan->blk_bound_w);
     (void)hipFree(plan->row_perm);
     (void)hipFree(plan->col_counts);
     (void)hipFree(plan->chunks);

@@ -139,3 +139,4 @@ def test_calibration_calls_check_their_arguments_without_a_device():
     assert lib.gnn_calib_gather(one, 10, one, 1 << 20, one, 1 << 23, None) == bad           # fewer than 16 lines per lane group
     assert lib.gnn_calib_gather(one, 10, one, 1 << 28, one, (1 << 23) - 1, None) == bad     # output too small
     assert lib.gnn_calib_gather(ctypes.c_void_p(64), 10, one, 1 << 28, one, 1 << 23, None) == bad  # table not line-aligned
+    assert lib.gnn_plan_bind_edge_weights(None, one, None) == bad                           # no plan

@@ -123,6 +123,65 @@ def test_blocked_aggregation_with_blocks_at_and_beyond_the_16_bit_range(hot_line
     assert_close(dX, dXo, St, False, "bwd")
 
 
+def test_weights_bound_to_the_plan_are_streamed_in_piece_order():
+    """Explicit weights keep a plan that blocks automatically on the path without pieces, unless they are bound
+    to it: then the long rows are pieces that read the plan's copy, which gives the bits of the pieces that read
+    the caller's array (a plan with blocking asked for explicitly), and the oracle's values before and after
+    the weights change and are bound again."""
+    el = synth.rmat_symmetric(140000, 6000000, (0.57, 0.19, 0.19, 0.05), 8)
+    indptr, indices, indptr_t, indices_t, perm = host_csr(el)
+    weights = synth.uniform_features(el.e, 1, 31).reshape(-1) + 0.25
+    w = weights.numpy()
+    f = 72
+    X = synth.normal_features(el.n, f, 22)
+    Xd = X.to(DEV)
+    dg = device_graph(el, weights=weights)                       # automatic blocking
+    explicit = device_graph(el, weights=weights)
+    for plan in (explicit.plan_fwd, explicit.plan_bwd):
+        plan.set_blocking(min_degree=256)                        # pieces whatever the weights
+
+    def run(g, scale=1.0):
+        Y = torch.full((el.n, f), float("nan"), device=DEV)
+        dX = torch.full((el.n, f), float("nan"), device=DEV)
+        gnn.gnn_aggregate_fwd(g.indptr, g.indices, g.edge_w, Xd, Y, el.n, f, gnn.GNN_SUM, plan=g.plan_fwd)
+        gnn.gnn_aggregate_bwd(g.indptr_t, g.indices_t, g.edge_w_t, Xd, dX, el.n, f, gnn.GNN_SUM, plan=g.plan_bwd)
+        torch.cuda.synchronize()
+        return Y, dX
+
+    Yo, S = oracle.aggregate_fwd(indptr, indices, X.numpy(), op=oracle.OP_SUM, w=w, nthreads=8, want_scale=True)
+    dXo, St = oracle.aggregate_bwd(indptr_t, indices_t, X.numpy(), op=oracle.OP_SUM, wt=w[perm], nthreads=8, want_scale=True)
+    Y0, dX0 = run(dg)                                            # unbound: no pieces
+    assert_close(Y0, Yo, S, False, "unbound fwd")
+    assert_close(dX0, dXo, St, False, "unbound bwd")
+    assert dg.plan_fwd.blocked_sizes()[2] > 0, "the graph is meant to be one that the plan blocks by itself"
+    Y2, dX2 = run(explicit)
+    assert_close(Y2, Yo, S, False, "explicit blocking fwd")
+    assert not torch.equal(Y2, Y0), "pieces add in another order: the two paths should differ in some bit"
+    dg.plan_fwd.bind_edge_weights(dg.edge_w)
+    dg.plan_bwd.bind_edge_weights(dg.edge_w_t)
+    Y1, dX1 = run(dg)
+    assert_close(Y1, Yo, S, False, "bound fwd")
+    assert_close(dX1, dXo, St, False, "bound bwd")
+    assert torch.equal(Y1, Y2) and torch.equal(dX1, dX2), "bound weights: the pieces' results"
+    # the weights change: bind again
+    dg.edge_w.mul_(-2.0)
+    dg.edge_w_t.mul_(-2.0)
+    dg.plan_fwd.bind_edge_weights(dg.edge_w)
+    dg.plan_bwd.bind_edge_weights(dg.edge_w_t)
+    Y3, dX3 = run(dg)
+    assert_close(Y3, -2.0 * Yo, 2.0 * S, False, "rebound fwd")
+    assert_close(dX3, -2.0 * dXo, 2.0 * St, False, "rebound bwd")
+    # another array, or no binding: the path without pieces again
+    other = dg.edge_w.clone()
+    Y4 = torch.full((el.n, f), float("nan"), device=DEV)
+    gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, other, Xd, Y4, el.n, f, gnn.GNN_SUM, plan=dg.plan_fwd)
+    dg.plan_fwd.bind_edge_weights(None)
+    Y5 = torch.full((el.n, f), float("nan"), device=DEV)
+    gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, dg.edge_w, Xd, Y5, el.n, f, gnn.GNN_SUM, plan=dg.plan_fwd)
+    torch.cuda.synchronize()
+    assert torch.equal(Y4, Y5) and torch.equal(Y4, -2.0 * Y0)
+
+
 def test_blocked_results_are_reproducible_and_parameters_are_checked():
     el = _graph()
     dg = _dg(el)
