@@ -582,6 +582,10 @@ __global__ void __launch_bounds__(256) hub_finalize_kernel(const int32_t *__rest
 }
 
 // ---- source-blocked pieces of the long rows (see blocked.hip) ----
+// Four consecutive elements of a per-edge stream, loaded at the alignment of one element.
+template <typename E>
+struct __attribute__((packed, aligned(alignof(E)))) Packed { E e[4]; };
+
 struct PieceArgs {
     const int32_t *pieces;   // [n_pieces * 4] (begin, length, partial slot, row index)
     int64_t n_pieces;
@@ -637,42 +641,82 @@ __global__ void __launch_bounds__(kBlockThreads) piece_kernel(const PieceArgs a)
 #pragma unroll
     for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
 
-    auto fetch = [&](int t, int &u_out, float &cf_out) {
-        u_out = 0;
-        cf_out = 0.0f;
-        const int j = t + c;
+    // The per-edge streams are read a window of 32 edges at a time: lane c of the group holds edges
+    // [t + 4c, t + 4c + 4) of the piece, one 8- or 16-byte load per stream (at the 2- or 4-byte
+    // alignment of the element: a piece begins anywhere), so a group touches each line of a stream once
+    // instead of once per eight edges.  The loads of a lane may run up to three elements past the piece's
+    // end (into the next piece, or into the padding behind the arrays); those elements are never used.
+    auto fetch = [&](int t, int (&u_out)[4], float (&cf_out)[4]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { u_out[i] = 0; cf_out[i] = 0.0f; }
+        const int j = t + 4 * c;
         if (j < len) {
-            u_out = narrow ? base + int(a.idx16[begin + uint32_t(j)]) : a.idx[begin + uint32_t(j)];
+            const uint32_t pos = begin + uint32_t(j);
+            if (narrow) {
+                Packed<uint16_t> v;
+                __builtin_memcpy(&v, a.idx16 + pos, sizeof(v));
+#pragma unroll
+                for (int i = 0; i < 4; ++i) u_out[i] = base + int(v.e[i]);
+            } else {
+                Packed<int32_t> v;
+                __builtin_memcpy(&v, a.idx + pos, sizeof(v));
+#pragma unroll
+                for (int i = 0; i < 4; ++i) u_out[i] = v.e[i];
+            }
             if (COEF) {
-                cf_out = a.w_blk ? a.w_blk[begin + uint32_t(j)] : (a.w ? a.w[a.epos[begin + uint32_t(j)]] : 1.0f);
-                if (a.scale_blk) cf_out *= a.scale_blk[begin + uint32_t(j)];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) cf_out[i] = 1.0f;
+                if (a.w_blk) {
+                    Packed<float> v;
+                    __builtin_memcpy(&v, a.w_blk + pos, sizeof(v));
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) cf_out[i] = v.e[i];
+                } else if (a.w) {
+                    Packed<uint32_t> v;
+                    __builtin_memcpy(&v, a.epos + pos, sizeof(v));
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) cf_out[i] = j + i < len ? a.w[v.e[i]] : 0.0f;
+                }
+                if (a.scale_blk) {
+                    Packed<float> v;
+                    __builtin_memcpy(&v, a.scale_blk + pos, sizeof(v));
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) cf_out[i] *= v.e[i];
+                }
             }
         }
     };
-    int nxt_u;
-    float nxt_cf;
+    int nxt_u[4];
+    float nxt_cf[4];
     fetch(0, nxt_u, nxt_cf);
-    for (int t = 0; __any(t < len); t += U) {
-        const int my_u = nxt_u;
-        const float my_cf = nxt_cf;
-        fetch(t + U, nxt_u, nxt_cf);
-        typename Strip<T, VEC>::raw_t x[U];
-        float cf[U];
+    for (int t0 = 0; __any(t0 < len); t0 += 32) {
+        int my_u[4];
+        float my_cf[4];
 #pragma unroll
-        for (int k = 0; k < U; ++k) {
-            const int u = __shfl(my_u, gbase + k);
-            if (COEF) cf[k] = __shfl(my_cf, gbase + k);
-            if (t + k < len) x[k] = Strip<T, VEC>::load(X + int64_t(u) * LINE);
-            else x[k] = Strip<T, VEC>::zero();
-        }
+        for (int i = 0; i < 4; ++i) { my_u[i] = nxt_u[i]; my_cf[i] = nxt_cf[i]; }
+        fetch(t0 + 32, nxt_u, nxt_cf);
+        for (int m = 0; m < 4; ++m) {
+            const int t = t0 + U * m;
+            if (!__any(t < len)) break;
+            typename Strip<T, VEC>::raw_t x[U];
+            float cf[U];
 #pragma unroll
-        for (int k = 0; k < U; ++k) {
-            float xv[VEC];
-            Strip<T, VEC>::unpack(x[k], xv);
+            for (int k = 0; k < U; ++k) {
+                const int src = gbase + 2 * m + (k >> 2);
+                const int u = __shfl(my_u[k & 3], src);
+                if (COEF) cf[k] = __shfl(my_cf[k & 3], src);
+                if (t + k < len) x[k] = Strip<T, VEC>::load(X + int64_t(u) * LINE);
+                else x[k] = Strip<T, VEC>::zero();
+            }
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) {
-                if (COEF) acc[i] = fmaf(t + k < len ? cf[k] : 0.0f, xv[i], acc[i]);
-                else acc[i] += xv[i];
+            for (int k = 0; k < U; ++k) {
+                float xv[VEC];
+                Strip<T, VEC>::unpack(x[k], xv);
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) {
+                    if (COEF) acc[i] = fmaf(t + k < len ? cf[k] : 0.0f, xv[i], acc[i]);
+                    else acc[i] += xv[i];
+                }
             }
         }
     }

@@ -22,6 +22,10 @@
 
 namespace {
 
+// The piece kernel reads the per-edge streams four elements at a time and may run up to three
+// elements past a piece's end: every stream is allocated with this many elements to spare.
+constexpr int64_t kStreamPad = 8;
+
 struct BlockMap {
     int32_t hot;         // block 0 = ranks [0, hot)
     int32_t block;       // blocks 1 .. n_blocks-2 hold `block` ranks each
@@ -248,7 +252,7 @@ int gnn_plan_blocked_edge_scale(gnn_plan *plan, int mode, hipStream_t stream, co
     float *&arr = plan->blk_edge_scale[mode - 1];
     if (!arr) {
         (void)hipGetLastError();
-        if (hipMalloc(&arr, sizeof(float) * size_t(plan->blk_n_edges)) != hipSuccess) { arr = nullptr; return GNN_ERR_ALLOC; }
+        if (hipMalloc(&arr, sizeof(float) * size_t(plan->blk_n_edges + kStreamPad)) != hipSuccess) { arr = nullptr; return GNN_ERR_ALLOC; }
         blk_gather_u32_kernel<<<grid_for(plan->blk_n_edges, 256), 256, 0, stream>>>(
             reinterpret_cast<const uint32_t *>(plan->edge_scale[mode - 1]), plan->blk_epos, plan->blk_n_edges, 0xFFFFFFFFu,
             reinterpret_cast<uint32_t *>(arr));
@@ -266,7 +270,7 @@ int gnn_plan_blocked_bound_weights(gnn_plan *plan, hipStream_t stream, const flo
     if (!plan || !out || plan->blk_n_edges <= 0 || !plan->bound_w) return GNN_ERR_INVALID_ARG;
     if (!plan->blk_bound_w) {
         (void)hipGetLastError();
-        if (hipMalloc(&plan->blk_bound_w, sizeof(float) * size_t(plan->blk_n_edges)) != hipSuccess) {
+        if (hipMalloc(&plan->blk_bound_w, sizeof(float) * size_t(plan->blk_n_edges + kStreamPad)) != hipSuccess) {
             plan->blk_bound_w = nullptr;
             return GNN_ERR_ALLOC;
         }
@@ -374,8 +378,8 @@ int gnn_plan_blocked(gnn_plan *plan, const void *indptr, hipStream_t stream, gnn
                       dev_alloc(&table, gnn_sort_table_elems(n_edges)) && dev_alloc(&sums, sums_n) &&
                       dev_alloc(&cell_start, n_cells) && dev_alloc(&cell_count, n_cells) && dev_alloc(&cell_pieces, n_cells + 1) &&
                       dev_alloc(&edge_off, n_cells + 1) && dev_alloc(&row_prefix, n_cells) && dev_alloc(&rowbase, n_hot + 1) &&
-                      dev_alloc(&blk_indices, n_edges) && dev_alloc(&blk_epos, n_edges);
-            if (ok && narrow) ok = dev_alloc(&blk_idx16, n_edges) && dev_alloc(&block_first, int64_t(m.n_blocks) + 1);
+                      dev_alloc(&blk_indices, n_edges + kStreamPad) && dev_alloc(&blk_epos, n_edges + kStreamPad);
+            if (ok && narrow) ok = dev_alloc(&blk_idx16, n_edges + kStreamPad) && dev_alloc(&block_first, int64_t(m.n_blocks) + 1);
             if (!ok) return fail(GNN_ERR_ALLOC);
 
             blk_expand_rows_kernel<<<grid_for(n_hot * 64, 256), 256, 0, stream>>>(plan->p_indptr, hot_begin, n_hot, p0, h_of);
