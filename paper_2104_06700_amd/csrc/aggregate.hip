@@ -591,7 +591,7 @@ struct PieceArgs {
     int64_t n_pieces;
     const int32_t *idx;      // source ranks, block-major piece order
     const uint16_t *idx16;   // the same as offsets from the block's first rank (null: none); not for the last block
-    const uint32_t *block_first;  // [n_blocks + 1] first piece of each block
+    const uint16_t *piece_block;  // [n_pieces] block of each piece
     int32_t n_blocks, hot_lines, block_lines;
     const uint32_t *epos;    // CSR position of each edge (for the caller's per-edge streams)
     const float *w;          // the caller's weights, read at epos (a random 4-byte read per edge) ...
@@ -624,17 +624,13 @@ __global__ void __launch_bounds__(kBlockThreads) piece_kernel(const PieceArgs a)
         const int4 d = *reinterpret_cast<const int4 *>(a.pieces + 4 * piece);
         begin = uint32_t(d.x); len = d.y; slot = d.z;
     }
-    // the piece's block, for the 16-bit indices: the last k whose first piece is not after this one
+    // the piece's block and its first rank, for the 16-bit indices
     bool narrow = false;
     int base = 0;
     if (a.idx16 && len > 0) {
-        int lo = 0, hi = a.n_blocks;
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (int64_t(a.block_first[mid]) <= piece) lo = mid; else hi = mid;
-        }
-        narrow = lo < a.n_blocks - 1;
-        base = lo == 0 ? 0 : a.hot_lines + (lo - 1) * a.block_lines;
+        const int k = a.piece_block[piece];
+        narrow = k < a.n_blocks - 1;
+        base = k == 0 ? 0 : a.hot_lines + (k - 1) * a.block_lines;
     }
     const T *__restrict__ X = static_cast<const T *>(a.X) + int64_t(slice) * a.slice_stride + c * VEC;
     float acc[VEC];
@@ -1357,7 +1353,7 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
             pa.idx = bl.indices;
             pa.epos = bl.epos;
             pa.idx16 = bl.idx16;
-            pa.block_first = bl.block_first;
+            pa.piece_block = bl.piece_block;
             pa.n_blocks = bl.n_blocks;
             pa.hot_lines = bl.hot_lines;
             pa.block_lines = bl.block_lines;

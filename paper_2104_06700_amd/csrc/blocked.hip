@@ -130,7 +130,8 @@ __global__ void __launch_bounds__(256) blk_fill_pieces_kernel(int64_t n_hot, int
                                                               const uint32_t *__restrict__ edge_off,
                                                               const uint32_t *__restrict__ piece_off,
                                                               const uint32_t *__restrict__ row_prefix,
-                                                              const uint32_t *__restrict__ rowbase, int32_t *__restrict__ pieces) {
+                                                              const uint32_t *__restrict__ rowbase, int32_t *__restrict__ pieces,
+                                                              uint16_t *__restrict__ piece_block) {
     const int64_t n_cells = int64_t(n_blocks) * n_hot;
     const int64_t stride = int64_t(gridDim.x) * blockDim.x;
     for (int64_t c = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; c < n_cells; c += stride) {
@@ -145,6 +146,7 @@ __global__ void __launch_bounds__(256) blk_fill_pieces_kernel(int64_t n_hot, int
             p[1] = int32_t(cnt - b < max_piece ? cnt - b : max_piece);
             p[2] = int32_t(slot0 + uint32_t(j));
             p[3] = int32_t(h);
+            if (piece_block) piece_block[int64_t(piece_off[c]) + j] = uint16_t(c / n_hot);
         }
     }
 }
@@ -175,14 +177,6 @@ __global__ void __launch_bounds__(256) blk_scatter_edges_kernel(int64_t n, const
         const int64_t csr_begin = ip64 ? static_cast<const int64_t *>(indptr)[v] : int64_t(static_cast<const int32_t *>(indptr)[v]);
         blk_epos[dest] = uint32_t(csr_begin + (int64_t(sorted_pos[i]) - row_begin));
     }
-}
-
-// first piece of every block = the piece offset of the block's first cell; one more entry closes the list
-__global__ void __launch_bounds__(256) blk_block_first_kernel(int n_blocks, int64_t n_hot, const uint32_t *__restrict__ piece_off,
-                                                              uint32_t n_pieces, uint32_t *__restrict__ block_first) {
-    const int k = int(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (k < n_blocks) block_first[k] = piece_off[int64_t(k) * n_hot];
-    else if (k == n_blocks) block_first[k] = n_pieces;
 }
 
 template <typename T>
@@ -357,7 +351,7 @@ int gnn_plan_blocked(gnn_plan *plan, const void *indptr, hipStream_t stream, gnn
             uint32_t *rowbase = nullptr, *blk_epos = nullptr;
             int32_t *blk_indices = nullptr, *pieces = nullptr;
             uint16_t *blk_idx16 = nullptr;
-            uint32_t *block_first = nullptr;
+            uint16_t *piece_block = nullptr;
             const bool narrow = m.hot <= 65536 && m.block <= 65536;
             auto cleanup_tmp = [&]() {
                 (void)hipFree(h_of); (void)hipFree(buf_k[0]); (void)hipFree(buf_k[1]); (void)hipFree(buf_v[0]); (void)hipFree(buf_v[1]);
@@ -368,7 +362,7 @@ int gnn_plan_blocked(gnn_plan *plan, const void *indptr, hipStream_t stream, gnn
                 (void)hipStreamSynchronize(stream);
                 cleanup_tmp();
                 (void)hipFree(rowbase); (void)hipFree(blk_epos); (void)hipFree(blk_indices); (void)hipFree(pieces);
-                (void)hipFree(blk_idx16); (void)hipFree(block_first);
+                (void)hipFree(blk_idx16); (void)hipFree(piece_block);
                 return s;
             };
             const int64_t scan_n = n_cells > n_hot + 1 ? n_cells : n_hot + 1;
@@ -379,7 +373,7 @@ int gnn_plan_blocked(gnn_plan *plan, const void *indptr, hipStream_t stream, gnn
                       dev_alloc(&cell_start, n_cells) && dev_alloc(&cell_count, n_cells) && dev_alloc(&cell_pieces, n_cells + 1) &&
                       dev_alloc(&edge_off, n_cells + 1) && dev_alloc(&row_prefix, n_cells) && dev_alloc(&rowbase, n_hot + 1) &&
                       dev_alloc(&blk_indices, n_edges + kStreamPad) && dev_alloc(&blk_epos, n_edges + kStreamPad);
-            if (ok && narrow) ok = dev_alloc(&blk_idx16, n_edges + kStreamPad) && dev_alloc(&block_first, int64_t(m.n_blocks) + 1);
+            if (ok && narrow) ok = dev_alloc(&blk_idx16, n_edges + kStreamPad);
             if (!ok) return fail(GNN_ERR_ALLOC);
 
             blk_expand_rows_kernel<<<grid_for(n_hot * 64, 256), 256, 0, stream>>>(plan->p_indptr, hot_begin, n_hot, p0, h_of);
@@ -417,15 +411,13 @@ int gnn_plan_blocked(gnn_plan *plan, const void *indptr, hipStream_t stream, gnn
             if (int64_t(total_slots) != n_pieces || n_pieces <= 0 || n_pieces >= int64_t(INT32_MAX)) return fail(GNN_ERR_LAUNCH);
             if ((hipMemcpyAsync(rowbase + n_hot, &total_slots, 4, hipMemcpyHostToDevice, stream)) != hipSuccess) return fail(GNN_ERR_LAUNCH);
             if (!dev_alloc(&pieces, 4 * n_pieces)) return fail(GNN_ERR_ALLOC);
+            if (narrow && !dev_alloc(&piece_block, n_pieces)) return fail(GNN_ERR_ALLOC);
             blk_fill_pieces_kernel<<<grid_for(n_cells, 256), 256, 0, stream>>>(n_hot, m.n_blocks, prm.max_piece, cell_count, edge_off,
-                                                                              cell_pieces, row_prefix, rowbase, pieces);
+                                                                              cell_pieces, row_prefix, rowbase, pieces, piece_block);
             blk_scatter_edges_kernel<<<grid_for(n_edges, 256), 256, 0, stream>>>(n_edges, h_of, sorted_r, sorted_pos, plan->p_indptr,
                                                                                 hot_begin, n_hot, p0, plan->row_perm, indptr,
                                                                                 plan->indptr_is_64, m, cell_start, edge_off,
                                                                                 blk_indices, blk_epos, blk_idx16);
-            if (narrow)
-                blk_block_first_kernel<<<grid_for(m.n_blocks + 1, 256), 256, 0, stream>>>(m.n_blocks, n_hot, cell_pieces,
-                                                                                         uint32_t(n_pieces), block_first);
             if (hipGetLastError() != hipSuccess) return fail(GNN_ERR_LAUNCH);
             if (hipStreamSynchronize(stream) != hipSuccess) return fail(GNN_ERR_LAUNCH);
             cleanup_tmp();
@@ -438,7 +430,7 @@ int gnn_plan_blocked(gnn_plan *plan, const void *indptr, hipStream_t stream, gnn
             plan->blk_indices = blk_indices;
             plan->blk_epos = blk_epos;
             plan->blk_idx16 = blk_idx16;
-            plan->blk_block_first = block_first;
+            plan->blk_piece_block = piece_block;
             plan->blk_hot_lines = m.hot;
             plan->blk_block_lines = m.block;
             plan->blk_pieces = pieces;
@@ -456,7 +448,7 @@ int gnn_plan_blocked(gnn_plan *plan, const void *indptr, hipStream_t stream, gnn
         out->indices = plan->blk_indices;
         out->epos = plan->blk_epos;
         out->idx16 = plan->blk_idx16;
-        out->block_first = plan->blk_block_first;
+        out->piece_block = plan->blk_piece_block;
         out->n_blocks = plan->blk_n_blocks;
         out->hot_lines = plan->blk_hot_lines;
         out->block_lines = plan->blk_block_lines;

@@ -79,10 +79,9 @@ struct gnn_plan {
     uint32_t *blk_epos = nullptr;     // [blk_n_edges] CSR position of each (the caller's per-edge streams are read there)
     // blk_indices again as 16-bit offsets from the first rank of each edge's block, for the kernel to
     // read in place of the 32-bit ranks in all blocks but the last (whose range is not bounded); null
-    // when a block spans more than 65,536 ranks.  blk_block_first[k] = first piece of block k,
-    // [blk_n_blocks] = blk_n_pieces.
+    // when a block spans more than 65,536 ranks.  blk_piece_block[p] = block of piece p.
     uint16_t *blk_idx16 = nullptr;
-    uint32_t *blk_block_first = nullptr;
+    uint16_t *blk_piece_block = nullptr;
     int32_t blk_hot_lines = 0, blk_block_lines = 0;
     int32_t *blk_pieces = nullptr;    // [blk_n_pieces * 4] (begin, length, partial slot, row index in the hot range)
     uint32_t *blk_rowbase = nullptr;  // [blk_n_hot + 1] first partial slot of each hot row
@@ -111,10 +110,10 @@ struct gnn_blocked_layout {
     int64_t hot_begin, n_hot, n_pieces;
     const int32_t *indices;  // block-major
     const uint32_t *epos;
-    // 16-bit form of `indices` (null: none): block k < n_blocks - 1 begins at piece block_first[k] and at
+    // 16-bit form of `indices` (null: none): piece p lies in block k = piece_block[p], which begins at
     // rank 0 (k = 0) or hot_lines + (k - 1) * block_lines; the last block keeps the 32-bit ranks
     const uint16_t *idx16;
-    const uint32_t *block_first;
+    const uint16_t *piece_block;
     int32_t n_blocks, hot_lines, block_lines;
     const int32_t *pieces;
     const uint32_t *rowbase;

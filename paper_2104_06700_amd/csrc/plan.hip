@@ -521,7 +521,7 @@ extern "C" GNN_API void gnn_plan_destroy(gnn_plan *plan) {
     (void)hipFree(plan->blk_indices);
     (void)hipFree(plan->blk_epos);
     (void)hipFree(plan->blk_idx16);
-    (void)hipFree(plan->blk_block_first);
+    (void)hipFree(plan->blk_piece_block);
     (void)hipFree(plan->blk_pieces);
     (void)hipFree(plan->blk_rowbase);
     (void)hipFree(plan->blk_partial);
