@@ -726,9 +726,13 @@ __global__ void __launch_bounds__(kBlockThreads) piece_kernel(const PieceArgs a)
     }
 }
 
-// Adds the partial lines of every long row in slot order (the block order of its pieces) and writes
-// the columns [0, fw) of the launch.  Eight lanes own one (row, slice) pair, 16 bytes of the output
-// row each, so a wavefront finishes eight rows of a slice whose partial lines lie back to back.
+// Adds the partial lines of every long row in a fixed order and writes the columns [0, fw) of the
+// launch.  Eight lanes own one (row, slice) pair, 16 bytes of the output row each, so a wavefront
+// finishes eight rows of a slice.  The sums themselves are formed by the whole wavefront, one of its
+// eight pairs after the other: lane group g adds the partial lines g, g + 8, g + 16, ... of the pair (a
+// wavefront load covers eight consecutive lines, 1 KB), and the eight group sums are added pairwise
+// (groups 0+1, 2+3, ... then 0..1 + 2..3, ...).  A hub row has thousands of partial lines: added by its
+// own eight lanes alone, one such row set the duration of the launch.
 template <typename T>
 __global__ void __launch_bounds__(256) blk_finalize_kernel(const int32_t *__restrict__ rows, int64_t n_rows,
                                                            const uint32_t *__restrict__ rowbase,
@@ -740,46 +744,65 @@ __global__ void __launch_bounds__(256) blk_finalize_kernel(const int32_t *__rest
                                                            const float *__restrict__ bias, int relu) {
     constexpr int VEC = 16 / int(sizeof(T));  // output columns per lane
     constexpr int LINE = 8 * VEC;             // columns per slice = floats per partial line
-    const int64_t item = (int64_t(blockIdx.x) * blockDim.x + threadIdx.x) >> 3;
-    if (item >= n_rows * n_slices) return;
+    const int lane = threadIdx.x & 63;
+    const int g = lane >> 3, c = lane & 7;
+    const int64_t n_items = n_rows * n_slices;
+    const int64_t first_item = ((int64_t(blockIdx.x) * blockDim.x + threadIdx.x) >> 6) << 3;  // wave-uniform
+    if (first_item >= n_items) return;
+    float mine[VEC];  // the sum of this group's own pair
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) mine[k] = 0.0f;
+    for (int j = 0; j < 8; ++j) {
+        const int64_t item = first_item + j;
+        if (item >= n_items) break;
+        const int64_t i = item % n_rows;
+        const int slice = int(item / n_rows);
+        const int64_t p0 = rowbase[i], p1 = rowbase[i + 1];
+        const float *__restrict__ src = partial + int64_t(slice) * n_pieces * LINE + c * VEC;
+        float sum[VEC];
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) sum[k] = 0.0f;
+        auto load_line = [&](int64_t p, f32x4 (&v)[VEC / 4]) {
+#pragma unroll
+            for (int q = 0; q < VEC / 4; ++q) {
+                v[q] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+                if (p < p1) v[q] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(src + p * LINE) + q);
+            }
+        };
+        auto add_line = [&](const f32x4 (&v)[VEC / 4]) {
+#pragma unroll
+            for (int q = 0; q < VEC / 4; ++q) {
+                sum[4 * q] += v[q].x; sum[4 * q + 1] += v[q].y; sum[4 * q + 2] += v[q].z; sum[4 * q + 3] += v[q].w;
+            }
+        };
+        for (int64_t p = p0 + g; p < p1; p += 32) {  // four lines per group in flight
+            f32x4 v0[VEC / 4], v1[VEC / 4], v2[VEC / 4], v3[VEC / 4];
+            load_line(p, v0); load_line(p + 8, v1); load_line(p + 16, v2); load_line(p + 24, v3);
+            add_line(v0); add_line(v1); add_line(v2); add_line(v3);
+        }
+#pragma unroll
+        for (int off = 8; off < 64; off <<= 1)
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) sum[k] += __shfl_xor(sum[k], off);
+        if (g == j) {
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) mine[k] = sum[k];
+        }
+    }
+    const int64_t item = first_item + g;
+    if (item >= n_items) return;
     const int64_t i = item % n_rows;
     const int slice = int(item / n_rows);
-    const int col0 = slice * LINE + int(threadIdx.x & 7) * VEC;
+    const int col0 = slice * LINE + c * VEC;
     if (col0 >= fw) return;
     const int64_t row = rows[i];
-    const int64_t p0 = rowbase[i], p1 = rowbase[i + 1];
-    const float *__restrict__ src = partial + int64_t(slice) * n_pieces * LINE + int(threadIdx.x & 7) * VEC;
-    float sum[VEC];
-#pragma unroll
-    for (int k = 0; k < VEC; ++k) sum[k] = 0.0f;
-    auto load_line = [&](int64_t p, f32x4 (&v)[VEC / 4]) {
-#pragma unroll
-        for (int q = 0; q < VEC / 4; ++q) v[q] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(src + p * LINE) + q);
-    };
-    auto add_line = [&](const f32x4 (&v)[VEC / 4]) {
-#pragma unroll
-        for (int q = 0; q < VEC / 4; ++q) {
-            sum[4 * q] += v[q].x; sum[4 * q + 1] += v[q].y; sum[4 * q + 2] += v[q].z; sum[4 * q + 3] += v[q].w;
-        }
-    };
-    int64_t p = p0;
-    for (; p + 4 <= p1; p += 4) {  // four lines in flight, added in slot order
-        f32x4 v0[VEC / 4], v1[VEC / 4], v2[VEC / 4], v3[VEC / 4];
-        load_line(p, v0); load_line(p + 1, v1); load_line(p + 2, v2); load_line(p + 3, v3);
-        add_line(v0); add_line(v1); add_line(v2); add_line(v3);
-    }
-    for (; p < p1; ++p) {
-        f32x4 v0[VEC / 4];
-        load_line(p, v0);
-        add_line(v0);
-    }
     const int ncols = fw - col0 < VEC ? fw - col0 : VEC;
     const float ds = scale_of(dst_mode, load_ip(indptr, ip64, row + 1) - load_ip(indptr, ip64, row));
     const float self_cf = self_mode == kSelfInvPlus1 ? scale_of(kScaleInvPlus1, col_counts[row]) : 1.0f;
     float o[VEC];
 #pragma unroll
     for (int k = 0; k < VEC; ++k) {
-        float v = sum[k];
+        float v = mine[k];
         if (k < ncols) {
             if (self_mode != kSelfNone) v = fmaf(self_cf, own_row_value<T>(own, row, col0 + k), v);
             v *= ds;
