@@ -246,3 +246,47 @@ def test_blocked_call_with_its_second_stream_can_be_captured_into_a_graph():
         step()
         torch.cuda.synchronize()
         want = (Y.clone(), dX.clone())
+
+
+def test_calls_with_bound_weights_can_be_captured_into_a_graph():
+    """Once the weights are bound and one eager call has run, a weighted call allocates nothing and reads the
+    plan's copy: captured, it replays bit for bit, also after the weights were changed and bound again (the
+    binding refreshes the copy in place, outside the graph)."""
+    el = _graph()
+    weights = synth.uniform_features(el.e, 1, 9).reshape(-1) + 0.5
+    dg = _dg(el, weights=weights)
+    dg.plan_fwd.bind_edge_weights(dg.edge_w)
+    dg.plan_bwd.bind_edge_weights(dg.edge_w_t)
+    f = 100
+    X = synth.normal_features(el.n, f, 6).to(DEV)
+    Y, dX = torch.empty_like(X), torch.empty_like(X)
+
+    def step():
+        gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, dg.edge_w, X, Y, el.n, f, gnn.GNN_SUM, plan=dg.plan_fwd, flags=SLICED, max_slices=4)
+        gnn.gnn_aggregate_bwd(dg.indptr_t, dg.indices_t, dg.edge_w_t, Y, dX, el.n, f, gnn.GNN_SUM, plan=dg.plan_bwd, flags=SLICED, max_slices=4)
+
+    step()
+    torch.cuda.synchronize()
+    assert dg.plan_fwd.blocked_sizes()[2] > 0
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        step()
+        torch.cuda.synchronize()
+        want = (Y.clone(), dX.clone())
+        Y.fill_(float("nan"))
+        dX.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y, want[0]) and torch.equal(dX, want[1]), f"replay {rep}"
+        dg.edge_w.mul_(0.5)
+        dg.edge_w_t.mul_(0.5)
+        dg.plan_fwd.bind_edge_weights(dg.edge_w)
+        dg.plan_bwd.bind_edge_weights(dg.edge_w_t)
+        torch.cuda.synchronize()

@@ -54,6 +54,18 @@ def _fullsize(name, f, op_name, weighted=False, dtype=torch.float32):
         torch.cuda.synchronize()
         del buf
 
+    # explicit weights, bound to the plans as bench.py binds them: the long rows as source-blocked pieces
+    Yb = dXb = None
+    if weighted:
+        dg.plan_fwd.bind_edge_weights(dg.edge_w)
+        dg.plan_bwd.bind_edge_weights(dg.edge_w_t)
+        Yb, dXb = torch.full_like(X, float("nan")), torch.full_like(dY, float("nan"))
+        gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, dg.edge_w, X, Yb, n, f, op, plan=dg.plan_fwd)
+        gnn.gnn_aggregate_bwd(dg.indptr_t, dg.indices_t, dg.edge_w_t, dY, dXb, n, f, op, plan=dg.plan_bwd)
+        torch.cuda.synchronize()
+        dg.plan_fwd.bind_edge_weights(None)
+        dg.plan_bwd.bind_edge_weights(None)
+
     # adjoint identity on the whole output, fp64 dot products (holds at any size)
     lhs = (Y.double() * dY.double()).sum().item()
     rhs = (X.double() * dX.double()).sum().item()
@@ -81,6 +93,8 @@ def _fullsize(name, f, op_name, weighted=False, dtype=torch.float32):
     assert_close(Y[torch.from_numpy(rows).to(DEV)], Yo, S, dtype == torch.bfloat16, f"{name} fwd rows")
     if Yp is not None:
         assert_close(Yp[torch.from_numpy(rows).to(DEV)], Yo, S, dtype == torch.bfloat16, f"{name} fwd rows from the packed copy")
+    if Yb is not None:
+        assert_close(Yb[torch.from_numpy(rows).to(DEV)], Yo, S, dtype == torch.bfloat16, f"{name} fwd rows with bound weights")
     del Xh
     indptr_t, indices_t, perm = oracle.transpose(indptr, src_h)
     rows_t = _sample_rows(np.diff(indptr_t), 8)
@@ -90,6 +104,8 @@ def _fullsize(name, f, op_name, weighted=False, dtype=torch.float32):
     assert_close(dX[torch.from_numpy(rows_t).to(DEV)], dXo, St, dtype == torch.bfloat16, f"{name} bwd rows")
     if dXp is not None:
         assert_close(dXp[torch.from_numpy(rows_t).to(DEV)], dXo, St, dtype == torch.bfloat16, f"{name} bwd rows from the packed copy")
+    if dXb is not None:
+        assert_close(dXb[torch.from_numpy(rows_t).to(DEV)], dXo, St, dtype == torch.bfloat16, f"{name} bwd rows with bound weights")
     # the integer structure at full size, bit for bit
     assert np.array_equal(dg.indptr.cpu().numpy().astype(np.int64), indptr)
     assert np.array_equal(dg.indptr_t.cpu().numpy().astype(np.int64), indptr_t)
