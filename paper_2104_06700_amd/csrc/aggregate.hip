@@ -421,27 +421,45 @@ __global__ void __launch_bounds__(kBlockThreads) aggregate_kernel(const AggArgs 
         ncols[p] = Fk - lc < VEC ? Fk - lc : VEC;
     }
 
-    // Neighbour ids (and coefficients) travel one coalesced tile of G edges per group at a
-    // time; the next tile is requested before the current one is consumed, so only the first
-    // index load of a row is exposed latency.
-    auto fetch_tile = [&](int64_t e, int &u_out, float &cf_out) {
-        u_out = 0;
-        cf_out = 0.0f;
-        if (e < e1) {
-            u_out = a.indices[e];
-            if (COEF) {
-                cf_out = a.w ? a.w[e + wdelta] : 1.0f;
-                if (a.edge_scale) cf_out *= a.edge_scale[e + wdelta];
+    // Neighbour ids (and coefficients) travel in coalesced tiles of G edges per group; the next tiles
+    // are requested before the current ones are consumed, so only the first index loads of a row are
+    // exposed latency.  The one-strip fp32 kernel (the sliced launches) asks for two tiles at a time: the
+    // lines of the index stream that a row spans are then touched once instead of once per tile, with
+    // some thousand gathers of the compute unit in between (worth 1 %; the other variants would pay for
+    // the registers with a wavefront of occupancy).
+    constexpr int Q = (sizeof(T) == 4 && NPASS == 1) ? 2 : 1;
+    auto fetch_tiles = [&](int64_t e_first, int (&u_out)[Q], float (&cf_out)[Q]) {
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            const int64_t e = e_first + q * G;
+            u_out[q] = 0;
+            cf_out[q] = 0.0f;
+            if (e < e1) {
+                u_out[q] = a.indices[e];
+                if (COEF) {
+                    cf_out[q] = a.w ? a.w[e + wdelta] : 1.0f;
+                    if (a.edge_scale) cf_out[q] *= a.edge_scale[e + wdelta];
+                }
             }
         }
     };
-    int nxt_u;
-    float nxt_cf;
-    fetch_tile(e0 + lane_in_g, nxt_u, nxt_cf);
-    for (int64_t tile = e0; __any(tile < e1); tile += G) {
-        const int my_u = nxt_u;
-        const float my_cf = nxt_cf;
-        fetch_tile(tile + G + lane_in_g, nxt_u, nxt_cf);
+    int nxt_u[Q];
+    float nxt_cf[Q];
+    fetch_tiles(e0 + lane_in_g, nxt_u, nxt_cf);
+    for (int64_t first = e0; __any(first < e1); first += Q * G) {
+    int cur_u[Q];
+    float cur_cf[Q];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) { cur_u[q] = nxt_u[q]; cur_cf[q] = nxt_cf[q]; }
+    fetch_tiles(first + Q * G + lane_in_g, nxt_u, nxt_cf);
+#pragma unroll 1
+    for (int q = 0; q < Q; ++q) {
+        const int64_t tile = first + q * G;
+        if (Q > 1 && !__any(tile < e1)) break;
+        const int my_u = cur_u[0];
+        const float my_cf = cur_cf[0];
+#pragma unroll
+        for (int i = 0; i + 1 < Q; ++i) { cur_u[i] = cur_u[i + 1]; cur_cf[i] = cur_cf[i + 1]; }
         const int64_t left = e1 - tile;
         const int n_tile = left < G ? (left > 0 ? int(left) : 0) : G;
 
@@ -508,6 +526,7 @@ __global__ void __launch_bounds__(kBlockThreads) aggregate_kernel(const AggArgs 
                     }
                 }
         }
+    }
     }
 
     // combine the edge slots of the group
