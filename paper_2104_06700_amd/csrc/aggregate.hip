@@ -1046,9 +1046,12 @@ int run_aggregate(const void *indptr, const int32_t *indices, const float *w, co
     // small next to the E*F gather, buys 16-byte loads and the XCD column slices below.
     int64_t ldg = ldx;  // row stride of the matrix the kernel gathers from
     bool padded = false;
+    // explicit weights keep a plan that blocks by itself on the path without pieces unless they are bound to it
+    const bool blocks_expected = plan && !(o.flags & GNN_FLAG_NO_SOURCE_BLOCKS) && gnn_plan_blocks_expected(plan, int(esz)) &&
+                                 (!w || w == plan->bound_w || plan->blocking.min_degree > 0);
     const gnn_layout layout = gnn_choose_layout(plan, N, F, esz, ldx, reinterpret_cast<uintptr_t>(gathered) % 128 == 0,
                                                 o.flags, o.max_slices, /*allow_tail=*/o.max_slices != 1,
-                                                /*scaled_source=*/src_mode != kScaleNone);
+                                                /*scaled_source=*/src_mode != kScaleNone, blocks_expected);
     // what a producer can write into: the slice tables in rank order (the layout gnn_packed_target_for describes)
     if ((prepacked || pack_only) &&
         !(layout.padded_copy && layout.slice_major && !(o.flags & GNN_FLAG_NO_RANK_ORDER) && plan->n_edges > 0))
@@ -1500,7 +1503,8 @@ int gnn_packed_target_for(gnn_plan *plan, const void *indptr, const int32_t *ind
     else if (op == GNN_GCN_SYM) src_mode = kScaleRsqrt;
     else if (op == GNN_SAGE_GCN && backward) src_mode = kScaleInvPlus1;
     const gnn_layout layout = gnn_choose_layout(plan, N, F, 4, F, true, force ? GNN_FLAG_FORCE_PADDED_COPY : 0, force ? 8 : 0,
-                                                /*allow_tail=*/true, /*scaled_source=*/src_mode != kScaleNone);
+                                                /*allow_tail=*/true, /*scaled_source=*/src_mode != kScaleNone,
+                                                gnn_plan_blocks_expected(plan, 4));
     if (!(layout.padded_copy && layout.slice_major)) return GNN_OK;  // that call gathers rows where they lie
     const int64_t lines = (F + 31) / 32;
     if (lines < 2 || lines > 256) return GNN_OK;
@@ -1539,7 +1543,7 @@ int gnn_aggregate_prepacked(const void *indptr, const int32_t *indices, void *ou
 static void packed_opts(const gnn_opts *opts, gnn_opts &o) {
     o = gnn_opts{};
     if (opts) o = *opts;
-    o.flags = (o.flags | GNN_FLAG_FORCE_PADDED_COPY) &
+    o.flags = (o.flags | GNN_FLAG_FORCE_PADDED_COPY | GNN_FLAG_KEEP_DENSE_TAIL) &
               ~(GNN_FLAG_NO_PADDED_COPY | GNN_FLAG_NO_RANK_ORDER | GNN_FLAG_NO_COLUMN_SLICES | GNN_FLAG_NO_SLICE_TABLES);
     o.max_slices = 8;
 }

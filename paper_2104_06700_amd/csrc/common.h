@@ -23,6 +23,7 @@ struct gnn_plan {
     int32_t indptr_is_64 = 0;
     gnn_plan_params params{};
     int64_t bin_offsets[GNN_MAX_BINS + 1] = {0};  // host copy
+    int64_t bin_edges[GNN_MAX_BINS] = {0};        // edges of the rows of each bin (host)
     int32_t *row_perm = nullptr;      // [n_rows]
     int32_t *col_counts = nullptr;    // [n_rows] occurrences of each vertex in indices
     // hub rows = rows of the last bin when params.hub_chunk > 0
@@ -187,9 +188,33 @@ struct gnn_layout {
     int64_t bytes;        // size of the whole copy for N rows
 };
 
+// Internal gnn_opts.flags bit (not part of the public header): the layout keeps the dense tail table
+// whatever the plan (set by the calls that work on a caller-kept packed copy).
+constexpr int GNN_FLAG_KEEP_DENSE_TAIL = 1 << 30;
+
+// Will calls with this plan serve their long rows as source-blocked pieces (gnn_plan_blocked)?  Known
+// once the layout is built; before that, the gate of the automatic choice evaluated on the plan's host
+// figures (an explicit gnn_plan_set_blocking counts as yes).
+static inline bool gnn_plan_blocks_expected(const gnn_plan *plan, int esz) {
+    if (!plan || plan->n_edges <= 0 || plan->n_edges >= int64_t(INT32_MAX)) return false;
+    const bool automatic = plan->blocking.min_degree == 0;
+    if (esz == 2 && automatic && plan->n_rows < 8 * int64_t(32768)) return false;
+    if (plan->blk_decided) return plan->blk_n_pieces > 0;
+    if (plan->blocking.min_degree < 0) return false;
+    const int64_t min_degree = automatic ? 256 : plan->blocking.min_degree;
+    int first_bin = -1;
+    for (int i = 0; i < plan->params.n_thresholds; ++i)
+        if (plan->params.thresholds[i] == min_degree) first_bin = i + 1;
+    if (first_bin < 0 || plan->n_rows - plan->bin_offsets[first_bin] <= 0) return false;
+    int64_t long_edges = 0;
+    for (int b = first_bin; b < plan->n_bins; ++b) long_edges += plan->bin_edges[b];
+    if (long_edges <= 0) return false;
+    return !automatic || (plan->n_rows >= 4 * int64_t(32768) && long_edges * 4 >= plan->n_edges);
+}
+
 static inline gnn_layout gnn_choose_layout(const gnn_plan *plan, int64_t N, int64_t F, int esz, int64_t ldx,
                                            bool base_line_aligned, int flags, int max_slices, bool allow_tail = false,
-                                           bool scaled_source = false) {
+                                           bool scaled_source = false, bool blocks_expected = false) {
     gnn_layout L{};
     const int64_t line_elems = 128 / esz;
     const int64_t lines = (F + line_elems - 1) / line_elems;
@@ -227,7 +252,11 @@ static inline gnn_layout gnn_choose_layout(const gnn_plan *plan, int64_t N, int6
     // line-aligned rows with an even stride only when the matrix is large and slices are wanted.
     bool worth_it = row_bytes > 128 &&
                     ((!lines_ok && pays_at_any_size) || (folds_factor && pays_at_any_size) ||
-                     (big && L.slices_wanted && even_stride && plan && plan->n_edges >= (row_bytes >= 512 ? 16 : 128) * N));
+                     (big && L.slices_wanted && even_stride && plan && plan->n_edges >= (row_bytes >= 512 ? 16 : 128) * N) ||
+                     // the long rows as source-blocked pieces need the slice tables: whatever the stride, the copy
+                     // (N rows) buys the pieces (2.45 M vertices, 50 edges each, forward MEAN: F=96 4.42 in place,
+                     // 3.53 ms copied; F=64 3.09 / 2.45; F=160 7.48 / 5.81)
+                     (blocks_expected && big && L.slices_wanted && allow_tail && lines <= 256));
     // Rows of at most one line are copied into rows of the next power of two bytes (16 ... 128), in
     // rank order: no row straddles two lines, the most-gathered rows share lines (up to 8 per
     // line), and 16-byte loads apply.  Worth it when rows would straddle in place (F = 24: 96-byte
@@ -246,7 +275,13 @@ static inline gnn_layout gnn_choose_layout(const gnn_plan *plan, int64_t N, int6
     L.tail_elems = 0;
     L.tail_ld = 0;
     const int64_t rest = F % line_elems;
-    if (allow_tail && L.padded_copy && L.slices_wanted && lines >= 2 && lines <= 256 && rest > 0 && rest * esz <= 64) {
+    // A dense table for a short last line saves its padding and packs eight rows' tails into a line, but it
+    // is a launch of its own over all rows; where the long rows are source-blocked pieces the last line
+    // does better as one more slice of whole lines, which the pieces serve like the others (2.45 M
+    // vertices: F=100 4.84 -> 4.74 ms, F=112 5.08 -> 4.55; 233 K vertices F=100 2.63 -> 2.44).  Packed
+    // copies kept by a caller always have the tail table: their size must not depend on the plan.
+    const bool dense_tail = allow_tail && (!blocks_expected || (flags & GNN_FLAG_KEEP_DENSE_TAIL));
+    if (dense_tail && L.padded_copy && L.slices_wanted && lines >= 2 && lines <= 256 && rest > 0 && rest * esz <= 64) {
         const int64_t group = 16 / esz;
         L.tail_elems = rest;
         L.tail_ld = (rest + group - 1) / group * group;

@@ -63,6 +63,21 @@ __global__ void __launch_bounds__(256) count_buckets_kernel(const int32_t *__res
     if (se[threadIdx.x]) atomicAdd(&edges[threadIdx.x], se[threadIdx.x]);
 }
 
+// edges[b] += edges of the rows of bin b
+__global__ void __launch_bounds__(256) bin_edges_kernel(const void *__restrict__ indptr, int ip64, int64_t N, Thresholds thr,
+                                                        unsigned long long *__restrict__ edges) {
+    __shared__ unsigned long long se[GNN_MAX_BINS];
+    if (threadIdx.x < GNN_MAX_BINS) se[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t stride = int64_t(gridDim.x) * blockDim.x;
+    for (int64_t v = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; v < N; v += stride) {
+        const int64_t deg = load_ip(indptr, ip64, v + 1) - load_ip(indptr, ip64, v);
+        if (deg > 0) atomicAdd(&se[bin_of(deg, thr)], static_cast<unsigned long long>(deg));  // integer sums: any order
+    }
+    __syncthreads();
+    if (threadIdx.x < GNN_MAX_BINS && se[threadIdx.x]) atomicAdd(&edges[threadIdx.x], se[threadIdx.x]);
+}
+
 // block_counts[b * n_blocks + blk] = rows of bin b among rows [blk*1024, blk*1024+1024)
 __global__ void __launch_bounds__(kSplitThreads) bin_count_kernel(const void *__restrict__ indptr, int ip64,
                                                                   int64_t N, Thresholds thr, int64_t n_blocks,
@@ -466,7 +481,8 @@ extern "C" GNN_API int gnn_plan_prepare(gnn_plan *plan, const int32_t *indices, 
     {   // the padded copy a hot call on a dense, line-aligned matrix (ld = F) would use, if any
         // (a weight-less GCN call is assumed: with explicit weights the rows carry no factor)
         const bool scaled_source = ((op == GNN_MEAN || op == GNN_SAGE_GCN) && backward) || op == GNN_GCN_SYM;
-        const gnn_layout layout = gnn_choose_layout(plan, plan->n_rows, F, esz, F, true, 0, 0, /*allow_tail=*/true, scaled_source);
+        const gnn_layout layout = gnn_choose_layout(plan, plan->n_rows, F, esz, F, true, 0, 0, /*allow_tail=*/true, scaled_source,
+                                                    gnn_plan_blocks_expected(plan, esz));
         if (layout.padded_copy) {
             rc = gnn_plan_padded(plan, layout.bytes);
             if (rc != GNN_OK) return rc;
@@ -607,6 +623,21 @@ extern "C" GNN_API int gnn_plan_create(const void *indptr, const int32_t *indice
             }
         }
         (void)hipFree(buckets);
+        if (!ok) return fail(GNN_ERR_LAUNCH);
+    }
+
+    {   // edges per bin (host copy: which share of the edges the long rows hold decides the layout of a call)
+        unsigned long long *bin_edges = nullptr;
+        if (hipMalloc(&bin_edges, sizeof(unsigned long long) * GNN_MAX_BINS) != hipSuccess) return fail(GNN_ERR_ALLOC);
+        bool ok = hipMemsetAsync(bin_edges, 0, sizeof(unsigned long long) * GNN_MAX_BINS, stream) == hipSuccess;
+        if (ok) {
+            bin_edges_kernel<<<grid_for(N, 256, 2048), 256, 0, stream>>>(indptr, plan->indptr_is_64, N, thr, bin_edges);
+            unsigned long long host[GNN_MAX_BINS];
+            ok = hipMemcpyAsync(host, bin_edges, sizeof(host), hipMemcpyDeviceToHost, stream) == hipSuccess &&
+                 hipStreamSynchronize(stream) == hipSuccess;
+            for (int b = 0; ok && b < GNN_MAX_BINS; ++b) plan->bin_edges[b] = static_cast<int64_t>(host[b]);
+        }
+        (void)hipFree(bin_edges);
         if (!ok) return fail(GNN_ERR_LAUNCH);
     }
 
