@@ -210,8 +210,12 @@ GNN_API int gnn_aggregate_bwd(const void *indptr_t, const int32_t *indices_t, co
  *   is that plan's), else GNN_ERR_UNSUPPORTED; a graph without edges is GNN_ERR_UNSUPPORTED too.
  * gnn_aggregate_packed: gnn_aggregate_fwd (backward == 0: the arrays describe the graph) or
  *   gnn_aggregate_bwd (backward != 0: the transposed graph) reading `packed` in place of the
- *   matrix; same result as those calls with GNN_FLAG_FORCE_PADDED_COPY and max_slices = 8, bit
- *   for bit, without their copy.  opts->ldx is ignored; the layout flags of opts are overridden.
+ *   matrix; same result as those calls with GNN_FLAG_FORCE_PADDED_COPY and max_slices = 8,
+ *   without their copy -- bit for bit wherever both lay the matrix out alike, i.e. always except
+ *   for a width with a short last line on a plan whose long rows are source-blocked pieces (the
+ *   copying call then makes that line a slice of whole lines; the packed copy keeps a dense
+ *   table for it, since gnn_packed_bytes must not depend on the plan), where sums are added
+ *   in another order.  opts->ldx is ignored; the layout flags of opts are overridden.
  * The buffer stays the caller's; the library keeps no reference to it after the call's work has
  * run. */
 GNN_API int64_t gnn_packed_bytes(int64_t N, int64_t F, int dtype);

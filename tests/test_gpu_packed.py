@@ -153,3 +153,32 @@ def test_packed_calls_can_be_captured_into_a_graph():
         step()
         torch.cuda.synchronize()
         want = (Y.clone(), dX.clone())
+
+
+def test_packed_copy_on_a_plan_with_source_blocks_keeps_its_tail_table():
+    """With source blocks the copying call lays a short last line out as one more slice of whole lines; the
+    caller-kept copy keeps the dense tail table (its size depends on N, F and the type only).  Both give the
+    oracle's values, and the pieces read the packed copy's tail through the plain path."""
+    el = _graph()
+    indptr, indices, indptr_t, indices_t, _ = host_csr(el)
+    f = 100
+    X = synth.normal_features(el.n, f, 14)
+    Xd = X.to(DEV)
+    dg = device_graph(el, plan_params=gnn.make_plan_params([4, 32, 256], 64))
+    for plan in (dg.plan_fwd, dg.plan_bwd):
+        plan.set_blocking(min_degree=32, hot_lines=96, block_lines=200, max_piece=24, rest_min_count=3)
+    Yo, S = oracle.aggregate_fwd(indptr, indices, X.numpy(), op=oracle.OP_MEAN, nthreads=8, want_scale=True)
+    dXo, St = oracle.aggregate_bwd(indptr_t, indices_t, X.numpy(), op=oracle.OP_MEAN, din=np.diff(indptr), nthreads=8, want_scale=True)
+    pf, pb = _packed(dg, Xd, f, gnn.GNN_MEAN, False), _packed(dg, Xd, f, gnn.GNN_MEAN, True)
+    assert pf.numel() * 4 == el.n * (3 * 32 + 4) * 4
+    Y, dX, Yc, dXc = (torch.full((el.n, f), float("nan"), device=DEV) for _ in range(4))
+    gnn.gnn_aggregate_packed(dg.indptr, dg.indices, None, pf, Y, el.n, f, gnn.GNN_MEAN, False, plan=dg.plan_fwd)
+    gnn.gnn_aggregate_packed(dg.indptr_t, dg.indices_t, None, pb, dX, el.n, f, gnn.GNN_MEAN, True, plan=dg.plan_bwd)
+    gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, None, Xd, Yc, el.n, f, gnn.GNN_MEAN, plan=dg.plan_fwd,
+                          flags=gnn.GNN_FLAG_FORCE_PADDED_COPY, max_slices=8)
+    gnn.gnn_aggregate_bwd(dg.indptr_t, dg.indices_t, None, Xd, dXc, el.n, f, gnn.GNN_MEAN, plan=dg.plan_bwd,
+                          flags=gnn.GNN_FLAG_FORCE_PADDED_COPY, max_slices=8)
+    torch.cuda.synchronize()
+    assert dg.plan_fwd.blocked_sizes()[2] > 0 and dg.plan_bwd.blocked_sizes()[2] > 0
+    for what, g, o, s in (("packed fwd", Y, Yo, S), ("packed bwd", dX, dXo, St), ("copying fwd", Yc, Yo, S), ("copying bwd", dXc, dXo, St)):
+        assert_close(g, o, s, False, what)
