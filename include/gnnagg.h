@@ -117,6 +117,11 @@ typedef struct gnn_opts {
  * on the caller's stream, one launch after the other (also for A/B measurements).  Results do not
  * depend on it. */
 #define GNN_FLAG_NO_SHORT_ROW_OVERLAP 512
+/* A plan-owned copy in slice tables normally keeps a last line of at most 64 bytes in a dense table
+ * of its own (16-byte groups back to back, eight rows to a line, gathered by a launch of its own),
+ * except where the long rows are source-blocked pieces: there that line is one more table of whole
+ * lines, which the pieces serve like the others.  NO: always the table of whole lines. */
+#define GNN_FLAG_NO_DENSE_TAIL 1024
 
 /* Degree-binning parameters.  thresholds t[0] < ... < t[k-1], all > 0, cut the
  * row-length axis into k+1 bins, bin(v) = #{i : t[i] <= deg(v)}.  If
@@ -196,9 +201,9 @@ GNN_API int gnn_aggregate_bwd(const void *indptr_t, const int32_t *indices_t, co
 
 /* Packed copies that the caller keeps (Section 3: full-batch training aggregates the SAME input
  * features in every epoch).  A call on a large graph first copies the gathered matrix into the
- * plan's layout: one table per 128-byte column slice, rows ordered by descending gather count,
- * plus one dense table for a last slice of at most 64 bytes.  A caller whose matrix does not
- * change between calls makes that copy once, into a buffer of its own, and gathers from it.
+ * plan's layout: one table per 128-byte column slice (the last one padded to whole lines), rows
+ * ordered by descending gather count.  A caller whose matrix does not change between calls makes
+ * that copy once, into a buffer of its own, and gathers from it.
  *
  * gnn_packed_bytes: size of the copy of an [N, F] matrix; 0 when F is at most one line of 128
  *   bytes or more than 256 lines (such rows are not laid out as tables) or an argument is invalid.
@@ -210,12 +215,9 @@ GNN_API int gnn_aggregate_bwd(const void *indptr_t, const int32_t *indices_t, co
  *   is that plan's), else GNN_ERR_UNSUPPORTED; a graph without edges is GNN_ERR_UNSUPPORTED too.
  * gnn_aggregate_packed: gnn_aggregate_fwd (backward == 0: the arrays describe the graph) or
  *   gnn_aggregate_bwd (backward != 0: the transposed graph) reading `packed` in place of the
- *   matrix; same result as those calls with GNN_FLAG_FORCE_PADDED_COPY and max_slices = 8,
- *   without their copy -- bit for bit wherever both lay the matrix out alike, i.e. always except
- *   for a width with a short last line on a plan whose long rows are source-blocked pieces (the
- *   copying call then makes that line a slice of whole lines; the packed copy keeps a dense
- *   table for it, since gnn_packed_bytes must not depend on the plan), where sums are added
- *   in another order.  opts->ldx is ignored; the layout flags of opts are overridden.
+ *   matrix; same result as those calls with GNN_FLAG_FORCE_PADDED_COPY | GNN_FLAG_NO_DENSE_TAIL
+ *   and max_slices = 8, bit for bit, without their copy.  opts->ldx is ignored; the layout flags
+ *   of opts are overridden.
  * The buffer stays the caller's; the library keeps no reference to it after the call's work has
  * run. */
 GNN_API int64_t gnn_packed_bytes(int64_t N, int64_t F, int dtype);

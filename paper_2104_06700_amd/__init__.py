@@ -9,7 +9,7 @@ HIP kernels.
 from .binding import (  # noqa: F401
     GNN_OK, GNN_ERR_INVALID_ARG, GNN_ERR_UNSUPPORTED, GNN_ERR_ALLOC, GNN_ERR_LAUNCH, GNN_ERR_INVALID_GRAPH,
     GNN_ERR_SCRATCH_CAPACITY, GNN_NOALLOC_SCRATCH_BYTES, gnn_aggregate_fwd_noalloc, gnn_packed_bytes, gnn_pack_rows, gnn_aggregate_packed,
-    GNN_SUM, GNN_MEAN, GNN_GCN_SYM, GNN_SAGE_GCN, GNN_F32, GNN_BF16, GNN_MAX_THRESHOLDS, GNN_FLAG_NO_COLUMN_SLICES, GNN_FLAG_NO_PADDED_COPY, GNN_FLAG_FORCE_PADDED_COPY, GNN_FLAG_PADDED_ROWS, GNN_FLAG_NO_COLD_HINTS, GNN_FLAG_FORCE_COLD_HINTS, GNN_FLAG_NO_RANK_ORDER, GNN_FLAG_NO_SLICE_TABLES, GNN_FLAG_NO_SOURCE_BLOCKS, GNN_FLAG_NO_SHORT_ROW_OVERLAP, GNN_LAYER_FORCE_PRODUCER_LAYOUT, GNN_LAYER_NO_PRODUCER_LAYOUT, GNN_LAYER_NO_GATE_FOLD, GnnBlockingParams, EXPORTED_SYMBOLS, LIB_PATH,
+    GNN_SUM, GNN_MEAN, GNN_GCN_SYM, GNN_SAGE_GCN, GNN_F32, GNN_BF16, GNN_MAX_THRESHOLDS, GNN_FLAG_NO_COLUMN_SLICES, GNN_FLAG_NO_PADDED_COPY, GNN_FLAG_FORCE_PADDED_COPY, GNN_FLAG_PADDED_ROWS, GNN_FLAG_NO_COLD_HINTS, GNN_FLAG_FORCE_COLD_HINTS, GNN_FLAG_NO_RANK_ORDER, GNN_FLAG_NO_SLICE_TABLES, GNN_FLAG_NO_SOURCE_BLOCKS, GNN_FLAG_NO_SHORT_ROW_OVERLAP, GNN_FLAG_NO_DENSE_TAIL, GNN_LAYER_FORCE_PRODUCER_LAYOUT, GNN_LAYER_NO_PRODUCER_LAYOUT, GNN_LAYER_NO_GATE_FOLD, GnnBlockingParams, EXPORTED_SYMBOLS, LIB_PATH,
     GNN_BIN_ADD, GNN_BIN_SUB, GNN_BIN_MUL, GNN_BIN_DIV, GNN_BIN_COPY_LHS, GNN_BIN_COPY_RHS, GNN_RED_SUM, GNN_RED_MAX, GNN_RED_MIN,
     GnnError, GnnOpts, GnnApOpts, GnnLayerOpts, GnnPlanParams, Plan,
     load_library, status_string, make_plan_params,

@@ -31,6 +31,7 @@ GNN_FLAG_NO_RANK_ORDER = 64
 GNN_FLAG_NO_SLICE_TABLES = 128
 GNN_FLAG_NO_SOURCE_BLOCKS = 256
 GNN_FLAG_NO_SHORT_ROW_OVERLAP = 512
+GNN_FLAG_NO_DENSE_TAIL = 1024
 GNN_BIN_ADD, GNN_BIN_SUB, GNN_BIN_MUL, GNN_BIN_DIV, GNN_BIN_COPY_LHS, GNN_BIN_COPY_RHS = range(6)
 GNN_RED_SUM, GNN_RED_MAX, GNN_RED_MIN = range(3)
 

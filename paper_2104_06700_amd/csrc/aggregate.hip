@@ -1543,7 +1543,7 @@ int gnn_aggregate_prepacked(const void *indptr, const int32_t *indices, void *ou
 static void packed_opts(const gnn_opts *opts, gnn_opts &o) {
     o = gnn_opts{};
     if (opts) o = *opts;
-    o.flags = (o.flags | GNN_FLAG_FORCE_PADDED_COPY | GNN_FLAG_KEEP_DENSE_TAIL) &
+    o.flags = (o.flags | GNN_FLAG_FORCE_PADDED_COPY | GNN_FLAG_NO_DENSE_TAIL) &
               ~(GNN_FLAG_NO_PADDED_COPY | GNN_FLAG_NO_RANK_ORDER | GNN_FLAG_NO_COLUMN_SLICES | GNN_FLAG_NO_SLICE_TABLES);
     o.max_slices = 8;
 }
@@ -1553,10 +1553,7 @@ extern "C" GNN_API int64_t gnn_packed_bytes(int64_t N, int64_t F, int dtype) {
     const int64_t esz = dtype == GNN_BF16 ? 2 : 4, line_elems = 128 / esz;
     const int64_t lines = (F + line_elems - 1) / line_elems;
     if (lines < 2 || lines > 256) return 0;  // rows of one line are not laid out as slice tables
-    const int64_t rest = F % line_elems;
-    const bool tail = rest > 0 && rest * esz <= 64;
-    const int64_t group = 16 / esz;
-    return N * ((tail ? lines - 1 : lines) * line_elems + (tail ? (rest + group - 1) / group * group : 0)) * esz;
+    return N * lines * 128;
 }
 
 extern "C" GNN_API int gnn_pack_rows(const void *indptr, const int32_t *indices, const void *X, void *packed,

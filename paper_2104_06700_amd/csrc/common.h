@@ -188,10 +188,6 @@ struct gnn_layout {
     int64_t bytes;        // size of the whole copy for N rows
 };
 
-// Internal gnn_opts.flags bit (not part of the public header): the layout keeps the dense tail table
-// whatever the plan (set by the calls that work on a caller-kept packed copy).
-constexpr int GNN_FLAG_KEEP_DENSE_TAIL = 1 << 30;
-
 // Will calls with this plan serve their long rows as source-blocked pieces (gnn_plan_blocked)?  Known
 // once the layout is built; before that, the gate of the automatic choice evaluated on the plan's host
 // figures (an explicit gnn_plan_set_blocking counts as yes).
@@ -279,8 +275,9 @@ static inline gnn_layout gnn_choose_layout(const gnn_plan *plan, int64_t N, int6
     // is a launch of its own over all rows; where the long rows are source-blocked pieces the last line
     // does better as one more slice of whole lines, which the pieces serve like the others (2.45 M
     // vertices: F=100 4.84 -> 4.74 ms, F=112 5.08 -> 4.55; 233 K vertices F=100 2.63 -> 2.44).  Packed
-    // copies kept by a caller always have the tail table: their size must not depend on the plan.
-    const bool dense_tail = allow_tail && (!blocks_expected || (flags & GNN_FLAG_KEEP_DENSE_TAIL));
+    // copies kept by a caller never have the tail table (GNN_FLAG_NO_DENSE_TAIL): their size must not depend
+    // on the plan.
+    const bool dense_tail = allow_tail && !blocks_expected && !(flags & GNN_FLAG_NO_DENSE_TAIL);
     if (dense_tail && L.padded_copy && L.slices_wanted && lines >= 2 && lines <= 256 && rest > 0 && rest * esz <= 64) {
         const int64_t group = 16 / esz;
         L.tail_elems = rest;

@@ -106,13 +106,13 @@ def test_argument_checks_that_need_no_device():
 
 
 def test_packed_copy_sizes_and_argument_checks_that_need_no_device():
-    """gnn_packed_bytes is host arithmetic: one table per whole 128-byte line of a row, a dense table of
-    16-byte groups for a last line of at most 64 bytes; nothing for rows of one line or of more than 256."""
-    assert gnn.gnn_packed_bytes(1000, 100, gnn.GNN_F32) == 1000 * (3 * 32 + 4) * 4
+    """gnn_packed_bytes is host arithmetic: one table of whole 128-byte lines per line of a row (two to 256
+    lines; the last one padded)."""
+    assert gnn.gnn_packed_bytes(1000, 100, gnn.GNN_F32) == 1000 * 4 * 128
     assert gnn.gnn_packed_bytes(1000, 256, gnn.GNN_F32) == 1000 * 256 * 4
     assert gnn.gnn_packed_bytes(1000, 50, gnn.GNN_F32) == 1000 * 64 * 4
-    assert gnn.gnn_packed_bytes(1000, 47, gnn.GNN_F32) == 1000 * (32 + 16) * 4
-    assert gnn.gnn_packed_bytes(7, 65, gnn.GNN_BF16) == 7 * (64 + 8) * 2
+    assert gnn.gnn_packed_bytes(1000, 47, gnn.GNN_F32) == 1000 * 2 * 128
+    assert gnn.gnn_packed_bytes(7, 65, gnn.GNN_BF16) == 7 * 2 * 128
     assert gnn.gnn_packed_bytes(1000, 32, gnn.GNN_F32) == 0 and gnn.gnn_packed_bytes(1000, 64, gnn.GNN_BF16) == 0
     assert gnn.gnn_packed_bytes(1000, 256 * 32, gnn.GNN_F32) == 1000 * 256 * 32 * 4
     assert gnn.gnn_packed_bytes(1000, 256 * 32 + 1, gnn.GNN_F32) == 0

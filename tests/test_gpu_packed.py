@@ -55,9 +55,9 @@ def test_packed_aggregation_matches_the_oracle_and_the_copying_call(dtype, f):
             assert_close(dX, dXo, St, bf16, f"packed bwd {op_name} F={f}")
             Yc, dXc = torch.empty_like(Y), torch.empty_like(dX)
             gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, None, Xd, Yc, el.n, f, op, plan=dg.plan_fwd,
-                                  flags=gnn.GNN_FLAG_FORCE_PADDED_COPY, max_slices=8)
+                                  flags=gnn.GNN_FLAG_FORCE_PADDED_COPY | gnn.GNN_FLAG_NO_DENSE_TAIL, max_slices=8)
             gnn.gnn_aggregate_bwd(dg.indptr_t, dg.indices_t, None, Xd, dXc, el.n, f, op, plan=dg.plan_bwd,
-                                  flags=gnn.GNN_FLAG_FORCE_PADDED_COPY, max_slices=8)
+                                  flags=gnn.GNN_FLAG_FORCE_PADDED_COPY | gnn.GNN_FLAG_NO_DENSE_TAIL, max_slices=8)
             torch.cuda.synchronize()
             assert torch.equal(Y, Yc), f"fwd {op_name} F={f}: differs from the copying call"
             assert torch.equal(dX, dXc), f"bwd {op_name} F={f}: differs from the copying call"
@@ -86,10 +86,10 @@ def test_packed_aggregation_with_edge_weights_and_strided_input():
 
 
 def test_packed_sizes_and_argument_checks():
-    assert gnn.gnn_packed_bytes(1000, 100, gnn.GNN_F32) == 1000 * (3 * 32 + 4) * 4     # three lines and a 16-byte tail
+    assert gnn.gnn_packed_bytes(1000, 100, gnn.GNN_F32) == 1000 * 4 * 128              # four lines, the last one padded
     assert gnn.gnn_packed_bytes(1000, 256, gnn.GNN_F32) == 1000 * 256 * 4
-    assert gnn.gnn_packed_bytes(1000, 50, gnn.GNN_F32) == 1000 * 64 * 4                # 72 bytes in the last line: a whole line
-    assert gnn.gnn_packed_bytes(1000, 65, gnn.GNN_BF16) == 1000 * (64 + 8) * 2
+    assert gnn.gnn_packed_bytes(1000, 50, gnn.GNN_F32) == 1000 * 64 * 4
+    assert gnn.gnn_packed_bytes(1000, 65, gnn.GNN_BF16) == 1000 * 2 * 128
     assert gnn.gnn_packed_bytes(1000, 32, gnn.GNN_F32) == 0                            # one line: no tables
     assert gnn.gnn_packed_bytes(1000, 257 * 32, gnn.GNN_F32) == 0
     assert gnn.gnn_packed_bytes(0, 100, gnn.GNN_F32) == 0 and gnn.gnn_packed_bytes(10, 100, 7) == 0
@@ -155,10 +155,10 @@ def test_packed_calls_can_be_captured_into_a_graph():
         want = (Y.clone(), dX.clone())
 
 
-def test_packed_copy_on_a_plan_with_source_blocks_keeps_its_tail_table():
-    """With source blocks the copying call lays a short last line out as one more slice of whole lines; the
-    caller-kept copy keeps the dense tail table (its size depends on N, F and the type only).  Both give the
-    oracle's values, and the pieces read the packed copy's tail through the plain path."""
+def test_packed_copy_on_a_plan_with_source_blocks():
+    """The caller-kept copy has no dense tail table (its size depends on N, F and the type only): on a plan with
+    source blocks a short last line is one more table of whole lines, served by the pieces like the others, and
+    the call gives the bits of the copying call with the same flags."""
     el = _graph()
     indptr, indices, indptr_t, indices_t, _ = host_csr(el)
     f = 100
@@ -170,15 +170,15 @@ def test_packed_copy_on_a_plan_with_source_blocks_keeps_its_tail_table():
     Yo, S = oracle.aggregate_fwd(indptr, indices, X.numpy(), op=oracle.OP_MEAN, nthreads=8, want_scale=True)
     dXo, St = oracle.aggregate_bwd(indptr_t, indices_t, X.numpy(), op=oracle.OP_MEAN, din=np.diff(indptr), nthreads=8, want_scale=True)
     pf, pb = _packed(dg, Xd, f, gnn.GNN_MEAN, False), _packed(dg, Xd, f, gnn.GNN_MEAN, True)
-    assert pf.numel() * 4 == el.n * (3 * 32 + 4) * 4
+    assert pf.numel() * 4 == el.n * 4 * 128
     Y, dX, Yc, dXc = (torch.full((el.n, f), float("nan"), device=DEV) for _ in range(4))
     gnn.gnn_aggregate_packed(dg.indptr, dg.indices, None, pf, Y, el.n, f, gnn.GNN_MEAN, False, plan=dg.plan_fwd)
     gnn.gnn_aggregate_packed(dg.indptr_t, dg.indices_t, None, pb, dX, el.n, f, gnn.GNN_MEAN, True, plan=dg.plan_bwd)
-    gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, None, Xd, Yc, el.n, f, gnn.GNN_MEAN, plan=dg.plan_fwd,
-                          flags=gnn.GNN_FLAG_FORCE_PADDED_COPY, max_slices=8)
-    gnn.gnn_aggregate_bwd(dg.indptr_t, dg.indices_t, None, Xd, dXc, el.n, f, gnn.GNN_MEAN, plan=dg.plan_bwd,
-                          flags=gnn.GNN_FLAG_FORCE_PADDED_COPY, max_slices=8)
+    flags = gnn.GNN_FLAG_FORCE_PADDED_COPY | gnn.GNN_FLAG_NO_DENSE_TAIL
+    gnn.gnn_aggregate_fwd(dg.indptr, dg.indices, None, Xd, Yc, el.n, f, gnn.GNN_MEAN, plan=dg.plan_fwd, flags=flags, max_slices=8)
+    gnn.gnn_aggregate_bwd(dg.indptr_t, dg.indices_t, None, Xd, dXc, el.n, f, gnn.GNN_MEAN, plan=dg.plan_bwd, flags=flags, max_slices=8)
     torch.cuda.synchronize()
     assert dg.plan_fwd.blocked_sizes()[2] > 0 and dg.plan_bwd.blocked_sizes()[2] > 0
-    for what, g, o, s in (("packed fwd", Y, Yo, S), ("packed bwd", dX, dXo, St), ("copying fwd", Yc, Yo, S), ("copying bwd", dXc, dXo, St)):
-        assert_close(g, o, s, False, what)
+    for what, g, o, s_ in (("packed fwd", Y, Yo, S), ("packed bwd", dX, dXo, St)):
+        assert_close(g, o, s_, False, what)
+    assert torch.equal(Y, Yc) and torch.equal(dX, dXc)
